@@ -1,0 +1,211 @@
+"""CPU oracle, part 2: serial propagation and MGRIT over the layer axis.
+
+TEST INFRASTRUCTURE ONLY (see transformer_ode.py).  float64, plain loops, every
+level has its own arrays; nothing is fused, aliased or skipped.
+
+MGRIT is an iteration: its limit is serial propagation, its nu-th iterate is
+not.  So this file holds both the definition (serial_*) and the algorithm
+taken step by step in the paper's order (section 3.2, the two-level box of
+Fig. 2, the V-cycle paragraph, and FCF-relaxation of Appendix A / Algorithm 1).
+
+Level l (l = 0 .. L-1) has N_l = N / cf^l steps of size cf^l * h and the level
+equation  w_j = Phi^l_{j-1}(w_{j-1}) + g_j,  j = 1..N_l,  w_0 = the initial
+value; on level 0 g == 0 and the equation is serial propagation written as the
+block-bidiagonal system A_0 W_0 = G_0.  C-points of a level are the indices
+k*cf, the others are F-points.
+
+One V-cycle on level l < L-1:
+  1. relaxation: F-relaxation (cf-1 steps from every C-point, all intervals
+     independent), and for FCF also C-relaxation (one step into every C-point)
+     followed by F-relaxation again;
+  2. residual of the level equation at the C-points, r_k = Phi(w_{k cf - 1})
+     + g_{k cf} - w_{k cf}; it is zero at F-points after F-relaxation; on
+     level 0 its 2-norm is recorded (the convergence indicator is the ratio of
+     consecutive norms);
+  3. restriction by injection: coarse unknowns = the C-point values; because
+     the operator is nonlinear the coarse error equation A_1 e_1 = r_1 is posed
+     in full-approximation form: solve  v_k = Phi^{l+1}_{k-1}(v_{k-1}) + g^{l+1}_k
+     with  g^{l+1}_k = what_k - Phi^{l+1}_{k-1}(what_{k-1}) + r_k  (what = injected
+     values) -- for a linear F this is exactly A_1 e_1 = r_1 with e = v - what;
+  4. coarse solve: serially on the coarsest level, else recursively a V-cycle;
+  5. correction w_{k cf} += v_k - what_k, then F-relaxation so that the
+     F-points follow the corrected C-points ("interpolation").
+
+A coarse step that starts at coarse point j of level l uses the parameters of
+the fine layer j*cf^l (theta is a function of time sampled at t_n) and the step
+size cf^l * h.
+
+The adjoint problem is the same algorithm on the reversed index m = N - n with
+mu_m = lambda_{N-m}: the level-l step from m=j to j+1 is
+mu + cf^l h J(Z_n; theta_n)^T mu with n = N - (j+1) cf^l, i.e. the transpose of
+the coarse forward step that starts at layer n.
+
+Pins (tests/test_oracle_mgrit.py): one level or cf = 1 == serial; exactness
+front of two-level MGRIT (k C-points per F-iteration, 2k per FCF-iteration);
+serial solution is a fixed point with zero residual; closed-form recurrences
+for a scalar linear F; three-level fixed point and limit.
+"""
+from __future__ import annotations
+
+from typing import Callable, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import transformer_ode as tode
+
+# A propagator is step(level, j, w) -> Phi^level_j(w): the step that starts at
+# point j of that level (without the right-hand side g).
+Propagator = Callable[[int, int, np.ndarray], np.ndarray]
+
+
+def serial_solve(step: Propagator, w0: np.ndarray, N: int) -> List[np.ndarray]:
+    """w_{n+1} = Phi^0_n(w_n), n = 0..N-1.  Returns [w_0 .. w_N]."""
+    W = [np.array(w0, dtype=np.float64)]
+    for n in range(N):
+        W.append(step(0, n, W[n]))
+    return W
+
+
+def _f_relax(step, lvl, W, g, cf, M):
+    for k in range(M):                         # parallel-for over coarse intervals
+        n = cf * k
+        for i in range(cf - 1):
+            W[n + i + 1] = step(lvl, n + i, W[n + i]) + g[n + i + 1]
+
+
+def _c_relax(step, lvl, W, g, cf, M):
+    new = {}
+    for k in range(1, M + 1):                  # parallel-for: reads only F-points
+        n = cf * k
+        new[n] = step(lvl, n - 1, W[n - 1]) + g[n]
+    for n, v in new.items():
+        W[n] = v
+
+
+def _vcycle(step, lvl, W, g, cf, levels, relax, resnorms, counts):
+    N_l = len(W) - 1
+    if lvl == levels - 1:                      # coarsest level: serial solve
+        for j in range(1, N_l + 1):
+            W[j] = step(lvl, j - 1, W[j - 1]) + g[j]
+        counts[lvl] += N_l
+        return
+    M = N_l // cf
+    _f_relax(step, lvl, W, g, cf, M)
+    counts[lvl] += M * (cf - 1)
+    if relax == "FCF":
+        _c_relax(step, lvl, W, g, cf, M)
+        _f_relax(step, lvl, W, g, cf, M)
+        counts[lvl] += M * cf
+    # residual at the C-points
+    r = [None] * (M + 1)
+    for k in range(1, M + 1):
+        n = cf * k
+        r[k] = step(lvl, n - 1, W[n - 1]) + g[n] - W[n]
+    counts[lvl] += M
+    if lvl == 0:
+        resnorms.append(float(np.sqrt(sum(float(np.sum(rk * rk)) for rk in r[1:]))))
+    # restriction by injection + FAS right-hand side
+    Wc = [W[cf * k].copy() for k in range(M + 1)]
+    What = [w.copy() for w in Wc]
+    gc = [np.zeros_like(W[0]) for _ in range(M + 1)]
+    for k in range(1, M + 1):
+        gc[k] = What[k] - step(lvl + 1, k - 1, What[k - 1]) + r[k]
+    counts[lvl + 1] += M
+    _vcycle(step, lvl + 1, Wc, gc, cf, levels, relax, resnorms, counts)
+    # correction at the C-points, then interpolation by F-relaxation
+    for k in range(1, M + 1):
+        W[cf * k] = W[cf * k] + (Wc[k] - What[k])
+    _f_relax(step, lvl, W, g, cf, M)
+    counts[lvl] += M * (cf - 1)
+
+
+def mgrit_solve(step: Propagator, w0: np.ndarray, N: int, cf: int, levels: int, iters: int,
+                relax: str = "FCF", init: Optional[Sequence[np.ndarray]] = None
+                ) -> Tuple[List[np.ndarray], List[float], List[int]]:
+    """`iters` V-cycles of `levels`-level MGRIT for w_{n+1} = Phi_n(w_n).
+
+    Initial guess: w0 copied into every point (only the C-point values matter,
+    the first F-relaxation overwrites the F-points), or `init` (N+1 states).
+    Returns (states [w_0..w_N], residual norms per iteration, step
+    evaluations per level).
+    """
+    assert relax in ("F", "FCF")
+    assert cf >= 1 and levels >= 1 and iters >= 0
+    if levels == 1 or cf == 1:
+        W = serial_solve(step, w0, N)
+        return W, [], [N]
+    assert N % (cf ** (levels - 1)) == 0, "N must be divisible by cf^(levels-1)"
+    w0 = np.array(w0, dtype=np.float64)
+    if init is None:
+        W = [w0.copy() for _ in range(N + 1)]
+    else:
+        assert len(init) == N + 1
+        W = [np.array(x, dtype=np.float64) for x in init]
+        W[0] = w0.copy()
+    g = [np.zeros_like(w0) for _ in range(N + 1)]
+    resnorms: List[float] = []
+    counts = [0] * levels
+    for _ in range(iters):
+        _vcycle(step, 0, W, g, cf, levels, relax, resnorms, counts)
+    return W, resnorms, counts
+
+
+# ----------------------------------------------------------------------------
+# propagators
+# ----------------------------------------------------------------------------
+def forward_propagator(theta: Sequence[dict], h: float, cf: int, sh: tode.Shape,
+                       mem=None) -> Propagator:
+    """Phi^l_j(w) = w + cf^l h F(w; theta_{j cf^l})."""
+    def step(lvl, j, w):
+        s = cf ** lvl
+        return tode.phi(w, theta[j * s], s * h, sh, mem)
+    return step
+
+
+def adjoint_propagator(theta: Sequence[dict], Z: Sequence[np.ndarray], h: float, cf: int,
+                       sh: tode.Shape, mem=None) -> Propagator:
+    """Step of the reversed-index adjoint system, linearised at the stored states Z_n."""
+    N = len(Z) - 1
+
+    def step(lvl, j, mu):
+        s = cf ** lvl
+        n = N - (j + 1) * s
+        return tode.psi(mu, Z[n], theta[n], s * h, sh, mem)
+    return step
+
+
+def linear_propagator(a: float, h: float, cf: int) -> Propagator:
+    """Toy problem dz/dt = a z: Phi^l(w) = (1 + cf^l h a) w (same at every point)."""
+    def step(lvl, j, w):
+        return (1.0 + (cf ** lvl) * h * a) * w
+    return step
+
+
+# ----------------------------------------------------------------------------
+# the four entry points the HIP library is compared with
+# ----------------------------------------------------------------------------
+def serial_forward(Z0, theta, h, sh, mem=None):
+    return serial_solve(forward_propagator(theta, h, 1, sh, mem), Z0, len(theta))
+
+
+def mgrit_forward(Z0, theta, h, cf, levels, iters, sh, mem=None, relax="FCF", init=None):
+    """Returns (Z_0..Z_N, residual norms, evaluation counts per level)."""
+    return mgrit_solve(forward_propagator(theta, h, cf, sh, mem), Z0, len(theta),
+                       cf, levels, iters, relax, init)
+
+
+def serial_adjoint(lamN, Z, theta, h, sh, mem=None):
+    """lambda_n for n = 0..N (index n, not the reversed index)."""
+    N = len(theta)
+    mu = serial_solve(adjoint_propagator(theta, Z, h, 1, sh, mem), lamN, N)
+    return mu[::-1]
+
+
+def mgrit_adjoint(lamN, Z, theta, h, cf, levels, iters, sh, mem=None, relax="FCF", init=None):
+    """Returns (lambda_0..lambda_N, residual norms, evaluation counts per level)."""
+    N = len(theta)
+    if init is not None:
+        init = list(init)[::-1]
+    mu, res, counts = mgrit_solve(adjoint_propagator(theta, Z, h, cf, sh, mem), lamN, N,
+                                  cf, levels, iters, relax, init)
+    return mu[::-1], res, counts

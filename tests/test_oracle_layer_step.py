@@ -1,0 +1,199 @@
+"""Pins for the oracle's layer step and its adjoint (CPU only).
+
+The oracle is compared with things other than itself:
+* with h = 1 the step is the ordinary pre-LN transformer block (paper section
+  3.1: "h = 1 for standard transformers"), so it must equal torch's own
+  TransformerEncoderLayer / TransformerDecoderLayer (norm_first) in float64;
+* lambda is "the backpropagated gradient", so the hand-written adjoint must
+  equal torch.autograd through an independent torch forward, central finite
+  differences, and satisfy the transpose identity <c, J v> = <J^T c, v>;
+* zero weights give F == 0.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import transformer_ode as tode
+from paper_2601_09026_amd import workloads as wls
+
+
+def small(arch, d=32, H=4, f=64, B=2, S=5, Sm=7, N=3, std=0.3, seed=7):
+    wl = wls.Workload("t", arch, d, H, f, B, S, Sm if arch == wls.ARCH_CROSS else 0,
+                      N, 1.0, 1, 1, 0, wls.DTYPE_F32, seed)
+    sh = tode.Shape(arch, d, H, B, S, wl.mem_seq)
+    th = [wls.layer_params(wl, n, weight_std=std) for n in range(N)]
+    return wl, sh, th
+
+
+def torch_layer(wl, th):
+    d, H, f = wl.d_model, wl.n_heads, wl.d_ff
+    t = lambda a: torch.tensor(a, dtype=torch.float64)
+    if wl.arch == wls.ARCH_CROSS:
+        L = torch.nn.TransformerDecoderLayer(d, H, f, dropout=0.0, activation="gelu",
+                                             batch_first=True, norm_first=True,
+                                             dtype=torch.float64)
+    else:
+        L = torch.nn.TransformerEncoderLayer(d, H, f, dropout=0.0, activation="gelu",
+                                             batch_first=True, norm_first=True,
+                                             dtype=torch.float64)
+    with torch.no_grad():
+        L.self_attn.in_proj_weight.copy_(t(th["Wqkv"]))
+        L.self_attn.in_proj_bias.copy_(t(th["bqkv"]))
+        L.self_attn.out_proj.weight.copy_(t(th["Wo"]))
+        L.self_attn.out_proj.bias.copy_(t(th["bo"]))
+        L.norm1.weight.copy_(t(th["ln1_g"])); L.norm1.bias.copy_(t(th["ln1_b"]))
+        L.linear1.weight.copy_(t(th["W1"])); L.linear1.bias.copy_(t(th["b1"]))
+        L.linear2.weight.copy_(t(th["W2"])); L.linear2.bias.copy_(t(th["b2"]))
+        if wl.arch == wls.ARCH_CROSS:
+            # torch's decoder layer: norm2 precedes cross-attention, norm3 the MLP
+            L.norm2.weight.copy_(t(th["ln3_g"])); L.norm2.bias.copy_(t(th["ln3_b"]))
+            L.norm3.weight.copy_(t(th["ln2_g"])); L.norm3.bias.copy_(t(th["ln2_b"]))
+            w = torch.cat([t(th["Wq_c"]), t(th["Wkv_c"])], 0)
+            b = torch.cat([t(th["bq_c"]), t(th["bkv_c"])], 0)
+            L.multihead_attn.in_proj_weight.copy_(w)
+            L.multihead_attn.in_proj_bias.copy_(b)
+            L.multihead_attn.out_proj.weight.copy_(t(th["Wo_c"]))
+            L.multihead_attn.out_proj.bias.copy_(t(th["bo_c"]))
+        else:
+            L.norm2.weight.copy_(t(th["ln2_g"])); L.norm2.bias.copy_(t(th["ln2_b"]))
+    L.train()   # the eval-mode fast path may fuse; train mode with dropout 0 is the plain path
+    return L
+
+
+def torch_step(wl, L, X, mem, h):
+    """X + h * (block(X) - X) with torch's own block (block(X) = X + F(X) at h = 1)."""
+    B, S, d = wl.batch, wl.seq, wl.d_model
+    x = X.reshape(B, S, d)
+    if wl.arch == wls.ARCH_CROSS:
+        causal = torch.nn.Transformer.generate_square_subsequent_mask(S, dtype=torch.float64)
+        y = L(x, mem.reshape(B, wl.mem_seq, d), tgt_mask=causal)
+    elif wl.arch == wls.ARCH_CAUSAL:
+        causal = torch.nn.Transformer.generate_square_subsequent_mask(S, dtype=torch.float64)
+        y = L(x, src_mask=causal)
+    else:
+        y = L(x)
+    return (x + h * (y - x)).reshape(B * S, d)
+
+
+ARCHS = [wls.ARCH_ENCODER, wls.ARCH_CAUSAL, wls.ARCH_CROSS]
+
+
+@pytest.mark.parametrize("arch", ARCHS)
+def test_h1_step_is_standard_prelayernorm_block(arch):
+    wl, sh, th = small(arch)
+    X = wls.initial_state(wl).astype(np.float64)
+    mem = wls.cross_memory(wl)
+    L = torch_layer(wl, th[0])
+    tm = None if mem is None else torch.tensor(mem, dtype=torch.float64)
+    with torch.no_grad():
+        ref = torch_step(wl, L, torch.tensor(X), tm, 1.0).numpy()
+    got = tode.phi(X, th[0], 1.0, sh, mem)
+    assert np.abs(got - ref).max() < 1e-12 * max(1.0, np.abs(ref).max())
+    # the step size scales F only, never the inner residuals
+    with torch.no_grad():
+        ref_h = torch_step(wl, L, torch.tensor(X), tm, 0.25).numpy()
+    got_h = tode.phi(X, th[0], 0.25, sh, mem)
+    assert np.abs(got_h - ref_h).max() < 1e-12 * max(1.0, np.abs(ref_h).max())
+
+
+@pytest.mark.parametrize("arch", ARCHS)
+def test_vjp_equals_autograd(arch):
+    wl, sh, th = small(arch)
+    X = wls.initial_state(wl).astype(np.float64)
+    c = wls.terminal_adjoint(wl).astype(np.float64)
+    mem = wls.cross_memory(wl)
+    L = torch_layer(wl, th[0])
+    xt = torch.tensor(X, requires_grad=True)
+    mt = None if mem is None else torch.tensor(mem, dtype=torch.float64, requires_grad=True)
+    # F = block(X) - X
+    Fx = torch_step(wl, L, xt, mt, 1.0) - xt
+    inputs = [xt] if mt is None else [xt, mt]
+    grads = torch.autograd.grad((Fx * torch.tensor(c)).sum(), inputs)
+    dX, dE = tode.F_vjp(X, th[0], c, sh, mem)
+    assert np.abs(dX - grads[0].numpy()).max() < 1e-11 * max(1.0, np.abs(dX).max())
+    if mt is not None:
+        assert np.abs(dE - grads[1].numpy()).max() < 1e-11 * max(1.0, np.abs(dE).max())
+    else:
+        assert dE is None
+
+
+@pytest.mark.parametrize("arch", ARCHS)
+def test_vjp_finite_differences_and_transpose_identity(arch):
+    wl, sh, th = small(arch, d=16, H=2, f=24, B=1, S=4, Sm=3)
+    rng = np.random.default_rng(3)
+    X = wls.initial_state(wl).astype(np.float64)
+    c = wls.terminal_adjoint(wl).astype(np.float64)
+    mem = wls.cross_memory(wl)
+    dX, dE = tode.F_vjp(X, th[0], c, sh, mem)
+    eps = 1e-6
+    for _ in range(6):
+        v = rng.standard_normal(X.shape)
+        Jv = (tode.F(X + eps * v, th[0], sh, mem) - tode.F(X - eps * v, th[0], sh, mem)) / (2 * eps)
+        lhs, rhs = float((c * Jv).sum()), float((dX * v).sum())
+        assert abs(lhs - rhs) < 1e-7 * max(1.0, abs(lhs))
+    # entry-wise central differences of <c, F(X)>
+    for (i, j) in [(0, 0), (1, 5), (3, 15)]:
+        E = np.zeros_like(X); E[i, j] = eps
+        fd = ((c * tode.F(X + E, th[0], sh, mem)).sum() - (c * tode.F(X - E, th[0], sh, mem)).sum()) / (2 * eps)
+        assert abs(fd - dX[i, j]) < 1e-7 * max(1.0, abs(fd))
+    if mem is not None:
+        for _ in range(3):
+            v = rng.standard_normal(mem.shape)
+            Jv = (tode.F(X, th[0], sh, mem + eps * v) - tode.F(X, th[0], sh, mem - eps * v)) / (2 * eps)
+            lhs, rhs = float((c * Jv).sum()), float((dE * v).sum())
+            assert abs(lhs - rhs) < 1e-7 * max(1.0, abs(lhs))
+
+
+@pytest.mark.parametrize("arch", ARCHS)
+def test_psi_is_adjoint_of_phi_through_a_serial_stack(arch):
+    """lambda_0 from chained psi equals d<C, Z_N>/dZ_0 by autograd through N torch blocks."""
+    wl, sh, th = small(arch, N=3)
+    h = 0.5
+    X = wls.initial_state(wl).astype(np.float64)
+    C = wls.terminal_adjoint(wl).astype(np.float64)
+    mem = wls.cross_memory(wl)
+    mt = None if mem is None else torch.tensor(mem, dtype=torch.float64)
+    xt = torch.tensor(X, requires_grad=True)
+    z = xt
+    for n in range(wl.N):
+        z = torch_step(wl, torch_layer(wl, th[n]), z, mt, h)
+    (g,) = torch.autograd.grad((z * torch.tensor(C)).sum(), [xt])
+    Z = [X]
+    for n in range(wl.N):
+        Z.append(tode.phi(Z[n], th[n], h, sh, mem))
+    lam = C
+    for n in reversed(range(wl.N)):
+        lam = tode.psi(lam, Z[n], th[n], h, sh, mem)
+    assert np.abs(lam - g.numpy()).max() < 1e-11 * max(1.0, np.abs(lam).max())
+
+
+@pytest.mark.parametrize("arch", ARCHS)
+def test_zero_weights_give_zero_F(arch):
+    wl, sh, th = small(arch)
+    z = {k: np.zeros_like(v) for k, v in th[0].items()}
+    X = wls.initial_state(wl).astype(np.float64)
+    mem = wls.cross_memory(wl)
+    assert np.abs(tode.F(X, z, sh, mem)).max() == 0.0
+    dX, _ = tode.F_vjp(X, z, X, sh, mem)
+    assert np.abs(dX).max() == 0.0
+
+
+def test_causal_mask_blocks_the_future():
+    """Changing token t must not change outputs at positions < t (decoder-only)."""
+    wl, sh, th = small(wls.ARCH_CAUSAL, B=1, S=6)
+    X = wls.initial_state(wl).astype(np.float64)
+    Y = X.copy(); Y[4] += np.linspace(-1.0, 1.0, X.shape[1])   # not a pure shift: LN removes those
+    a, b = tode.F(X, th[0], sh), tode.F(Y, th[0], sh)
+    assert np.abs(a[:4] - b[:4]).max() == 0.0
+    assert np.abs(a[4:] - b[4:]).max() > 1e-3
+
+
+def test_sequences_are_independent():
+    """The step acts per sequence: a batch equals its sequences done one by one."""
+    wl, sh, th = small(wls.ARCH_ENCODER, B=3, S=4)
+    X = wls.initial_state(wl).astype(np.float64)
+    full = tode.phi(X, th[0], 0.3, sh)
+    sh1 = tode.Shape(sh.arch, sh.d_model, sh.n_heads, 1, sh.seq)
+    for b in range(3):
+        one = tode.phi(X[b * 4:(b + 1) * 4], th[0], 0.3, sh1)
+        assert np.abs(one - full[b * 4:(b + 1) * 4]).max() < 1e-13

@@ -1,0 +1,319 @@
+"""Pins for the oracle's MGRIT driver (CPU only).
+
+What the paper and the mathematics fix, independent of the oracle's own code:
+* the exact solution of the level-0 system is serial forward propagation
+  (Remark in section 3.2.1): one level or cf = 1 must equal the serial pass,
+  and the serial solution must be a fixed point with zero residual;
+* two-level MGRIT is exact on one more C-point per iteration with F-relaxation
+  and on two more with FCF-relaxation (so it reproduces serial propagation after
+  N/cf, resp. ceil(N/(2 cf)), iterations) -- and is NOT exact beyond that front;
+* for the scalar linear problem dz/dt = a z every iterate has a closed form,
+  computed below by a short scalar recurrence that never calls the oracle;
+* the adjoint run obeys the same statements on the reversed index.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import mgrit, transformer_ode as tode
+from paper_2601_09026_amd import workloads as wls
+
+
+def tiny(arch=wls.ARCH_ENCODER, N=16, cf=4, levels=2, d=16, H=2, f=32, B=1, S=4, std=0.5, h=None,
+         seed=21):
+    h = 1.0 / N if h is None else h
+    wl = wls.Workload("t", arch, d, H, f, B, S, 3 if arch == wls.ARCH_CROSS else 0,
+                      N, h, cf, levels, 1, wls.DTYPE_F32, seed)
+    sh = tode.Shape(arch, d, H, B, S, wl.mem_seq)
+    th = [wls.layer_params(wl, n, weight_std=std) for n in range(N)]
+    return wl, sh, th
+
+
+def relerr(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+# ------------------------------------------------------------------ limits
+@pytest.mark.parametrize("levels,cf", [(1, 4), (2, 1), (3, 1)])
+def test_single_level_or_cf1_is_serial(levels, cf):
+    wl, sh, th = tiny(h=1.0)
+    Z0 = wls.initial_state(wl)
+    ser = mgrit.serial_forward(Z0, th, wl.h, sh)
+    W, res, _ = mgrit.mgrit_forward(Z0, th, wl.h, cf, levels, 3, sh)
+    assert max(np.abs(a - b).max() for a, b in zip(W, ser)) == 0.0
+
+
+def test_serial_forward_is_the_plain_recursion():
+    """Z_{n+1} = Z_n + h F(Z_n, theta_n), written out here without the oracle's driver."""
+    wl, sh, th = tiny(N=5, h=0.7)
+    Z = wls.initial_state(wl).astype(np.float64)
+    ser = mgrit.serial_forward(Z, th, wl.h, sh)
+    for n in range(5):
+        assert np.array_equal(ser[n], Z)
+        Z = Z + wl.h * tode.F(Z, th[n], sh)
+    assert np.array_equal(ser[5], Z)
+
+
+# ------------------------------------------------------------------ exactness front
+@pytest.mark.parametrize("relax,speed", [("F", 1), ("FCF", 2)])
+@pytest.mark.parametrize("arch", [wls.ARCH_ENCODER, wls.ARCH_CAUSAL])
+def test_two_level_exactness_front(relax, speed, arch):
+    wl, sh, th = tiny(arch=arch, N=24, cf=3, h=1.0, std=0.4)   # h = 1: the paper's own setting
+    Z0 = wls.initial_state(wl)
+    ser = mgrit.serial_forward(Z0, th, wl.h, sh)
+    M = wl.N // wl.cf
+    scale = np.abs(ser[-1]).max()
+    for it in range(1, M // speed + 1):
+        W, res, _ = mgrit.mgrit_forward(Z0, th, wl.h, wl.cf, 2, it, sh, relax=relax)
+        front = min(M, speed * it)
+        # every point up to the front C-point (and the F-points that follow it) is exact
+        last_exact = min(wl.N, front * wl.cf + wl.cf - 1)
+        for n in range(last_exact + 1):
+            assert np.abs(W[n] - ser[n]).max() < 1e-11 * scale, (it, n)
+        # beyond the front it is a genuine, inexact iterate
+        if front + 1 <= M:
+            assert np.abs(W[(front + 1) * wl.cf] - ser[(front + 1) * wl.cf]).max() > 1e-6, it
+    W, res, _ = mgrit.mgrit_forward(Z0, th, wl.h, wl.cf, 2, math.ceil(M / speed), sh, relax=relax)
+    assert max(np.abs(a - b).max() for a, b in zip(W, ser)) < 1e-11 * scale
+
+
+def test_benchmark_config_1_is_exact_after_two_fcf_iterations():
+    """M = 4 coarse intervals, FCF, 2 iterations: the front covers everything."""
+    wl = wls.named_workloads()["tiny_encoder"]
+    sh = tode.Shape(wl.arch, wl.d_model, wl.n_heads, wl.batch, wl.seq)
+    th = [wls.layer_params(wl, n) for n in range(wl.N)]
+    Z0 = wls.initial_state(wl)
+    ser = mgrit.serial_forward(Z0, th, wl.h, sh)
+    W, res, counts = mgrit.mgrit_forward(Z0, th, wl.h, wl.cf, wl.levels, wl.iters, sh)
+    assert max(np.abs(a - b).max() for a, b in zip(W, ser)) < 1e-12
+    assert len(res) == 2 and res[1] < res[0]
+    lamN = wls.terminal_adjoint(wl)
+    sa = mgrit.serial_adjoint(lamN, ser, th, wl.h, sh)
+    la, ares, _ = mgrit.mgrit_adjoint(lamN, ser, th, wl.h, wl.cf, wl.levels, wl.iters, sh)
+    assert max(np.abs(a - b).max() for a, b in zip(la, sa)) < 1e-12
+
+
+# ------------------------------------------------------------------ fixed point
+@pytest.mark.parametrize("levels", [2, 3])
+@pytest.mark.parametrize("relax", ["F", "FCF"])
+def test_serial_solution_is_a_fixed_point(levels, relax):
+    wl, sh, th = tiny(N=16, cf=2, levels=levels, h=1.0)
+    Z0 = wls.initial_state(wl)
+    ser = mgrit.serial_forward(Z0, th, wl.h, sh)
+    W, res, _ = mgrit.mgrit_forward(Z0, th, wl.h, wl.cf, levels, 2, sh, relax=relax, init=ser)
+    scale = np.abs(ser[-1]).max()
+    assert all(r < 1e-11 * scale for r in res)
+    assert max(np.abs(a - b).max() for a, b in zip(W, ser)) < 1e-11 * scale
+
+
+@pytest.mark.parametrize("levels,cf,N", [(3, 2, 16), (3, 4, 32), (4, 2, 16)])
+def test_multilevel_converges_to_serial(levels, cf, N):
+    wl, sh, th = tiny(N=N, cf=cf, levels=levels, h=1.0, std=0.3)
+    Z0 = wls.initial_state(wl)
+    ser = mgrit.serial_forward(Z0, th, wl.h, sh)
+    errs, allres = [], None
+    for it in (1, 2, 4, N // cf):
+        W, res, _ = mgrit.mgrit_forward(Z0, th, wl.h, cf, levels, it, sh)
+        errs.append(relerr(W[-1], ser[-1]))
+        allres = res
+    assert errs[0] > 1e-8            # a genuine iterate first
+    assert errs[-1] < 1e-10          # converged
+    assert errs[2] < errs[0]
+    assert allres[-1] < 1e-9 * allres[0]
+
+
+# ------------------------------------------------------------------ scalar linear closed forms
+def scalar_two_level(a, h, cf, N, iters, relax, z0=1.0):
+    """Closed-form two-level iterates for dz/dt = a z, C-point values only.
+
+    phi = 1 + h a (fine step), phic = 1 + cf h a (coarse step).  With u the old
+    C-point values: F-relaxation makes the residual at C-point k equal to
+    phi^cf u_{k-1} - u_k, so the coarse solve gives
+        v_k = phic v_{k-1} + (phi^cf - phic) u_{k-1};
+    FCF first replaces u_k by phi^cf u_{k-1} (all k at once), then does the same.
+    Residual norms are those of the relaxed values.
+    """
+    phi, phic = 1.0 + h * a, 1.0 + cf * h * a
+    M = N // cf
+    u = [z0] * (M + 1)
+    res = []
+    for _ in range(iters):
+        if relax == "FCF":
+            u = [u[0]] + [phi ** cf * u[k - 1] for k in range(1, M + 1)]
+        r = [phi ** cf * u[k - 1] - u[k] for k in range(1, M + 1)]
+        res.append(math.sqrt(sum(x * x for x in r)))
+        v = [u[0]]
+        for k in range(1, M + 1):
+            v.append(phic * v[k - 1] + (phi ** cf - phic) * u[k - 1])
+        u = v
+    return u, res
+
+
+@pytest.mark.parametrize("relax", ["F", "FCF"])
+@pytest.mark.parametrize("a", [-1.5, 0.8])
+def test_scalar_linear_two_level_closed_form(relax, a):
+    N, cf, h = 12, 3, 0.25
+    for iters in (1, 2, 3):
+        u, res = scalar_two_level(a, h, cf, N, iters, relax, z0=2.0)
+        W, r, _ = mgrit.mgrit_solve(mgrit.linear_propagator(a, h, cf), np.array([2.0]), N, cf, 2,
+                                    iters, relax)
+        for k in range(N // cf + 1):
+            assert abs(W[k * cf][0] - u[k]) < 1e-13 * max(1.0, abs(u[k]))
+            for i in range(1, cf):       # F-points follow their C-point
+                if k * cf + i <= N:
+                    assert abs(W[k * cf + i][0] - (1 + h * a) ** i * u[k]) < 1e-13 * max(1.0, abs(u[k]))
+        assert np.allclose(r, res, rtol=1e-11, atol=1e-13)
+
+
+def test_scalar_linear_limit_is_the_stability_function_power():
+    a, h, cf, N = -0.9, 0.1, 2, 16
+    for levels in (2, 3, 4):
+        W, _, _ = mgrit.mgrit_solve(mgrit.linear_propagator(a, h, cf), np.array([1.0]), N, cf, levels,
+                                    N, "FCF")
+        for n in range(N + 1):
+            assert abs(W[n][0] - (1 + h * a) ** n) < 1e-13
+
+
+def test_three_level_scalar_first_iterate():
+    """One FCF V-cycle of three-level MGRIT for dz/dt = a z, worked out by hand below.
+
+    Level 1 is itself the two-level method applied to the level-1 equation
+    v_k = phi1 v_{k-1} + g_k, where g is the full-approximation right-hand side.
+    """
+    a, h, cf, N, z0 = 0.6, 0.2, 2, 8, 1.0
+    phi0, phi1, phi2 = 1 + h * a, 1 + 2 * h * a, 1 + 4 * h * a
+    M0, M1 = 4, 2
+    # level 0: FCF from the constant guess
+    u = [z0] + [phi0 ** 2 * z0] * M0           # C-relaxed C-points (F-points were phi0*z0)
+    r0 = [phi0 ** 2 * u[k - 1] - u[k] for k in range(1, M0 + 1)]
+    g1 = [0.0] + [u[k] - phi1 * u[k - 1] + r0[k - 1] for k in range(1, M0 + 1)]
+    # level 1 (points v_0..v_4 = u): FCF with right-hand side g1, cf = 2
+    v = list(u)
+    for k in range(M1):                         # F-relax
+        v[2 * k + 1] = phi1 * v[2 * k] + g1[2 * k + 1]
+    c = {2 * k: phi1 * v[2 * k - 1] + g1[2 * k] for k in range(1, M1 + 1)}
+    for n, x in c.items():                      # C-relax
+        v[n] = x
+    for k in range(M1):                         # F-relax
+        v[2 * k + 1] = phi1 * v[2 * k] + g1[2 * k + 1]
+    r1 = [phi1 * v[2 * k - 1] + g1[2 * k] - v[2 * k] for k in range(1, M1 + 1)]
+    what = [v[0], v[2], v[4]]
+    g2 = [0.0] + [what[k] - phi2 * what[k - 1] + r1[k - 1] for k in range(1, M1 + 1)]
+    x = [what[0]]
+    for k in range(1, M1 + 1):                  # coarsest: serial
+        x.append(phi2 * x[k - 1] + g2[k])
+    for k in range(1, M1 + 1):                  # correct level 1, interpolate
+        v[2 * k] += x[k] - what[k]
+    for k in range(M1):
+        v[2 * k + 1] = phi1 * v[2 * k] + g1[2 * k + 1]
+    # correct level 0 C-points: u_k += v_k - u_k  =>  u = v
+    W, res, counts = mgrit.mgrit_solve(mgrit.linear_propagator(a, h, cf), np.array([z0]), N, cf, 3, 1,
+                                       "FCF")
+    for k in range(M0 + 1):
+        assert abs(W[2 * k][0] - v[k]) < 1e-14
+    assert abs(res[0] - math.sqrt(sum(t * t for t in r0))) < 1e-14
+    # evaluation counts: level 0: F(4) C(4) F(4) resid(4) interp(4) = 20; level 1: rhs 4 + F2 C2 F2
+    # resid 2 interp 2 = 14; level 2: rhs 2 + solve 2 = 4
+    assert counts == [20, 14, 4]
+
+
+def test_two_level_evaluation_counts():
+    wl, sh, th = tiny(N=16, cf=4)
+    _, _, counts = mgrit.mgrit_forward(wls.initial_state(wl), th, wl.h, 4, 2, 2, sh)
+    # per iteration, level 0: F 12 + C 4 + F 12 + residual 4 + interpolation 12; level 1: rhs 4 + solve 4
+    assert counts == [2 * 44, 2 * 8]
+
+
+# ------------------------------------------------------------------ adjoint
+@pytest.mark.parametrize("relax,speed", [("F", 1), ("FCF", 2)])
+def test_adjoint_exactness_front_and_limit(relax, speed):
+    wl, sh, th = tiny(arch=wls.ARCH_CAUSAL, N=12, cf=3, h=1.0, std=0.4)
+    Z = mgrit.serial_forward(wls.initial_state(wl), th, wl.h, sh)
+    lamN = wls.terminal_adjoint(wl)
+    ser = mgrit.serial_adjoint(lamN, Z, th, wl.h, sh)
+    assert np.array_equal(ser[wl.N], lamN.astype(np.float64))
+    M = wl.N // wl.cf
+    scale = np.abs(ser[0]).max()
+    for it in range(1, M // speed + 1):
+        lam, res, _ = mgrit.mgrit_adjoint(lamN, Z, th, wl.h, wl.cf, 2, it, sh, relax=relax)
+        front = min(M, speed * it)
+        for m in range(min(wl.N, front * wl.cf + wl.cf - 1) + 1):      # reversed index
+            assert np.abs(lam[wl.N - m] - ser[wl.N - m]).max() < 1e-11 * scale, (it, m)
+        if front + 1 <= M:
+            n = wl.N - (front + 1) * wl.cf
+            assert np.abs(lam[n] - ser[n]).max() > 1e-7
+    lam1, _, _ = mgrit.mgrit_adjoint(lamN, Z, th, wl.h, wl.cf, 1, 1, sh)
+    assert max(np.abs(a - b).max() for a, b in zip(lam1, ser)) == 0.0
+
+
+def test_adjoint_serial_is_the_gradient_of_the_serial_forward():
+    """lambda_0 = d<C, Z_N>/dZ_0: directional finite differences through the serial pass."""
+    wl, sh, th = tiny(N=6, h=0.5, std=0.4)
+    Z0 = wls.initial_state(wl).astype(np.float64)
+    C = wls.terminal_adjoint(wl).astype(np.float64)
+    Z = mgrit.serial_forward(Z0, th, wl.h, sh)
+    lam = mgrit.serial_adjoint(C, Z, th, wl.h, sh)
+    rng = np.random.default_rng(0)
+    eps = 1e-6
+    for _ in range(4):
+        v = rng.standard_normal(Z0.shape)
+        Lp = (C * mgrit.serial_forward(Z0 + eps * v, th, wl.h, sh)[-1]).sum()
+        Lm = (C * mgrit.serial_forward(Z0 - eps * v, th, wl.h, sh)[-1]).sum()
+        fd = (Lp - Lm) / (2 * eps)
+        assert abs(fd - (lam[0] * v).sum()) < 1e-7 * max(1.0, abs(fd))
+    # and the gradient at an interior layer: perturb Z_3, propagate layers 3..5
+    v = rng.standard_normal(Z0.shape)
+    def tail(z):
+        for n in range(3, 6):
+            z = tode.phi(z, th[n], wl.h, sh)
+        return (C * z).sum()
+    fd = (tail(Z[3] + eps * v) - tail(Z[3] - eps * v)) / (2 * eps)
+    assert abs(fd - (lam[3] * v).sum()) < 1e-7 * max(1.0, abs(fd))
+
+
+def test_adjoint_coarse_step_is_transpose_of_coarse_forward_step():
+    """<mu, dPhi^1_j(Z) v> = <Psi^1(mu) , v> for the coarse propagators (injected theta, step cf h)."""
+    wl, sh, th = tiny(N=8, cf=4, h=0.25, std=0.4)
+    Z = mgrit.serial_forward(wls.initial_state(wl), th, wl.h, sh)
+    fwd = mgrit.forward_propagator(th, wl.h, wl.cf, sh)
+    adj = mgrit.adjoint_propagator(th, Z, wl.h, wl.cf, sh)
+    rng = np.random.default_rng(1)
+    mu, v = rng.standard_normal(Z[0].shape), rng.standard_normal(Z[0].shape)
+    eps = 1e-6
+    # coarse forward step j=1 starts at layer n=4; its transpose is the reversed-index step
+    # landing on n=4: N - (j'+1)*cf = 4  =>  j' = 0
+    Jv = (fwd(1, 1, Z[4] + eps * v) - fwd(1, 1, Z[4] - eps * v)) / (2 * eps)
+    assert abs((mu * Jv).sum() - (adj(1, 0, mu) * v).sum()) < 1e-7 * abs((mu * Jv).sum())
+
+
+def test_cross_attention_decoder_mgrit_runs_and_converges():
+    wl, sh, th = tiny(arch=wls.ARCH_CROSS, N=8, cf=2, h=1.0, std=0.3)
+    mem = wls.cross_memory(wl)
+    Z0 = wls.initial_state(wl)
+    ser = mgrit.serial_forward(Z0, th, wl.h, sh, mem)
+    W1, r1, _ = mgrit.mgrit_forward(Z0, th, wl.h, 2, 2, 1, sh, mem)
+    W2, r2, _ = mgrit.mgrit_forward(Z0, th, wl.h, 2, 2, 2, sh, mem)
+    assert relerr(W1[-1], ser[-1]) > 1e-8
+    assert max(np.abs(a - b).max() for a, b in zip(W2, ser)) < 1e-11 * np.abs(ser[-1]).max()
+
+
+def test_coarse_level_is_first_order_approximation():
+    """Remark of section 3.2.1: level l+1 approximates level l to O(h).
+
+    Halving h (same weights reused as a function of time) should roughly halve the gap between
+    the coarse-grid and fine-grid solutions at the final time.
+    """
+    d, H, f, B, S = 16, 2, 32, 1, 4
+    gaps = []
+    base = wls.Workload("t", wls.ARCH_ENCODER, d, H, f, B, S, 0, 1, 1.0, 2, 1, 0, wls.DTYPE_F32, 5)
+    th1 = wls.layer_params(base, 0, weight_std=0.4)
+    sh = tode.Shape(wls.ARCH_ENCODER, d, H, B, S)
+    Z0 = wls.initial_state(base)
+    for N in (8, 16, 32):
+        h = 1.0 / N
+        th = [th1] * N                                    # theta constant in time
+        fine = mgrit.serial_forward(Z0, th, h, sh)[-1]
+        coarse = mgrit.serial_forward(Z0, th[: N // 2], 2 * h, sh)[-1]
+        gaps.append(np.linalg.norm(fine - coarse))
+    assert 1.6 < gaps[0] / gaps[1] < 2.4 and 1.6 < gaps[1] / gaps[2] < 2.4
