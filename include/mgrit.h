@@ -1,0 +1,175 @@
+/*
+ * mgrit.h -- C ABI of the MI355X (gfx950) layer-parallel hot path.
+ *
+ * The library solves the layer ODE of a pre-layer-norm transformer,
+ *     Z_{n+1} = Z_n + h F(Z_n, theta_n),   n = 0 .. N-1          (paper sec. 3.1),
+ * and its discrete adjoint  lambda_n = lambda_{n+1} + h (dF/dZ(Z_n))^T lambda_{n+1}
+ * (sec. 3.1, the backward problem), with multigrid-reduction-in-time over the layer
+ * index (sec. 3.2, Fig. 2, Appendix A): F- or FCF-relaxation batched over all
+ * coarse intervals, injection restriction, full-approximation coarse equation,
+ * serial coarsest solve, correction, recursion into V-cycles for more levels.
+ *
+ * General rules for every entry point
+ *  - All pointers named "device" are HIP device pointers on the current device;
+ *    "host" pointers are ordinary host memory.  The caller owns every buffer.
+ *  - The library never allocates, frees or synchronises.  All work is enqueued on
+ *    `stream` (a hipStream_t passed as void*; NULL = the null stream); outputs are
+ *    valid once the caller has synchronised that stream.
+ *  - Scratch memory comes from the caller's `workspace` (device, 256-byte aligned);
+ *    query its size first.  Its contents are undefined afterwards.
+ *  - Return value: MGRIT_OK (0) or a negative mgrit_status.  On MGRIT_INVALID_ARG,
+ *    MGRIT_UNSUPPORTED and MGRIT_WORKSPACE_TOO_SMALL nothing has been enqueued or
+ *    written.  No exception or abort crosses this boundary.
+ *  - Results are run-to-run bit-identical (no atomics feed any state).
+ *
+ * State layout: a state is [T, d_model] row-major fp32 with T = batch*seq tokens,
+ * sequence b owning rows b*seq .. (b+1)*seq-1.  States, lambda, and every
+ * residual update stay fp32 in both dtypes (the Euler sum is an accumulation).
+ */
+#ifndef MGRIT_H
+#define MGRIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mgrit_status {
+  MGRIT_OK = 0,
+  MGRIT_INVALID_ARG = -1,        /* null pointer, bad size, N not divisible by cf^(levels-1), ... */
+  MGRIT_UNSUPPORTED = -2,        /* valid request this build has no kernel for */
+  MGRIT_WORKSPACE_TOO_SMALL = -3,
+  MGRIT_HIP_ERROR = -4           /* a HIP call failed; see mgrit_last_hip_error() */
+} mgrit_status;
+
+enum { MGRIT_ARCH_ENCODER = 0,   /* self-attention, no mask          (eq. "encoder") */
+       MGRIT_ARCH_CAUSAL  = 1,   /* causal self-attention            (decoder-only)  */
+       MGRIT_ARCH_CROSS   = 2 }; /* causal self-attn + cross-attn    (eq. "decoder") */
+
+enum { MGRIT_DTYPE_F32  = 0,     /* fp32 parameters and matmul operands                      */
+       MGRIT_DTYPE_BF16 = 1 };   /* bf16 matrices and matmul operands, fp32 accumulate,      */
+                                 /* fp32 vectors (biases, LayerNorm), fp32 state             */
+
+enum { MGRIT_RELAX_F = 0, MGRIT_RELAX_FCF = 1 };
+
+/* Model shape (paper Table 2 families).  F is the pre-LN block of sec. 3.1:
+ * LayerNorm eps = ln_eps with biased variance, exact erf GELU, a bias on every
+ * projection, attention scale 1/sqrt(d_model/n_heads). */
+typedef struct mgrit_model_desc {
+  int32_t arch;
+  int32_t d_model, n_heads, d_ff;
+  int32_t batch, seq;
+  int32_t mem_seq;               /* cross-attention memory length, 0 unless MGRIT_ARCH_CROSS */
+  int32_t dtype;
+  float   ln_eps;
+} mgrit_model_desc;
+
+/* MGRIT knobs (sec. 3.2, Table 3): N fine steps of size h, coarsening factor cf,
+ * `levels` grid levels (level l has N/cf^l steps of size cf^l h), `iters`
+ * V-cycles.  levels == 1 or cf == 1 means plain serial propagation.
+ * init_guess: 0 = the initial value copied into every C-point; 1 = the caller has
+ * filled rows 1..N of the output array with a guess (row 0 is overwritten). */
+typedef struct mgrit_opts {
+  int32_t N;
+  float   h;
+  int32_t cf, levels, iters;
+  int32_t relax;
+  int32_t init_guess;
+} mgrit_opts;
+
+/* ---- packed parameter block of one layer ------------------------------------
+ * One contiguous device block per layer.  Tensors, in this order:
+ *   vectors (always fp32): ln1_g[d] ln1_b[d] bqkv[3d] bo[d] ln2_g[d] ln2_b[d] b1[f] b2[d]
+ *                          (+ arch 2: ln3_g[d] ln3_b[d] bq_c[d] bkv_c[2d] bo_c[d])
+ *   matrices (fp32 or bf16 by dtype), each [out_features, in_features] row-major
+ *   (y = x W^T + b; reduction dimension contiguous):
+ *                          Wqkv[3d,d] Wo[d,d] W1[f,d] W2[d,f]
+ *                          (+ arch 2: Wq_c[d,d] Wkv_c[2d,d] Wo_c[d,d])
+ * Wqkv rows are Q | K | V, head j owning rows j*d_h..(j+1)*d_h of each third;
+ * Wkv_c rows are K | V likewise.  Every tensor starts on a 16-byte boundary; the
+ * block itself must be 16-byte aligned.  mgrit_theta_layout() reports offsets. */
+enum { MGRIT_P_LN1_G = 0, MGRIT_P_LN1_B, MGRIT_P_BQKV, MGRIT_P_BO, MGRIT_P_LN2_G, MGRIT_P_LN2_B,
+       MGRIT_P_B1, MGRIT_P_B2, MGRIT_P_LN3_G, MGRIT_P_LN3_B, MGRIT_P_BQ_C, MGRIT_P_BKV_C,
+       MGRIT_P_BO_C,
+       MGRIT_P_WQKV, MGRIT_P_WO, MGRIT_P_W1, MGRIT_P_W2, MGRIT_P_WQ_C, MGRIT_P_WKV_C, MGRIT_P_WO_C,
+       MGRIT_P_COUNT };
+
+typedef struct mgrit_theta_layout_t {
+  int64_t block_bytes;                    /* size of one layer's block                 */
+  int64_t offset[MGRIT_P_COUNT];          /* byte offset of each tensor, -1 if absent   */
+  int32_t rows[MGRIT_P_COUNT];            /* out_features (or length for vectors)       */
+  int32_t cols[MGRIT_P_COUNT];            /* in_features  (1 for vectors)               */
+  int32_t elem_bytes[MGRIT_P_COUNT];      /* 4 or 2                                     */
+} mgrit_theta_layout_t;
+
+/* Fills *out for the given model.  Host only, no GPU needed. */
+int mgrit_theta_layout(const mgrit_model_desc* desc, mgrit_theta_layout_t* out);
+
+/* Workspace sizes in bytes (0 on invalid arguments).  Host only. */
+size_t mgrit_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts, int adjoint);
+size_t mgrit_layer_step_workspace_bytes(const mgrit_model_desc* desc, int adjoint, int n_groups);
+
+/* Number of layer-step evaluations (Phi or Psi, all levels, each on T tokens) that
+ * mgrit_forward / mgrit_adjoint enqueue for these options; -1 on invalid
+ * arguments.  The adjoint count excludes its one-off N-layer linearisation pass.
+ * Host only. */
+int64_t mgrit_step_evaluations(const mgrit_opts* opts);
+
+/* MGRIT forward propagation (sec. 3.2.1).
+ *   Z0        device, [T,d] fp32: initial value (embedded input)
+ *   theta     HOST array of N device pointers, one packed block per layer
+ *   memory    device, [batch*mem_seq, d] fp32 encoder output (arch 2), else NULL
+ *   Z_all     device, [(N+1),T,d] fp32 out: row n = Z_n after `iters` V-cycles;
+ *             row 0 = copy of Z0, row N = the network output.  F-points are
+ *             consistent with their C-point (each cycle ends with an F-relaxation).
+ *   resnorm   device, [iters] fp32 out or NULL: 2-norm of the level-0 residual at the
+ *             C-points after relaxation in each V-cycle (ratio of consecutive entries
+ *             = the convergence factor of sec. 3.2.3).  Untouched when the run is serial.
+ */
+int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                  const void* Z0, const void* const* theta, const void* memory,
+                  void* Z_all, float* resnorm,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* MGRIT adjoint propagation (sec. 3.2.2): the same algorithm on the reversed layer
+ * index with the transposed, linearised step.
+ *   Z_all      device, [(N+1),T,d] fp32: forward states to linearise about (exact or inexact)
+ *   lambda_N   device, [T,d] fp32: dL/dZ_N
+ *   lambda_all device, [(N+1),T,d] fp32 out: row n = lambda_n; row N = copy of lambda_N,
+ *              row 0 = dL/dZ_0
+ *   dmemory, dtheta  reserved, must be NULL in this build
+ * arch 2 is not supported by the adjoint in this build (MGRIT_UNSUPPORTED).
+ */
+int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                  const void* Z_all, const void* const* theta, const void* memory,
+                  const void* lambda_N, void* lambda_all,
+                  void* dmemory, void* const* dtheta, float* resnorm,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* One batched layer step over n_groups independent (state, layer) pairs -- the
+ * launch that F-/C-relaxation of Algorithm 1 is made of.
+ *   adjoint == 0:  out[g] = in[g] + hstep * F(in[g]; theta[g])            (+ rhs[g])
+ *   adjoint != 0:  out[g] = in[g] + hstep * (dF/dZ(lin_state[g]; theta[g]))^T in[g]  (+ rhs[g])
+ * in, out, theta, lin_state, rhs: HOST arrays of n_groups device pointers
+ * ([T,d] fp32 states; packed blocks).  rhs may be NULL (no right-hand side);
+ * lin_state is required iff adjoint.  out[g] must not alias any in[], lin_state[] or
+ * rhs[] of the same call. */
+int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups,
+                             const void* const* in, void* const* out,
+                             const void* const* theta, const void* const* lin_state,
+                             const void* const* rhs, const void* memory, float hstep,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+const char* mgrit_status_string(int status);
+int         mgrit_last_hip_error(void);          /* hipError_t of the last MGRIT_HIP_ERROR */
+
+/* Tuning knob: at most this many groups go into one kernel launch (larger sweeps
+ * are split into chunks that run one after another).  0 restores the default. */
+void mgrit_set_max_groups_per_launch(int n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MGRIT_H */

@@ -1,0 +1,236 @@
+"""Thin ctypes binding over the C-ABI HIP library (argument marshalling only).
+
+Function names mirror include/mgrit.h.  PyTorch is used for device memory and
+streams; every computation happens inside the library's kernels.  There is no
+CPU fallback: if the shared library is missing, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmgrit_hip.so")
+
+MGRIT_OK = 0
+P_NAMES = ["ln1_g", "ln1_b", "bqkv", "bo", "ln2_g", "ln2_b", "b1", "b2", "ln3_g", "ln3_b", "bq_c",
+           "bkv_c", "bo_c", "Wqkv", "Wo", "W1", "W2", "Wq_c", "Wkv_c", "Wo_c"]
+P_COUNT = len(P_NAMES)
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("arch", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ff", C.c_int32),
+                ("batch", C.c_int32), ("seq", C.c_int32), ("mem_seq", C.c_int32), ("dtype", C.c_int32),
+                ("ln_eps", C.c_float)]
+
+
+class Opts(C.Structure):
+    _fields_ = [("N", C.c_int32), ("h", C.c_float), ("cf", C.c_int32), ("levels", C.c_int32),
+                ("iters", C.c_int32), ("relax", C.c_int32), ("init_guess", C.c_int32)]
+
+
+class ThetaLayout(C.Structure):
+    _fields_ = [("block_bytes", C.c_int64), ("offset", C.c_int64 * P_COUNT), ("rows", C.c_int32 * P_COUNT),
+                ("cols", C.c_int32 * P_COUNT), ("elem_bytes", C.c_int32 * P_COUNT)]
+
+
+class MgritError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().mgrit_status_string(status).decode()
+        hip = lib().mgrit_last_hip_error() if status == -4 else 0
+        super().__init__(f"{where}: {msg} (status {status}" + (f", hipError {hip})" if hip else ")"))
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load the HIP library (built by `python -m paper_2601_09026_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2601_09026_amd.build` (no CPU fallback exists)")
+        L = C.CDLL(LIB_PATH)
+        vp, vpp = C.c_void_p, C.POINTER(C.c_void_p)
+        L.mgrit_theta_layout.argtypes = [C.POINTER(ModelDesc), C.POINTER(ThetaLayout)]
+        L.mgrit_theta_layout.restype = C.c_int
+        L.mgrit_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.c_int]
+        L.mgrit_workspace_bytes.restype = C.c_size_t
+        L.mgrit_layer_step_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.c_int, C.c_int]
+        L.mgrit_layer_step_workspace_bytes.restype = C.c_size_t
+        L.mgrit_step_evaluations.argtypes = [C.POINTER(Opts)]
+        L.mgrit_step_evaluations.restype = C.c_int64
+        L.mgrit_forward.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), vp, vpp, vp, vp, vp, vp,
+                                    C.c_size_t, vp]
+        L.mgrit_forward.restype = C.c_int
+        L.mgrit_adjoint.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), vp, vpp, vp, vp, vp, vp, vpp, vp,
+                                    vp, C.c_size_t, vp]
+        L.mgrit_adjoint.restype = C.c_int
+        L.layer_step_batched.argtypes = [C.POINTER(ModelDesc), C.c_int, C.c_int, vpp, vpp, vpp, vpp, vpp, vp,
+                                         C.c_float, vp, C.c_size_t, vp]
+        L.layer_step_batched.restype = C.c_int
+        L.mgrit_status_string.argtypes = [C.c_int]
+        L.mgrit_status_string.restype = C.c_char_p
+        L.mgrit_last_hip_error.argtypes = []
+        L.mgrit_last_hip_error.restype = C.c_int
+        L.mgrit_set_max_groups_per_launch.argtypes = [C.c_int]
+        L.mgrit_set_max_groups_per_launch.restype = None
+        L.mgrit_debug_force_simple_kernels.argtypes = [C.c_int, C.c_int]
+        L.mgrit_debug_force_simple_kernels.restype = None
+        _lib = L
+    return _lib
+
+
+# ------------------------------------------------------------------ descriptors
+def model_desc(wl) -> ModelDesc:
+    """ModelDesc from any object with the Workload fields."""
+    return ModelDesc(wl.arch, wl.d_model, wl.n_heads, wl.d_ff, wl.batch, wl.seq, wl.mem_seq, wl.dtype,
+                     wl.ln_eps)
+
+
+def mgrit_opts(N, h, cf, levels, iters, relax=1, init_guess=0) -> Opts:
+    return Opts(N, h, cf, levels, iters, relax, init_guess)
+
+
+def mgrit_theta_layout(desc: ModelDesc) -> ThetaLayout:
+    out = ThetaLayout()
+    st = lib().mgrit_theta_layout(C.byref(desc), C.byref(out))
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_theta_layout")
+    return out
+
+
+def mgrit_workspace_bytes(desc: ModelDesc, opts: Opts, adjoint: bool) -> int:
+    return int(lib().mgrit_workspace_bytes(C.byref(desc), C.byref(opts), int(adjoint)))
+
+
+def mgrit_layer_step_workspace_bytes(desc: ModelDesc, adjoint: bool, n_groups: int) -> int:
+    return int(lib().mgrit_layer_step_workspace_bytes(C.byref(desc), int(adjoint), n_groups))
+
+
+def mgrit_step_evaluations(opts: Opts) -> int:
+    return int(lib().mgrit_step_evaluations(C.byref(opts)))
+
+
+def mgrit_set_max_groups_per_launch(n: int) -> None:
+    lib().mgrit_set_max_groups_per_launch(int(n))
+
+
+# ------------------------------------------------------------------ parameter packing (byte copies only)
+def pack_theta(desc: ModelDesc, params: Dict[str, np.ndarray], device="cuda") -> torch.Tensor:
+    """One layer's named fp32 arrays -> packed device block (uint8 tensor) in the library's layout."""
+    lay = mgrit_theta_layout(desc)
+    host = torch.zeros(int(lay.block_bytes), dtype=torch.uint8)
+    for i, name in enumerate(P_NAMES):
+        off = int(lay.offset[i])
+        if off < 0:
+            continue
+        a = torch.from_numpy(np.ascontiguousarray(params[name], dtype=np.float32))
+        assert a.numel() == lay.rows[i] * lay.cols[i], name
+        if lay.elem_bytes[i] == 2:
+            raw = a.to(torch.bfloat16).view(torch.uint8).reshape(-1)
+        else:
+            raw = a.view(torch.uint8).reshape(-1)
+        host[off:off + raw.numel()] = raw
+    return host.to(device)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> C.c_void_p:
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _ptr_array(ts: Optional[Sequence[torch.Tensor]]):
+    if ts is None:
+        return None
+    arr = (C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+    return arr
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]) -> C.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _check_state(t: torch.Tensor, shape, name: str):
+    if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"{name}: expected contiguous fp32 device tensor of shape {tuple(shape)}, "
+                         f"got {t.dtype} {tuple(t.shape)} on {t.device}")
+
+
+# ------------------------------------------------------------------ entry points
+def mgrit_forward(desc: ModelDesc, opts: Opts, Z0: torch.Tensor, theta: List[torch.Tensor],
+                  memory: Optional[torch.Tensor] = None, Z_all: Optional[torch.Tensor] = None,
+                  resnorm: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                  stream: Optional[torch.cuda.Stream] = None):
+    """Returns (Z_all [(N+1),T,d], resnorm [iters]).  Buffers are allocated here if not given."""
+    T, d = desc.batch * desc.seq, desc.d_model
+    _check_state(Z0, (T, d), "Z0")
+    if len(theta) != opts.N:
+        raise ValueError("theta must hold N blocks")
+    if Z_all is None:
+        Z_all = torch.empty((opts.N + 1, T, d), dtype=torch.float32, device=Z0.device)
+    _check_state(Z_all, (opts.N + 1, T, d), "Z_all")
+    if resnorm is None:
+        resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z0.device)
+    need = mgrit_workspace_bytes(desc, opts, False)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Z0.device)
+    st = lib().mgrit_forward(C.byref(desc), C.byref(opts), _ptr(Z0), _ptr_array(theta), _ptr(memory),
+                             _ptr(Z_all), _ptr(resnorm), _ptr(workspace), workspace.numel(),
+                             _stream_handle(stream))
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_forward")
+    return Z_all, resnorm
+
+
+def mgrit_adjoint(desc: ModelDesc, opts: Opts, Z_all: torch.Tensor, theta: List[torch.Tensor],
+                  lambda_N: torch.Tensor, memory: Optional[torch.Tensor] = None,
+                  lambda_all: Optional[torch.Tensor] = None, resnorm: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """Returns (lambda_all [(N+1),T,d], resnorm [iters])."""
+    T, d = desc.batch * desc.seq, desc.d_model
+    _check_state(Z_all, (opts.N + 1, T, d), "Z_all")
+    _check_state(lambda_N, (T, d), "lambda_N")
+    if len(theta) != opts.N:
+        raise ValueError("theta must hold N blocks")
+    if lambda_all is None:
+        lambda_all = torch.empty((opts.N + 1, T, d), dtype=torch.float32, device=Z_all.device)
+    _check_state(lambda_all, (opts.N + 1, T, d), "lambda_all")
+    if resnorm is None:
+        resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z_all.device)
+    need = mgrit_workspace_bytes(desc, opts, True)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Z_all.device)
+    st = lib().mgrit_adjoint(C.byref(desc), C.byref(opts), _ptr(Z_all), _ptr_array(theta), _ptr(memory),
+                             _ptr(lambda_N), _ptr(lambda_all), None, None, _ptr(resnorm), _ptr(workspace),
+                             workspace.numel(), _stream_handle(stream))
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_adjoint")
+    return lambda_all, resnorm
+
+
+def layer_step_batched(desc: ModelDesc, adjoint: bool, inputs: List[torch.Tensor], outputs: List[torch.Tensor],
+                       theta: List[torch.Tensor], hstep: float,
+                       lin_state: Optional[List[torch.Tensor]] = None,
+                       rhs: Optional[List[torch.Tensor]] = None, memory: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """out[g] = in[g] + hstep*F(in[g]; theta[g]) (+rhs[g]), or its adjoint at lin_state[g]."""
+    G = len(inputs)
+    T, d = desc.batch * desc.seq, desc.d_model
+    for t in list(inputs) + list(outputs) + list(lin_state or []) + list(rhs or []):
+        _check_state(t, (T, d), "state")
+    need = mgrit_layer_step_workspace_bytes(desc, adjoint, G)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=inputs[0].device)
+    st = lib().layer_step_batched(C.byref(desc), int(adjoint), G, _ptr_array(inputs), _ptr_array(outputs),
+                                  _ptr_array(theta), _ptr_array(lin_state), _ptr_array(rhs), _ptr(memory),
+                                  float(hstep), _ptr(workspace), workspace.numel(), _stream_handle(stream))
+    if st != MGRIT_OK:
+        raise MgritError(st, "layer_step_batched")
+    return outputs

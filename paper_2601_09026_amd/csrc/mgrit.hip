@@ -1,0 +1,760 @@
+// C ABI, batched layer step (forward and adjoint) and the MGRIT driver.
+//
+// Everything here is host code that only enqueues kernels on the caller's stream.
+//
+// Layer step (paper sec. 3.1, eq. "encoder" / "decoder"), per launch chunk of groups:
+//   LN1 -> QKV projection -> fused attention -> output projection            (s, fp32)
+//   [-> LN3(X+s) -> cross-attention projections -> fused attention -> projection (ybar = s + c)]
+//   -> LN2(X+ybar) -> FFN1 (+GELU) -> FFN2 with the Euler update  out = X + h(ybar + m) + rhs
+// Adjoint step (the discrete transpose, sec. 3.1 backward problem): the block internals at
+// the linearisation state are produced once per layer by a forward pass that stops before
+// FFN2 ("linearisation cache": qkv, attention output and log-sum-exp, s, pre-GELU z);
+// each adjoint evaluation then runs only the transposed chain.  The cache is independent
+// of the step size, so coarse-level adjoint steps reuse the fine layer's entry.
+//
+// MGRIT driver (sec. 3.2, Fig. 2, Appendix A / Algorithm 1), full-approximation form.
+// All levels live in the one [(N+1),T,d] state array: point j of level l is row j*cf^l
+// (the reversed row for the adjoint).  Injection and correction are therefore free:
+// the coarse solve overwrites the C-points in place.  With R_k = Phi(w_{k cf-1}) + g_{k cf}
+// the coarse right-hand side g'_k = what_k - Phi'(what_{k-1}) + (R_k - w_{k cf}) collapses to
+// R_k - Phi'(w_{(k-1) cf}) because what_k = w_{k cf}.
+#include <math.h>
+#include <string.h>
+
+#include <vector>
+
+#include "../../include/mgrit.h"
+#include "common.h"
+#include "kernels.h"
+
+using namespace mg;
+
+namespace mg { int resnorm_partials_per_group(); }
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+int g_max_groups = 0;                       // 0 = default
+constexpr int DEFAULT_MAX_GROUPS = 8;
+
+inline int max_groups() { return g_max_groups > 0 ? g_max_groups : DEFAULT_MAX_GROUPS; }
+
+#define HIPCHK(expr)                                   \
+  do {                                                 \
+    hipError_t e_ = (expr);                            \
+    if (e_ != hipSuccess) {                            \
+      g_last_hip_error = (int)e_;                      \
+      return MGRIT_HIP_ERROR;                          \
+    }                                                  \
+  } while (0)
+
+#define STCHK(expr)                                    \
+  do {                                                 \
+    int s_ = (expr);                                   \
+    if (s_ != MGRIT_OK) return s_;                     \
+  } while (0)
+
+// ---------------------------------------------------------------------------
+// parameter block layout
+// ---------------------------------------------------------------------------
+int compute_layout(const mgrit_model_desc* md, mgrit_theta_layout_t* L) {
+  const int d = md->d_model, f = md->d_ff;
+  const bool cross = md->arch == MGRIT_ARCH_CROSS;
+  const int wbytes = md->dtype == MGRIT_DTYPE_BF16 ? 2 : 4;
+  for (int i = 0; i < MGRIT_P_COUNT; ++i) { L->offset[i] = -1; L->rows[i] = L->cols[i] = L->elem_bytes[i] = 0; }
+  int64_t off = 0;
+  auto vec = [&](int id, int n) {
+    L->offset[id] = off; L->rows[id] = n; L->cols[id] = 1; L->elem_bytes[id] = 4;
+    off += ((int64_t)n * 4 + 15) / 16 * 16;
+  };
+  auto mat = [&](int id, int r, int c) {
+    L->offset[id] = off; L->rows[id] = r; L->cols[id] = c; L->elem_bytes[id] = wbytes;
+    off += ((int64_t)r * c * wbytes + 15) / 16 * 16;
+  };
+  vec(MGRIT_P_LN1_G, d); vec(MGRIT_P_LN1_B, d); vec(MGRIT_P_BQKV, 3 * d); vec(MGRIT_P_BO, d);
+  vec(MGRIT_P_LN2_G, d); vec(MGRIT_P_LN2_B, d); vec(MGRIT_P_B1, f); vec(MGRIT_P_B2, d);
+  if (cross) {
+    vec(MGRIT_P_LN3_G, d); vec(MGRIT_P_LN3_B, d); vec(MGRIT_P_BQ_C, d); vec(MGRIT_P_BKV_C, 2 * d);
+    vec(MGRIT_P_BO_C, d);
+  }
+  mat(MGRIT_P_WQKV, 3 * d, d); mat(MGRIT_P_WO, d, d); mat(MGRIT_P_W1, f, d); mat(MGRIT_P_W2, d, f);
+  if (cross) { mat(MGRIT_P_WQ_C, d, d); mat(MGRIT_P_WKV_C, 2 * d, d); mat(MGRIT_P_WO_C, d, d); }
+  L->block_bytes = (off + 255) / 256 * 256;
+  return MGRIT_OK;
+}
+
+int validate_desc(const mgrit_model_desc* md) {
+  if (!md) return MGRIT_INVALID_ARG;
+  if (md->arch < 0 || md->arch > 2) return MGRIT_INVALID_ARG;
+  if (md->dtype != MGRIT_DTYPE_F32 && md->dtype != MGRIT_DTYPE_BF16) return MGRIT_INVALID_ARG;
+  if (md->d_model <= 0 || md->n_heads <= 0 || md->d_ff <= 0 || md->batch <= 0 || md->seq <= 0)
+    return MGRIT_INVALID_ARG;
+  if (md->d_model % md->n_heads != 0) return MGRIT_INVALID_ARG;
+  if (md->arch == MGRIT_ARCH_CROSS ? md->mem_seq <= 0 : md->mem_seq != 0) return MGRIT_INVALID_ARG;
+  if (!(md->ln_eps > 0.f) || !isfinite(md->ln_eps)) return MGRIT_INVALID_ARG;
+  const int dh = md->d_model / md->n_heads;
+  // kernel limits of this build
+  if (md->d_model % 8 || md->d_ff % 8 || dh % 4 || dh > 128 || md->d_model > 2048) return MGRIT_UNSUPPORTED;
+  if ((int64_t)md->batch * md->seq > (1 << 24)) return MGRIT_UNSUPPORTED;
+  return MGRIT_OK;
+}
+
+int validate_opts(const mgrit_opts* o) {
+  if (!o) return MGRIT_INVALID_ARG;
+  if (o->N < 1 || o->cf < 1 || o->levels < 1 || o->iters < 0) return MGRIT_INVALID_ARG;
+  if (!isfinite(o->h)) return MGRIT_INVALID_ARG;
+  if (o->relax != MGRIT_RELAX_F && o->relax != MGRIT_RELAX_FCF) return MGRIT_INVALID_ARG;
+  if (o->init_guess != 0 && o->init_guess != 1) return MGRIT_INVALID_ARG;
+  if (o->levels > 1 && o->cf > 1) {
+    int64_t p = 1;
+    for (int l = 1; l < o->levels; ++l) {
+      p *= o->cf;
+      if (p > o->N) return MGRIT_INVALID_ARG;
+    }
+    if (o->N % p != 0) return MGRIT_INVALID_ARG;
+  }
+  return MGRIT_OK;
+}
+
+inline bool serial_run(const mgrit_opts* o) { return o->levels == 1 || o->cf == 1; }
+
+// ---------------------------------------------------------------------------
+// workspace carving (same code measures and allocates)
+// ---------------------------------------------------------------------------
+struct Bump {
+  char* base;
+  size_t off = 0;
+  explicit Bump(void* b) : base(static_cast<char*>(b)) {}
+  template <typename T> T* take(size_t count) {
+    off = (off + 255) / 256 * 256;
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+  void* take_bytes(size_t bytes) { return take<char>(bytes); }
+};
+
+struct Engine {
+  mgrit_model_desc md;
+  mgrit_theta_layout_t lay;
+  bool bf16;
+  int T, Tm, d, f, H, dh;
+  size_t esz;                      // operand element size
+  hipStream_t st;
+  int Gc;                          // groups per launch chunk
+  // forward work buffers, Gc slots each
+  void *u, *qkv, *o, *act, *qc, *kvc, *memb;
+  float *xin, *x3;
+  // adjoint: linearisation cache (n_cache slots) and work buffers (Gc slots)
+  int n_cache;
+  void *c_qkv, *c_o, *c_z;
+  float *c_lse, *c_xin;
+  void *cb, *dz, *du, *ds, *da, *dqkv;
+  float *dxin, *Dbuf;
+
+  long Td() const { return (long)T * d; }
+
+  void init(const mgrit_model_desc* m, hipStream_t s) {
+    md = *m;
+    compute_layout(m, &lay);
+    bf16 = m->dtype == MGRIT_DTYPE_BF16;
+    T = m->batch * m->seq; Tm = m->batch * m->mem_seq; d = m->d_model; f = m->d_ff; H = m->n_heads;
+    dh = d / H; esz = bf16 ? 2 : 4; st = s;
+  }
+  void carve_forward(Bump& b, int gc) {
+    Gc = gc;
+    const size_t G = gc;
+    u = b.take_bytes(G * T * d * esz);
+    qkv = b.take_bytes(G * T * 3 * d * esz);
+    o = b.take_bytes(G * T * d * esz);
+    xin = b.take<float>(G * T * d);
+    act = b.take_bytes(G * T * f * esz);
+    x3 = nullptr; qc = kvc = memb = nullptr;
+    if (md.arch == MGRIT_ARCH_CROSS) {
+      x3 = b.take<float>(G * T * d);
+      qc = b.take_bytes(G * T * d * esz);
+      kvc = b.take_bytes(G * Tm * 2 * d * esz);
+      memb = b.take_bytes((size_t)Tm * d * esz);
+    }
+  }
+  void carve_adjoint(Bump& b, int gc, int ncache) {
+    Gc = gc; n_cache = ncache;
+    const size_t G = gc, C = ncache;
+    c_qkv = b.take_bytes(C * T * 3 * d * esz);
+    c_o = b.take_bytes(C * T * d * esz);
+    c_z = b.take_bytes(C * T * f * esz);
+    c_lse = b.take<float>(C * md.batch * H * md.seq);
+    c_xin = b.take<float>(C * T * d);
+    u = b.take_bytes(G * T * d * esz);
+    cb = b.take_bytes(G * T * d * esz);
+    dz = b.take_bytes(G * T * f * esz);
+    du = b.take_bytes(G * T * d * esz);
+    ds = b.take_bytes(G * T * d * esz);
+    da = b.take_bytes(G * T * d * esz);
+    dqkv = b.take_bytes(G * T * 3 * d * esz);
+    dxin = b.take<float>(G * T * d);
+    Dbuf = b.take<float>(G * md.batch * H * md.seq);
+    qkv = o = act = nullptr; xin = nullptr;
+  }
+};
+
+inline Rows shift(Rows r, int c0) { if (r.tab) r.i0 += c0 * r.is; return r; }
+inline Params shift(Params p, int c0) { p.i0 += c0 * p.is; return p; }
+inline Slots shift(Slots s, int c0) { s.s0 += c0 * s.ss; return s; }
+const Rows NO_ROWS = {nullptr, 0, 0};
+
+GemmArgs gemm_base(int n, int M, int N, int K, const void* A, long a_stride, Slots a_slots, Params B, long b_off,
+                   long bias_off) {
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.n_groups = n; g.M = M; g.N = N; g.K = K;
+  g.A = A; g.a_slot_stride = a_stride; g.a_slots = a_slots;
+  g.B = B; g.b_off = b_off; g.bias = B; g.bias_off = bias_off;
+  return g;
+}
+
+// One chunk (n <= Gc groups) of the forward layer step.  `cache`: write the linearisation
+// cache at `cslots` instead of advancing the state (stops before FFN2).
+int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, float hstep, bool cache,
+                  Slots cslots) {
+  const int T = E.T, d = E.d, f = E.f;
+  const auto& L = E.lay;
+  const Slots loc = {0, 1};
+  const Slots cs = cache ? cslots : loc;
+  void* qkv = cache ? E.c_qkv : E.qkv;
+  void* ob = cache ? E.c_o : E.o;
+  float* xin = cache ? E.c_xin : E.xin;
+  const size_t esz = E.esz;
+  const bool causal = E.md.arch != MGRIT_ARCH_ENCODER;
+
+  LnFwdArgs ln;
+  memset(&ln, 0, sizeof(ln));
+  ln.n_groups = n; ln.T = T; ln.d = d; ln.X = IN; ln.P = TH;
+  ln.gamma_off = L.offset[MGRIT_P_LN1_G]; ln.beta_off = L.offset[MGRIT_P_LN1_B];
+  ln.out = E.u; ln.out_slot_stride = E.Td(); ln.out_slots = loc; ln.eps = E.md.ln_eps;
+  HIPCHK(launch_ln_fwd(ln, E.bf16, E.st));
+
+  GemmArgs g = gemm_base(n, T, 3 * d, d, E.u, E.Td(), loc, TH, L.offset[MGRIT_P_WQKV], L.offset[MGRIT_P_BQKV]);
+  g.out = qkv; g.out_slot_stride = (long)T * 3 * d; g.out_slots = cs;
+  HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+
+  AttnArgs at;
+  memset(&at, 0, sizeof(at));
+  at.n_groups = n; at.B = E.md.batch; at.H = E.H; at.dh = E.dh; at.Sq = E.md.seq; at.Sk = E.md.seq;
+  at.causal = causal;
+  at.q = qkv; at.k = (char*)qkv + (size_t)d * esz; at.v = (char*)qkv + (size_t)2 * d * esz;
+  at.q_row_stride = at.k_row_stride = at.v_row_stride = 3 * d;
+  at.q_slot_stride = at.k_slot_stride = at.v_slot_stride = (long)T * 3 * d;
+  at.q_slots = at.k_slots = cs;
+  at.o = ob; at.o_row_stride = d; at.o_slot_stride = E.Td(); at.o_slots = cs;
+  if (cache) { at.lse = E.c_lse; at.lse_slot_stride = (long)E.md.batch * E.H * E.md.seq; at.lse_slots = cs; }
+  HIPCHK(launch_attn_fwd(at, E.bf16, E.st));
+
+  const bool cross = E.md.arch == MGRIT_ARCH_CROSS;
+  // s = SA(LN1(X)) kept in fp32 (never X + s: the Euler sum must not lose the small increment)
+  g = gemm_base(n, T, d, d, ob, E.Td(), cs, TH, L.offset[MGRIT_P_WO], L.offset[MGRIT_P_BO]);
+  g.out = cross ? E.x3 : xin; g.out_slot_stride = E.Td(); g.out_slots = cross ? loc : cs;
+  HIPCHK(launch_gemm(g, EPI_RESID_INNER, E.bf16, E.st));
+
+  if (cross) {
+    ln.X = IN; ln.xp = E.x3; ln.xp_slot_stride = E.Td(); ln.xp_slots = loc;      // LN3(X + s)
+    ln.gamma_off = L.offset[MGRIT_P_LN3_G]; ln.beta_off = L.offset[MGRIT_P_LN3_B];
+    HIPCHK(launch_ln_fwd(ln, E.bf16, E.st));
+    g = gemm_base(n, T, d, d, E.u, E.Td(), loc, TH, L.offset[MGRIT_P_WQ_C], L.offset[MGRIT_P_BQ_C]);
+    g.out = E.qc; g.out_slot_stride = E.Td(); g.out_slots = loc;
+    HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+    g = gemm_base(n, E.Tm, 2 * d, d, E.memb, 0, loc, TH, L.offset[MGRIT_P_WKV_C], L.offset[MGRIT_P_BKV_C]);
+    g.out = E.kvc; g.out_slot_stride = (long)E.Tm * 2 * d; g.out_slots = loc;
+    HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+    memset(&at, 0, sizeof(at));
+    at.n_groups = n; at.B = E.md.batch; at.H = E.H; at.dh = E.dh; at.Sq = E.md.seq; at.Sk = E.md.mem_seq;
+    at.causal = 0;
+    at.q = E.qc; at.q_row_stride = d; at.q_slot_stride = E.Td(); at.q_slots = loc;
+    at.k = E.kvc; at.v = (char*)E.kvc + (size_t)d * esz;
+    at.k_row_stride = at.v_row_stride = 2 * d;
+    at.k_slot_stride = at.v_slot_stride = (long)E.Tm * 2 * d; at.k_slots = loc;
+    at.o = E.o; at.o_row_stride = d; at.o_slot_stride = E.Td(); at.o_slots = loc;
+    HIPCHK(launch_attn_fwd(at, E.bf16, E.st));
+    g = gemm_base(n, T, d, d, E.o, E.Td(), loc, TH, L.offset[MGRIT_P_WO_C], L.offset[MGRIT_P_BO_C]);
+    g.base = E.x3; g.base_slot_stride = E.Td(); g.base_slots = loc;
+    g.out = xin; g.out_slot_stride = E.Td(); g.out_slots = cs;
+    HIPCHK(launch_gemm(g, EPI_RESID_INNER, E.bf16, E.st));
+  }
+
+  ln.X = IN; ln.xp = xin; ln.xp_slot_stride = E.Td(); ln.xp_slots = cs;          // LN2(X + ybar)
+  ln.gamma_off = L.offset[MGRIT_P_LN2_G]; ln.beta_off = L.offset[MGRIT_P_LN2_B];
+  HIPCHK(launch_ln_fwd(ln, E.bf16, E.st));
+
+  g = gemm_base(n, T, f, d, E.u, E.Td(), loc, TH, L.offset[MGRIT_P_W1], L.offset[MGRIT_P_B1]);
+  if (cache) {
+    g.out = E.c_z; g.out_slot_stride = (long)T * f; g.out_slots = cs;
+    HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+    return MGRIT_OK;
+  }
+  g.out = E.act; g.out_slot_stride = (long)T * f; g.out_slots = loc;
+  HIPCHK(launch_gemm(g, EPI_GELU, E.bf16, E.st));
+
+  g = gemm_base(n, T, d, f, E.act, (long)T * f, loc, TH, L.offset[MGRIT_P_W2], L.offset[MGRIT_P_B2]);
+  g.aux = xin; g.aux_slot_stride = E.Td(); g.aux_slots = loc;                   // ybar
+  g.X = IN; g.OUT = OUT; g.RHS = RHS; g.hstep = hstep;
+  HIPCHK(launch_gemm(g, EPI_RESID_OUTER, E.bf16, E.st));
+  return MGRIT_OK;
+}
+
+// One chunk of the adjoint step:  OUT = IN + hstep * J(LIN; theta)^T IN (+ RHS), from the cache.
+// THT: parameter blocks whose matrices are stored transposed; TH: the original blocks.
+int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Params THT, Rows LIN, Slots cs,
+                  float hstep) {
+  const int T = E.T, d = E.d, f = E.f;
+  const auto& L = E.lay;
+  const Slots loc = {0, 1};
+  const size_t esz = E.esz;
+
+  HIPCHK(launch_cast_rows(n, E.Td(), IN, E.cb, E.Td(), loc, E.bf16, E.st));
+
+  // dz = (c W2) * gelu'(z)        [T,d] x [d,f]: transposed W2 is [f,d]
+  GemmArgs g = gemm_base(n, T, f, d, E.cb, E.Td(), loc, THT, L.offset[MGRIT_P_W2], -1);
+  g.out = E.dz; g.out_slot_stride = (long)T * f; g.out_slots = loc;
+  g.aux = E.c_z; g.aux_slot_stride = (long)T * f; g.aux_slots = cs;
+  HIPCHK(launch_gemm(g, EPI_DGELU, E.bf16, E.st));
+
+  // du2 = dz W1                   [T,f] x [f,d]: transposed W1 is [d,f]
+  g = gemm_base(n, T, d, f, E.dz, (long)T * f, loc, THT, L.offset[MGRIT_P_W1], -1);
+  g.out = E.du; g.out_slot_stride = E.Td(); g.out_slots = loc;
+  HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+
+  // dX' = LN2^T du2 ;  ds = c + dX'
+  LnBwdArgs lb;
+  memset(&lb, 0, sizeof(lb));
+  lb.n_groups = n; lb.T = T; lb.d = d; lb.eps = E.md.ln_eps;
+  lb.dy = E.du; lb.dy_slot_stride = E.Td(); lb.dy_slots = loc;
+  lb.X = LIN; lb.xp = E.c_xin; lb.xp_slot_stride = E.Td(); lb.xp_slots = cs;    // LN2 input X + s
+  lb.P = TH; lb.gamma_off = L.offset[MGRIT_P_LN2_G];
+  lb.out_f32 = E.dxin; lb.of_slot_stride = E.Td(); lb.of_slots = loc;
+  lb.C = IN; lb.out_op = E.ds; lb.oo_slot_stride = E.Td(); lb.oo_slots = loc;
+  HIPCHK(launch_ln_bwd(lb, E.bf16, E.st));
+
+  // da = ds Wo
+  g = gemm_base(n, T, d, d, E.ds, E.Td(), loc, THT, L.offset[MGRIT_P_WO], -1);
+  g.out = E.da; g.out_slot_stride = E.Td(); g.out_slots = loc;
+  HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+
+  // attention backward
+  AttnArgs at;
+  memset(&at, 0, sizeof(at));
+  at.n_groups = n; at.B = E.md.batch; at.H = E.H; at.dh = E.dh; at.Sq = E.md.seq; at.Sk = E.md.seq;
+  at.causal = E.md.arch != MGRIT_ARCH_ENCODER;
+  at.q = E.c_qkv; at.k = (char*)E.c_qkv + (size_t)d * esz; at.v = (char*)E.c_qkv + (size_t)2 * d * esz;
+  at.q_row_stride = at.k_row_stride = at.v_row_stride = 3 * d;
+  at.q_slot_stride = at.k_slot_stride = at.v_slot_stride = (long)T * 3 * d;
+  at.q_slots = at.k_slots = cs;
+  at.o = E.c_o; at.o_row_stride = d; at.o_slot_stride = E.Td(); at.o_slots = cs;
+  at.lse = E.c_lse; at.lse_slot_stride = (long)E.md.batch * E.H * E.md.seq; at.lse_slots = cs;
+  at.dO = E.da; at.do_row_stride = d; at.do_slot_stride = E.Td(); at.do_slots = loc;
+  at.dq = E.dqkv; at.dk = (char*)E.dqkv + (size_t)d * esz; at.dv = (char*)E.dqkv + (size_t)2 * d * esz;
+  at.dqkv_row_stride = 3 * d; at.dqkv_slot_stride = (long)T * 3 * d; at.dqkv_slots = loc;
+  at.D = E.Dbuf; at.D_slot_stride = (long)E.md.batch * E.H * E.md.seq; at.D_slots = loc;
+  HIPCHK(launch_attn_bwd(at, E.bf16, E.st));
+
+  // du1 = dqkv Wqkv               [T,3d] x [3d,d]: transposed Wqkv is [d,3d]
+  g = gemm_base(n, T, d, 3 * d, E.dqkv, (long)T * 3 * d, loc, THT, L.offset[MGRIT_P_WQKV], -1);
+  g.out = E.du; g.out_slot_stride = E.Td(); g.out_slots = loc;
+  HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+
+  // dX = dX' + LN1^T du1 ;  OUT = c + hstep dX (+ RHS)
+  memset(&lb, 0, sizeof(lb));
+  lb.n_groups = n; lb.T = T; lb.d = d; lb.eps = E.md.ln_eps;
+  lb.dy = E.du; lb.dy_slot_stride = E.Td(); lb.dy_slots = loc;
+  lb.X = LIN;
+  lb.P = TH; lb.gamma_off = L.offset[MGRIT_P_LN1_G];
+  lb.add = E.dxin; lb.add_slot_stride = E.Td(); lb.add_slots = loc;
+  lb.C = IN; lb.OUT = OUT; lb.RHS = RHS; lb.hstep = hstep;
+  HIPCHK(launch_ln_bwd(lb, E.bf16, E.st));
+  return MGRIT_OK;
+}
+
+int forward_groups(Engine& E, int G, Rows IN, Rows OUT, Rows RHS, Params TH, float hstep, bool cache,
+                   Slots cslots) {
+  for (int c0 = 0; c0 < G; c0 += E.Gc) {
+    const int n = G - c0 < E.Gc ? G - c0 : E.Gc;
+    STCHK(forward_chunk(E, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), hstep, cache,
+                        shift(cslots, c0)));
+  }
+  return MGRIT_OK;
+}
+
+int adjoint_groups(Engine& E, int G, Rows IN, Rows OUT, Rows RHS, Params TH, Params THT, Rows LIN, Slots cs,
+                   float hstep) {
+  for (int c0 = 0; c0 < G; c0 += E.Gc) {
+    const int n = G - c0 < E.Gc ? G - c0 : E.Gc;
+    STCHK(adjoint_chunk(E, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), shift(THT, c0),
+                        shift(LIN, c0), shift(cs, c0), hstep));
+  }
+  return MGRIT_OK;
+}
+
+int transpose_blocks(Engine& E, int n, Params TH, Params THT) {
+  static const int mats[] = {MGRIT_P_WQKV, MGRIT_P_WO, MGRIT_P_W1, MGRIT_P_W2};
+  for (int id : mats)
+    HIPCHK(launch_transpose(n, TH, THT, E.lay.offset[id], E.lay.rows[id], E.lay.cols[id], E.lay.elem_bytes[id],
+                            E.st));
+  return MGRIT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// MGRIT driver
+// ---------------------------------------------------------------------------
+struct Driver {
+  Engine* E = nullptr;             // null: dry run that only counts evaluations
+  bool adjoint = false;
+  int N = 0, cf = 1, L = 1, relax = MGRIT_RELAX_FCF;
+  float h = 0.f;
+  // device pointer tables
+  void** tabW = nullptr;           // level-0 point m -> state row (forward: m, adjoint: N-m)
+  void** tabZ = nullptr;           // adjoint: forward state n (linearisation)
+  void** tabTh = nullptr;          // layer n -> parameter block
+  void** tabThT = nullptr;         // layer n -> transposed block (adjoint)
+  std::vector<void**> tabG;        // level l >= 1: point j -> right-hand side g^l_j
+  void** tabR = nullptr;           // k -> scratch state R_k
+  double* partial = nullptr;
+  int max_partial = 0;
+  float* resnorm = nullptr;
+  int64_t evals = 0;
+
+  static int ipow(int b, int e) { int r = 1; while (e-- > 0) r *= b; return r; }
+
+  // cnt steps of level `lvl`, group k starting at point j = j0 + k*js
+  int step(int lvl, int j0, int js, int cnt, Rows OUT, Rows RHS) {
+    evals += cnt;
+    if (!E) return MGRIT_OK;
+    const int s = ipow(cf, lvl);
+    const float hstep = (float)((double)s * (double)h);
+    Rows IN = {(const void* const*)tabW, j0 * s, js * s};
+    if (!adjoint) {
+      Params TH = {(const void* const*)tabTh, j0 * s, js * s};
+      return forward_groups(*E, cnt, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
+    }
+    const int n0 = N - (j0 + 1) * s, ns = -js * s;       // layer the coarse step lands on
+    Params TH = {(const void* const*)tabTh, n0, ns};
+    Params THT = {(const void* const*)tabThT, n0, ns};
+    Rows LIN = {(const void* const*)tabZ, n0, ns};
+    return adjoint_groups(*E, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep);
+  }
+
+  Rows W(int lvl, int j0, int js) const {
+    const int s = ipow(cf, lvl);
+    return Rows{(const void* const*)tabW, j0 * s, js * s};
+  }
+  Rows Gr(int lvl, int j0, int js) const {
+    if (lvl == 0) return NO_ROWS;
+    return Rows{(const void* const*)tabG[lvl], j0, js};
+  }
+
+  int f_relax(int lvl, int M) {
+    for (int i = 0; i + 1 < cf; ++i) STCHK(step(lvl, i, cf, M, W(lvl, i + 1, cf), Gr(lvl, i + 1, cf)));
+    return MGRIT_OK;
+  }
+
+  int vcycle(int lvl, int iter, bool skip_first_f) {
+    const int Nl = N / ipow(cf, lvl);
+    if (lvl == L - 1) {
+      for (int j = 1; j <= Nl; ++j) STCHK(step(lvl, j - 1, 1, 1, W(lvl, j, 1), Gr(lvl, j, 1)));
+      return MGRIT_OK;
+    }
+    const int M = Nl / cf;
+    if (!skip_first_f) STCHK(f_relax(lvl, M));
+    if (relax == MGRIT_RELAX_FCF) {
+      STCHK(step(lvl, cf - 1, cf, M, W(lvl, cf, cf), Gr(lvl, cf, cf)));
+      STCHK(f_relax(lvl, M));
+    }
+    // R_k = Phi(w_{k cf - 1}) + g_{k cf}
+    Rows R = {(const void* const*)tabR, 0, 1};
+    STCHK(step(lvl, cf - 1, cf, M, R, Gr(lvl, cf, cf)));
+    if (E && lvl == 0 && resnorm)
+      HIPCHK(launch_resnorm(M, E->Td(), R, W(lvl, cf, cf), partial, max_partial, resnorm + iter, E->st));
+    // g'_k = R_k - Phi'(w_{(k-1) cf}),  k = 1..M
+    Rows Gn = {(const void* const*)(E ? tabG[lvl + 1] : nullptr), 1, 1};
+    STCHK(step(lvl + 1, 0, 1, M, Gn, NO_ROWS));
+    if (E) HIPCHK(launch_sub_rows(M, E->Td(), R, Gn, Gn, E->st));
+    STCHK(vcycle(lvl + 1, iter, false));
+    STCHK(f_relax(lvl, M));
+    return MGRIT_OK;
+  }
+
+  int run(int iters) {
+    if (L == 1 || cf == 1) {
+      for (int n = 0; n < N; ++n) STCHK(step(0, n, 1, 1, W(0, n + 1, 1), NO_ROWS));
+      return MGRIT_OK;
+    }
+    for (int it = 0; it < iters; ++it) STCHK(vcycle(0, it, it > 0));
+    return MGRIT_OK;
+  }
+};
+
+struct Plan {                       // workspace of mgrit_forward / mgrit_adjoint
+  Engine E;
+  Driver D;
+  void* thT_blocks = nullptr;
+  size_t bytes = 0;
+};
+
+int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, bool adjoint, void* ws, hipStream_t st) {
+  Bump b(ws);
+  Engine& E = P.E;
+  E.init(md, st);
+  const int N = op->N;
+  const bool serial = serial_run(op);
+  const int M0 = serial ? 1 : N / op->cf;
+  int gc = max_groups();
+  const int widest = adjoint ? (N > M0 ? N : M0) : M0;      // the cache pass batches over all N layers
+  if (gc > widest) gc = widest;
+  if (adjoint) E.carve_adjoint(b, gc, N); else E.carve_forward(b, gc);
+  Driver& D = P.D;
+  D.E = &E; D.adjoint = adjoint; D.N = N; D.cf = op->cf; D.L = serial ? 1 : op->levels; D.relax = op->relax;
+  D.h = op->h;
+  D.tabW = b.take<void*>(N + 1);
+  D.tabTh = b.take<void*>(N);
+  if (adjoint) {
+    D.tabZ = b.take<void*>(N + 1);
+    D.tabThT = b.take<void*>(N);
+    P.thT_blocks = b.take_bytes((size_t)N * E.lay.block_bytes);
+  }
+  D.tabG.assign(D.L, nullptr);
+  if (!serial) {
+    D.tabR = b.take<void*>(M0);
+    D.max_partial = M0 * resnorm_partials_per_group();
+    D.partial = b.take<double>(D.max_partial);
+    const size_t state = (size_t)E.T * E.d * sizeof(float);
+    char* Rbuf = static_cast<char*>(b.take_bytes(M0 * state));
+    std::vector<char*> Gbuf(D.L, nullptr);
+    for (int l = 1; l < D.L; ++l) {
+      const int Nl = N / Driver::ipow(op->cf, l);
+      D.tabG[l] = b.take<void*>(Nl + 1);
+      Gbuf[l] = static_cast<char*>(b.take_bytes((size_t)(Nl + 1) * state));
+    }
+    if (ws) {
+      if (launch_fill_table(D.tabR, Rbuf, (long)state, M0, st) != hipSuccess) return MGRIT_HIP_ERROR;
+      for (int l = 1; l < D.L; ++l) {
+        const int Nl = N / Driver::ipow(op->cf, l);
+        if (launch_fill_table(D.tabG[l], Gbuf[l], (long)state, Nl + 1, st) != hipSuccess) return MGRIT_HIP_ERROR;
+      }
+    }
+  }
+  P.bytes = (b.off + 255) / 256 * 256;
+  return MGRIT_OK;
+}
+
+int check_ptr_array(const void* const* a, int n) {
+  if (!a) return MGRIT_INVALID_ARG;
+  for (int i = 0; i < n; ++i) if (!a[i]) return MGRIT_INVALID_ARG;
+  return MGRIT_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// exported functions
+// ---------------------------------------------------------------------------
+extern "C" {
+
+int mgrit_theta_layout(const mgrit_model_desc* desc, mgrit_theta_layout_t* out) {
+  if (!out) return MGRIT_INVALID_ARG;
+  int s = validate_desc(desc);
+  if (s != MGRIT_OK) return s;
+  return compute_layout(desc, out);
+}
+
+size_t mgrit_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts, int adjoint) {
+  if (validate_desc(desc) != MGRIT_OK || validate_opts(opts) != MGRIT_OK) return 0;
+  if (adjoint && desc->arch == MGRIT_ARCH_CROSS) return 0;
+  Plan P;
+  if (make_plan(P, desc, opts, adjoint != 0, nullptr, nullptr) != MGRIT_OK) return 0;
+  return P.bytes;
+}
+
+size_t mgrit_layer_step_workspace_bytes(const mgrit_model_desc* desc, int adjoint, int n_groups) {
+  if (validate_desc(desc) != MGRIT_OK || n_groups < 1) return 0;
+  if (adjoint && desc->arch == MGRIT_ARCH_CROSS) return 0;
+  Engine E;
+  E.init(desc, nullptr);
+  Bump b(nullptr);
+  int gc = max_groups() < n_groups ? max_groups() : n_groups;
+  if (adjoint) {
+    E.carve_adjoint(b, gc, n_groups);
+    b.take_bytes((size_t)n_groups * E.lay.block_bytes);
+    b.take<void*>((size_t)n_groups * 6);
+  } else {
+    E.carve_forward(b, gc);
+    b.take<void*>((size_t)n_groups * 4);
+  }
+  return (b.off + 255) / 256 * 256;
+}
+
+int64_t mgrit_step_evaluations(const mgrit_opts* opts) {
+  if (validate_opts(opts) != MGRIT_OK) return -1;
+  Driver D;
+  D.N = opts->N; D.cf = opts->cf; D.L = serial_run(opts) ? 1 : opts->levels; D.relax = opts->relax;
+  D.tabG.assign(D.L, nullptr);
+  D.run(opts->iters);
+  return D.evals;
+}
+
+int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z0,
+                  const void* const* theta, const void* memory, void* Z_all, float* resnorm, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+  STCHK(validate_desc(desc));
+  STCHK(validate_opts(opts));
+  if (!Z0 || !Z_all || !workspace) return MGRIT_INVALID_ARG;
+  STCHK(check_ptr_array(theta, opts->N));
+  if (desc->arch == MGRIT_ARCH_CROSS && !memory) return MGRIT_INVALID_ARG;
+  const size_t need = mgrit_workspace_bytes(desc, opts, 0);
+  if (need == 0) return MGRIT_INVALID_ARG;
+  if (workspace_bytes < need) return MGRIT_WORKSPACE_TOO_SMALL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  Plan P;
+  STCHK(make_plan(P, desc, opts, false, workspace, st));
+  Engine& E = P.E;
+  Driver& D = P.D;
+  const int N = opts->N;
+  const size_t state = (size_t)E.T * E.d * sizeof(float);
+  HIPCHK(launch_fill_table(D.tabW, static_cast<char*>(Z_all), (long)state, N + 1, st));
+  HIPCHK(upload_pointers(D.tabTh, theta, N, st));
+  if (desc->arch == MGRIT_ARCH_CROSS)
+    HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
+  // initial values
+  HIPCHK(hipMemcpyAsync(Z_all, Z0, state, hipMemcpyDeviceToDevice, st));
+  if (!serial_run(opts) && opts->init_guess == 0) {
+    for (int k = 1; k <= N / opts->cf; ++k)
+      HIPCHK(hipMemcpyAsync(static_cast<char*>(Z_all) + (size_t)k * opts->cf * state, Z0, state,
+                            hipMemcpyDeviceToDevice, st));
+  }
+  D.resnorm = resnorm;
+  return D.run(opts->iters);
+}
+
+int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z_all,
+                  const void* const* theta, const void* memory, const void* lambda_N, void* lambda_all,
+                  void* dmemory, void* const* dtheta, float* resnorm, void* workspace, size_t workspace_bytes,
+                  void* stream) {
+  STCHK(validate_desc(desc));
+  STCHK(validate_opts(opts));
+  if (desc->arch == MGRIT_ARCH_CROSS) return MGRIT_UNSUPPORTED;
+  if (dmemory || dtheta) return MGRIT_UNSUPPORTED;
+  (void)memory;
+  if (!Z_all || !lambda_N || !lambda_all || !workspace) return MGRIT_INVALID_ARG;
+  STCHK(check_ptr_array(theta, opts->N));
+  const size_t need = mgrit_workspace_bytes(desc, opts, 1);
+  if (need == 0) return MGRIT_INVALID_ARG;
+  if (workspace_bytes < need) return MGRIT_WORKSPACE_TOO_SMALL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  Plan P;
+  STCHK(make_plan(P, desc, opts, true, workspace, st));
+  Engine& E = P.E;
+  Driver& D = P.D;
+  const int N = opts->N;
+  const size_t state = (size_t)E.T * E.d * sizeof(float);
+  // reversed index: point m lives in row N-m
+  HIPCHK(launch_fill_table(D.tabW, static_cast<char*>(lambda_all) + (size_t)N * state, -(long)state, N + 1, st));
+  HIPCHK(launch_fill_table(D.tabZ, static_cast<char*>(const_cast<void*>(Z_all)), (long)state, N + 1, st));
+  HIPCHK(upload_pointers(D.tabTh, theta, N, st));
+  HIPCHK(launch_fill_table(D.tabThT, static_cast<char*>(P.thT_blocks), (long)E.lay.block_bytes, N, st));
+  Params TH = {(const void* const*)D.tabTh, 0, 1};
+  Params THT = {(const void* const*)D.tabThT, 0, 1};
+  STCHK(transpose_blocks(E, N, TH, THT));
+  // linearisation cache for all N layers, batched over layers
+  Rows Zrows = {(const void* const*)D.tabZ, 0, 1};
+  STCHK(forward_groups(E, N, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
+  // initial values
+  HIPCHK(hipMemcpyAsync(static_cast<char*>(lambda_all) + (size_t)N * state, lambda_N, state,
+                        hipMemcpyDeviceToDevice, st));
+  if (!serial_run(opts) && opts->init_guess == 0) {
+    for (int k = 1; k <= N / opts->cf; ++k)
+      HIPCHK(hipMemcpyAsync(static_cast<char*>(lambda_all) + (size_t)(N - k * opts->cf) * state, lambda_N, state,
+                            hipMemcpyDeviceToDevice, st));
+  }
+  D.resnorm = resnorm;
+  return D.run(opts->iters);
+}
+
+int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups, const void* const* in,
+                       void* const* out, const void* const* theta, const void* const* lin_state,
+                       const void* const* rhs, const void* memory, float hstep, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  STCHK(validate_desc(desc));
+  if (n_groups < 1 || !workspace || !isfinite(hstep)) return MGRIT_INVALID_ARG;
+  if (adjoint && desc->arch == MGRIT_ARCH_CROSS) return MGRIT_UNSUPPORTED;
+  STCHK(check_ptr_array(in, n_groups));
+  STCHK(check_ptr_array((const void* const*)out, n_groups));
+  STCHK(check_ptr_array(theta, n_groups));
+  if (rhs) STCHK(check_ptr_array(rhs, n_groups));
+  if (adjoint) STCHK(check_ptr_array(lin_state, n_groups));
+  if (desc->arch == MGRIT_ARCH_CROSS && !memory) return MGRIT_INVALID_ARG;
+  const size_t need = mgrit_layer_step_workspace_bytes(desc, adjoint, n_groups);
+  if (need == 0) return MGRIT_INVALID_ARG;
+  if (workspace_bytes < need) return MGRIT_WORKSPACE_TOO_SMALL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  Engine E;
+  E.init(desc, st);
+  Bump b(workspace);
+  const int gc = max_groups() < n_groups ? max_groups() : n_groups;
+  const int G = n_groups;
+  if (adjoint) {
+    E.carve_adjoint(b, gc, G);
+    char* tblocks = static_cast<char*>(b.take_bytes((size_t)G * E.lay.block_bytes));
+    void** tabs = b.take<void*>((size_t)G * 6);
+    void **tIn = tabs, **tOut = tabs + G, **tTh = tabs + 2 * G, **tLin = tabs + 3 * G, **tRhs = tabs + 4 * G,
+         **tThT = tabs + 5 * G;
+    HIPCHK(upload_pointers(tIn, in, G, st));
+    HIPCHK(upload_pointers(tOut, (const void* const*)out, G, st));
+    HIPCHK(upload_pointers(tTh, theta, G, st));
+    HIPCHK(upload_pointers(tLin, lin_state, G, st));
+    if (rhs) HIPCHK(upload_pointers(tRhs, rhs, G, st));
+    HIPCHK(launch_fill_table(tThT, tblocks, (long)E.lay.block_bytes, G, st));
+    Params TH = {(const void* const*)tTh, 0, 1}, THT = {(const void* const*)tThT, 0, 1};
+    Rows IN = {(const void* const*)tIn, 0, 1}, OUT = {(const void* const*)tOut, 0, 1};
+    Rows LIN = {(const void* const*)tLin, 0, 1};
+    Rows RHS = rhs ? Rows{(const void* const*)tRhs, 0, 1} : NO_ROWS;
+    STCHK(transpose_blocks(E, G, TH, THT));
+    STCHK(forward_groups(E, G, LIN, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
+    return adjoint_groups(E, G, IN, OUT, RHS, TH, THT, LIN, Slots{0, 1}, hstep);
+  }
+  E.carve_forward(b, gc);
+  void** tabs = b.take<void*>((size_t)G * 4);
+  void **tIn = tabs, **tOut = tabs + G, **tTh = tabs + 2 * G, **tRhs = tabs + 3 * G;
+  HIPCHK(upload_pointers(tIn, in, G, st));
+  HIPCHK(upload_pointers(tOut, (const void* const*)out, G, st));
+  HIPCHK(upload_pointers(tTh, theta, G, st));
+  if (rhs) HIPCHK(upload_pointers(tRhs, rhs, G, st));
+  if (desc->arch == MGRIT_ARCH_CROSS)
+    HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
+  Params TH = {(const void* const*)tTh, 0, 1};
+  Rows IN = {(const void* const*)tIn, 0, 1}, OUT = {(const void* const*)tOut, 0, 1};
+  Rows RHS = rhs ? Rows{(const void* const*)tRhs, 0, 1} : NO_ROWS;
+  return forward_groups(E, G, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
+}
+
+const char* mgrit_status_string(int status) {
+  switch (status) {
+    case MGRIT_OK: return "ok";
+    case MGRIT_INVALID_ARG: return "invalid argument";
+    case MGRIT_UNSUPPORTED: return "unsupported configuration";
+    case MGRIT_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MGRIT_HIP_ERROR: return "HIP error";
+  }
+  return "unknown status";
+}
+
+int mgrit_last_hip_error(void) { return g_last_hip_error; }
+
+void mgrit_set_max_groups_per_launch(int n) { g_max_groups = n > 0 ? n : 0; }
+
+// test / tuning hooks (not part of the documented interface)
+void mgrit_debug_force_simple_kernels(int gemm, int attn) {
+  gemm_force_simple(gemm);
+  attn_force_simple(attn);
+}
+
+}  // extern "C"

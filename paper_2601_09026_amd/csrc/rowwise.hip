@@ -1,0 +1,344 @@
+// Bandwidth-bound kernels of the layer step and of the MGRIT driver: LayerNorm forward
+// and its VJP (one 64-lane wavefront per token row, 16-byte accesses, row kept in
+// registers, two-pass statistics), casts, residual differences and norms, pointer
+// tables, weight transposition for the adjoint.
+#include "common.h"
+#include "kernels.h"
+
+namespace mg {
+
+constexpr int LN_MAXV = 8;          // float4 per lane  =>  d <= 64*4*8 = 2048
+
+// ---------------------------------------------------------------------------
+// LayerNorm forward: fp32 row -> operand-type row
+// ---------------------------------------------------------------------------
+// LN input = state row (optional) + packed fp32 addend (optional); at least one is present
+__device__ __forceinline__ f32x4 load_sum(const float* x, const float* xa, int c) {
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (x) v = *reinterpret_cast<const f32x4*>(x + c);
+  if (xa) v += *reinterpret_cast<const f32x4*>(xa + c);
+  return v;
+}
+
+template <typename TO>
+__global__ void __launch_bounds__(256) ln_fwd_kernel(const LnFwdArgs a) {
+  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const long total = (long)a.n_groups * a.T;
+  if (row >= total) return;
+  const int g = (int)(row / a.T);
+  const int t = (int)(row - (long)g * a.T);
+  const int d = a.d;
+  const float* x = a.X.present() ? a.X.at(g) + (long)t * d : nullptr;
+  const float* xa = a.xp ? a.xp + a.xp_slots.of(g) * a.xp_slot_stride + (long)t * d : nullptr;
+  const char* pb = a.P.at(g);
+  const float* gamma = reinterpret_cast<const float*>(pb + a.gamma_off);
+  const float* beta = reinterpret_cast<const float*>(pb + a.beta_off);
+  TO* out = reinterpret_cast<TO*>(a.out) + a.out_slots.of(g) * a.out_slot_stride + (long)t * d;
+
+  f32x4 v[LN_MAXV];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < d) {
+      v[i] = load_sum(x, xa, c);
+      s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+    }
+  }
+  const float mu = wave_sum(s) / d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < d) {
+      f32x4 e = v[i] - mu;
+      q += (e[0] * e[0] + e[1] * e[1]) + (e[2] * e[2] + e[3] * e[3]);
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / d + a.eps);
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < d) {
+      f32x4 gm = *reinterpret_cast<const f32x4*>(gamma + c);
+      f32x4 bt = *reinterpret_cast<const f32x4*>(beta + c);
+      store4<TO>(out + c, (v[i] - mu) * rstd * gm + bt);
+    }
+  }
+}
+
+hipError_t launch_ln_fwd(const LnFwdArgs& a, bool is_bf16, hipStream_t st) {
+  const long rows = (long)a.n_groups * a.T;
+  if (rows <= 0) return hipSuccess;
+  const unsigned blocks = (unsigned)((rows + 3) / 4);
+  if (is_bf16) hipLaunchKernelGGL(ln_fwd_kernel<bf16>, dim3(blocks), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL(ln_fwd_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// LayerNorm VJP with fused residual bookkeeping
+//   xhat = (x-mu)*rstd, dxhat = dy*gamma,
+//   vjp  = rstd*(dxhat - mean(dxhat) - xhat*mean(dxhat*xhat))
+//   v = add + vjp;  out_f32 = v;  out_op = c + v;  OUT = c + hstep*v + RHS
+// ---------------------------------------------------------------------------
+template <typename TO>
+__global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
+  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const long total = (long)a.n_groups * a.T;
+  if (row >= total) return;
+  const int g = (int)(row / a.T);
+  const int t = (int)(row - (long)g * a.T);
+  const int d = a.d;
+  const long ro = (long)t * d;
+  const float* x = a.X.present() ? a.X.at(g) + ro : nullptr;
+  const float* xa = a.xp ? a.xp + a.xp_slots.of(g) * a.xp_slot_stride + ro : nullptr;
+  const TO* dy = reinterpret_cast<const TO*>(a.dy) + a.dy_slots.of(g) * a.dy_slot_stride + ro;
+  const float* gamma = reinterpret_cast<const float*>(a.P.at(g) + a.gamma_off);
+
+  f32x4 v[LN_MAXV], w[LN_MAXV];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < d) {
+      v[i] = load_sum(x, xa, c);
+      s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+    }
+  }
+  const float mu = wave_sum(s) / d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < d) {
+      v[i] = v[i] - mu;
+      q += (v[i][0] * v[i][0] + v[i][1] * v[i][1]) + (v[i][2] * v[i][2] + v[i][3] * v[i][3]);
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / d + a.eps);
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < d) {
+      v[i] = v[i] * rstd;                                            // xhat
+      w[i] = load4<TO>(dy + c) * *reinterpret_cast<const f32x4*>(gamma + c);   // dxhat
+      s1 += (w[i][0] + w[i][1]) + (w[i][2] + w[i][3]);
+      s2 += (w[i][0] * v[i][0] + w[i][1] * v[i][1]) + (w[i][2] * v[i][2] + w[i][3] * v[i][3]);
+    }
+  }
+  const float m1 = wave_sum(s1) / d, m2 = wave_sum(s2) / d;
+  const float* add = a.add ? a.add + a.add_slots.of(g) * a.add_slot_stride + ro : nullptr;
+  float* of = a.out_f32 ? a.out_f32 + a.of_slots.of(g) * a.of_slot_stride + ro : nullptr;
+  TO* oo = a.out_op ? reinterpret_cast<TO*>(a.out_op) + a.oo_slots.of(g) * a.oo_slot_stride + ro : nullptr;
+  const bool need_c = oo != nullptr || a.OUT.present();
+  const float* cvec = need_c ? a.C.at(g) + ro : nullptr;
+  float* OUT = a.OUT.present() ? a.OUT.at(g) + ro : nullptr;
+  const float* RHS = a.RHS.present() ? a.RHS.at(g) + ro : nullptr;
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < d) {
+      f32x4 r = rstd * (w[i] - m1 - v[i] * m2);
+      if (add) r += *reinterpret_cast<const f32x4*>(add + c);
+      if (of) *reinterpret_cast<f32x4*>(of + c) = r;
+      if (need_c) {
+        f32x4 cc = *reinterpret_cast<const f32x4*>(cvec + c);
+        if (oo) store4<TO>(oo + c, cc + r);
+        if (OUT) {
+          f32x4 res = cc + a.hstep * r;
+          if (RHS) res += *reinterpret_cast<const f32x4*>(RHS + c);
+          *reinterpret_cast<f32x4*>(OUT + c) = res;
+        }
+      }
+    }
+  }
+}
+
+hipError_t launch_ln_bwd(const LnBwdArgs& a, bool is_bf16, hipStream_t st) {
+  const long rows = (long)a.n_groups * a.T;
+  if (rows <= 0) return hipSuccess;
+  const unsigned blocks = (unsigned)((rows + 3) / 4);
+  if (is_bf16) hipLaunchKernelGGL(ln_bwd_kernel<bf16>, dim3(blocks), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL(ln_bwd_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// casts
+// ---------------------------------------------------------------------------
+template <typename TO>
+__global__ void __launch_bounds__(256) cast_rows_kernel(long elems, Rows X, TO* out, long out_slot_stride,
+                                                        Slots out_slots) {
+  const int g = blockIdx.y;
+  const float* x = X.at(g);
+  TO* o = out + out_slots.of(g) * out_slot_stride;
+  for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (long)gridDim.x * 256 * 4)
+    store4<TO>(o + i, *reinterpret_cast<const f32x4*>(x + i));
+}
+
+hipError_t launch_cast_rows(int n_groups, long elems, Rows X, void* out, long out_slot_stride,
+                            Slots out_slots, bool is_bf16, hipStream_t st) {
+  if (n_groups <= 0 || elems <= 0) return hipSuccess;
+  long want = (elems / 4 + 255) / 256;
+  const unsigned bx = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+  if (is_bf16)
+    hipLaunchKernelGGL(cast_rows_kernel<bf16>, dim3(bx, n_groups), dim3(256), 0, st, elems, X, (bf16*)out,
+                       out_slot_stride, out_slots);
+  else
+    hipLaunchKernelGGL(cast_rows_kernel<float>, dim3(bx, n_groups), dim3(256), 0, st, elems, X, (float*)out,
+                       out_slot_stride, out_slots);
+  return hipGetLastError();
+}
+
+template <typename TO>
+__global__ void __launch_bounds__(256) cast_flat_kernel(const float* in, TO* out, long elems) {
+  for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (long)gridDim.x * 256 * 4)
+    store4<TO>(out + i, *reinterpret_cast<const f32x4*>(in + i));
+}
+
+hipError_t launch_cast_flat(const float* in, void* out, long elems, bool is_bf16, hipStream_t st) {
+  if (elems <= 0) return hipSuccess;
+  long want = (elems / 4 + 255) / 256;
+  const unsigned bx = (unsigned)(want < 1 ? 1 : (want > 4096 ? 4096 : want));
+  if (is_bf16) hipLaunchKernelGGL(cast_flat_kernel<bf16>, dim3(bx), dim3(256), 0, st, in, (bf16*)out, elems);
+  else hipLaunchKernelGGL(cast_flat_kernel<float>, dim3(bx), dim3(256), 0, st, in, (float*)out, elems);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// driver elementwise: differences and the residual norm
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) sub_rows_kernel(long elems, Rows A, Rows B, Rows D) {
+  const int g = blockIdx.y;
+  const float* pa = A.at(g);
+  const float* pb = B.at(g);
+  float* pd = D.at(g);
+  for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (long)gridDim.x * 256 * 4)
+    *reinterpret_cast<f32x4*>(pd + i) =
+        *reinterpret_cast<const f32x4*>(pa + i) - *reinterpret_cast<const f32x4*>(pb + i);
+}
+
+hipError_t launch_sub_rows(int n_groups, long elems, Rows A, Rows B, Rows D, hipStream_t st) {
+  if (n_groups <= 0 || elems <= 0) return hipSuccess;
+  long want = (elems / 4 + 255) / 256;
+  const unsigned bx = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+  hipLaunchKernelGGL(sub_rows_kernel, dim3(bx, n_groups), dim3(256), 0, st, elems, A, B, D);
+  return hipGetLastError();
+}
+
+constexpr int RN_BLOCKS = 32;       // partial sums per group
+
+__global__ void __launch_bounds__(256) resnorm_partial_kernel(long elems, Rows A, Rows B, double* partial) {
+  __shared__ double red[256];
+  const int g = blockIdx.y;
+  const float* pa = A.at(g);
+  const float* pb = B.at(g);
+  float s = 0.f;
+  double acc = 0.0;
+  int cnt = 0;
+  for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (long)gridDim.x * 256 * 4) {
+    f32x4 e = *reinterpret_cast<const f32x4*>(pa + i) - *reinterpret_cast<const f32x4*>(pb + i);
+    s += (e[0] * e[0] + e[1] * e[1]) + (e[2] * e[2] + e[3] * e[3]);
+    if (++cnt == 64) { acc += (double)s; s = 0.f; cnt = 0; }
+  }
+  acc += (double)s;
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) partial[(long)g * gridDim.x + blockIdx.x] = red[0];
+}
+
+__global__ void __launch_bounds__(256) resnorm_final_kernel(const double* partial, int n, float* out) {
+  __shared__ double red[256];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) acc += partial[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[0] = (float)sqrt(red[0]);
+}
+
+hipError_t launch_resnorm(int n_groups, long elems, Rows A, Rows B, double* partial, int max_partial,
+                          float* out, hipStream_t st) {
+  if (n_groups <= 0 || elems <= 0) return hipSuccess;
+  if (n_groups * RN_BLOCKS > max_partial) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(resnorm_partial_kernel, dim3(RN_BLOCKS, n_groups), dim3(256), 0, st, elems, A, B, partial);
+  hipLaunchKernelGGL(resnorm_final_kernel, dim3(1), dim3(256), 0, st, partial, n_groups * RN_BLOCKS, out);
+  return hipGetLastError();
+}
+int resnorm_partials_per_group() { return RN_BLOCKS; }
+
+// ---------------------------------------------------------------------------
+// pointer tables
+// ---------------------------------------------------------------------------
+__global__ void fill_table_kernel(void** tab, char* base, long stride_bytes, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) tab[i] = base + (long)i * stride_bytes;
+}
+
+hipError_t launch_fill_table(void** tab, char* base, long stride_bytes, int n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, tab, base, stride_bytes, n);
+  return hipGetLastError();
+}
+
+struct PtrPack { const void* p[32]; };
+__global__ void upload_ptrs_kernel(void** tab, PtrPack pack, int n) {
+  const int i = threadIdx.x;
+  if (i < n) tab[i] = const_cast<void*>(pack.p[i]);
+}
+
+hipError_t upload_pointers(void** tab, const void* const* host_ptrs, int n, hipStream_t st) {
+  for (int i0 = 0; i0 < n; i0 += 32) {
+    PtrPack pack;
+    const int m = n - i0 < 32 ? n - i0 : 32;
+    for (int i = 0; i < 32; ++i) pack.p[i] = i < m ? host_ptrs[i0 + i] : nullptr;
+    hipLaunchKernelGGL(upload_ptrs_kernel, dim3(1), dim3(32), 0, st, tab + i0, pack, m);
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// weight transposition (adjoint): out_g[c,r] = in_g[r,c]
+// ---------------------------------------------------------------------------
+template <typename U>
+__global__ void __launch_bounds__(256) transpose_kernel(Params in, Params out, long off, int rows, int cols) {
+  __shared__ U tile[32][33];
+  const int g = blockIdx.z;
+  const U* src = reinterpret_cast<const U*>(in.at(g) + off);
+  U* dst = reinterpret_cast<U*>(const_cast<char*>(out.at(g)) + off);
+  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int i = ty; i < 32; i += 8) {
+    const int r = r0 + i, c = c0 + tx;
+    if (r < rows && c < cols) tile[i][tx] = src[(long)r * cols + c];
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int c = c0 + i, r = r0 + tx;
+    if (r < rows && c < cols) dst[(long)c * rows + r] = tile[tx][i];
+  }
+}
+
+hipError_t launch_transpose(int n_groups, Params in, Params out, long off, int rows, int cols, int elem_bytes,
+                            hipStream_t st) {
+  if (n_groups <= 0) return hipSuccess;
+  dim3 grid((cols + 31) / 32, (rows + 31) / 32, n_groups);
+  if (elem_bytes == 2)
+    hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, st, in, out, off, rows, cols);
+  else
+    hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, st, in, out, off, rows, cols);
+  return hipGetLastError();
+}
+
+}  // namespace mg

@@ -1,0 +1,68 @@
+"""Helpers shared by the GPU parity tests: move a seeded workload to the device, run the
+oracle on the same inputs, compare."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import transformer_ode as tode
+from paper_2601_09026_amd import binding as mb
+from paper_2601_09026_amd import workloads as wls
+
+TOL = {wls.DTYPE_F32: 1e-5, wls.DTYPE_BF16: 2e-2}   # normwise relative tolerance per dtype
+
+
+def shape_of(wl, batch=None):
+    return tode.Shape(wl.arch, wl.d_model, wl.n_heads, wl.batch if batch is None else batch, wl.seq,
+                      wl.mem_seq, wl.ln_eps)
+
+
+class DeviceModel:
+    """Packed parameter blocks on the GPU plus the same parameters as named host arrays."""
+
+    def __init__(self, wl, n_layers=None, weight_std=0.02, keep_host=True):
+        self.wl = wl
+        self.desc = mb.model_desc(wl)
+        n_layers = wl.N if n_layers is None else n_layers
+        self.host = []
+        self.blocks = []
+        for n in range(n_layers):
+            p = wls.layer_params(wl, n, weight_std)
+            self.blocks.append(mb.pack_theta(self.desc, p))
+            self.host.append(p if keep_host else None)
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def relerr(got, ref) -> float:
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def increment_tolerance(tol, ref, base, n_steps):
+    """Bar for the error of (state - start value) relative to that increment.
+
+    The state is stored in fp32, so each of the n_steps Euler updates rounds it by up to
+    2^-24 |Z| per element no matter how accurate F is; these roundings add up like a random
+    walk.  Relative to the (small) increment that floor is sqrt(n) 2^-24 |Z| / |dZ|; a factor
+    4 covers the spread.  It is added to the dtype's relative tolerance."""
+    ref = np.asarray(ref, np.float64)
+    inc = np.linalg.norm(ref - base)
+    if inc == 0.0:
+        return float("inf")
+    return tol + 4.0 * np.sqrt(max(n_steps, 1)) * 2.0 ** -24 * np.linalg.norm(ref) / inc
+
+
+def assert_close(got, ref, base, tol, what, n_steps=1):
+    """Normwise relative error on the value and on its increment over `base` (the state it
+    started from): a few-percent error in F must not hide behind the O(1) state."""
+    e_val = relerr(got, ref)
+    e_inc = relerr(np.asarray(got, np.float64) - base, np.asarray(ref, np.float64) - base)
+    tol_inc = increment_tolerance(tol, ref, base, n_steps)
+    assert np.isfinite(np.asarray(got)).all(), f"{what}: non-finite values"
+    assert e_val <= tol, f"{what}: value error {e_val:.3e} > {tol}"
+    assert e_inc <= tol_inc, f"{what}: increment error {e_inc:.3e} > {tol_inc:.3e} (value error {e_val:.3e})"
+    return e_val, e_inc

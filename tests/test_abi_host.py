@@ -1,0 +1,109 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, reports a consistent parameter layout, counts evaluations like the oracle's
+driver does, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import mgrit as omgrit
+from paper_2601_09026_amd import binding as mb
+from paper_2601_09026_amd import workloads as wls
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "mgrit.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(mgrit_[a-z_]+|layer_step_batched)\s*\(", hdr))
+    assert {"mgrit_forward", "mgrit_adjoint", "layer_step_batched", "mgrit_workspace_bytes",
+            "mgrit_theta_layout", "mgrit_status_string"} <= names
+    L = mb.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+@pytest.mark.parametrize("name", list(wls.named_workloads()))
+def test_theta_layout_matches_the_documented_order(name):
+    wl = wls.named_workloads()[name]
+    desc = mb.model_desc(wl)
+    lay = mb.mgrit_theta_layout(desc)
+    shapes = wls.param_shapes(wl)
+    prev_end = 0
+    for i, pname in enumerate(mb.P_NAMES):
+        if pname not in shapes:
+            assert lay.offset[i] == -1
+            continue
+        shp = shapes[pname]
+        rows, cols = (shp[0], 1) if len(shp) == 1 else shp
+        assert (lay.rows[i], lay.cols[i]) == (rows, cols), pname
+        eb = 4 if (len(shp) == 1 or wl.dtype == wls.DTYPE_F32) else 2
+        assert lay.elem_bytes[i] == eb
+        assert lay.offset[i] % 16 == 0 and lay.offset[i] >= prev_end      # in order, no overlap
+        prev_end = lay.offset[i] + rows * cols * eb
+    assert lay.block_bytes >= prev_end and lay.block_bytes % 256 == 0
+
+
+def oracle_counts(N, cf, levels, iters, relax):
+    step = omgrit.linear_propagator(-0.3, 0.1, cf)
+    _, _, counts = omgrit.mgrit_solve(step, np.array([1.0]), N, cf, levels, iters, relax)
+    return counts
+
+
+@pytest.mark.parametrize("N,cf,levels,iters,relax", [
+    (16, 4, 2, 2, 1), (64, 4, 2, 2, 1), (128, 4, 3, 2, 1), (32, 2, 2, 3, 1), (32, 4, 2, 2, 1),
+    (16, 2, 4, 1, 0), (24, 3, 2, 3, 0), (16, 4, 1, 5, 1), (16, 1, 3, 2, 1)])
+def test_evaluation_count_equals_oracle_minus_redundant_relaxations(N, cf, levels, iters, relax):
+    """The library skips the opening F-relaxation of V-cycles 2..nu on level 0 (it would recompute
+    what the previous cycle's closing F-relaxation left); everything else is counted alike."""
+    got = mb.mgrit_step_evaluations(mb.mgrit_opts(N, 0.1, cf, levels, iters, relax))
+    want = sum(oracle_counts(N, cf, levels, iters, "FCF" if relax else "F"))
+    if levels > 1 and cf > 1 and iters > 1:
+        want -= (iters - 1) * (N // cf) * (cf - 1)
+    assert got == want
+    if (N, cf, levels, iters, relax) == (64, 4, 2, 2, 1):
+        assert got == 368            # BERT-shaped configuration: 304 fine + 64 coarse
+    if (N, cf, levels, iters, relax) == (128, 4, 3, 2, 1):
+        assert got == 880
+
+
+def test_invalid_arguments_are_rejected_without_a_device():
+    wl = wls.named_workloads()["tiny_encoder"]
+    desc = mb.model_desc(wl)
+    L = mb.lib()
+    # N not divisible by cf^(levels-1)
+    assert mb.mgrit_workspace_bytes(desc, mb.mgrit_opts(10, 0.1, 4, 2, 1), False) == 0
+    assert mb.mgrit_step_evaluations(mb.mgrit_opts(10, 0.1, 4, 2, 1)) == -1
+    assert mb.mgrit_step_evaluations(mb.mgrit_opts(16, 0.1, 0, 2, 1)) == -1
+    assert mb.mgrit_step_evaluations(mb.mgrit_opts(16, 0.1, 4, 2, -1)) == -1
+    ok = mb.mgrit_opts(16, 1 / 16, 4, 2, 2)
+    assert mb.mgrit_workspace_bytes(desc, ok, False) > 0
+    assert mb.mgrit_workspace_bytes(desc, ok, True) > mb.mgrit_workspace_bytes(desc, ok, False)
+    # null pointers
+    st = L.mgrit_forward(C.byref(desc), C.byref(ok), None, None, None, None, None, None, 0, None)
+    assert st == -1
+    bad = mb.ModelDesc(0, 65, 4, 256, 2, 32, 0, 0, 1e-5)        # d_model % n_heads != 0
+    lay = mb.ThetaLayout()
+    assert L.mgrit_theta_layout(C.byref(bad), C.byref(lay)) == -1
+    odd = mb.ModelDesc(0, 36, 6, 72, 2, 32, 0, 0, 1e-5)         # head size 6: no kernel
+    assert L.mgrit_theta_layout(C.byref(odd), C.byref(lay)) == -2
+    cross_no_mem = mb.ModelDesc(2, 64, 4, 256, 2, 32, 0, 0, 1e-5)
+    assert L.mgrit_theta_layout(C.byref(cross_no_mem), C.byref(lay)) == -1
+    assert L.mgrit_status_string(-3) == b"workspace too small"
+    # adjoint of the cross-attention decoder is not built yet
+    dec = mb.model_desc(wls.named_workloads()["mt_decoder"])
+    assert mb.mgrit_workspace_bytes(dec, mb.mgrit_opts(32, 1 / 32, 4, 2, 2), True) == 0
+    assert mb.mgrit_workspace_bytes(dec, mb.mgrit_opts(32, 1 / 32, 4, 2, 2), False) > 0
+
+
+def test_workspace_grows_with_groups_and_levels():
+    desc = mb.model_desc(wls.named_workloads()["bert_base"])
+    a = mb.mgrit_layer_step_workspace_bytes(desc, False, 1)
+    b = mb.mgrit_layer_step_workspace_bytes(desc, False, 4)
+    assert 0 < a < b
+    two = mb.mgrit_workspace_bytes(desc, mb.mgrit_opts(64, 1 / 64, 4, 2, 2), False)
+    three = mb.mgrit_workspace_bytes(desc, mb.mgrit_opts(64, 1 / 64, 4, 3, 2), False)
+    assert three > two

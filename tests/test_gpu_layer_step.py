@@ -1,0 +1,147 @@
+"""GPU parity of layer_step_batched (forward and adjoint) against the CPU oracle, element by
+element on the same seeded inputs.  Shapes span several GEMM/attention tiles and a ragged
+tail (T = 150 rows against 64/128-row tiles, S = 50 or 75 against 16/64-row attention tiles)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import transformer_ode as tode
+from paper_2601_09026_amd import binding as mb
+from paper_2601_09026_amd import workloads as wls
+
+from gpu_util import TOL, DeviceModel, assert_close, dev, relerr, shape_of
+
+pytestmark = pytest.mark.gpu
+
+
+def make(arch, dtype, d=128, H=4, f=512, B=3, S=50, Sm=40, seed=31):
+    return wls.Workload("t", arch, d, H, f, B, S, Sm if arch == wls.ARCH_CROSS else 0,
+                        4, 0.25, 2, 2, 1, dtype, seed)
+
+
+def run_forward_case(wl, G, hstep, with_rhs, weight_std, force_simple, max_groups=0):
+    print(f"[case] fwd arch={wl.arch} dtype={wl.dtype} d={wl.d_model} H={wl.n_heads} f={wl.d_ff} "
+          f"B={wl.batch} S={wl.seq} G={G} rhs={with_rhs} simple={force_simple} mg={max_groups}", flush=True)
+    mb.lib().mgrit_debug_force_simple_kernels(int(force_simple), int(force_simple))
+    mb.mgrit_set_max_groups_per_launch(max_groups)
+    try:
+        dm = DeviceModel(wl, n_layers=G, weight_std=weight_std)
+        sh = shape_of(wl)
+        rng = np.random.default_rng(wl.seed)
+        X = [rng.standard_normal((wl.tokens, wl.d_model)).astype(np.float32) for _ in range(G)]
+        R = [0.1 * rng.standard_normal((wl.tokens, wl.d_model)).astype(np.float32) for _ in range(G)]
+        mem = wls.cross_memory(wl)
+        ins = [dev(x) for x in X]
+        outs = [torch.full_like(t, float("nan")) for t in ins]
+        rhs = [dev(r) for r in R] if with_rhs else None
+        mb.layer_step_batched(dm.desc, False, ins, outs, dm.blocks, hstep, rhs=rhs,
+                              memory=None if mem is None else dev(mem))
+        torch.cuda.synchronize()
+        for g in range(G):
+            ref = tode.phi(X[g], dm.host[g], hstep, sh, mem)
+            if with_rhs:
+                ref = ref + R[g]
+            base = X[g].astype(np.float64) + (R[g] if with_rhs else 0.0)
+            assert_close(outs[g].cpu().numpy(), ref, base, TOL[wl.dtype], f"group {g}")
+            assert torch.equal(ins[g].cpu(), torch.from_numpy(X[g])), "input was modified"
+    finally:
+        mb.lib().mgrit_debug_force_simple_kernels(0, 0)
+        mb.mgrit_set_max_groups_per_launch(0)
+
+
+@pytest.mark.parametrize("force_simple", [1, 0])
+@pytest.mark.parametrize("arch", [wls.ARCH_ENCODER, wls.ARCH_CAUSAL, wls.ARCH_CROSS])
+@pytest.mark.parametrize("dtype", [wls.DTYPE_F32, wls.DTYPE_BF16])
+def test_forward_step_matches_oracle(arch, dtype, force_simple):
+    if dtype == wls.DTYPE_F32 and not force_simple:
+        pytest.skip("fp32 has a single kernel path")
+    run_forward_case(make(arch, dtype), G=3, hstep=0.37, with_rhs=True, weight_std=0.05,
+                     force_simple=force_simple)
+
+
+@pytest.mark.parametrize("dtype", [wls.DTYPE_F32, wls.DTYPE_BF16])
+def test_forward_step_without_rhs_and_chunked_groups(dtype):
+    # 5 groups split into launches of 2, 2, 1
+    run_forward_case(make(wls.ARCH_ENCODER, dtype, S=75, B=2), G=5, hstep=1.0, with_rhs=False,
+                     weight_std=0.05, force_simple=0, max_groups=2)
+
+
+def test_forward_step_tiny_config_shape_fp32():
+    """d=64, 4 heads of 16, f=256, S=32: the shape of the smallest benchmark configuration."""
+    wl = wls.named_workloads()["tiny_encoder"]
+    run_forward_case(wl, G=4, hstep=wl.h * wl.cf, with_rhs=True, weight_std=0.02, force_simple=0)
+
+
+def test_forward_step_odd_sequence_length_bf16():
+    """ViT-like odd sequence length (197 = 196 patches + cls), d_head = 64."""
+    wl = wls.Workload("t", wls.ARCH_ENCODER, 384, 6, 1536, 2, 197, 0, 2, 0.5, 2, 2, 1, wls.DTYPE_BF16, 9)
+    run_forward_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.02, force_simple=0)
+
+
+def run_adjoint_case(wl, G, hstep, with_rhs, weight_std, force_simple, max_groups=0):
+    print(f"[case] adj arch={wl.arch} dtype={wl.dtype} d={wl.d_model} S={wl.seq} G={G} rhs={with_rhs} "
+          f"simple={force_simple} mg={max_groups}", flush=True)
+    mb.lib().mgrit_debug_force_simple_kernels(int(force_simple), int(force_simple))
+    mb.mgrit_set_max_groups_per_launch(max_groups)
+    try:
+        dm = DeviceModel(wl, n_layers=G, weight_std=weight_std)
+        sh = shape_of(wl)
+        rng = np.random.default_rng(wl.seed + 1)
+        Z = [rng.standard_normal((wl.tokens, wl.d_model)).astype(np.float32) for _ in range(G)]
+        Lm = [rng.standard_normal((wl.tokens, wl.d_model)).astype(np.float32) for _ in range(G)]
+        R = [0.1 * rng.standard_normal((wl.tokens, wl.d_model)).astype(np.float32) for _ in range(G)]
+        ins = [dev(x) for x in Lm]
+        lin = [dev(z) for z in Z]
+        outs = [torch.full_like(t, float("nan")) for t in ins]
+        rhs = [dev(r) for r in R] if with_rhs else None
+        mb.layer_step_batched(dm.desc, True, ins, outs, dm.blocks, hstep, lin_state=lin, rhs=rhs)
+        torch.cuda.synchronize()
+        for g in range(G):
+            ref = tode.psi(Lm[g], Z[g], dm.host[g], hstep, sh)
+            if with_rhs:
+                ref = ref + R[g]
+            base = Lm[g].astype(np.float64) + (R[g] if with_rhs else 0.0)
+            assert_close(outs[g].cpu().numpy(), ref, base, TOL[wl.dtype], f"group {g}")
+    finally:
+        mb.lib().mgrit_debug_force_simple_kernels(0, 0)
+        mb.mgrit_set_max_groups_per_launch(0)
+
+
+@pytest.mark.parametrize("force_simple", [1, 0])
+@pytest.mark.parametrize("arch", [wls.ARCH_ENCODER, wls.ARCH_CAUSAL])
+@pytest.mark.parametrize("dtype", [wls.DTYPE_F32, wls.DTYPE_BF16])
+def test_adjoint_step_matches_oracle(arch, dtype, force_simple):
+    if dtype == wls.DTYPE_F32 and not force_simple:
+        pytest.skip("fp32 has a single kernel path")
+    run_adjoint_case(make(arch, dtype), G=3, hstep=0.37, with_rhs=True, weight_std=0.05,
+                     force_simple=force_simple)
+
+
+def test_adjoint_step_chunked_no_rhs_bf16():
+    run_adjoint_case(make(wls.ARCH_CAUSAL, wls.DTYPE_BF16, S=75, B=2), G=3, hstep=1.0, with_rhs=False,
+                     weight_std=0.05, force_simple=0, max_groups=2)
+
+
+def test_step_is_bit_deterministic():
+    wl = make(wls.ARCH_CAUSAL, wls.DTYPE_BF16)
+    dm = DeviceModel(wl, n_layers=2, weight_std=0.05)
+    X = [dev(wls.initial_state(wl)) for _ in range(2)]
+    a = [torch.empty_like(x) for x in X]
+    b = [torch.empty_like(x) for x in X]
+    mb.layer_step_batched(dm.desc, False, X, a, dm.blocks, 0.5)
+    mb.layer_step_batched(dm.desc, False, X, b, dm.blocks, 0.5)
+    torch.cuda.synchronize()
+    assert all(torch.equal(x, y) for x, y in zip(a, b))
+
+
+def test_errors_leave_outputs_untouched():
+    wl = make(wls.ARCH_ENCODER, wls.DTYPE_F32)
+    dm = DeviceModel(wl, n_layers=1)
+    x = dev(wls.initial_state(wl))
+    out = torch.full_like(x, 7.0)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(mb.MgritError) as ei:
+        mb.layer_step_batched(dm.desc, False, [x], [out], dm.blocks, 0.5, workspace=small)
+    assert ei.value.status == -3
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
