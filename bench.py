@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the MGRIT hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input:
+mgrit_forward followed by mgrit_adjoint (linearised about the forward result) at the named
+workload.  The headline value is layer-steps*tokens/s = (Phi + Psi evaluations enqueued on
+all levels) x (batch*seq) / wall time, with all inputs resident in HBM before the timed
+region.  The adjoint's one-off N-layer linearisation pass is timed but not counted as
+evaluations.
+
+Prints ONE JSON line (see README for the fields).  Everything runs on one GPU;
+--gpus above 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="bert_base",
+                    help="tiny_encoder | bert_base | gpt2_small | vit_small | mt_encoder | mt_decoder")
+    ap.add_argument("--no-adjoint", action="store_true", help="time mgrit_forward only")
+    ap.add_argument("--max-groups", type=int, default=0, help="groups per kernel launch (0 = library default)")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not record per-kernel HIP events in the timed region")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing sample")
+    ap.add_argument("--breakdown", action="store_true", help="print a per-kernel-class table to stderr")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, n_phi, n_psi, budget_s):
+    """Time the fp64 numpy oracle (as it stands) on a bounded sample of the same workload."""
+    from oracle import transformer_ode as tode
+    from paper_2601_09026_amd import workloads as wls
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    sh = tode.Shape(wl.arch, wl.d_model, wl.n_heads, wl.batch, wl.seq, wl.mem_seq, wl.ln_eps)
+    th = wls.layer_params(wl, 0)
+    Z = wls.initial_state(wl).astype(np.float64)
+    lam = wls.terminal_adjoint(wl).astype(np.float64)
+    mem = wls.cross_memory(wl)
+    t_phi, t_psi, n1, n2 = 0.0, 0.0, 0, 0
+    t0 = time.perf_counter()
+    while True:
+        t = time.perf_counter(); Z = tode.phi(Z, th, wl.h, sh, mem); t_phi += time.perf_counter() - t; n1 += 1
+        if n_psi:
+            t = time.perf_counter(); lam = tode.psi(lam, Z, th, wl.h, sh, mem); t_psi += time.perf_counter() - t
+            n2 += 1
+        if time.perf_counter() - t0 > budget_s or n1 >= 64:
+            break
+    est = n_phi * (t_phi / n1) + (n_psi * (t_psi / n2) if n2 else 0.0)
+    value = (n_phi + n_psi) * wl.tokens / est
+    return {"value": value, "unit": "layer-steps*tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n1} forward + {n2} adjoint layer steps of the fp64 numpy oracle at the full "
+                      f"{wl.name} shape (T={wl.tokens}); per-step times weighted by the step's "
+                      f"{n_phi} forward / {n_psi} adjoint evaluations",
+            "s_per_forward_step": t_phi / n1, "s_per_adjoint_step": (t_psi / n2) if n2 else None}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2601_09026_amd import binding as mb
+    from paper_2601_09026_amd import workloads as wls
+
+    wl = wls.named_workloads()[args.workload]
+    adjoint = not args.no_adjoint and wl.arch != wls.ARCH_CROSS
+    torch.cuda.set_device(0)
+    if args.max_groups:
+        mb.mgrit_set_max_groups_per_launch(args.max_groups)
+    desc = mb.model_desc(wl)
+    opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters)
+    T, d = wl.tokens, wl.d_model
+
+    # inputs resident in HBM before anything is timed
+    theta = [mb.pack_theta(desc, wls.layer_params(wl, n)) for n in range(wl.N)]
+    Z0 = torch.from_numpy(wls.initial_state(wl)).cuda()
+    lamN = torch.from_numpy(wls.terminal_adjoint(wl)).cuda()
+    mem = wls.cross_memory(wl)
+    mem = None if mem is None else torch.from_numpy(mem).cuda()
+    Z_all = torch.empty((wl.N + 1, T, d), dtype=torch.float32, device="cuda")
+    lam_all = torch.empty_like(Z_all) if adjoint else None
+    res_f = torch.zeros(max(wl.iters, 1), dtype=torch.float32, device="cuda")
+    res_a = torch.zeros(max(wl.iters, 1), dtype=torch.float32, device="cuda")
+    ws_bytes = max(mb.mgrit_workspace_bytes(desc, opts, False),
+                   mb.mgrit_workspace_bytes(desc, opts, True) if adjoint else 0, 256)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    n_phi = mb.mgrit_step_evaluations(opts)
+    n_psi = n_phi if adjoint else 0
+    stream = torch.cuda.current_stream()
+
+    def step():
+        mb.mgrit_forward(desc, opts, Z0, theta, memory=mem, Z_all=Z_all, resnorm=res_f, workspace=ws,
+                         stream=stream)
+        if adjoint:
+            mb.mgrit_adjoint(desc, opts, Z_all, theta, lamN, memory=mem, lambda_all=lam_all, resnorm=res_a,
+                             workspace=ws, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = not args.no_kernel_events
+    totals = {}
+    if events:
+        # size the event pool from one untimed step, then create it outside the timed region
+        mb.mgrit_profile_enable(200000)
+        step()
+        torch.cuda.synchronize()
+        per_step = sum(v["launches"] for v in mb.mgrit_profile_read().values())
+        mb.mgrit_profile_enable(per_step * args.steps + 64)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    if events:
+        fold(mb, totals)
+        mb.mgrit_profile_enable(0)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = (n_phi + n_psi) * T / (ms_per_step * 1e-3)
+
+    # roofline of the dominant kernel: the MFMA grouped GEMM (all epilogues together)
+    roofline = None
+    if totals:
+        gemm = [v for k, v in totals.items() if k.startswith("gemm_mfma")]
+        if gemm:
+            fl = sum(v["flops"] for v in gemm); ms = sum(v["ms"] for v in gemm); n = sum(v["launches"] for v in gemm)
+            ach = fl / (ms * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel (grouped projection GEMMs, all epilogues)",
+                        "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                        "launches_per_step": n / args.steps, "avg_launch_us": ms * 1e3 / n,
+                        "flop_per_launch": fl / n, "share_of_step_time": ms / args.steps / ms_per_step}
+        else:
+            gen = totals.get("gemm_generic")
+            if gen:
+                ach = gen["flops"] / (gen["ms"] * 1e-3) / 1e12
+                roofline = {"bound": "alu", "kernel": "gemm_simple_kernel (fp32 FMA)", "achieved": ach,
+                            "peak": 157.3, "unit": "TFLOP/s", "frac": ach / 157.3, "traffic": None,
+                            "avg_launch_us": gen["ms"] * 1e3 / gen["launches"]}
+        hbm = {}
+        for k in ("ln_fwd", "ln_vjp", "elementwise"):
+            if k in totals and totals[k]["ms"] > 0:
+                gbs = totals[k]["bytes"] / (totals[k]["ms"] * 1e-3) / 1e9
+                hbm[k] = {"achieved_GBs": gbs, "frac_of_8TBs": gbs / PEAK_HBM_GBS,
+                          "avg_launch_us": totals[k]["ms"] * 1e3 / totals[k]["launches"]}
+        if roofline is not None:
+            roofline["hbm_bound_kernels"] = hbm
+    if args.breakdown and totals:
+        print(f"{'class':28s} {'launches/step':>13s} {'ms/step':>9s} {'TFLOP/s':>9s} {'GB/s':>9s}", file=sys.stderr)
+        for k, v in sorted(totals.items(), key=lambda kv: -kv[1]["ms"]):
+            ms = v["ms"] / args.steps
+            print(f"{k:28s} {v['launches'] / args.steps:13.1f} {ms:9.3f} "
+                  f"{v['flops'] / (v['ms'] * 1e-3) / 1e12:9.1f} {v['bytes'] / (v['ms'] * 1e-3) / 1e9:9.0f}",
+                  file=sys.stderr)
+        print(f"{'wall':28s} {'':13s} {ms_per_step:9.3f}", file=sys.stderr)
+
+    out = {
+        "metric": "MGRIT fwd+adjoint layer-steps*tokens/sec" if adjoint else "MGRIT fwd layer-steps*tokens/sec",
+        "value": value, "unit": "layer-steps*tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if wl.dtype == wls.DTYPE_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "d_model": wl.d_model, "n_heads": wl.n_heads, "d_ff": wl.d_ff,
+                   "batch": wl.batch, "seq": wl.seq, "N": wl.N, "h": wl.h, "cf": wl.cf, "levels": wl.levels,
+                   "iters": wl.iters, "relax": "FCF", "adjoint": adjoint,
+                   "phi_evaluations": n_phi, "psi_evaluations": n_psi,
+                   "max_groups_per_launch": args.max_groups or "default"},
+        "residual_norms": {"forward": [float(x) for x in res_f.cpu()[:wl.iters]],
+                           "adjoint": [float(x) for x in res_a.cpu()[:wl.iters]] if adjoint else None},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, n_phi, n_psi, args.cpu_seconds)
+        out["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
+    print(json.dumps(out))
+
+
+def fold(mb, totals):
+    """Add the event pool's per-class totals to `totals` and reset the pool."""
+    for k, v in mb.mgrit_profile_read().items():
+        t = totals.setdefault(k, {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
+        for f in ("ms", "flops", "bytes", "launches"):
+            t[f] += v[f]
+        if v.get("overflow"):
+            t["overflow"] = True
+    mb.mgrit_profile_reset()
+
+
+if __name__ == "__main__":
+    main()

@@ -169,6 +169,23 @@ int         mgrit_last_hip_error(void);          /* hipError_t of the last MGRIT
  * are split into chunks that run one after another).  0 restores the default. */
 void mgrit_set_max_groups_per_launch(int n);
 
+/* ---- instrumentation (benchmark and tests; not needed for normal use) ------------------
+ * Per-launch timing with HIP events recorded on the launch stream around every kernel of
+ * a class.  mgrit_profile_enable(n > 0) creates a pool of n records (this call allocates
+ * events; do it outside timed regions) and starts recording; n = 0 stops and frees it.
+ * After synchronising the stream, mgrit_profile_read() returns the totals of one class
+ * since the last mgrit_profile_reset(): summed kernel time, algorithmic flops and bytes,
+ * launches.  Classes: 0 generic GEMM, 1 attention fwd, 2 attention bwd, 3 LayerNorm fwd,
+ * 4 LayerNorm VJP, 5 other elementwise, 8+e MFMA grouped GEMM with epilogue e
+ * (0 store, 1 bias+GELU, 2 sublayer sum, 3 Euler update, 4 GELU', 5 fp32 store).
+ * Returns 0, -1 for a bad class, -3 if the pool overflowed. */
+int  mgrit_profile_enable(int max_records);
+void mgrit_profile_reset(void);
+int  mgrit_profile_read(int cls, double* total_ms, double* flops, double* bytes, int64_t* launches);
+
+/* Test hook: route GEMMs (first flag) / attention (second flag) to the generic kernels. */
+void mgrit_debug_force_simple_kernels(int gemm, int attn);
+
 #ifdef __cplusplus
 }
 #endif

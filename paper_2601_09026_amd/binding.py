@@ -83,6 +83,13 @@ def lib() -> C.CDLL:
         L.mgrit_set_max_groups_per_launch.restype = None
         L.mgrit_debug_force_simple_kernels.argtypes = [C.c_int, C.c_int]
         L.mgrit_debug_force_simple_kernels.restype = None
+        L.mgrit_profile_enable.argtypes = [C.c_int]
+        L.mgrit_profile_enable.restype = C.c_int
+        L.mgrit_profile_reset.argtypes = []
+        L.mgrit_profile_reset.restype = None
+        L.mgrit_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                         C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.mgrit_profile_read.restype = C.c_int
         _lib = L
     return _lib
 
@@ -120,6 +127,35 @@ def mgrit_step_evaluations(opts: Opts) -> int:
 
 def mgrit_set_max_groups_per_launch(n: int) -> None:
     lib().mgrit_set_max_groups_per_launch(int(n))
+
+
+PROFILE_CLASSES = {0: "gemm_generic", 1: "attn_fwd", 2: "attn_bwd", 3: "ln_fwd", 4: "ln_vjp", 5: "elementwise",
+                   8: "gemm_mfma_store", 9: "gemm_mfma_gelu", 10: "gemm_mfma_sublayer_sum",
+                   11: "gemm_mfma_euler", 12: "gemm_mfma_dgelu", 13: "gemm_mfma_store_f32"}
+
+
+def mgrit_profile_enable(max_records: int) -> None:
+    st = lib().mgrit_profile_enable(int(max_records))
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_profile_enable")
+
+
+def mgrit_profile_reset() -> None:
+    lib().mgrit_profile_reset()
+
+
+def mgrit_profile_read() -> Dict[str, dict]:
+    """Totals per kernel class since the last reset (synchronise the stream first)."""
+    out = {}
+    for cls, name in PROFILE_CLASSES.items():
+        ms, fl, by, n = C.c_double(), C.c_double(), C.c_double(), C.c_int64()
+        st = lib().mgrit_profile_read(cls, C.byref(ms), C.byref(fl), C.byref(by), C.byref(n))
+        if st not in (0, -3):
+            raise MgritError(st, "mgrit_profile_read")
+        if n.value:
+            out[name] = {"ms": ms.value, "flops": fl.value, "bytes": by.value, "launches": n.value,
+                         "overflow": st == -3}
+    return out
 
 
 # ------------------------------------------------------------------ parameter packing (byte copies only)

@@ -13,6 +13,7 @@
 //   pass 2, per key row j   : dV_j = sum_i p_ij dO_i,  dK_j = scale * sum_i dA_ij Q_i
 #include "common.h"
 #include "kernels.h"
+#include "prof.h"
 
 namespace mg {
 
@@ -371,12 +372,19 @@ static hipError_t attn_bwd_simple(const AttnArgs& a, hipStream_t st) {
 hipError_t launch_attn_fwd(const AttnArgs& a, bool is_bf16, hipStream_t st) {
   if (a.n_groups <= 0) return hipSuccess;
   if (a.dh > 128 || (a.dh & 3)) return hipErrorInvalidValue;
+  const double heads = (double)a.n_groups * a.B * a.H, esz = is_bf16 ? 2 : 4;
+  const double pairs = a.causal ? 0.5 * a.Sq * (a.Sk + 1.0) : (double)a.Sq * a.Sk;   // unmasked scores
+  ProfScope ps(PC_ATTN_FWD, heads * pairs * a.dh * 4.0, heads * (2.0 * a.Sq + 2.0 * a.Sk) * a.dh * esz, st);
   return is_bf16 ? attn_fwd_simple<bf16>(a, st) : attn_fwd_simple<float>(a, st);
 }
 
 hipError_t launch_attn_bwd(const AttnArgs& a, bool is_bf16, hipStream_t st) {
   if (a.n_groups <= 0) return hipSuccess;
   if (a.dh > 128 || (a.dh & 3)) return hipErrorInvalidValue;
+  const double heads = (double)a.n_groups * a.B * a.H, esz = is_bf16 ? 2 : 4;
+  const double pairs = a.causal ? 0.5 * a.Sq * (a.Sk + 1.0) : (double)a.Sq * a.Sk;
+  // recompute scores + dP, dV, dQ, dK: five contractions over the unmasked pairs
+  ProfScope ps(PC_ATTN_BWD, heads * pairs * a.dh * 10.0, heads * (4.0 * a.Sq + 4.0 * a.Sk) * a.dh * esz, st);
   return is_bf16 ? attn_bwd_simple<bf16>(a, st) : attn_bwd_simple<float>(a, st);
 }
 

@@ -12,6 +12,7 @@
 //  * gemm_simple: any operand type (fp32 path and odd shapes), LDS-tiled FMA.
 #include "common.h"
 #include "kernels.h"
+#include "prof.h"
 
 namespace mg {
 
@@ -274,11 +275,27 @@ static hipError_t launch_simple(const GemmArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+// algorithmic HBM bytes of one grouped GEMM launch: operands once, outputs once, epilogue operands once
+template <int EPI>
+static double gemm_bytes(const GemmArgs& a, double esz) {
+  const double G = a.n_groups, MN = (double)a.M * a.N;
+  double b = G * ((a.a_slot_stride ? 1.0 : 1.0 / G) * a.M * a.K * esz + (double)a.N * a.K * esz);
+  if (EPI == EPI_STORE) b += G * MN * esz;
+  if (EPI == EPI_GELU) b += G * MN * esz * (a.aux ? 2 : 1);
+  if (EPI == EPI_DGELU) b += G * MN * esz * 2;
+  if (EPI == EPI_STORE_F32) b += G * MN * 4;
+  if (EPI == EPI_RESID_INNER) b += G * MN * 4 * (a.base ? 2 : 1);
+  if (EPI == EPI_RESID_OUTER) b += G * MN * 4 * (a.RHS.present() ? 4 : 3);
+  return b;
+}
+
 template <int EPI>
 static hipError_t launch_epi(const GemmArgs& a, bool is_bf16, hipStream_t st) {
   if (a.n_groups <= 0 || a.M <= 0) return hipSuccess;
+  const double flops = 2.0 * a.n_groups * a.M * (double)a.N * a.K;
+  const bool mfma_ok = is_bf16 && !g_force_simple && (a.K % GEMM_BK == 0) && (a.N % 128 == 0);
+  ProfScope ps(mfma_ok ? PC_GEMM_MFMA + EPI : PC_GEMM_SIMPLE, flops, gemm_bytes<EPI>(a, is_bf16 ? 2 : 4), st);
   if (!is_bf16) return launch_simple<float, EPI>(a, st);
-  const bool mfma_ok = !g_force_simple && (a.K % GEMM_BK == 0) && (a.N % 128 == 0);
   if (!mfma_ok) return launch_simple<bf16, EPI>(a, st);
   return launch_mfma<128, 128, 2, 2, EPI>(a, st);
 }

@@ -1,0 +1,26 @@
+// Optional per-launch timing with HIP events on the launch stream (off by default).
+// Used by the benchmark to report achieved FLOP/s and bytes/s of each kernel class.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace mg {
+
+enum ProfClass : int {
+  PC_GEMM_SIMPLE = 0, PC_ATTN_FWD = 1, PC_ATTN_BWD = 2, PC_LN_FWD = 3, PC_LN_BWD = 4, PC_ELEMENTWISE = 5,
+  PC_GEMM_MFMA = 8,          // + epilogue id (0..5)
+  PC_COUNT = 16
+};
+
+bool prof_enabled();
+void prof_begin(int cls, double flops, double bytes, hipStream_t st);
+void prof_end(hipStream_t st);
+
+struct ProfScope {
+  hipStream_t st; bool on;
+  ProfScope(int cls, double flops, double bytes, hipStream_t s) : st(s), on(prof_enabled()) {
+    if (on) prof_begin(cls, flops, bytes, st);
+  }
+  ~ProfScope() { if (on) prof_end(st); }
+};
+
+}  // namespace mg

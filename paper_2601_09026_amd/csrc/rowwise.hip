@@ -4,6 +4,7 @@
 // tables, weight transposition for the adjoint.
 #include "common.h"
 #include "kernels.h"
+#include "prof.h"
 
 namespace mg {
 
@@ -72,6 +73,9 @@ hipError_t launch_ln_fwd(const LnFwdArgs& a, bool is_bf16, hipStream_t st) {
   const long rows = (long)a.n_groups * a.T;
   if (rows <= 0) return hipSuccess;
   const unsigned blocks = (unsigned)((rows + 3) / 4);
+  const double esz = is_bf16 ? 2 : 4;
+  ProfScope ps(PC_LN_FWD, 8.0 * rows * a.d,
+               (double)rows * a.d * ((a.X.present() ? 4 : 0) + (a.xp ? 4 : 0) + esz), st);
   if (is_bf16) hipLaunchKernelGGL(ln_fwd_kernel<bf16>, dim3(blocks), dim3(256), 0, st, a);
   else hipLaunchKernelGGL(ln_fwd_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
   return hipGetLastError();
@@ -162,6 +166,11 @@ hipError_t launch_ln_bwd(const LnBwdArgs& a, bool is_bf16, hipStream_t st) {
   const long rows = (long)a.n_groups * a.T;
   if (rows <= 0) return hipSuccess;
   const unsigned blocks = (unsigned)((rows + 3) / 4);
+  const double esz = is_bf16 ? 2 : 4;
+  const double per_elem = esz + (a.X.present() ? 4 : 0) + (a.xp ? 4 : 0) + (a.add ? 4 : 0) + (a.out_f32 ? 4 : 0) +
+                          ((a.out_op || a.OUT.present()) ? 4 : 0) + (a.out_op ? esz : 0) +
+                          (a.OUT.present() ? 4 : 0) + (a.RHS.present() ? 4 : 0);
+  ProfScope ps(PC_LN_BWD, 16.0 * rows * a.d, (double)rows * a.d * per_elem, st);
   if (is_bf16) hipLaunchKernelGGL(ln_bwd_kernel<bf16>, dim3(blocks), dim3(256), 0, st, a);
   else hipLaunchKernelGGL(ln_bwd_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
   return hipGetLastError();
@@ -185,6 +194,7 @@ hipError_t launch_cast_rows(int n_groups, long elems, Rows X, void* out, long ou
   if (n_groups <= 0 || elems <= 0) return hipSuccess;
   long want = (elems / 4 + 255) / 256;
   const unsigned bx = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+  ProfScope ps(PC_ELEMENTWISE, 0.0, (double)n_groups * elems * (4 + (is_bf16 ? 2 : 4)), st);
   if (is_bf16)
     hipLaunchKernelGGL(cast_rows_kernel<bf16>, dim3(bx, n_groups), dim3(256), 0, st, elems, X, (bf16*)out,
                        out_slot_stride, out_slots);
@@ -226,6 +236,7 @@ hipError_t launch_sub_rows(int n_groups, long elems, Rows A, Rows B, Rows D, hip
   if (n_groups <= 0 || elems <= 0) return hipSuccess;
   long want = (elems / 4 + 255) / 256;
   const unsigned bx = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+  ProfScope ps(PC_ELEMENTWISE, (double)n_groups * elems, (double)n_groups * elems * 12, st);
   hipLaunchKernelGGL(sub_rows_kernel, dim3(bx, n_groups), dim3(256), 0, st, elems, A, B, D);
   return hipGetLastError();
 }
@@ -272,6 +283,7 @@ hipError_t launch_resnorm(int n_groups, long elems, Rows A, Rows B, double* part
                           float* out, hipStream_t st) {
   if (n_groups <= 0 || elems <= 0) return hipSuccess;
   if (n_groups * RN_BLOCKS > max_partial) return hipErrorInvalidValue;
+  ProfScope ps(PC_ELEMENTWISE, 3.0 * n_groups * elems, (double)n_groups * elems * 8, st);
   hipLaunchKernelGGL(resnorm_partial_kernel, dim3(RN_BLOCKS, n_groups), dim3(256), 0, st, elems, A, B, partial);
   hipLaunchKernelGGL(resnorm_final_kernel, dim3(1), dim3(256), 0, st, partial, n_groups * RN_BLOCKS, out);
   return hipGetLastError();
@@ -334,6 +346,7 @@ hipError_t launch_transpose(int n_groups, Params in, Params out, long off, int r
                             hipStream_t st) {
   if (n_groups <= 0) return hipSuccess;
   dim3 grid((cols + 31) / 32, (rows + 31) / 32, n_groups);
+  ProfScope ps(PC_ELEMENTWISE, 0.0, 2.0 * n_groups * rows * cols * elem_bytes, st);
   if (elem_bytes == 2)
     hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, st, in, out, off, rows, cols);
   else
