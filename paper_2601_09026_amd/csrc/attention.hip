@@ -328,6 +328,10 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_simple_kernel(const AttnArgs
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
+bool attn_mfma_supported(const AttnArgs& a);
+hipError_t attn_fwd_mfma(const AttnArgs& a, hipStream_t st);
+hipError_t attn_bwd_mfma(const AttnArgs& a, hipStream_t st);
+
 static int g_attn_force_simple = 0;
 void attn_force_simple(int on) { g_attn_force_simple = on; }
 
@@ -375,6 +379,7 @@ hipError_t launch_attn_fwd(const AttnArgs& a, bool is_bf16, hipStream_t st) {
   const double heads = (double)a.n_groups * a.B * a.H, esz = is_bf16 ? 2 : 4;
   const double pairs = a.causal ? 0.5 * a.Sq * (a.Sk + 1.0) : (double)a.Sq * a.Sk;   // unmasked scores
   ProfScope ps(PC_ATTN_FWD, heads * pairs * a.dh * 4.0, heads * (2.0 * a.Sq + 2.0 * a.Sk) * a.dh * esz, st);
+  if (is_bf16 && !g_attn_force_simple && attn_mfma_supported(a)) return attn_fwd_mfma(a, st);
   return is_bf16 ? attn_fwd_simple<bf16>(a, st) : attn_fwd_simple<float>(a, st);
 }
 
@@ -385,6 +390,7 @@ hipError_t launch_attn_bwd(const AttnArgs& a, bool is_bf16, hipStream_t st) {
   const double pairs = a.causal ? 0.5 * a.Sq * (a.Sk + 1.0) : (double)a.Sq * a.Sk;
   // recompute scores + dP, dV, dQ, dK: five contractions over the unmasked pairs
   ProfScope ps(PC_ATTN_BWD, heads * pairs * a.dh * 10.0, heads * (4.0 * a.Sq + 4.0 * a.Sk) * a.dh * esz, st);
+  if (is_bf16 && !g_attn_force_simple && attn_mfma_supported(a)) return attn_bwd_mfma(a, st);
   return is_bf16 ? attn_bwd_simple<bf16>(a, st) : attn_bwd_simple<float>(a, st);
 }
 

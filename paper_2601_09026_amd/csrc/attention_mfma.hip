@@ -1,0 +1,384 @@
+// Fused softmax attention on the 32x32x16 bf16 MFMA (d_head = 64), forward and backward.
+//
+// Every product is arranged as  D[i][j] = sum_k A[i][k] B[k][j]  with the wavefront's own 32
+// rows (queries in the forward and dQ kernels, keys in the dK/dV kernel) on the j axis.  In
+// the MFMA result layout lane l then owns column j = l%32 and its 16 registers hold rows
+// i = 8q + 4*(l/32) + r  (q, r = 0..3).  Consequences:
+//   * the softmax statistics of a query are private to a lane (plus one exchange between
+//     lanes l and l+32): no cross-lane reductions over the score tile;
+//   * a score / probability tile, converted to bf16, already IS the B operand of the next
+//     product (registers 8t..8t+7 feed k-step t), provided the A operand enumerates the
+//     reduction index the same way: k-slot (half, e) <-> row 16t + 8*(e/4) + 4*half + e%4.
+//     A operands of that kind are read from a transposed LDS tile as two 8-byte pieces;
+//   * per-row scalars (running max, denominator, lse, D) scale whole accumulators in place.
+// A operands come from LDS (row-major tile, or the transposed copy made while staging), B
+// operands stay in registers for the whole kernel.
+//
+// Forward :  S^T = K Q^T,  P^T = exp2(c S^T - m),  O^T += V^T P^T           (online softmax)
+// dQ pass :  S^T, dP^T = V dO^T,  dA^T = P^T (dP^T - D),  dQ^T += K^T dA^T
+// dKV pass:  S = Q K^T, dP = dO V^T, P, dA;  dV^T += dO^T P,  dK^T += Q^T dA
+// No atomics: dQ and dK/dV are separate passes, so results are bit-reproducible.
+#include "common.h"
+#include "kernels.h"
+
+namespace mg {
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+constexpr int FA_LD = 72;                 // padded LDS row of a 64-wide bf16 tile (144 bytes)
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+// 64 rows x 64 cols of bf16 from global (rows clamped to nrows-1) into a row-major LDS tile
+// and/or its transpose.  Work item = (row pair, 8-column chunk); row pairs vary fastest so
+// that the 4-byte transposed stores of a wavefront fall into distinct banks.
+template <int NT, bool PLAIN, bool TRANS>
+__device__ __forceinline__ void stage64(bf16* plain, bf16* trans, const bf16* src, long rs, int row0, int nrows) {
+#pragma unroll
+  for (int item = threadIdx.x; item < 256; item += NT) {
+    const int rp = item & 31, cc = item >> 5;
+    int r0 = row0 + 2 * rp, r1 = r0 + 1;
+    r0 = r0 < nrows ? r0 : nrows - 1;
+    r1 = r1 < nrows ? r1 : nrows - 1;
+    const bf16x8 v0 = *reinterpret_cast<const bf16x8*>(src + (long)r0 * rs + 8 * cc);
+    const bf16x8 v1 = *reinterpret_cast<const bf16x8*>(src + (long)r1 * rs + 8 * cc);
+    if (PLAIN) {
+      *reinterpret_cast<bf16x8*>(plain + (2 * rp) * FA_LD + 8 * cc) = v0;
+      *reinterpret_cast<bf16x8*>(plain + (2 * rp + 1) * FA_LD + 8 * cc) = v1;
+    }
+    if (TRANS) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        bf16x2 pr = {v0[i], v1[i]};
+        *reinterpret_cast<bf16x2*>(trans + (8 * cc + i) * FA_LD + 2 * rp) = pr;
+      }
+    }
+  }
+}
+
+// A operand from a row-major tile: row `row`, reduction chunk of k-step ks
+__device__ __forceinline__ bf16x8 frag_plain(const bf16* tile, int row, int ks, int lh) {
+  return *reinterpret_cast<const bf16x8*>(tile + row * FA_LD + 16 * ks + 8 * lh);
+}
+// A operand from a transposed tile: row `row` (a feature), reduction over the tile's 64
+// staged rows, k-step t of 32-row tile rt, in the register-order enumeration
+__device__ __forceinline__ bf16x8 frag_trans(const bf16* tile, int row, int rt, int t, int lh) {
+  const bf16* p = tile + row * FA_LD + 32 * rt + 16 * t + 4 * lh;
+  const bf16x4 lo = *reinterpret_cast<const bf16x4*>(p);
+  const bf16x4 hi = *reinterpret_cast<const bf16x4*>(p + 8);
+  bf16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return r;
+}
+// registers 8t..8t+7 of a result tile as the bf16 B operand of k-step t
+__device__ __forceinline__ bf16x8 regs_to_b(const f32x16& v, int t) {
+  bf16x8 r = {(bf16)v[8 * t], (bf16)v[8 * t + 1], (bf16)v[8 * t + 2], (bf16)v[8 * t + 3],
+              (bf16)v[8 * t + 4], (bf16)v[8 * t + 5], (bf16)v[8 * t + 6], (bf16)v[8 * t + 7]};
+  return r;
+}
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) z[i] = 0.f;
+  return z;
+}
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+
+struct HeadPtrs {
+  const bf16 *Q, *K, *V, *O, *dO;
+  bf16 *Ow, *dQ, *dK, *dV;
+  float *lse, *D;
+};
+
+__device__ __forceinline__ HeadPtrs head_ptrs(const AttnArgs& a, int g, int b, int h) {
+  HeadPtrs p;
+  const int dh = 64;
+  p.Q = reinterpret_cast<const bf16*>(a.q) + a.q_slots.of(g) * a.q_slot_stride + (long)b * a.Sq * a.q_row_stride + h * dh;
+  p.K = reinterpret_cast<const bf16*>(a.k) + a.k_slots.of(g) * a.k_slot_stride + (long)b * a.Sk * a.k_row_stride + h * dh;
+  p.V = reinterpret_cast<const bf16*>(a.v) + a.k_slots.of(g) * a.v_slot_stride + (long)b * a.Sk * a.v_row_stride + h * dh;
+  p.O = reinterpret_cast<const bf16*>(a.o) + a.o_slots.of(g) * a.o_slot_stride + (long)b * a.Sq * a.o_row_stride + h * dh;
+  p.Ow = const_cast<bf16*>(p.O);
+  p.lse = a.lse ? a.lse + a.lse_slots.of(g) * a.lse_slot_stride + ((long)b * a.H + h) * a.Sq : nullptr;
+  p.dO = nullptr; p.dQ = p.dK = p.dV = nullptr; p.D = nullptr;
+  if (a.dO) {
+    p.dO = reinterpret_cast<const bf16*>(a.dO) + a.do_slots.of(g) * a.do_slot_stride + (long)b * a.Sq * a.do_row_stride + h * dh;
+    const long base = a.dqkv_slots.of(g) * a.dqkv_slot_stride;
+    p.dQ = reinterpret_cast<bf16*>(a.dq) + base + (long)b * a.Sq * a.dqkv_row_stride + h * dh;
+    p.dK = reinterpret_cast<bf16*>(a.dk) + base + (long)b * a.Sk * a.dqkv_row_stride + h * dh;
+    p.dV = reinterpret_cast<bf16*>(a.dv) + base + (long)b * a.Sk * a.dqkv_row_stride + h * dh;
+    p.D = a.D + a.D_slots.of(g) * a.D_slot_stride + ((long)b * a.H + h) * a.Sq;
+  }
+  return p;
+}
+
+// store a [64 features][32 rows] accumulator pair (transposed result) as rows of 64 bf16
+__device__ __forceinline__ void store_rows_T(bf16* dst, long row_stride, int row, const f32x16* acc, float mul,
+                                             int lh) {
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      f32x4 v = {acc[dt][4 * q] * mul, acc[dt][4 * q + 1] * mul, acc[dt][4 * q + 2] * mul, acc[dt][4 * q + 3] * mul};
+      store4<bf16>(dst + (long)row * row_stride + 32 * dt + 8 * q + 4 * lh, v);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// forward
+// ---------------------------------------------------------------------------
+template <int NW>
+__global__ void __launch_bounds__(NW * 64) attn_fwd_mfma_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * FA_LD];     // [key][d]
+  __shared__ __attribute__((aligned(16))) bf16 Vt[64 * FA_LD];     // [d][key]
+  const int g = blockIdx.z;
+  const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
+  const int q0 = blockIdx.x * (NW * 32);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 31, lh = lane >> 5;
+  const HeadPtrs P = head_ptrs(a, g, b, h);
+  const int qi = q0 + wave * 32 + lr;
+  const int qc = qi < a.Sq ? qi : a.Sq - 1;
+  bf16x8 qf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    qf[ks] = *reinterpret_cast<const bf16x8*>(P.Q + (long)qc * a.q_row_stride + 16 * ks + 8 * lh);
+
+  const float c = rsqrtf(64.f) * LOG2E;
+  float m = -INFINITY, l = 0.f;
+  f32x16 o[2] = {zero16(), zero16()};
+  const int q_blk_last = min(q0 + NW * 32, a.Sq) - 1;
+  const int k_end = a.causal ? min(a.Sk, q_blk_last + 1) : a.Sk;
+  const int q_wave_last = q0 + wave * 32 + 31;
+  for (int k0 = 0; k0 < k_end; k0 += 64) {
+    __syncthreads();
+    stage64<NW * 64, true, false>(Ks, nullptr, P.K, a.k_row_stride, k0, a.Sk);
+    stage64<NW * 64, false, true>(nullptr, Vt, P.V, a.v_row_stride, k0, a.Sk);
+    __syncthreads();
+    if (a.causal && k0 > q_wave_last) continue;          // wave-uniform; barriers are above
+    f32x16 s[2] = {zero16(), zero16()};
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) s[kt] = MFMA(frag_plain(Ks, 32 * kt + lr, ks, lh), qf[ks], s[kt]);
+    float mloc = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = k0 + 32 * kt + 8 * (i >> 2) + 4 * lh + (i & 3);
+        const bool valid = key < a.Sk && (!a.causal || key <= qi);
+        const float v = valid ? s[kt][i] * c : -INFINITY;
+        s[kt][i] = v;
+        mloc = fmaxf(mloc, v);
+      }
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    const float mn = fmaxf(m, mloc);
+    const float ms = mn == -INFINITY ? 0.f : mn;         // fully masked so far: keep exp2 finite
+    const float corr = exp2f(m - ms);
+    float lsum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float p = exp2f(s[kt][i] - ms);
+        s[kt][i] = p;
+        lsum += p;
+      }
+    lsum += __shfl_xor(lsum, 32, 64);
+    l = l * corr + lsum;
+    m = mn;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[dt][i] *= corr;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 pb = regs_to_b(s[kt], t);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) o[dt] = MFMA(frag_trans(Vt, 32 * dt + lr, kt, t, lh), pb, o[dt]);
+      }
+  }
+  if (qi < a.Sq) {
+    store_rows_T(P.Ow, a.o_row_stride, qi, o, 1.0f / l, lh);
+    if (P.lse && lh == 0) P.lse[qi] = (m + log2f(l)) * LN2;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// backward pass 1: D and dQ, one wavefront per 32 query rows
+// ---------------------------------------------------------------------------
+template <int NW>
+__global__ void __launch_bounds__(NW * 64) attn_bwd_dq_mfma_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * FA_LD];     // [key][d]
+  __shared__ __attribute__((aligned(16))) bf16 Vs[64 * FA_LD];     // [key][d]
+  __shared__ __attribute__((aligned(16))) bf16 Kt[64 * FA_LD];     // [d][key]
+  const int g = blockIdx.z;
+  const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
+  const int q0 = blockIdx.x * (NW * 32);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 31, lh = lane >> 5;
+  const HeadPtrs P = head_ptrs(a, g, b, h);
+  const int qi = q0 + wave * 32 + lr;
+  const int qc = qi < a.Sq ? qi : a.Sq - 1;
+  bf16x8 qf[4], dof[4];
+  float Dq = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    qf[ks] = *reinterpret_cast<const bf16x8*>(P.Q + (long)qc * a.q_row_stride + 16 * ks + 8 * lh);
+    dof[ks] = *reinterpret_cast<const bf16x8*>(P.dO + (long)qc * a.do_row_stride + 16 * ks + 8 * lh);
+    const bf16x8 of = *reinterpret_cast<const bf16x8*>(P.O + (long)qc * a.o_row_stride + 16 * ks + 8 * lh);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) Dq = fmaf((float)dof[ks][e], (float)of[e], Dq);
+  }
+  Dq += __shfl_xor(Dq, 32, 64);
+  const float lse2 = P.lse[qc] * LOG2E;
+  if (qi < a.Sq && lh == 0) P.D[qi] = Dq;
+
+  const float c = rsqrtf(64.f) * LOG2E;
+  f32x16 dq[2] = {zero16(), zero16()};
+  const int q_blk_last = min(q0 + NW * 32, a.Sq) - 1;
+  const int k_end = a.causal ? min(a.Sk, q_blk_last + 1) : a.Sk;
+  const int q_wave_last = q0 + wave * 32 + 31;
+  for (int k0 = 0; k0 < k_end; k0 += 64) {
+    __syncthreads();
+    stage64<NW * 64, true, true>(Ks, Kt, P.K, a.k_row_stride, k0, a.Sk);
+    stage64<NW * 64, true, false>(Vs, nullptr, P.V, a.v_row_stride, k0, a.Sk);
+    __syncthreads();
+    if (a.causal && k0 > q_wave_last) continue;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        s = MFMA(frag_plain(Ks, 32 * kt + lr, ks, lh), qf[ks], s);
+        dp = MFMA(frag_plain(Vs, 32 * kt + lr, ks, lh), dof[ks], dp);
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = k0 + 32 * kt + 8 * (i >> 2) + 4 * lh + (i & 3);
+        const bool valid = key < a.Sk && (!a.causal || key <= qi);
+        const float p = valid ? exp2f(s[i] * c - lse2) : 0.f;
+        s[i] = p * (dp[i] - Dq);                            // dA^T
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 ab = regs_to_b(s, t);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) dq[dt] = MFMA(frag_trans(Kt, 32 * dt + lr, kt, t, lh), ab, dq[dt]);
+      }
+    }
+  }
+  if (qi < a.Sq) store_rows_T(P.dQ, a.dqkv_row_stride, qi, dq, rsqrtf(64.f), lh);
+}
+
+// ---------------------------------------------------------------------------
+// backward pass 2: dK and dV, one wavefront per 32 key rows
+// ---------------------------------------------------------------------------
+template <int NW>
+__global__ void __launch_bounds__(NW * 64) attn_bwd_dkv_mfma_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16 Qs[64 * FA_LD];     // [query][d]
+  __shared__ __attribute__((aligned(16))) bf16 dOs[64 * FA_LD];    // [query][d]
+  __shared__ __attribute__((aligned(16))) bf16 Qt[64 * FA_LD];     // [d][query]
+  __shared__ __attribute__((aligned(16))) bf16 dOt[64 * FA_LD];    // [d][query]
+  __shared__ float Ls[64], Ds[64];
+  const int g = blockIdx.z;
+  const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
+  const int j0 = blockIdx.x * (NW * 32);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 31, lh = lane >> 5;
+  const HeadPtrs P = head_ptrs(a, g, b, h);
+  const int kj = j0 + wave * 32 + lr;
+  const int kc = kj < a.Sk ? kj : a.Sk - 1;
+  bf16x8 kf[4], vf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    kf[ks] = *reinterpret_cast<const bf16x8*>(P.K + (long)kc * a.k_row_stride + 16 * ks + 8 * lh);
+    vf[ks] = *reinterpret_cast<const bf16x8*>(P.V + (long)kc * a.v_row_stride + 16 * ks + 8 * lh);
+  }
+  const float c = rsqrtf(64.f) * LOG2E;
+  f32x16 dk[2] = {zero16(), zero16()}, dv[2] = {zero16(), zero16()};
+  // causal: key j only receives from queries i >= j
+  const int i_begin = a.causal ? (j0 / 64) * 64 : 0;
+  const int k_wave_first = j0 + wave * 32;
+  for (int i0 = i_begin; i0 < a.Sq; i0 += 64) {
+    __syncthreads();
+    stage64<NW * 64, true, true>(Qs, Qt, P.Q, a.q_row_stride, i0, a.Sq);
+    stage64<NW * 64, true, true>(dOs, dOt, P.dO, a.do_row_stride, i0, a.Sq);
+    if (threadIdx.x < 64) {
+      const int qq = i0 + threadIdx.x;
+      const int qcl = qq < a.Sq ? qq : a.Sq - 1;
+      Ls[threadIdx.x] = P.lse[qcl] * LOG2E;
+      Ds[threadIdx.x] = P.D[qcl];
+    }
+    __syncthreads();
+    if (a.causal && i0 + 63 < k_wave_first) continue;      // every query of the tile precedes this wave's keys
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        s = MFMA(frag_plain(Qs, 32 * qt + lr, ks, lh), kf[ks], s);
+        dp = MFMA(frag_plain(dOs, 32 * qt + lr, ks, lh), vf[ks], dp);
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int ql = 32 * qt + 8 * (i >> 2) + 4 * lh + (i & 3);
+        const int qq = i0 + ql;
+        const bool valid = qq < a.Sq && kj < a.Sk && (!a.causal || kj <= qq);
+        const float p = valid ? exp2f(s[i] * c - Ls[ql]) : 0.f;
+        s[i] = p;
+        dp[i] = p * (dp[i] - Ds[ql]);
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 pb = regs_to_b(s, t), ab = regs_to_b(dp, t);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+          dv[dt] = MFMA(frag_trans(dOt, 32 * dt + lr, qt, t, lh), pb, dv[dt]);
+          dk[dt] = MFMA(frag_trans(Qt, 32 * dt + lr, qt, t, lh), ab, dk[dt]);
+        }
+      }
+    }
+  }
+  if (kj < a.Sk) {
+    store_rows_T(P.dK, a.dqkv_row_stride, kj, dk, rsqrtf(64.f), lh);
+    store_rows_T(P.dV, a.dqkv_row_stride, kj, dv, 1.0f, lh);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+bool attn_mfma_supported(const AttnArgs& a) {
+  return a.dh == 64 && (a.q_row_stride % 8 == 0) && (a.k_row_stride % 8 == 0) && (a.v_row_stride % 8 == 0) &&
+         (a.o_row_stride % 8 == 0);
+}
+
+hipError_t attn_fwd_mfma(const AttnArgs& a, hipStream_t st) {
+  if (a.Sq <= 64) {
+    dim3 grid((a.Sq + 63) / 64, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL(attn_fwd_mfma_kernel<2>, grid, dim3(128), 0, st, a);
+  } else {
+    dim3 grid((a.Sq + 127) / 128, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL(attn_fwd_mfma_kernel<4>, grid, dim3(256), 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t attn_bwd_mfma(const AttnArgs& a, hipStream_t st) {
+  if (a.Sq <= 64) {
+    dim3 grid((a.Sq + 63) / 64, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel<2>, grid, dim3(128), 0, st, a);
+  } else {
+    dim3 grid((a.Sq + 127) / 128, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel<4>, grid, dim3(256), 0, st, a);
+  }
+  if (a.Sk <= 64) {
+    dim3 grid((a.Sk + 63) / 64, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel<2>, grid, dim3(128), 0, st, a);
+  } else {
+    dim3 grid((a.Sk + 127) / 128, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel<4>, grid, dim3(256), 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace mg

@@ -74,6 +74,33 @@ __device__ __forceinline__ float gelu_prime_f(float z) {
   return cdf + z * pdf;
 }
 
+// Fast erf for the bf16 path: rational-exponential approximation (Abramowitz & Stegun 7.1.26),
+// absolute error below 1.5e-7, about a dozen instructions instead of the library routine.
+__device__ __forceinline__ float erf_fast(float x) {
+  const float ax = fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float r = 1.0f - p * t * __expf(-ax * ax);
+  return copysignf(r, x);
+}
+__device__ __forceinline__ float gelu_fast(float z) {
+  return 0.5f * z * (1.0f + erf_fast(z * 0.70710678118654752440f));
+}
+__device__ __forceinline__ float gelu_prime_fast(float z) {
+  const float cdf = 0.5f * (1.0f + erf_fast(z * 0.70710678118654752440f));
+  const float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+  return cdf + z * pdf;
+}
+template <typename T> __device__ __forceinline__ float gelu_t(float z);
+template <> __device__ __forceinline__ float gelu_t<float>(float z) { return gelu_f(z); }
+template <> __device__ __forceinline__ float gelu_t<bf16>(float z) { return gelu_fast(z); }
+template <typename T> __device__ __forceinline__ float gelu_prime_t(float z);
+template <> __device__ __forceinline__ float gelu_prime_t<float>(float z) { return gelu_prime_f(z); }
+template <> __device__ __forceinline__ float gelu_prime_t<bf16>(float z) { return gelu_prime_fast(z); }
+
 // load / store 4 consecutive elements as floats
 template <typename T> __device__ __forceinline__ f32x4 load4(const T* p);
 template <> __device__ __forceinline__ f32x4 load4<float>(const float* p) {

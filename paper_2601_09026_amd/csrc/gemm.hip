@@ -4,11 +4,8 @@
 // parameter pointer table.
 //
 // Two kernels:
-//  * gemm_mfma  : bf16 operands, fp32 accumulate on the 32x32x16 MFMA of gfx950.
-//                 Block tile BM x BN x 64 staged through double-buffered, padded LDS;
-//                 (BM/WM) x (BN/WN) per 64-lane wavefront.  The weight fragment is
-//                 fed as the first MFMA operand so that each lane ends up with 4
-//                 consecutive output columns per register quad (vector stores).
+//  * gemm_mfma  : bf16 operands, fp32 accumulate on the 32x32x16 MFMA of gfx950; operands
+//                 stream global -> LDS directly through a ring of k-tiles, see below.
 //  * gemm_simple: any operand type (fp32 path and odd shapes), LDS-tiled FMA.
 #include "common.h"
 #include "kernels.h"
@@ -17,71 +14,196 @@
 namespace mg {
 
 // ---------------------------------------------------------------------------
-// epilogue on 4 consecutive columns n..n+3 of row m of group g
+// Epilogue.  EpiPtrs holds the launch's epilogue operands resolved for one group; apply4
+// finishes 4 consecutive columns n..n+3 of row m (idx = m*N + n) from the accumulated
+// products `acc` (bias not yet added).
 // ---------------------------------------------------------------------------
+struct EpiPtrs {
+  const float* bias;          // [N] or null
+  void* out;                  // packed output (operand type or fp32)
+  void* aux;                  // EPI_GELU: z out (optional); EPI_DGELU: z in; EPI_RESID_OUTER: ybar
+  const float* base;          // EPI_RESID_INNER: optional addend
+  const float* X;             // EPI_RESID_OUTER
+  const float* RHS;           // EPI_RESID_OUTER, optional
+  float* OUT;                 // EPI_RESID_OUTER
+};
+
+template <typename TO>
+__device__ __forceinline__ EpiPtrs resolve_epi(const GemmArgs& a, int g, int epi) {
+  EpiPtrs p;
+  p.bias = a.bias_off >= 0 ? reinterpret_cast<const float*>(a.bias.at(g) + a.bias_off) : nullptr;
+  const bool f32_out = epi == EPI_STORE_F32 || epi == EPI_RESID_INNER;
+  const long osz = f32_out ? 4 : (long)sizeof(TO);
+  p.out = a.out ? static_cast<char*>(a.out) + a.out_slots.of(g) * a.out_slot_stride * osz : nullptr;
+  const long asz = epi == EPI_RESID_OUTER ? 4 : (long)sizeof(TO);
+  p.aux = a.aux ? static_cast<char*>(a.aux) + a.aux_slots.of(g) * a.aux_slot_stride * asz : nullptr;
+  p.base = a.base ? a.base + a.base_slots.of(g) * a.base_slot_stride : nullptr;
+  p.X = a.X.present() ? a.X.at(g) : nullptr;
+  p.RHS = a.RHS.present() ? a.RHS.at(g) : nullptr;
+  p.OUT = a.OUT.present() ? a.OUT.at(g) : nullptr;
+  return p;
+}
+
 template <int EPI, typename TO>
-__device__ __forceinline__ void epilogue4(const GemmArgs& a, int g, const char* pblock, int m, int n,
-                                          f32x4 acc) {
-  if (a.bias_off >= 0) {
-    const float* bias = reinterpret_cast<const float*>(a.bias.at(g) + a.bias_off);
-    acc += *reinterpret_cast<const f32x4*>(bias + n);
-  }
-  (void)pblock;
-  const long idx = (long)m * a.N + n;
+__device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restrict__ out_f32,
+                                       TO* __restrict__ z_out, const TO* __restrict__ z_in,
+                                       const float* __restrict__ base, const float* __restrict__ X,
+                                       const float* __restrict__ ybar, const float* __restrict__ RHS,
+                                       float* __restrict__ OUT, float hstep, long idx, f32x4 acc) {
   if constexpr (EPI == EPI_STORE) {
-    TO* out = reinterpret_cast<TO*>(a.out) + a.out_slots.of(g) * a.out_slot_stride;
-    store4<TO>(out + idx, acc);
+    store4<TO>(out_op + idx, acc);
   } else if constexpr (EPI == EPI_STORE_F32) {
-    float* out = reinterpret_cast<float*>(a.out) + a.out_slots.of(g) * a.out_slot_stride;
-    store4<float>(out + idx, acc);
+    store4<float>(out_f32 + idx, acc);
   } else if constexpr (EPI == EPI_GELU) {
-    TO* out = reinterpret_cast<TO*>(a.out) + a.out_slots.of(g) * a.out_slot_stride;
-    if (a.aux) {
-      TO* z = reinterpret_cast<TO*>(a.aux) + a.aux_slots.of(g) * a.aux_slot_stride;
-      store4<TO>(z + idx, acc);
-    }
-    f32x4 y = {gelu_f(acc[0]), gelu_f(acc[1]), gelu_f(acc[2]), gelu_f(acc[3])};
-    store4<TO>(out + idx, y);
+    if (z_out) store4<TO>(z_out + idx, acc);
+    f32x4 y = {gelu_t<TO>(acc[0]), gelu_t<TO>(acc[1]), gelu_t<TO>(acc[2]), gelu_t<TO>(acc[3])};
+    store4<TO>(out_op + idx, y);
   } else if constexpr (EPI == EPI_DGELU) {
-    TO* out = reinterpret_cast<TO*>(a.out) + a.out_slots.of(g) * a.out_slot_stride;
-    const TO* z = reinterpret_cast<const TO*>(a.aux) + a.aux_slots.of(g) * a.aux_slot_stride;
-    f32x4 zz = load4<TO>(z + idx);
-    f32x4 y = {acc[0] * gelu_prime_f(zz[0]), acc[1] * gelu_prime_f(zz[1]),
-               acc[2] * gelu_prime_f(zz[2]), acc[3] * gelu_prime_f(zz[3])};
-    store4<TO>(out + idx, y);
+    f32x4 zz = load4<TO>(z_in + idx);
+    f32x4 y = {acc[0] * gelu_prime_t<TO>(zz[0]), acc[1] * gelu_prime_t<TO>(zz[1]),
+               acc[2] * gelu_prime_t<TO>(zz[2]), acc[3] * gelu_prime_t<TO>(zz[3])};
+    store4<TO>(out_op + idx, y);
   } else if constexpr (EPI == EPI_RESID_INNER) {
-    float* out = reinterpret_cast<float*>(a.out) + a.out_slots.of(g) * a.out_slot_stride;
-    if (a.base) acc += *reinterpret_cast<const f32x4*>(a.base + a.base_slots.of(g) * a.base_slot_stride + idx);
-    store4<float>(out + idx, acc);
+    if (base) acc += *reinterpret_cast<const f32x4*>(base + idx);
+    store4<float>(out_f32 + idx, acc);
   } else if constexpr (EPI == EPI_RESID_OUTER) {
-    const float* ybar = reinterpret_cast<const float*>(a.aux) + a.aux_slots.of(g) * a.aux_slot_stride;
-    f32x4 x = *reinterpret_cast<const f32x4*>(a.X.at(g) + idx);
+    f32x4 x = *reinterpret_cast<const f32x4*>(X + idx);
     f32x4 yb = *reinterpret_cast<const f32x4*>(ybar + idx);
-    f32x4 r = x + a.hstep * (yb + acc);
-    if (a.RHS.present()) r += *reinterpret_cast<const f32x4*>(a.RHS.at(g) + idx);
-    store4<float>(a.OUT.at(g) + idx, r);
+    f32x4 r = x + hstep * (yb + acc);
+    if (RHS) r += *reinterpret_cast<const f32x4*>(RHS + idx);
+    store4<float>(OUT + idx, r);
+  }
+}
+
+// one-off form for the generic kernel
+template <int EPI, typename TO>
+__device__ __forceinline__ void epilogue4(const EpiPtrs& p, float hstep, int N, int m, int n, f32x4 acc) {
+  if (p.bias) acc += *reinterpret_cast<const f32x4*>(p.bias + n);
+  apply4<EPI, TO>(static_cast<TO*>(p.out), static_cast<float*>(p.out), static_cast<TO*>(p.aux),
+                  static_cast<const TO*>(p.aux), p.base, p.X, static_cast<const float*>(p.aux), p.RHS, p.OUT,
+                  hstep, (long)m * N + n, acc);
+}
+
+// Whole-tile epilogue of one wavefront of the MFMA kernel.  All operand pointers are
+// restrict-qualified parameters of this one function, so that the compiler may hoist the
+// loads of later rows above the stores of earlier ones (outputs never alias inputs).
+template <int EPI, typename TO, int TM, int TN, bool STAGED>
+__device__ __forceinline__ void tile_epilogue(
+    f32x16 (&acc)[TM][TN], unsigned char* ep, const float* __restrict__ bias, TO* __restrict__ out_op,
+    float* __restrict__ out_f32, TO* __restrict__ z_out, const TO* __restrict__ z_in,
+    const float* __restrict__ base, const float* __restrict__ X, const float* __restrict__ ybar,
+    const float* __restrict__ RHS, float* __restrict__ OUT, float hstep, int N, int M, int mrow0, int ncol0,
+    int lane) {
+  constexpr int WTN = TN * 32;
+  const int lr = lane & 31, lh = lane >> 5;
+  if constexpr (STAGED) {
+    constexpr int EP_LD = WTN * 4 + 16;                  // bytes per staged row (padded)
+    constexpr int C4 = WTN / 4;                          // float4 per row
+    static_assert(64 % C4 == 0, "a lane keeps its column group over all iterations");
+    const int c4 = lane % C4, rsub = lane / C4;
+    const int n = ncol0 + 4 * c4;
+    f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+    if (bias) bv = *reinterpret_cast<const f32x4*>(bias + n);   // one column group per lane for the whole tile
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+          *reinterpret_cast<f32x4*>(ep + lr * EP_LD + (32 * j + 8 * q + 4 * lh) * 4) = v;
+        }
+#pragma unroll
+      for (int it = 0; it < 32 * C4 / 64; ++it) {
+        const int row = it * (64 / C4) + rsub;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + c4 * 16) + bv;
+        const int m = mrow0 + 32 * i + row;
+        if (m < M)
+          apply4<EPI, TO>(out_op, out_f32, z_out, z_in, base, X, ybar, RHS, OUT, hstep, (long)m * N + n, v);
+      }
+    }
+  } else {
+    // acc[i][j] register 4q+r of lane l  =  C[m = 32i + l%32][n = 32j + 8q + 4*(l/32) + r]
+    f32x4 bv[TN][4];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        bv[j][q] = bias ? *reinterpret_cast<const f32x4*>(bias + ncol0 + j * 32 + q * 8 + lh * 4) : z;
+      }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int m = mrow0 + i * 32 + lr;
+      if (m < M) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int n = ncol0 + j * 32 + q * 8 + lh * 4;
+            f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            apply4<EPI, TO>(out_op, out_f32, z_out, z_in, base, X, ybar, RHS, OUT, hstep, (long)m * N + n,
+                            v + bv[j][q]);
+          }
+      }
+    }
   }
 }
 
 // ---------------------------------------------------------------------------
-// MFMA kernel
+// MFMA kernel.  4 wavefronts as 2 x 2, each owning a (BM/2) x (BN/2) tile of the output.
+//  * Operands go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
+//    no register staging) through a ring of STAGES k-tiles of depth BK (32 or 64).
+//  * An LDS row holds the BK bf16 of one matrix row (64 or 128 bytes) unpadded; its 16-byte
+//    chunks are XOR-swizzled by the row number so that the 16-byte fragment reads of 32
+//    consecutive rows are bank-conflict free.  A load instruction of a wavefront fills 1 KB
+//    = 8 (or 16) consecutive rows; the lane that will land at position p of row r fetches
+//    logical chunk p ^ f(r) of that row.
+//  * MFMA fragments are double-buffered in registers (LDS reads of k-step s+1 overlap the
+//    MFMAs of s) and the next tile's load instructions are issued one at a time between
+//    MFMA groups, so their issue time overlaps matrix work.
+//  * The weight fragment is the first MFMA operand: a lane then holds 4 consecutive output
+//    columns per register quad.
+//  * Epilogue, STAGED: each wavefront transposes 32 rows at a time through a private padded
+//    LDS region and walks them row-major (32 lanes per row), so every global access of the
+//    epilogue covers whole contiguous rows.  Otherwise: straight from the MFMA layout.
 // ---------------------------------------------------------------------------
-constexpr int GEMM_BK = 64;
-constexpr int GEMM_LDK = GEMM_BK + 8;   // padded LDS row (144 B): conflict-free 16-byte fragment reads
+typedef __attribute__((address_space(1))) const void* gas_ptr;
+typedef __attribute__((address_space(3))) void* las_ptr;
 
-template <int BM, int BN, int WM, int WN, int EPI, typename TO>
-__global__ void __launch_bounds__(WM * WN * 64)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  else if constexpr (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+  else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  else if constexpr (N == 18) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
+  else if constexpr (N == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+  else if constexpr (N == 32) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+template <int BK> __device__ __forceinline__ int swz(int row) {
+  return BK == 64 ? (row & 7) : ((row >> 1) & 3);
+}
+
+template <int BM, int BN, int BK, int STAGES, int OCC, bool STAGED, int EPI, typename TO, int DBG = 0>
+__global__ void __launch_bounds__(256, OCC)
 gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd) {
-  constexpr int NT = WM * WN * 64;
-  constexpr int WTM = BM / WM, WTN = BN / WN;      // wave tile
-  constexpr int TM = WTM / 32, TN = WTN / 32;      // 32x32 MFMA tiles per wave
-  constexpr int A_CH = BM * (GEMM_BK / 8) / NT;    // 16-byte chunks per thread
-  constexpr int B_CH = BN * (GEMM_BK / 8) / NT;
-  static_assert(BM * (GEMM_BK / 8) % NT == 0 && BN * (GEMM_BK / 8) % NT == 0, "tile/threads");
-
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16* As = reinterpret_cast<bf16*>(smem_raw);                   // [2][BM][LDK]
-  bf16* Bs = As + 2 * BM * GEMM_LDK;                              // [2][BN][LDK]
+  constexpr int WTM = BM / 2, WTN = BN / 2;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int RB = BK * 2;                             // bytes per LDS row
+  constexpr int CPR = RB / 16;                           // 16-byte chunks per row
+  constexpr int RPL = 1024 / RB;                         // rows per load instruction
+  constexpr int KS = BK / 16;                            // MFMA k-steps per tile
+  constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB, STAGE = A_BYTES + B_BYTES;
+  constexpr int A_LD = BM / RPL / 4, B_LD = BN / RPL / 4;   // load instructions per wave per k-tile
+  constexpr int PER_TILE = A_LD + B_LD;
+  constexpr int SLOTS = KS * TM;                         // MFMA groups per k-tile
+  constexpr int PER_SLOT = (PER_TILE + SLOTS - 1) / SLOTS;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem2[];
 
   // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, so give each
   // XCD one contiguous range of tiles (neighbouring tiles share an activation row panel and
@@ -102,39 +224,41 @@ gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, in
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
-  const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int wm0 = (wave >> 1) * WTM, wn0 = (wave & 1) * WTN;
 
-  bf16x8 ra[A_CH], rb[B_CH];
-  auto gload = [&](int k0) {
+  // global -> LDS: this lane's element offsets (row clamped at the ragged tail of M)
+  const int lrow = lane / CPR, lchunk = (lane % CPR) ^ swz<BK>(lrow);
+  unsigned aoff[A_LD], boff[B_LD];
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      const int c = tid + i * NT;
-      const int row = c >> 3, kc = c & 7;
-      int gm = m0 + row;
-      gm = gm < M ? gm : M - 1;                     // ragged tail: clamp (never stored)
-      ra[i] = *reinterpret_cast<const bf16x8*>(A + (long)gm * K + k0 + kc * 8);
-    }
+  for (int j = 0; j < A_LD; ++j) {
+    int gm = m0 + (wave * A_LD + j) * RPL + lrow;
+    gm = gm < M ? gm : M - 1;
+    aoff[j] = (unsigned)gm * (unsigned)K + lchunk * 8;
+  }
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-      const int c = tid + i * NT;
-      const int row = c >> 3, kc = c & 7;
-      rb[i] = *reinterpret_cast<const bf16x8*>(B + (long)(n0 + row) * K + k0 + kc * 8);
-    }
+  for (int j = 0; j < B_LD; ++j)
+    boff[j] = (unsigned)(n0 + (wave * B_LD + j) * RPL + lrow) * (unsigned)K + lchunk * 8;
+
+  auto issue_one = [&](int stage, int k0, int idx) {
+    if (DBG == 2 || DBG == 3) return;
+    unsigned char* sa = smem2 + stage * STAGE;
+    if (idx < A_LD)
+      __builtin_amdgcn_global_load_lds((gas_ptr)(A + aoff[idx] + k0), (las_ptr)(sa + (wave * A_LD + idx) * 1024),
+                                       16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds((gas_ptr)(B + boff[idx - A_LD] + k0),
+                                       (las_ptr)(sa + A_BYTES + (wave * B_LD + idx - A_LD) * 1024), 16, 0, 0);
   };
-  auto sstore = [&](int buf) {
-    bf16* as = As + buf * BM * GEMM_LDK;
-    bf16* bs = Bs + buf * BN * GEMM_LDK;
+  auto issue = [&](int stage, int k0) {
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      const int c = tid + i * NT;
-      *reinterpret_cast<bf16x8*>(as + (c >> 3) * GEMM_LDK + (c & 7) * 8) = ra[i];
-    }
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-      const int c = tid + i * NT;
-      *reinterpret_cast<bf16x8*>(bs + (c >> 3) * GEMM_LDK + (c & 7) * 8) = rb[i];
-    }
+    for (int idx = 0; idx < PER_TILE; ++idx) issue_one(stage, k0, idx);
   };
+
+  // fragment byte offsets inside a tile region: row lr, swizzled chunk of k-step ks
+  int foff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) foff[ks] = lr * RB + (((2 * ks + lh) ^ swz<BK>(lr)) << 4);
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -144,51 +268,64 @@ gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, in
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int KT = K / GEMM_BK;
-  gload(0);
-  sstore(0);
+  const int KT = K / BK;
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < KT) issue(s, s * BK);
+  if (KT > STAGES - 2) wait_vmcnt<(STAGES - 2) * PER_TILE>(); else wait_vmcnt<0>();
   __syncthreads();
-  const int lr = lane & 31, lk = lane >> 5;
+
   for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) gload((kt + 1) * GEMM_BK);
-    const bf16* as = As + buf * BM * GEMM_LDK + (wm0 + lr) * GEMM_LDK + lk * 8;
-    const bf16* bs = Bs + buf * BN * GEMM_LDK + (wn0 + lr) * GEMM_LDK + lk * 8;
+    const int cur = kt % STAGES;
+    const bool pf = kt + STAGES - 1 < KT;
+    const int pstage = (kt + STAGES - 1) % STAGES, pk0 = (kt + STAGES - 1) * BK;
+    const unsigned char* sA = smem2 + cur * STAGE + wm0 * RB;
+    const unsigned char* sB = smem2 + cur * STAGE + A_BYTES + wn0 * RB;
+    bf16x8 fa[2][TM], fb[2][TN];
+    if (DBG != 1 && DBG != 3) {
 #pragma unroll
-    for (int ks = 0; ks < GEMM_BK / 16; ++ks) {
-      bf16x8 fa[TM], fb[TN];
+      for (int i = 0; i < TM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * RB + foff[0]);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        fa[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * GEMM_LDK + ks * 16);
+      for (int j = 0; j < TN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * RB + foff[0]);
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        fb[j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * GEMM_LDK + ks * 16);
+      for (int ks = 0; ks < KS; ++ks) {
+        const int cb = ks & 1, nb = cb ^ 1;
+        if (ks + 1 < KS) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+          for (int i = 0; i < TM; ++i)
+            fa[nb][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * RB + foff[ks + 1 < KS ? ks + 1 : 0]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < TN; ++j)
+            fb[nb][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * RB + foff[ks + 1 < KS ? ks + 1 : 0]);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cb][j], fa[cb][i], acc[i][j], 0, 0, 0);
+#pragma unroll
+          for (int u = 0; u < PER_SLOT; ++u) {
+            const int idx = (ks * TM + i) * PER_SLOT + u;
+            if (idx < PER_TILE && pf) issue_one(pstage, pk0, idx);
+          }
+        }
+      }
+    } else if (pf) {
+      issue(pstage, pk0);
     }
-    if (kt + 1 < KT) sstore(buf ^ 1);
+    // tile kt+1 must have landed (later tiles may still be in flight), and every wave must be
+    // done reading this stage before it is refilled
+    if (kt + STAGES - 1 < KT) wait_vmcnt<(STAGES - 2) * PER_TILE>(); else wait_vmcnt<0>();
     __syncthreads();
   }
 
-  // acc[i][j] register 4q+r of lane l  =  C[m = wm0+32i + l%32][n = wn0+32j + 8q + 4*(l/32) + r]
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wm0 + i * 32 + lr;
-    if (m < M) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + wn0 + j * 32 + q * 8 + lk * 4;
-          f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-          epilogue4<EPI, TO>(a, g, pblock, m, n, v);
-        }
-      }
-    }
-  }
+  static_assert(!STAGED || 32 * (WTN * 4 + 16) <= STAGES * STAGE / 4, "epilogue staging does not fit");
+  const EpiPtrs P = resolve_epi<TO>(a, g, EPI);
+  tile_epilogue<EPI, TO, TM, TN, STAGED>(acc, smem2 + wave * (STAGES * STAGE / 4), P.bias, static_cast<TO*>(P.out),
+                                         static_cast<float*>(P.out), static_cast<TO*>(P.aux),
+                                         static_cast<const TO*>(P.aux), P.base, P.X,
+                                         static_cast<const float*>(P.aux), P.RHS, P.OUT, a.hstep, a.N, M,
+                                         m0 + wm0, n0 + wn0, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -231,12 +368,13 @@ gemm_simple_kernel(const GemmArgs a, int tiles_m, int tiles_n) {
   }
   const int n = n0 + tx * 4;
   if (n < N) {
+    const EpiPtrs P = resolve_epi<TO>(a, g, EPI);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int m = m0 + ty * 4 + i;
       if (m < M) {
         f32x4 v = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
-        epilogue4<EPI, TO>(a, g, pblock, m, n, v);
+        epilogue4<EPI, TO>(P, a.hstep, N, m, n, v);
       }
     }
   }
@@ -246,15 +384,19 @@ gemm_simple_kernel(const GemmArgs a, int tiles_m, int tiles_n) {
 // host launchers
 // ---------------------------------------------------------------------------
 static int g_force_simple = 0;
+static int g_tile_cfg = 0;                 // 0 = choose by shape
+static int g_dbg_mode = 0;
 void gemm_force_simple(int on) { g_force_simple = on; }
+void gemm_set_tile_config(int cfg) { g_tile_cfg = cfg; }
+void gemm_set_debug_mode(int m) { g_dbg_mode = m; }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int BK, int STAGES, int OCC, bool STAGED, int EPI>
 static hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = a.N / BN;
   const int total = tiles_m * tiles_n * a.n_groups;
   const int per_xcd = (total + 7) / 8;
-  const size_t smem = (size_t)2 * (BM + BN) * GEMM_LDK * sizeof(bf16);
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, bf16>;
+  const size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -262,8 +404,18 @@ static hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(WM * WN * 64), smem, st, a, tiles_m, tiles_n, total,
-                     per_xcd);
+#ifdef MG_GEMM_DEBUG
+  if (g_dbg_mode >= 1 && g_dbg_mode <= 3) {
+    auto k1 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 1>;
+    auto k2 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 2>;
+    auto k3 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 3>;
+    auto kd = g_dbg_mode == 1 ? k1 : (g_dbg_mode == 2 ? k2 : k3);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kd), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipLaunchKernelGGL(kd, dim3(per_xcd * 8), dim3(256), smem, st, a, tiles_m, tiles_n, total, per_xcd);
+    return hipGetLastError();
+  }
+#endif
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), smem, st, a, tiles_m, tiles_n, total, per_xcd);
   return hipGetLastError();
 }
 
@@ -293,11 +445,29 @@ template <int EPI>
 static hipError_t launch_epi(const GemmArgs& a, bool is_bf16, hipStream_t st) {
   if (a.n_groups <= 0 || a.M <= 0) return hipSuccess;
   const double flops = 2.0 * a.n_groups * a.M * (double)a.N * a.K;
-  const bool mfma_ok = is_bf16 && !g_force_simple && (a.K % GEMM_BK == 0) && (a.N % 128 == 0);
+  // the MFMA kernel needs whole 64-deep k-tiles and 128-wide column tiles, and 32-bit element offsets
+  const bool mfma_ok = is_bf16 && !g_force_simple && (a.K % 64 == 0) && (a.N % 128 == 0) &&
+                       (double)a.M * a.K < 4e9 && (double)a.N * a.K < 4e9;
   ProfScope ps(mfma_ok ? PC_GEMM_MFMA + EPI : PC_GEMM_SIMPLE, flops, gemm_bytes<EPI>(a, is_bf16 ? 2 : 4), st);
   if (!is_bf16) return launch_simple<float, EPI>(a, st);
   if (!mfma_ok) return launch_simple<bf16, EPI>(a, st);
-  return launch_mfma<128, 128, 2, 2, EPI>(a, st);
+  // Tile choice (measured on MI355X at the benchmark shapes, 8 groups of 4096 rows):
+  //  * 128x128x64, two k-tile stages, two blocks per CU (their phases overlap) is the best
+  //    all-rounder;
+  //  * the activation epilogues (GELU and its derivative) are long, and a 256x128 tile with
+  //    32-deep k-tiles and a three-stage ring hides them better.
+  int cfg = g_tile_cfg;
+  if (cfg == 0) cfg = (EPI == EPI_GELU || EPI == EPI_DGELU) ? 2 : 1;
+  switch (cfg) {
+    case 2: return launch_mfma<256, 128, 32, 3, 2, true, EPI>(a, st);
+#ifdef MG_GEMM_DEBUG
+    case 3: if (a.N % 256 == 0) return launch_mfma<256, 256, 64, 2, 1, true, EPI>(a, st); break;
+    case 4: return launch_mfma<128, 128, 64, 2, 2, false, EPI>(a, st);
+    case 5: return launch_mfma<256, 128, 32, 2, 2, true, EPI>(a, st);
+#endif
+    default: break;
+  }
+  return launch_mfma<128, 128, 64, 2, 2, true, EPI>(a, st);
 }
 
 hipError_t launch_gemm(const GemmArgs& a, int epi, bool is_bf16, hipStream_t st) {

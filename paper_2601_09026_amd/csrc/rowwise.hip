@@ -8,11 +8,12 @@
 
 namespace mg {
 
-constexpr int LN_MAXV = 8;          // float4 per lane  =>  d <= 64*4*8 = 2048
+// One 64-lane wavefront walks token rows with a grid stride and keeps the next row's loads
+// in flight while it reduces and writes the current one (few long-lived waves instead of one
+// short-lived wave per row).  NV = float4 per lane (row kept in registers), d <= 256*NV.
+constexpr int LN_MAXV = 8;          // d <= 64*4*8 = 2048
+constexpr int LN_BLOCKS_PER_CU = 8;
 
-// ---------------------------------------------------------------------------
-// LayerNorm forward: fp32 row -> operand-type row
-// ---------------------------------------------------------------------------
 // LN input = state row (optional) + packed fp32 addend (optional); at least one is present
 __device__ __forceinline__ f32x4 load_sum(const float* x, const float* xa, int c) {
   f32x4 v = {0.f, 0.f, 0.f, 0.f};
@@ -21,63 +22,97 @@ __device__ __forceinline__ f32x4 load_sum(const float* x, const float* xa, int c
   return v;
 }
 
-template <typename TO>
-__global__ void __launch_bounds__(256) ln_fwd_kernel(const LnFwdArgs a) {
-  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  const long total = (long)a.n_groups * a.T;
-  if (row >= total) return;
-  const int g = (int)(row / a.T);
-  const int t = (int)(row - (long)g * a.T);
-  const int d = a.d;
-  const float* x = a.X.present() ? a.X.at(g) + (long)t * d : nullptr;
-  const float* xa = a.xp ? a.xp + a.xp_slots.of(g) * a.xp_slot_stride + (long)t * d : nullptr;
-  const char* pb = a.P.at(g);
-  const float* gamma = reinterpret_cast<const float*>(pb + a.gamma_off);
-  const float* beta = reinterpret_cast<const float*>(pb + a.beta_off);
-  TO* out = reinterpret_cast<TO*>(a.out) + a.out_slots.of(g) * a.out_slot_stride + (long)t * d;
+__device__ __forceinline__ float sum4(f32x4 v) { return (v[0] + v[1]) + (v[2] + v[3]); }
+__device__ __forceinline__ float dot4(f32x4 a, f32x4 b) { return (a[0] * b[0] + a[1] * b[1]) + (a[2] * b[2] + a[3] * b[3]); }
 
-  f32x4 v[LN_MAXV];
-  float s = 0.f;
+template <typename TO, int NV>
+__global__ void __launch_bounds__(256) ln_fwd_kernel(const LnFwdArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int total = a.n_groups * a.T;
+  const int nwaves = gridDim.x * 4;
+  const int d = a.d;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= total) return;
+
+  auto src = [&](int r, const float*& x, const float*& xa, int& g, int& t) {
+    g = r / a.T; t = r - g * a.T;
+    x = a.X.present() ? a.X.at(g) + (long)t * d : nullptr;
+    xa = a.xp ? a.xp + a.xp_slots.of(g) * a.xp_slot_stride + (long)t * d : nullptr;
+  };
+  auto load = [&](int r, f32x4* v) {
+    const float *x, *xa; int g, t;
+    src(r, x, xa, g, t);
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
-    const int c = (i * 64 + lane) * 4;
-    if (c < d) {
-      v[i] = load_sum(x, xa, c);
-      s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+    for (int i = 0; i < NV; ++i) {
+      const int c = (i * 64 + lane) * 4;
+      if (c < d) v[i] = load_sum(x, xa, c);
     }
-  }
-  const float mu = wave_sum(s) / d;
-  float q = 0.f;
+  };
+  constexpr bool PREFETCH = NV <= 4;
+  f32x4 cur[NV], nxt[PREFETCH ? NV : 1];
+  load(row, cur);
+  while (true) {
+    const int next = row + nwaves;
+    if (PREFETCH && next < total) load(next, nxt);
+    const int g = row / a.T, t = row - g * a.T;
+    float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
-    const int c = (i * 64 + lane) * 4;
-    if (c < d) {
-      f32x4 e = v[i] - mu;
-      q += (e[0] * e[0] + e[1] * e[1]) + (e[2] * e[2] + e[3] * e[3]);
-    }
-  }
-  const float rstd = 1.0f / sqrtf(wave_sum(q) / d + a.eps);
+    for (int i = 0; i < NV; ++i)
+      if ((i * 64 + lane) * 4 < d) s += sum4(cur[i]);
+    const float mu = wave_sum(s) / d;
+    float q = 0.f;
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
-    const int c = (i * 64 + lane) * 4;
-    if (c < d) {
-      f32x4 gm = *reinterpret_cast<const f32x4*>(gamma + c);
-      f32x4 bt = *reinterpret_cast<const f32x4*>(beta + c);
-      store4<TO>(out + c, (v[i] - mu) * rstd * gm + bt);
+    for (int i = 0; i < NV; ++i)
+      if ((i * 64 + lane) * 4 < d) { cur[i] = cur[i] - mu; q += dot4(cur[i], cur[i]); }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / d + a.eps);
+    const char* pb = a.P.at(g);
+    const float* gamma = reinterpret_cast<const float*>(pb + a.gamma_off);
+    const float* beta = reinterpret_cast<const float*>(pb + a.beta_off);
+    TO* out = reinterpret_cast<TO*>(a.out) + a.out_slots.of(g) * a.out_slot_stride + (long)t * d;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = (i * 64 + lane) * 4;
+      if (c < d)
+        store4<TO>(out + c, cur[i] * rstd * *reinterpret_cast<const f32x4*>(gamma + c) +
+                                *reinterpret_cast<const f32x4*>(beta + c));
     }
+    if (next >= total) break;
+    if constexpr (PREFETCH) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) cur[i] = nxt[i];
+    } else {
+      load(next, cur);
+    }
+    row = next;
   }
+}
+
+static unsigned ln_grid(long rows) {
+  long want = (rows + 3) / 4;
+  const long cap = 256L * LN_BLOCKS_PER_CU;
+  return (unsigned)(want < cap ? want : cap);
+}
+
+template <typename TO>
+static void ln_fwd_dispatch(const LnFwdArgs& a, unsigned blocks, hipStream_t st) {
+  const int nv = (a.d + 255) / 256;
+  if (nv <= 1) hipLaunchKernelGGL((ln_fwd_kernel<TO, 1>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 2) hipLaunchKernelGGL((ln_fwd_kernel<TO, 2>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 3) hipLaunchKernelGGL((ln_fwd_kernel<TO, 3>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 4) hipLaunchKernelGGL((ln_fwd_kernel<TO, 4>), dim3(blocks), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((ln_fwd_kernel<TO, 8>), dim3(blocks), dim3(256), 0, st, a);
 }
 
 hipError_t launch_ln_fwd(const LnFwdArgs& a, bool is_bf16, hipStream_t st) {
   const long rows = (long)a.n_groups * a.T;
   if (rows <= 0) return hipSuccess;
-  const unsigned blocks = (unsigned)((rows + 3) / 4);
+  if (rows > 0x7fffffffL || a.d > 256 * LN_MAXV) return hipErrorInvalidValue;
+  const unsigned blocks = ln_grid(rows);
   const double esz = is_bf16 ? 2 : 4;
   ProfScope ps(PC_LN_FWD, 8.0 * rows * a.d,
                (double)rows * a.d * ((a.X.present() ? 4 : 0) + (a.xp ? 4 : 0) + esz), st);
-  if (is_bf16) hipLaunchKernelGGL(ln_fwd_kernel<bf16>, dim3(blocks), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL(ln_fwd_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
+  if (is_bf16) ln_fwd_dispatch<bf16>(a, blocks, st);
+  else ln_fwd_dispatch<float>(a, blocks, st);
   return hipGetLastError();
 }
 
@@ -87,92 +122,116 @@ hipError_t launch_ln_fwd(const LnFwdArgs& a, bool is_bf16, hipStream_t st) {
 //   vjp  = rstd*(dxhat - mean(dxhat) - xhat*mean(dxhat*xhat))
 //   v = add + vjp;  out_f32 = v;  out_op = c + v;  OUT = c + hstep*v + RHS
 // ---------------------------------------------------------------------------
-template <typename TO>
+template <typename TO, int NV>
 __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
-  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const long total = (long)a.n_groups * a.T;
-  if (row >= total) return;
-  const int g = (int)(row / a.T);
-  const int t = (int)(row - (long)g * a.T);
+  const int total = a.n_groups * a.T;
+  const int nwaves = gridDim.x * 4;
   const int d = a.d;
-  const long ro = (long)t * d;
-  const float* x = a.X.present() ? a.X.at(g) + ro : nullptr;
-  const float* xa = a.xp ? a.xp + a.xp_slots.of(g) * a.xp_slot_stride + ro : nullptr;
-  const TO* dy = reinterpret_cast<const TO*>(a.dy) + a.dy_slots.of(g) * a.dy_slot_stride + ro;
-  const float* gamma = reinterpret_cast<const float*>(a.P.at(g) + a.gamma_off);
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= total) return;
 
-  f32x4 v[LN_MAXV], w[LN_MAXV];
-  float s = 0.f;
+  auto load = [&](int r, f32x4* v, f32x4* w) {
+    const int g = r / a.T, t = r - g * a.T;
+    const long ro = (long)t * d;
+    const float* x = a.X.present() ? a.X.at(g) + ro : nullptr;
+    const float* xa = a.xp ? a.xp + a.xp_slots.of(g) * a.xp_slot_stride + ro : nullptr;
+    const TO* dy = reinterpret_cast<const TO*>(a.dy) + a.dy_slots.of(g) * a.dy_slot_stride + ro;
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
-    const int c = (i * 64 + lane) * 4;
-    if (c < d) {
-      v[i] = load_sum(x, xa, c);
-      s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+    for (int i = 0; i < NV; ++i) {
+      const int c = (i * 64 + lane) * 4;
+      if (c < d) { v[i] = load_sum(x, xa, c); w[i] = load4<TO>(dy + c); }
     }
-  }
-  const float mu = wave_sum(s) / d;
-  float q = 0.f;
+  };
+  constexpr bool PREFETCH = NV <= 4;                 // wider rows would spill: load in place instead
+  f32x4 v[NV], w[NV], nv_[PREFETCH ? NV : 1], nw_[PREFETCH ? NV : 1];
+  load(row, v, w);
+  while (true) {
+    const int next = row + nwaves;
+    if (PREFETCH && next < total) load(next, nv_, nw_);
+    const int g = row / a.T, t = row - g * a.T;
+    const long ro = (long)t * d;
+    const float* gamma = reinterpret_cast<const float*>(a.P.at(g) + a.gamma_off);
+    float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
-    const int c = (i * 64 + lane) * 4;
-    if (c < d) {
-      v[i] = v[i] - mu;
-      q += (v[i][0] * v[i][0] + v[i][1] * v[i][1]) + (v[i][2] * v[i][2] + v[i][3] * v[i][3]);
+    for (int i = 0; i < NV; ++i)
+      if ((i * 64 + lane) * 4 < d) s += sum4(v[i]);
+    const float mu = wave_sum(s) / d;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      if ((i * 64 + lane) * 4 < d) { v[i] = v[i] - mu; q += dot4(v[i], v[i]); }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / d + a.eps);
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = (i * 64 + lane) * 4;
+      if (c < d) {
+        v[i] = v[i] * rstd;                                              // xhat
+        w[i] = w[i] * *reinterpret_cast<const f32x4*>(gamma + c);        // dxhat
+        s1 += sum4(w[i]);
+        s2 += dot4(w[i], v[i]);
+      }
     }
-  }
-  const float rstd = 1.0f / sqrtf(wave_sum(q) / d + a.eps);
-  float s1 = 0.f, s2 = 0.f;
+    const float m1 = wave_sum(s1) / d, m2 = wave_sum(s2) / d;
+    const float* add = a.add ? a.add + a.add_slots.of(g) * a.add_slot_stride + ro : nullptr;
+    float* of = a.out_f32 ? a.out_f32 + a.of_slots.of(g) * a.of_slot_stride + ro : nullptr;
+    TO* oo = a.out_op ? reinterpret_cast<TO*>(a.out_op) + a.oo_slots.of(g) * a.oo_slot_stride + ro : nullptr;
+    const bool need_c = oo != nullptr || a.OUT.present();
+    const float* cvec = need_c ? a.C.at(g) + ro : nullptr;
+    float* OUT = a.OUT.present() ? a.OUT.at(g) + ro : nullptr;
+    const float* RHS = a.RHS.present() ? a.RHS.at(g) + ro : nullptr;
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
-    const int c = (i * 64 + lane) * 4;
-    if (c < d) {
-      v[i] = v[i] * rstd;                                            // xhat
-      w[i] = load4<TO>(dy + c) * *reinterpret_cast<const f32x4*>(gamma + c);   // dxhat
-      s1 += (w[i][0] + w[i][1]) + (w[i][2] + w[i][3]);
-      s2 += (w[i][0] * v[i][0] + w[i][1] * v[i][1]) + (w[i][2] * v[i][2] + w[i][3] * v[i][3]);
-    }
-  }
-  const float m1 = wave_sum(s1) / d, m2 = wave_sum(s2) / d;
-  const float* add = a.add ? a.add + a.add_slots.of(g) * a.add_slot_stride + ro : nullptr;
-  float* of = a.out_f32 ? a.out_f32 + a.of_slots.of(g) * a.of_slot_stride + ro : nullptr;
-  TO* oo = a.out_op ? reinterpret_cast<TO*>(a.out_op) + a.oo_slots.of(g) * a.oo_slot_stride + ro : nullptr;
-  const bool need_c = oo != nullptr || a.OUT.present();
-  const float* cvec = need_c ? a.C.at(g) + ro : nullptr;
-  float* OUT = a.OUT.present() ? a.OUT.at(g) + ro : nullptr;
-  const float* RHS = a.RHS.present() ? a.RHS.at(g) + ro : nullptr;
-#pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
-    const int c = (i * 64 + lane) * 4;
-    if (c < d) {
-      f32x4 r = rstd * (w[i] - m1 - v[i] * m2);
-      if (add) r += *reinterpret_cast<const f32x4*>(add + c);
-      if (of) *reinterpret_cast<f32x4*>(of + c) = r;
-      if (need_c) {
-        f32x4 cc = *reinterpret_cast<const f32x4*>(cvec + c);
-        if (oo) store4<TO>(oo + c, cc + r);
-        if (OUT) {
-          f32x4 res = cc + a.hstep * r;
-          if (RHS) res += *reinterpret_cast<const f32x4*>(RHS + c);
-          *reinterpret_cast<f32x4*>(OUT + c) = res;
+    for (int i = 0; i < NV; ++i) {
+      const int c = (i * 64 + lane) * 4;
+      if (c < d) {
+        f32x4 r = rstd * (w[i] - m1 - v[i] * m2);
+        if (add) r += *reinterpret_cast<const f32x4*>(add + c);
+        if (of) *reinterpret_cast<f32x4*>(of + c) = r;
+        if (need_c) {
+          f32x4 cc = *reinterpret_cast<const f32x4*>(cvec + c);
+          if (oo) store4<TO>(oo + c, cc + r);
+          if (OUT) {
+            f32x4 res = cc + a.hstep * r;
+            if (RHS) res += *reinterpret_cast<const f32x4*>(RHS + c);
+            *reinterpret_cast<f32x4*>(OUT + c) = res;
+          }
         }
       }
     }
+    if (next >= total) break;
+    if constexpr (PREFETCH) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) { v[i] = nv_[i]; w[i] = nw_[i]; }
+    } else {
+      load(next, v, w);
+    }
+    row = next;
   }
+}
+
+template <typename TO>
+static void ln_bwd_dispatch(const LnBwdArgs& a, unsigned blocks, hipStream_t st) {
+  const int nv = (a.d + 255) / 256;
+  if (nv <= 1) hipLaunchKernelGGL((ln_bwd_kernel<TO, 1>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 2) hipLaunchKernelGGL((ln_bwd_kernel<TO, 2>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 3) hipLaunchKernelGGL((ln_bwd_kernel<TO, 3>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 4) hipLaunchKernelGGL((ln_bwd_kernel<TO, 4>), dim3(blocks), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((ln_bwd_kernel<TO, 8>), dim3(blocks), dim3(256), 0, st, a);
 }
 
 hipError_t launch_ln_bwd(const LnBwdArgs& a, bool is_bf16, hipStream_t st) {
   const long rows = (long)a.n_groups * a.T;
   if (rows <= 0) return hipSuccess;
-  const unsigned blocks = (unsigned)((rows + 3) / 4);
+  if (rows > 0x7fffffffL || a.d > 256 * LN_MAXV) return hipErrorInvalidValue;
+  const unsigned blocks = ln_grid(rows);
   const double esz = is_bf16 ? 2 : 4;
   const double per_elem = esz + (a.X.present() ? 4 : 0) + (a.xp ? 4 : 0) + (a.add ? 4 : 0) + (a.out_f32 ? 4 : 0) +
                           ((a.out_op || a.OUT.present()) ? 4 : 0) + (a.out_op ? esz : 0) +
                           (a.OUT.present() ? 4 : 0) + (a.RHS.present() ? 4 : 0);
   ProfScope ps(PC_LN_BWD, 16.0 * rows * a.d, (double)rows * a.d * per_elem, st);
-  if (is_bf16) hipLaunchKernelGGL(ln_bwd_kernel<bf16>, dim3(blocks), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL(ln_bwd_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
+  if (is_bf16) ln_bwd_dispatch<bf16>(a, blocks, st);
+  else ln_bwd_dispatch<float>(a, blocks, st);
   return hipGetLastError();
 }
 

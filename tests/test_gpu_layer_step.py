@@ -14,7 +14,7 @@ from gpu_util import TOL, DeviceModel, assert_close, dev, relerr, shape_of
 pytestmark = pytest.mark.gpu
 
 
-def make(arch, dtype, d=128, H=4, f=512, B=3, S=50, Sm=40, seed=31):
+def make(arch, dtype, d=256, H=4, f=512, B=3, S=50, Sm=40, seed=31):
     return wls.Workload("t", arch, d, H, f, B, S, Sm if arch == wls.ARCH_CROSS else 0,
                         4, 0.25, 2, 2, 1, dtype, seed)
 
@@ -64,6 +64,20 @@ def test_forward_step_without_rhs_and_chunked_groups(dtype):
     # 5 groups split into launches of 2, 2, 1
     run_forward_case(make(wls.ARCH_ENCODER, dtype, S=75, B=2), G=5, hstep=1.0, with_rhs=False,
                      weight_std=0.05, force_simple=0, max_groups=2)
+
+
+@pytest.mark.parametrize("arch", [wls.ARCH_ENCODER, wls.ARCH_CAUSAL])
+def test_long_sequence_several_key_blocks_bf16(arch):
+    """S = 200: four 64-key blocks with a ragged last one, two 128-query blocks; forward and adjoint."""
+    wl = make(arch, wls.DTYPE_BF16, B=1, S=200)
+    run_forward_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.05, force_simple=0)
+    run_adjoint_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.05, force_simple=0)
+
+
+def test_small_head_dimension_uses_generic_attention_bf16():
+    wl = make(wls.ARCH_CAUSAL, wls.DTYPE_BF16, d=128, H=4)       # d_head = 32
+    run_forward_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.05, force_simple=0)
+    run_adjoint_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.05, force_simple=0)
 
 
 def test_forward_step_tiny_config_shape_fp32():
