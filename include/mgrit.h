@@ -169,6 +169,14 @@ int         mgrit_last_hip_error(void);          /* hipError_t of the last MGRIT
  * are split into chunks that run one after another).  0 restores the default. */
 void mgrit_set_max_groups_per_launch(int n);
 
+/* Tuning knob: 2 (default) lets the independent launch chunks of a sweep alternate between the
+ * caller's stream and one helper stream, forked from and joined back into the caller's stream
+ * with events before the call's remaining work is enqueued (stream-ordered semantics for the
+ * caller are unchanged); 1 keeps everything on the caller's stream.  The helper stream and its
+ * two events are created once per process on first use.  Both knobs change the workspace
+ * size: set them before querying it. */
+void mgrit_set_lanes(int n);
+
 /* ---- instrumentation (benchmark and tests; not needed for normal use) ------------------
  * Per-launch timing with HIP events recorded on the launch stream around every kernel of
  * a class.  mgrit_profile_enable(n > 0) creates a pool of n records (this call allocates

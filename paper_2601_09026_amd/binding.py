@@ -81,6 +81,8 @@ def lib() -> C.CDLL:
         L.mgrit_last_hip_error.restype = C.c_int
         L.mgrit_set_max_groups_per_launch.argtypes = [C.c_int]
         L.mgrit_set_max_groups_per_launch.restype = None
+        L.mgrit_set_lanes.argtypes = [C.c_int]
+        L.mgrit_set_lanes.restype = None
         L.mgrit_debug_force_simple_kernels.argtypes = [C.c_int, C.c_int]
         L.mgrit_debug_force_simple_kernels.restype = None
         L.mgrit_profile_enable.argtypes = [C.c_int]
@@ -127,6 +129,10 @@ def mgrit_step_evaluations(opts: Opts) -> int:
 
 def mgrit_set_max_groups_per_launch(n: int) -> None:
     lib().mgrit_set_max_groups_per_launch(int(n))
+
+
+def mgrit_set_lanes(n: int) -> None:
+    lib().mgrit_set_lanes(int(n))
 
 
 PROFILE_CLASSES = {0: "gemm_generic", 1: "attn_fwd", 2: "attn_bwd", 3: "ln_fwd", 4: "ln_vjp", 5: "elementwise",

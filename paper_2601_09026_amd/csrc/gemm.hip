@@ -151,7 +151,7 @@ __device__ __forceinline__ void tile_epilogue(
 }
 
 // ---------------------------------------------------------------------------
-// MFMA kernel.  4 wavefronts as 2 x 2, each owning a (BM/2) x (BN/2) tile of the output.
+// MFMA kernel.  WM x WN wavefronts, each owning a (BM/WM) x (BN/WN) tile of the output.
 //  * Operands go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
 //    no register staging) through a ring of STAGES k-tiles of depth BK (32 or 64).
 //  * An LDS row holds the BK bf16 of one matrix row (64 or 128 bytes) unpadded; its 16-byte
@@ -185,21 +185,28 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
+// LDS has 64 four-byte banks (256 bytes per clock); a 16-byte read is served 16 lanes at a
+// time, so 16 consecutive rows must land on 16 distinct 16-byte slots modulo 256 bytes.  With
+// 128-byte rows two rows share a 256-byte bank row: swizzle by the row pair; with 64-byte
+// rows four rows share it: swizzle by the row quad.
 template <int BK> __device__ __forceinline__ int swz(int row) {
-  return BK == 64 ? (row & 7) : ((row >> 1) & 3);
+  return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 
-template <int BM, int BN, int BK, int STAGES, int OCC, bool STAGED, int EPI, typename TO, int DBG = 0>
-__global__ void __launch_bounds__(256, OCC)
+template <int BM, int BN, int BK, int STAGES, int OCC, bool STAGED, int EPI, typename TO, int DBG = 0,
+          int WM = 2, int WN = 2>
+__global__ void __launch_bounds__(64 * WM * WN, OCC)
 gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd) {
-  constexpr int WTM = BM / 2, WTN = BN / 2;
+  constexpr int NW = WM * WN;                            // wavefronts per block
+  constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int RB = BK * 2;                             // bytes per LDS row
   constexpr int CPR = RB / 16;                           // 16-byte chunks per row
   constexpr int RPL = 1024 / RB;                         // rows per load instruction
   constexpr int KS = BK / 16;                            // MFMA k-steps per tile
   constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB, STAGE = A_BYTES + B_BYTES;
-  constexpr int A_LD = BM / RPL / 4, B_LD = BN / RPL / 4;   // load instructions per wave per k-tile
+  constexpr int A_LD = BM / RPL / NW, B_LD = BN / RPL / NW; // load instructions per wave per k-tile
+  static_assert(A_LD >= 1 && B_LD >= 1 && A_LD * RPL * NW == BM && B_LD * RPL * NW == BN, "tile/wave split");
   constexpr int PER_TILE = A_LD + B_LD;
   constexpr int SLOTS = KS * TM;                         // MFMA groups per k-tile
   constexpr int PER_SLOT = (PER_TILE + SLOTS - 1) / SLOTS;
@@ -225,20 +232,23 @@ gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, in
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int lr = lane & 31, lh = lane >> 5;
-  const int wm0 = (wave >> 1) * WTM, wn0 = (wave & 1) * WTN;
+  const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
 
   // global -> LDS: this lane's element offsets (row clamped at the ragged tail of M)
-  const int lrow = lane / CPR, lchunk = (lane % CPR) ^ swz<BK>(lrow);
+  const int lrow = lane / CPR, lpos = lane % CPR;
   unsigned aoff[A_LD], boff[B_LD];
 #pragma unroll
   for (int j = 0; j < A_LD; ++j) {
-    int gm = m0 + (wave * A_LD + j) * RPL + lrow;
+    const int row = (wave * A_LD + j) * RPL + lrow;            // row inside the tile
+    int gm = m0 + row;
     gm = gm < M ? gm : M - 1;
-    aoff[j] = (unsigned)gm * (unsigned)K + lchunk * 8;
+    aoff[j] = (unsigned)gm * (unsigned)K + (lpos ^ swz<BK>(row)) * 8;
   }
 #pragma unroll
-  for (int j = 0; j < B_LD; ++j)
-    boff[j] = (unsigned)(n0 + (wave * B_LD + j) * RPL + lrow) * (unsigned)K + lchunk * 8;
+  for (int j = 0; j < B_LD; ++j) {
+    const int row = (wave * B_LD + j) * RPL + lrow;
+    boff[j] = (unsigned)(n0 + row) * (unsigned)K + (lpos ^ swz<BK>(row)) * 8;
+  }
 
   auto issue_one = [&](int stage, int k0, int idx) {
     if (DBG == 2 || DBG == 3) return;
@@ -319,9 +329,10 @@ gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, in
     __syncthreads();
   }
 
-  static_assert(!STAGED || 32 * (WTN * 4 + 16) <= STAGES * STAGE / 4, "epilogue staging does not fit");
+  // the staging regions reuse the (now idle) k-tile ring; the launcher sizes LDS for both
+  constexpr int EP_BYTES = (32 * (WTN * 4 + 16) + 1023) / 1024 * 1024;
   const EpiPtrs P = resolve_epi<TO>(a, g, EPI);
-  tile_epilogue<EPI, TO, TM, TN, STAGED>(acc, smem2 + wave * (STAGES * STAGE / 4), P.bias, static_cast<TO*>(P.out),
+  tile_epilogue<EPI, TO, TM, TN, STAGED>(acc, smem2 + wave * EP_BYTES, P.bias, static_cast<TO*>(P.out),
                                          static_cast<float*>(P.out), static_cast<TO*>(P.aux),
                                          static_cast<const TO*>(P.aux), P.base, P.X,
                                          static_cast<const float*>(P.aux), P.RHS, P.OUT, a.hstep, a.N, M,
@@ -390,13 +401,15 @@ void gemm_force_simple(int on) { g_force_simple = on; }
 void gemm_set_tile_config(int cfg) { g_tile_cfg = cfg; }
 void gemm_set_debug_mode(int m) { g_dbg_mode = m; }
 
-template <int BM, int BN, int BK, int STAGES, int OCC, bool STAGED, int EPI>
+template <int BM, int BN, int BK, int STAGES, int OCC, bool STAGED, int EPI, int WM = 2, int WN = 2>
 static hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = a.N / BN;
   const int total = tiles_m * tiles_n * a.n_groups;
   const int per_xcd = (total + 7) / 8;
-  const size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
-  auto kern = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16>;
+  const size_t ring = (size_t)STAGES * (BM + BN) * BK * 2;
+  const size_t staging = STAGED ? (size_t)WM * WN * ((32 * (BN / WN * 4 + 16) + 1023) / 1024 * 1024) : 0;
+  const size_t smem = ring > staging ? ring : staging;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 0, WM, WN>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -406,16 +419,16 @@ static hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
   }
 #ifdef MG_GEMM_DEBUG
   if (g_dbg_mode >= 1 && g_dbg_mode <= 3) {
-    auto k1 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 1>;
-    auto k2 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 2>;
-    auto k3 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 3>;
+    auto k1 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 1, WM, WN>;
+    auto k2 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 2, WM, WN>;
+    auto k3 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 3, WM, WN>;
     auto kd = g_dbg_mode == 1 ? k1 : (g_dbg_mode == 2 ? k2 : k3);
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kd), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    hipLaunchKernelGGL(kd, dim3(per_xcd * 8), dim3(256), smem, st, a, tiles_m, tiles_n, total, per_xcd);
+    hipLaunchKernelGGL(kd, dim3(per_xcd * 8), dim3(64 * WM * WN), smem, st, a, tiles_m, tiles_n, total, per_xcd);
     return hipGetLastError();
   }
 #endif
-  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), smem, st, a, tiles_m, tiles_n, total, per_xcd);
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(64 * WM * WN), smem, st, a, tiles_m, tiles_n, total, per_xcd);
   return hipGetLastError();
 }
 
@@ -452,22 +465,28 @@ static hipError_t launch_epi(const GemmArgs& a, bool is_bf16, hipStream_t st) {
   if (!is_bf16) return launch_simple<float, EPI>(a, st);
   if (!mfma_ok) return launch_simple<bf16, EPI>(a, st);
   // Tile choice (measured on MI355X at the benchmark shapes, 8 groups of 4096 rows):
-  //  * 128x128x64, two k-tile stages, two blocks per CU (their phases overlap) is the best
-  //    all-rounder;
-  //  * the activation epilogues (GELU and its derivative) are long, and a 256x128 tile with
-  //    32-deep k-tiles and a three-stage ring hides them better.
+  //  1: 256x256x64, two stages, 8 wavefronts (2x4, 128x64 each, two per SIMD so that one can
+  //     issue memory instructions while the other feeds the MFMA pipe): best where N is a
+  //     multiple of 256;
+  //  2: 256x128x32, three stages, 4 wavefronts, two blocks per CU: for the other widths.
   int cfg = g_tile_cfg;
-  if (cfg == 0) cfg = (EPI == EPI_GELU || EPI == EPI_DGELU) ? 2 : 1;
+  if (cfg == 0) cfg = (a.N % 256 == 0) ? 1 : 2;
   switch (cfg) {
+    case 1: if (a.N % 256 == 0) return launch_mfma<256, 256, 64, 2, 1, true, EPI, 2, 4>(a, st); break;
     case 2: return launch_mfma<256, 128, 32, 3, 2, true, EPI>(a, st);
 #ifdef MG_GEMM_DEBUG
     case 3: if (a.N % 256 == 0) return launch_mfma<256, 256, 64, 2, 1, true, EPI>(a, st); break;
     case 4: return launch_mfma<128, 128, 64, 2, 2, false, EPI>(a, st);
     case 5: return launch_mfma<256, 128, 32, 2, 2, true, EPI>(a, st);
+    case 6: if (a.N % 256 == 0) return launch_mfma<256, 256, 64, 2, 1, true, EPI, 2, 4>(a, st); break;
+    case 7: if (a.N % 256 == 0) return launch_mfma<256, 256, 32, 4, 1, true, EPI, 2, 4>(a, st); break;
+    case 8: return launch_mfma<128, 128, 64, 2, 2, true, EPI>(a, st);
+    case 9: return launch_mfma<256, 128, 64, 2, 1, true, EPI, 4, 2>(a, st);
+    case 10: return launch_mfma<256, 128, 32, 3, 2, true, EPI, 4, 2>(a, st);
 #endif
     default: break;
   }
-  return launch_mfma<128, 128, 64, 2, 2, true, EPI>(a, st);
+  return launch_mfma<256, 128, 32, 3, 2, true, EPI>(a, st);
 }
 
 hipError_t launch_gemm(const GemmArgs& a, int epi, bool is_bf16, hipStream_t st) {

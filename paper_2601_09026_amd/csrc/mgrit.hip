@@ -35,7 +35,7 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 int g_max_groups = 0;                       // 0 = default
-constexpr int DEFAULT_MAX_GROUPS = 8;
+constexpr int DEFAULT_MAX_GROUPS = 4;
 
 inline int max_groups() { return g_max_groups > 0 ? g_max_groups : DEFAULT_MAX_GROUPS; }
 
@@ -161,7 +161,8 @@ struct Engine {
     T = m->batch * m->seq; Tm = m->batch * m->mem_seq; d = m->d_model; f = m->d_ff; H = m->n_heads;
     dh = d / H; esz = bf16 ? 2 : 4; st = s;
   }
-  void carve_forward(Bump& b, int gc) {
+  // work buffers of one lane (a lane = a stream with its own intermediates)
+  void carve_forward_work(Bump& b, int gc) {
     Gc = gc;
     const size_t G = gc;
     u = b.take_bytes(G * T * d * esz);
@@ -169,22 +170,31 @@ struct Engine {
     o = b.take_bytes(G * T * d * esz);
     xin = b.take<float>(G * T * d);
     act = b.take_bytes(G * T * f * esz);
-    x3 = nullptr; qc = kvc = memb = nullptr;
+    x3 = nullptr; qc = kvc = nullptr;
     if (md.arch == MGRIT_ARCH_CROSS) {
       x3 = b.take<float>(G * T * d);
       qc = b.take_bytes(G * T * d * esz);
       kvc = b.take_bytes(G * Tm * 2 * d * esz);
-      memb = b.take_bytes((size_t)Tm * d * esz);
     }
   }
+  void carve_forward(Bump& b, int gc) {
+    memb = md.arch == MGRIT_ARCH_CROSS ? b.take_bytes((size_t)Tm * d * esz) : nullptr;
+    carve_forward_work(b, gc);
+  }
   void carve_adjoint(Bump& b, int gc, int ncache) {
-    Gc = gc; n_cache = ncache;
-    const size_t G = gc, C = ncache;
+    n_cache = ncache;
+    const size_t C = ncache;
     c_qkv = b.take_bytes(C * T * 3 * d * esz);
     c_o = b.take_bytes(C * T * d * esz);
     c_z = b.take_bytes(C * T * f * esz);
     c_lse = b.take<float>(C * md.batch * H * md.seq);
     c_xin = b.take<float>(C * T * d);
+    memb = nullptr;
+    carve_adjoint_work(b, gc);
+  }
+  void carve_adjoint_work(Bump& b, int gc) {
+    Gc = gc;
+    const size_t G = gc;
     u = b.take_bytes(G * T * d * esz);
     cb = b.take_bytes(G * T * d * esz);
     dz = b.take_bytes(G * T * f * esz);
@@ -197,6 +207,39 @@ struct Engine {
     qkv = o = act = nullptr; xin = nullptr;
   }
 };
+
+// Second lane: independent chunks of a sweep alternate between the caller's stream and one
+// helper stream (forked from and joined back into the caller's stream with events), so that
+// the bandwidth-bound kernels of one chunk overlap the matrix kernels of the other.  The
+// helper stream and its two events are created once per process, on first use.
+struct AuxStream {
+  hipStream_t s = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  bool tried = false, ok = false;
+};
+AuxStream& aux_stream() {
+  static AuxStream a;
+  if (!a.tried) {
+    a.tried = true;
+    a.ok = hipStreamCreateWithFlags(&a.s, hipStreamNonBlocking) == hipSuccess &&
+           hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&a.join, hipEventDisableTiming) == hipSuccess;
+  }
+  return a;
+}
+int g_lanes = 2;                            // 1 = everything on the caller's stream
+
+// Engine of the second lane: same model and shared buffers, own work buffers and stream.
+inline bool make_lane(Engine& E2, const Engine& E, Bump& b, bool adjoint, bool measure_only) {
+  if (g_lanes < 2) return false;
+  E2 = E;
+  if (adjoint) E2.carve_adjoint_work(b, E.Gc); else E2.carve_forward_work(b, E.Gc);
+  if (measure_only) return true;
+  AuxStream& a = aux_stream();
+  if (!a.ok) return false;
+  E2.st = a.s;
+  return true;
+}
 
 inline Rows shift(Rows r, int c0) { if (r.tab) r.i0 += c0 * r.is; return r; }
 inline Params shift(Params p, int c0) { p.i0 += c0 * p.is; return p; }
@@ -373,24 +416,42 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
   return MGRIT_OK;
 }
 
-int forward_groups(Engine& E, int G, Rows IN, Rows OUT, Rows RHS, Params TH, float hstep, bool cache,
-                   Slots cslots) {
-  for (int c0 = 0; c0 < G; c0 += E.Gc) {
-    const int n = G - c0 < E.Gc ? G - c0 : E.Gc;
-    STCHK(forward_chunk(E, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), hstep, cache,
-                        shift(cslots, c0)));
+// Runs `fn(lane engine, first group, count)` over chunks of a sweep; with a second lane the
+// chunks alternate between the two streams.
+template <typename F>
+int run_chunks(Engine& E, Engine* E2, int G, F fn) {
+  const bool two = E2 != nullptr && G >= 2;
+  int chunk = E.Gc;
+  if (two && (G + 1) / 2 < chunk) chunk = (G + 1) / 2;
+  if (!two) {
+    for (int c0 = 0; c0 < G; c0 += chunk) STCHK(fn(E, c0, G - c0 < chunk ? G - c0 : chunk));
+    return MGRIT_OK;
   }
+  AuxStream& a = aux_stream();
+  HIPCHK(hipEventRecord(a.fork, E.st));
+  HIPCHK(hipStreamWaitEvent(E2->st, a.fork, 0));
+  int lane = 0;
+  for (int c0 = 0; c0 < G; c0 += chunk, lane ^= 1)
+    STCHK(fn(lane ? *E2 : E, c0, G - c0 < chunk ? G - c0 : chunk));
+  HIPCHK(hipEventRecord(a.join, E2->st));
+  HIPCHK(hipStreamWaitEvent(E.st, a.join, 0));
   return MGRIT_OK;
 }
 
-int adjoint_groups(Engine& E, int G, Rows IN, Rows OUT, Rows RHS, Params TH, Params THT, Rows LIN, Slots cs,
-                   float hstep) {
-  for (int c0 = 0; c0 < G; c0 += E.Gc) {
-    const int n = G - c0 < E.Gc ? G - c0 : E.Gc;
-    STCHK(adjoint_chunk(E, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), shift(THT, c0),
-                        shift(LIN, c0), shift(cs, c0), hstep));
-  }
-  return MGRIT_OK;
+int forward_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Params TH, float hstep, bool cache,
+                   Slots cslots) {
+  return run_chunks(E, E2, G, [&](Engine& L, int c0, int n) {
+    return forward_chunk(L, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), hstep, cache,
+                         shift(cslots, c0));
+  });
+}
+
+int adjoint_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Params TH, Params THT, Rows LIN,
+                   Slots cs, float hstep) {
+  return run_chunks(E, E2, G, [&](Engine& L, int c0, int n) {
+    return adjoint_chunk(L, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), shift(THT, c0),
+                         shift(LIN, c0), shift(cs, c0), hstep);
+  });
 }
 
 int transpose_blocks(Engine& E, int n, Params TH, Params THT) {
@@ -406,6 +467,7 @@ int transpose_blocks(Engine& E, int n, Params TH, Params THT) {
 // ---------------------------------------------------------------------------
 struct Driver {
   Engine* E = nullptr;             // null: dry run that only counts evaluations
+  Engine* E2 = nullptr;            // second lane, or null
   bool adjoint = false;
   int N = 0, cf = 1, L = 1, relax = MGRIT_RELAX_FCF;
   float h = 0.f;
@@ -432,13 +494,13 @@ struct Driver {
     Rows IN = {(const void* const*)tabW, j0 * s, js * s};
     if (!adjoint) {
       Params TH = {(const void* const*)tabTh, j0 * s, js * s};
-      return forward_groups(*E, cnt, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
+      return forward_groups(*E, E2, cnt, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
     }
     const int n0 = N - (j0 + 1) * s, ns = -js * s;       // layer the coarse step lands on
     Params TH = {(const void* const*)tabTh, n0, ns};
     Params THT = {(const void* const*)tabThT, n0, ns};
     Rows LIN = {(const void* const*)tabZ, n0, ns};
-    return adjoint_groups(*E, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep);
+    return adjoint_groups(*E, E2, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep);
   }
 
   Rows W(int lvl, int j0, int js) const {
@@ -492,7 +554,8 @@ struct Driver {
 };
 
 struct Plan {                       // workspace of mgrit_forward / mgrit_adjoint
-  Engine E;
+  Engine E, E2;
+  bool two_lanes = false;
   Driver D;
   void* thT_blocks = nullptr;
   size_t bytes = 0;
@@ -509,8 +572,9 @@ int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, bool ad
   const int widest = adjoint ? (N > M0 ? N : M0) : M0;      // the cache pass batches over all N layers
   if (gc > widest) gc = widest;
   if (adjoint) E.carve_adjoint(b, gc, N); else E.carve_forward(b, gc);
+  P.two_lanes = widest >= 2 && make_lane(P.E2, E, b, adjoint, ws == nullptr);
   Driver& D = P.D;
-  D.E = &E; D.adjoint = adjoint; D.N = N; D.cf = op->cf; D.L = serial ? 1 : op->levels; D.relax = op->relax;
+  D.E = &E; D.E2 = P.two_lanes ? &P.E2 : nullptr; D.adjoint = adjoint; D.N = N; D.cf = op->cf; D.L = serial ? 1 : op->levels; D.relax = op->relax;
   D.h = op->h;
   D.tabW = b.take<void*>(N + 1);
   D.tabTh = b.take<void*>(N);
@@ -579,12 +643,15 @@ size_t mgrit_layer_step_workspace_bytes(const mgrit_model_desc* desc, int adjoin
   E.init(desc, nullptr);
   Bump b(nullptr);
   int gc = max_groups() < n_groups ? max_groups() : n_groups;
+  Engine E2;
   if (adjoint) {
     E.carve_adjoint(b, gc, n_groups);
+    if (n_groups >= 2) make_lane(E2, E, b, true, true);
     b.take_bytes((size_t)n_groups * E.lay.block_bytes);
     b.take<void*>((size_t)n_groups * 6);
   } else {
     E.carve_forward(b, gc);
+    if (n_groups >= 2) make_lane(E2, E, b, false, true);
     b.take<void*>((size_t)n_groups * 4);
   }
   return (b.off + 255) / 256 * 256;
@@ -665,7 +732,7 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
   STCHK(transpose_blocks(E, N, TH, THT));
   // linearisation cache for all N layers, batched over layers
   Rows Zrows = {(const void* const*)D.tabZ, 0, 1};
-  STCHK(forward_groups(E, N, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
+  STCHK(forward_groups(E, D.E2, N, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
   // initial values
   HIPCHK(hipMemcpyAsync(static_cast<char*>(lambda_all) + (size_t)N * state, lambda_N, state,
                         hipMemcpyDeviceToDevice, st));
@@ -701,8 +768,11 @@ int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups, 
   Bump b(workspace);
   const int gc = max_groups() < n_groups ? max_groups() : n_groups;
   const int G = n_groups;
+  Engine E2;
+  Engine* L2 = nullptr;
   if (adjoint) {
     E.carve_adjoint(b, gc, G);
+    if (G >= 2 && make_lane(E2, E, b, true, false)) L2 = &E2;
     char* tblocks = static_cast<char*>(b.take_bytes((size_t)G * E.lay.block_bytes));
     void** tabs = b.take<void*>((size_t)G * 6);
     void **tIn = tabs, **tOut = tabs + G, **tTh = tabs + 2 * G, **tLin = tabs + 3 * G, **tRhs = tabs + 4 * G,
@@ -718,10 +788,11 @@ int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups, 
     Rows LIN = {(const void* const*)tLin, 0, 1};
     Rows RHS = rhs ? Rows{(const void* const*)tRhs, 0, 1} : NO_ROWS;
     STCHK(transpose_blocks(E, G, TH, THT));
-    STCHK(forward_groups(E, G, LIN, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
-    return adjoint_groups(E, G, IN, OUT, RHS, TH, THT, LIN, Slots{0, 1}, hstep);
+    STCHK(forward_groups(E, L2, G, LIN, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
+    return adjoint_groups(E, L2, G, IN, OUT, RHS, TH, THT, LIN, Slots{0, 1}, hstep);
   }
   E.carve_forward(b, gc);
+  if (G >= 2 && make_lane(E2, E, b, false, false)) L2 = &E2;
   void** tabs = b.take<void*>((size_t)G * 4);
   void **tIn = tabs, **tOut = tabs + G, **tTh = tabs + 2 * G, **tRhs = tabs + 3 * G;
   HIPCHK(upload_pointers(tIn, in, G, st));
@@ -733,7 +804,7 @@ int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups, 
   Params TH = {(const void* const*)tTh, 0, 1};
   Rows IN = {(const void* const*)tIn, 0, 1}, OUT = {(const void* const*)tOut, 0, 1};
   Rows RHS = rhs ? Rows{(const void* const*)tRhs, 0, 1} : NO_ROWS;
-  return forward_groups(E, G, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
+  return forward_groups(E, L2, G, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
 }
 
 const char* mgrit_status_string(int status) {
@@ -750,6 +821,8 @@ const char* mgrit_status_string(int status) {
 int mgrit_last_hip_error(void) { return g_last_hip_error; }
 
 void mgrit_set_max_groups_per_launch(int n) { g_max_groups = n > 0 ? n : 0; }
+
+void mgrit_set_lanes(int n) { g_lanes = n >= 2 ? 2 : 1; }
 
 // test / tuning hooks (not part of the documented interface)
 void mgrit_debug_force_simple_kernels(int gemm, int attn) {
