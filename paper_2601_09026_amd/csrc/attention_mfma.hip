@@ -25,18 +25,24 @@ namespace mg {
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
-constexpr int FA_LD = 72;                 // padded LDS row of a 64-wide bf16 tile (144 bytes)
+// LDS has 64 four-byte banks.  Row-major tiles are read 16 bytes per lane (16 lanes per
+// clock): 144-byte rows put 16 consecutive rows on 16 distinct 16-byte slots.  Transposed
+// tiles are read 8 bytes per lane (32 lanes per clock): 136-byte rows (an odd number of
+// 8-byte units) put 32 consecutive rows on 32 distinct 8-byte slots.
+constexpr int FA_LD = 72;                 // row-major tile: 64 bf16 + 8 pad
+constexpr int FA_LDT = 68;                // transposed tile: 64 bf16 + 4 pad
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
 // 64 rows x 64 cols of bf16 from global (rows clamped to nrows-1) into a row-major LDS tile
-// and/or its transpose.  Work item = (row pair, 8-column chunk); row pairs vary fastest so
-// that the 4-byte transposed stores of a wavefront fall into distinct banks.
+// and/or its transpose.  Work item = (row pair, 8-column chunk); the chunk varies fastest so
+// that 8 consecutive lanes fetch one whole 128-byte row (coalesced global reads matter more
+// here than the two-way bank conflict the transposed 4-byte stores then have).
 template <int NT, bool PLAIN, bool TRANS>
 __device__ __forceinline__ void stage64(bf16* plain, bf16* trans, const bf16* src, long rs, int row0, int nrows) {
 #pragma unroll
   for (int item = threadIdx.x; item < 256; item += NT) {
-    const int rp = item & 31, cc = item >> 5;
+    const int cc = item & 7, rp = item >> 3;
     int r0 = row0 + 2 * rp, r1 = r0 + 1;
     r0 = r0 < nrows ? r0 : nrows - 1;
     r1 = r1 < nrows ? r1 : nrows - 1;
@@ -50,7 +56,7 @@ __device__ __forceinline__ void stage64(bf16* plain, bf16* trans, const bf16* sr
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         bf16x2 pr = {v0[i], v1[i]};
-        *reinterpret_cast<bf16x2*>(trans + (8 * cc + i) * FA_LD + 2 * rp) = pr;
+        *reinterpret_cast<bf16x2*>(trans + (8 * cc + i) * FA_LDT + 2 * rp) = pr;
       }
     }
   }
@@ -63,7 +69,7 @@ __device__ __forceinline__ bf16x8 frag_plain(const bf16* tile, int row, int ks, 
 // A operand from a transposed tile: row `row` (a feature), reduction over the tile's 64
 // staged rows, k-step t of 32-row tile rt, in the register-order enumeration
 __device__ __forceinline__ bf16x8 frag_trans(const bf16* tile, int row, int rt, int t, int lh) {
-  const bf16* p = tile + row * FA_LD + 32 * rt + 16 * t + 4 * lh;
+  const bf16* p = tile + row * FA_LDT + 32 * rt + 16 * t + 4 * lh;
   const bf16x4 lo = *reinterpret_cast<const bf16x4*>(p);
   const bf16x4 hi = *reinterpret_cast<const bf16x4*>(p + 8);
   bf16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -126,9 +132,9 @@ __device__ __forceinline__ void store_rows_T(bf16* dst, long row_stride, int row
 // forward
 // ---------------------------------------------------------------------------
 template <int NW>
-__global__ void __launch_bounds__(NW * 64) attn_fwd_mfma_kernel(const AttnArgs a) {
+__global__ void __launch_bounds__(NW * 64, 4) attn_fwd_mfma_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[64 * FA_LD];     // [key][d]
-  __shared__ __attribute__((aligned(16))) bf16 Vt[64 * FA_LD];     // [d][key]
+  __shared__ __attribute__((aligned(16))) bf16 Vt[64 * FA_LDT];     // [d][key]
   const int g = blockIdx.z;
   const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
   const int q0 = blockIdx.x * (NW * 32);
@@ -208,10 +214,10 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_mfma_kernel(const AttnArgs a
 // backward pass 1: D and dQ, one wavefront per 32 query rows
 // ---------------------------------------------------------------------------
 template <int NW>
-__global__ void __launch_bounds__(NW * 64) attn_bwd_dq_mfma_kernel(const AttnArgs a) {
+__global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dq_mfma_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[64 * FA_LD];     // [key][d]
   __shared__ __attribute__((aligned(16))) bf16 Vs[64 * FA_LD];     // [key][d]
-  __shared__ __attribute__((aligned(16))) bf16 Kt[64 * FA_LD];     // [d][key]
+  __shared__ __attribute__((aligned(16))) bf16 Kt[64 * FA_LDT];     // [d][key]
   const int g = blockIdx.z;
   const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
   const int q0 = blockIdx.x * (NW * 32);
@@ -274,11 +280,11 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_mfma_kernel(const AttnArg
 // backward pass 2: dK and dV, one wavefront per 32 key rows
 // ---------------------------------------------------------------------------
 template <int NW>
-__global__ void __launch_bounds__(NW * 64) attn_bwd_dkv_mfma_kernel(const AttnArgs a) {
+__global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dkv_mfma_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) bf16 Qs[64 * FA_LD];     // [query][d]
   __shared__ __attribute__((aligned(16))) bf16 dOs[64 * FA_LD];    // [query][d]
-  __shared__ __attribute__((aligned(16))) bf16 Qt[64 * FA_LD];     // [d][query]
-  __shared__ __attribute__((aligned(16))) bf16 dOt[64 * FA_LD];    // [d][query]
+  __shared__ __attribute__((aligned(16))) bf16 Qt[64 * FA_LDT];     // [d][query]
+  __shared__ __attribute__((aligned(16))) bf16 dOt[64 * FA_LDT];    // [d][query]
   __shared__ float Ls[64], Ds[64];
   const int g = blockIdx.z;
   const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
