@@ -89,7 +89,7 @@ def main():
     from paper_2601_09026_amd import workloads as wls
 
     wl = wls.named_workloads()[args.workload]
-    adjoint = not args.no_adjoint and wl.arch != wls.ARCH_CROSS
+    adjoint = not args.no_adjoint
     torch.cuda.set_device(0)
     if args.max_groups:
         mb.mgrit_set_max_groups_per_launch(args.max_groups)

@@ -139,8 +139,10 @@ int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts,
  *   lambda_N   device, [T,d] fp32: dL/dZ_N
  *   lambda_all device, [(N+1),T,d] fp32 out: row n = lambda_n; row N = copy of lambda_N,
  *              row 0 = dL/dZ_0
- *   dmemory, dtheta  reserved, must be NULL in this build
- * arch 2 is not supported by the adjoint in this build (MGRIT_UNSUPPORTED).
+ *   memory     as in mgrit_forward (required for arch 2: the decoder is linearised with it)
+ *   dmemory, dtheta  reserved, must be NULL in this build (MGRIT_UNSUPPORTED otherwise): the
+ *              gradients with respect to the cross-attention memory and the parameters are
+ *              not produced yet
  */
 int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts,
                   const void* Z_all, const void* const* theta, const void* memory,

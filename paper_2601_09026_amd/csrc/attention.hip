@@ -363,7 +363,7 @@ static hipError_t attn_bwd_simple(const AttnArgs& a, hipStream_t st) {
     dim3 grid((a.Sq + AT_RB - 1) / AT_RB, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL(attn_bwd_dq_simple_kernel<T>, grid, dim3(256), smem, st, a);
   }
-  {
+  if (a.dk) {                         // dK, dV pass (skipped when only dQ is wanted)
     const size_t smem = sizeof(float) * (2 * AT_CH * ld + 2 * AT_RB * a.dh + 8 * 64 + 2 * AT_CH);
     hipError_t e = set_smem(attn_bwd_dkv_simple_kernel<T>, smem);
     if (e != hipSuccess) return e;

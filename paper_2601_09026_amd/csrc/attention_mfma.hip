@@ -109,8 +109,10 @@ __device__ __forceinline__ HeadPtrs head_ptrs(const AttnArgs& a, int g, int b, i
     p.dO = reinterpret_cast<const bf16*>(a.dO) + a.do_slots.of(g) * a.do_slot_stride + (long)b * a.Sq * a.do_row_stride + h * dh;
     const long base = a.dqkv_slots.of(g) * a.dqkv_slot_stride;
     p.dQ = reinterpret_cast<bf16*>(a.dq) + base + (long)b * a.Sq * a.dqkv_row_stride + h * dh;
-    p.dK = reinterpret_cast<bf16*>(a.dk) + base + (long)b * a.Sk * a.dqkv_row_stride + h * dh;
-    p.dV = reinterpret_cast<bf16*>(a.dv) + base + (long)b * a.Sk * a.dqkv_row_stride + h * dh;
+    if (a.dk) {
+      p.dK = reinterpret_cast<bf16*>(a.dk) + base + (long)b * a.Sk * a.dqkv_row_stride + h * dh;
+      p.dV = reinterpret_cast<bf16*>(a.dv) + base + (long)b * a.Sk * a.dqkv_row_stride + h * dh;
+    }
     p.D = a.D + a.D_slots.of(g) * a.D_slot_stride + ((long)b * a.H + h) * a.Sq;
   }
   return p;
@@ -377,6 +379,7 @@ hipError_t attn_bwd_mfma(const AttnArgs& a, hipStream_t st) {
     dim3 grid((a.Sq + 127) / 128, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel<4>, grid, dim3(256), 0, st, a);
   }
+  if (!a.dk) return hipGetLastError();           // only dQ wanted (cross-attention: dK, dV feed the memory gradient)
   if (a.Sk <= 64) {
     dim3 grid((a.Sk + 63) / 64, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel<2>, grid, dim3(128), 0, st, a);

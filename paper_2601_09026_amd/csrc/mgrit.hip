@@ -149,6 +149,8 @@ struct Engine {
   int n_cache;
   void *c_qkv, *c_o, *c_z;
   float *c_lse, *c_xin;
+  void *c_qc, *c_kvc, *c_oc;       // cross-attention decoder only
+  float *c_lsec, *c_x3;
   void *cb, *dz, *du, *ds, *da, *dqkv;
   float *dxin, *Dbuf;
 
@@ -189,7 +191,15 @@ struct Engine {
     c_z = b.take_bytes(C * T * f * esz);
     c_lse = b.take<float>(C * md.batch * H * md.seq);
     c_xin = b.take<float>(C * T * d);
-    memb = nullptr;
+    memb = nullptr; c_qc = c_kvc = c_oc = nullptr; c_lsec = c_x3 = nullptr;
+    if (md.arch == MGRIT_ARCH_CROSS) {
+      c_qc = b.take_bytes(C * T * d * esz);
+      c_kvc = b.take_bytes(C * Tm * 2 * d * esz);
+      c_oc = b.take_bytes(C * T * d * esz);
+      c_lsec = b.take<float>(C * md.batch * H * md.seq);
+      c_x3 = b.take<float>(C * T * d);
+      memb = b.take_bytes((size_t)Tm * d * esz);
+    }
     carve_adjoint_work(b, gc);
   }
   void carve_adjoint_work(Bump& b, int gc) {
@@ -294,32 +304,37 @@ int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, floa
   HIPCHK(launch_attn_fwd(at, E.bf16, E.st));
 
   const bool cross = E.md.arch == MGRIT_ARCH_CROSS;
+  float* x3 = cache ? E.c_x3 : E.x3;
   // s = SA(LN1(X)) kept in fp32 (never X + s: the Euler sum must not lose the small increment)
   g = gemm_base(n, T, d, d, ob, E.Td(), cs, TH, L.offset[MGRIT_P_WO], L.offset[MGRIT_P_BO]);
-  g.out = cross ? E.x3 : xin; g.out_slot_stride = E.Td(); g.out_slots = cross ? loc : cs;
+  g.out = cross ? x3 : xin; g.out_slot_stride = E.Td(); g.out_slots = cs;
   HIPCHK(launch_gemm(g, EPI_RESID_INNER, E.bf16, E.st));
 
   if (cross) {
-    ln.X = IN; ln.xp = E.x3; ln.xp_slot_stride = E.Td(); ln.xp_slots = loc;      // LN3(X + s)
+    void* qc = cache ? E.c_qc : E.qc;
+    void* kvc = cache ? E.c_kvc : E.kvc;
+    void* oc = cache ? E.c_oc : E.o;
+    ln.X = IN; ln.xp = x3; ln.xp_slot_stride = E.Td(); ln.xp_slots = cs;         // LN3(X + s)
     ln.gamma_off = L.offset[MGRIT_P_LN3_G]; ln.beta_off = L.offset[MGRIT_P_LN3_B];
     HIPCHK(launch_ln_fwd(ln, E.bf16, E.st));
     g = gemm_base(n, T, d, d, E.u, E.Td(), loc, TH, L.offset[MGRIT_P_WQ_C], L.offset[MGRIT_P_BQ_C]);
-    g.out = E.qc; g.out_slot_stride = E.Td(); g.out_slots = loc;
+    g.out = qc; g.out_slot_stride = E.Td(); g.out_slots = cs;
     HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
     g = gemm_base(n, E.Tm, 2 * d, d, E.memb, 0, loc, TH, L.offset[MGRIT_P_WKV_C], L.offset[MGRIT_P_BKV_C]);
-    g.out = E.kvc; g.out_slot_stride = (long)E.Tm * 2 * d; g.out_slots = loc;
+    g.out = kvc; g.out_slot_stride = (long)E.Tm * 2 * d; g.out_slots = cs;
     HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
     memset(&at, 0, sizeof(at));
     at.n_groups = n; at.B = E.md.batch; at.H = E.H; at.dh = E.dh; at.Sq = E.md.seq; at.Sk = E.md.mem_seq;
     at.causal = 0;
-    at.q = E.qc; at.q_row_stride = d; at.q_slot_stride = E.Td(); at.q_slots = loc;
-    at.k = E.kvc; at.v = (char*)E.kvc + (size_t)d * esz;
+    at.q = qc; at.q_row_stride = d; at.q_slot_stride = E.Td(); at.q_slots = cs;
+    at.k = kvc; at.v = (char*)kvc + (size_t)d * esz;
     at.k_row_stride = at.v_row_stride = 2 * d;
-    at.k_slot_stride = at.v_slot_stride = (long)E.Tm * 2 * d; at.k_slots = loc;
-    at.o = E.o; at.o_row_stride = d; at.o_slot_stride = E.Td(); at.o_slots = loc;
+    at.k_slot_stride = at.v_slot_stride = (long)E.Tm * 2 * d; at.k_slots = cs;
+    at.o = oc; at.o_row_stride = d; at.o_slot_stride = E.Td(); at.o_slots = cs;
+    if (cache) { at.lse = E.c_lsec; at.lse_slot_stride = (long)E.md.batch * E.H * E.md.seq; at.lse_slots = cs; }
     HIPCHK(launch_attn_fwd(at, E.bf16, E.st));
-    g = gemm_base(n, T, d, d, E.o, E.Td(), loc, TH, L.offset[MGRIT_P_WO_C], L.offset[MGRIT_P_BO_C]);
-    g.base = E.x3; g.base_slot_stride = E.Td(); g.base_slots = loc;
+    g = gemm_base(n, T, d, d, oc, E.Td(), cs, TH, L.offset[MGRIT_P_WO_C], L.offset[MGRIT_P_BO_C]);
+    g.base = x3; g.base_slot_stride = E.Td(); g.base_slots = cs;
     g.out = xin; g.out_slot_stride = E.Td(); g.out_slots = cs;
     HIPCHK(launch_gemm(g, EPI_RESID_INNER, E.bf16, E.st));
   }
@@ -376,6 +391,44 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
   lb.out_f32 = E.dxin; lb.of_slot_stride = E.Td(); lb.of_slots = loc;
   lb.C = IN; lb.out_op = E.ds; lb.oo_slot_stride = E.Td(); lb.oo_slots = loc;
   HIPCHK(launch_ln_bwd(lb, E.bf16, E.st));
+
+  if (E.md.arch == MGRIT_ARCH_CROSS) {
+    // Here ds = c + dx2 is the cotangent of ybar = s + CA(LN3(Y + s), E); dxin = dx2.
+    // do_c = ds Wo_c
+    g = gemm_base(n, T, d, d, E.ds, E.Td(), loc, THT, L.offset[MGRIT_P_WO_C], -1);
+    g.out = E.da; g.out_slot_stride = E.Td(); g.out_slots = loc;
+    HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+    // cross-attention backward: only dQ is needed (dK, dV feed the gradient of the memory only)
+    AttnArgs ac;
+    memset(&ac, 0, sizeof(ac));
+    ac.n_groups = n; ac.B = E.md.batch; ac.H = E.H; ac.dh = E.dh; ac.Sq = E.md.seq; ac.Sk = E.md.mem_seq;
+    ac.causal = 0;
+    ac.q = E.c_qc; ac.q_row_stride = d; ac.q_slot_stride = E.Td(); ac.q_slots = cs;
+    ac.k = E.c_kvc; ac.v = (char*)E.c_kvc + (size_t)d * esz;
+    ac.k_row_stride = ac.v_row_stride = 2 * d;
+    ac.k_slot_stride = ac.v_slot_stride = (long)E.Tm * 2 * d; ac.k_slots = cs;
+    ac.o = E.c_oc; ac.o_row_stride = d; ac.o_slot_stride = E.Td(); ac.o_slots = cs;
+    ac.lse = E.c_lsec; ac.lse_slot_stride = (long)E.md.batch * E.H * E.md.seq; ac.lse_slots = cs;
+    ac.dO = E.da; ac.do_row_stride = d; ac.do_slot_stride = E.Td(); ac.do_slots = loc;
+    ac.dq = E.dqkv; ac.dk = nullptr; ac.dv = nullptr;
+    ac.dqkv_row_stride = d; ac.dqkv_slot_stride = (long)T * 3 * d; ac.dqkv_slots = loc;
+    ac.D = E.Dbuf; ac.D_slot_stride = (long)E.md.batch * E.H * E.md.seq; ac.D_slots = loc;
+    HIPCHK(launch_attn_bwd(ac, E.bf16, E.st));
+    // du3 = dq_c Wq_c
+    g = gemm_base(n, T, d, d, E.dqkv, (long)T * 3 * d, loc, THT, L.offset[MGRIT_P_WQ_C], -1);
+    g.out = E.du; g.out_slot_stride = E.Td(); g.out_slots = loc;
+    HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+    // dx3 = LN3^T du3 at Y + s;  dxin <- dx2 + dx3 (in place);  ds <- c + dx2 + dx3
+    memset(&lb, 0, sizeof(lb));
+    lb.n_groups = n; lb.T = T; lb.d = d; lb.eps = E.md.ln_eps;
+    lb.dy = E.du; lb.dy_slot_stride = E.Td(); lb.dy_slots = loc;
+    lb.X = LIN; lb.xp = E.c_x3; lb.xp_slot_stride = E.Td(); lb.xp_slots = cs;
+    lb.P = TH; lb.gamma_off = L.offset[MGRIT_P_LN3_G];
+    lb.add = E.dxin; lb.add_slot_stride = E.Td(); lb.add_slots = loc;
+    lb.out_f32 = E.dxin; lb.of_slot_stride = E.Td(); lb.of_slots = loc;
+    lb.C = IN; lb.out_op = E.ds; lb.oo_slot_stride = E.Td(); lb.oo_slots = loc;
+    HIPCHK(launch_ln_bwd(lb, E.bf16, E.st));
+  }
 
   // da = ds Wo
   g = gemm_base(n, T, d, d, E.ds, E.Td(), loc, THT, L.offset[MGRIT_P_WO], -1);
@@ -455,10 +508,12 @@ int adjoint_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Pa
 }
 
 int transpose_blocks(Engine& E, int n, Params TH, Params THT) {
-  static const int mats[] = {MGRIT_P_WQKV, MGRIT_P_WO, MGRIT_P_W1, MGRIT_P_W2};
-  for (int id : mats)
+  static const int mats[] = {MGRIT_P_WQKV, MGRIT_P_WO, MGRIT_P_W1, MGRIT_P_W2, MGRIT_P_WQ_C, MGRIT_P_WO_C};
+  for (int id : mats) {
+    if (E.lay.offset[id] < 0) continue;
     HIPCHK(launch_transpose(n, TH, THT, E.lay.offset[id], E.lay.rows[id], E.lay.cols[id], E.lay.elem_bytes[id],
                             E.st));
+  }
   return MGRIT_OK;
 }
 
@@ -630,7 +685,6 @@ int mgrit_theta_layout(const mgrit_model_desc* desc, mgrit_theta_layout_t* out) 
 
 size_t mgrit_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts, int adjoint) {
   if (validate_desc(desc) != MGRIT_OK || validate_opts(opts) != MGRIT_OK) return 0;
-  if (adjoint && desc->arch == MGRIT_ARCH_CROSS) return 0;
   Plan P;
   if (make_plan(P, desc, opts, adjoint != 0, nullptr, nullptr) != MGRIT_OK) return 0;
   return P.bytes;
@@ -638,7 +692,6 @@ size_t mgrit_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opt
 
 size_t mgrit_layer_step_workspace_bytes(const mgrit_model_desc* desc, int adjoint, int n_groups) {
   if (validate_desc(desc) != MGRIT_OK || n_groups < 1) return 0;
-  if (adjoint && desc->arch == MGRIT_ARCH_CROSS) return 0;
   Engine E;
   E.init(desc, nullptr);
   Bump b(nullptr);
@@ -706,9 +759,8 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
                   void* stream) {
   STCHK(validate_desc(desc));
   STCHK(validate_opts(opts));
-  if (desc->arch == MGRIT_ARCH_CROSS) return MGRIT_UNSUPPORTED;
   if (dmemory || dtheta) return MGRIT_UNSUPPORTED;
-  (void)memory;
+  if (desc->arch == MGRIT_ARCH_CROSS && !memory) return MGRIT_INVALID_ARG;
   if (!Z_all || !lambda_N || !lambda_all || !workspace) return MGRIT_INVALID_ARG;
   STCHK(check_ptr_array(theta, opts->N));
   const size_t need = mgrit_workspace_bytes(desc, opts, 1);
@@ -730,6 +782,8 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
   Params TH = {(const void* const*)D.tabTh, 0, 1};
   Params THT = {(const void* const*)D.tabThT, 0, 1};
   STCHK(transpose_blocks(E, N, TH, THT));
+  if (desc->arch == MGRIT_ARCH_CROSS)
+    HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
   // linearisation cache for all N layers, batched over layers
   Rows Zrows = {(const void* const*)D.tabZ, 0, 1};
   STCHK(forward_groups(E, D.E2, N, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
@@ -751,7 +805,6 @@ int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups, 
                        size_t workspace_bytes, void* stream) {
   STCHK(validate_desc(desc));
   if (n_groups < 1 || !workspace || !isfinite(hstep)) return MGRIT_INVALID_ARG;
-  if (adjoint && desc->arch == MGRIT_ARCH_CROSS) return MGRIT_UNSUPPORTED;
   STCHK(check_ptr_array(in, n_groups));
   STCHK(check_ptr_array((const void* const*)out, n_groups));
   STCHK(check_ptr_array(theta, n_groups));
@@ -788,6 +841,8 @@ int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups, 
     Rows LIN = {(const void* const*)tLin, 0, 1};
     Rows RHS = rhs ? Rows{(const void* const*)tRhs, 0, 1} : NO_ROWS;
     STCHK(transpose_blocks(E, G, TH, THT));
+    if (desc->arch == MGRIT_ARCH_CROSS)
+      HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
     STCHK(forward_groups(E, L2, G, LIN, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
     return adjoint_groups(E, L2, G, IN, OUT, RHS, TH, THT, LIN, Slots{0, 1}, hstep);
   }

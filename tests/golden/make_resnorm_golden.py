@@ -37,7 +37,7 @@ def run(name, memory=None):
     entry = {"forward": rf, "forward_evaluations": counts, "forward_seconds": time.time() - t,
              "Z_N_norm": float(np.linalg.norm(Z[-1])), "increment_norm": float(np.linalg.norm(Z[-1] - Z[0]))}
     print(name, "forward", rf, f"{entry['forward_seconds']:.0f}s", flush=True)
-    if wl.arch != wls.ARCH_CROSS:            # the adjoint of the cross-attention decoder is not built yet
+    if True:
         t = time.time()
         lam, ra, _ = omgrit.mgrit_adjoint(wls.terminal_adjoint(wl), Z, th, wl.h, wl.cf, wl.levels, wl.iters, sh,
                                           memory)

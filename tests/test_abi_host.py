@@ -93,10 +93,9 @@ def test_invalid_arguments_are_rejected_without_a_device():
     cross_no_mem = mb.ModelDesc(2, 64, 4, 256, 2, 32, 0, 0, 1e-5)
     assert L.mgrit_theta_layout(C.byref(cross_no_mem), C.byref(lay)) == -1
     assert L.mgrit_status_string(-3) == b"workspace too small"
-    # adjoint of the cross-attention decoder is not built yet
     dec = mb.model_desc(wls.named_workloads()["mt_decoder"])
-    assert mb.mgrit_workspace_bytes(dec, mb.mgrit_opts(32, 1 / 32, 4, 2, 2), True) == 0
-    assert mb.mgrit_workspace_bytes(dec, mb.mgrit_opts(32, 1 / 32, 4, 2, 2), False) > 0
+    assert mb.mgrit_workspace_bytes(dec, mb.mgrit_opts(32, 1 / 32, 4, 2, 2), True) > \
+        mb.mgrit_workspace_bytes(dec, mb.mgrit_opts(32, 1 / 32, 4, 2, 2), False) > 0
 
 
 def test_workspace_grows_with_groups_and_levels():

@@ -85,7 +85,7 @@ def run_full(name, fwd_seqs, adj_seqs, memory=None, memory_host=None, prefix=Non
     lg = None
     if adj_seqs:
         lamN = wls.terminal_adjoint(wl)
-        lg, ag = mb.mgrit_adjoint(desc, opts, Zg, dm.blocks, dev(lamN))
+        lg, ag = mb.mgrit_adjoint(desc, opts, Zg, dm.blocks, dev(lamN), memory=memory)
         torch.cuda.synchronize()
         sh1 = tode.Shape(wl.arch, wl.d_model, wl.n_heads, 1, wl.seq, wl.mem_seq, wl.ln_eps)
         for b in adj_seqs:
@@ -93,7 +93,9 @@ def run_full(name, fwd_seqs, adj_seqs, memory=None, memory_host=None, prefix=Non
             Zlin = Zg_host.get(b)
             if Zlin is None:
                 Zlin = Zg[:, r, :].cpu().numpy().astype(np.float64)
-            lr, _, _ = omgrit.mgrit_adjoint(lamN[r], list(Zlin), dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh1)
+            mem_b = None if memory_host is None else memory_host[rows_of(wl, b, wl.mem_seq)]
+            lr, _, _ = omgrit.mgrit_adjoint(lamN[r], list(Zlin), dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh1,
+                                            mem_b)
             got = lg[:, r, :].cpu().numpy().astype(np.float64)
             check_sequence(f"lambda(seq {b})", got, lr, wl.N, tol, {"far": 0, "mid": wl.N // 2})
         ag_host = ag.cpu().numpy()
@@ -114,7 +116,7 @@ def test_full_vit_small():
 def test_full_mt_encoder_then_decoder():
     Zg, _ = run_full("mt_encoder", fwd_seqs=[5, 60], adj_seqs=[60])
     enc_out = Zg[-1].contiguous()
-    run_full("mt_decoder", fwd_seqs=[5, 60], adj_seqs=[], memory=enc_out, memory_host=enc_out.cpu().numpy())
+    run_full("mt_decoder", fwd_seqs=[5, 60], adj_seqs=[60], memory=enc_out, memory_host=enc_out.cpu().numpy())
 
 
 def test_full_gpt2_small_forward():

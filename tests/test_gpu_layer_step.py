@@ -104,14 +104,16 @@ def run_adjoint_case(wl, G, hstep, with_rhs, weight_std, force_simple, max_group
         Z = [rng.standard_normal((wl.tokens, wl.d_model)).astype(np.float32) for _ in range(G)]
         Lm = [rng.standard_normal((wl.tokens, wl.d_model)).astype(np.float32) for _ in range(G)]
         R = [0.1 * rng.standard_normal((wl.tokens, wl.d_model)).astype(np.float32) for _ in range(G)]
+        mem = wls.cross_memory(wl)
         ins = [dev(x) for x in Lm]
         lin = [dev(z) for z in Z]
         outs = [torch.full_like(t, float("nan")) for t in ins]
         rhs = [dev(r) for r in R] if with_rhs else None
-        mb.layer_step_batched(dm.desc, True, ins, outs, dm.blocks, hstep, lin_state=lin, rhs=rhs)
+        mb.layer_step_batched(dm.desc, True, ins, outs, dm.blocks, hstep, lin_state=lin, rhs=rhs,
+                              memory=None if mem is None else dev(mem))
         torch.cuda.synchronize()
         for g in range(G):
-            ref = tode.psi(Lm[g], Z[g], dm.host[g], hstep, sh)
+            ref = tode.psi(Lm[g], Z[g], dm.host[g], hstep, sh, mem)
             if with_rhs:
                 ref = ref + R[g]
             base = Lm[g].astype(np.float64) + (R[g] if with_rhs else 0.0)
@@ -122,7 +124,7 @@ def run_adjoint_case(wl, G, hstep, with_rhs, weight_std, force_simple, max_group
 
 
 @pytest.mark.parametrize("force_simple", [1, 0])
-@pytest.mark.parametrize("arch", [wls.ARCH_ENCODER, wls.ARCH_CAUSAL])
+@pytest.mark.parametrize("arch", [wls.ARCH_ENCODER, wls.ARCH_CAUSAL, wls.ARCH_CROSS])
 @pytest.mark.parametrize("dtype", [wls.DTYPE_F32, wls.DTYPE_BF16])
 def test_adjoint_step_matches_oracle(arch, dtype, force_simple):
     if dtype == wls.DTYPE_F32 and not force_simple:

@@ -78,7 +78,8 @@ def run_case(wl, weight_std=0.02, relax="FCF", adjoint=False, init_from_serial=F
             lamN = wls.terminal_adjoint(wl)
             # linearise both sides about the same states: the GPU's own forward result
             Zlin = Zg.cpu().numpy()
-            lg, arg = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN))
+            lg, arg = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN),
+                                       memory=None if mem is None else dev(mem))
             torch.cuda.synchronize()
             lr, arr, _ = omgrit.mgrit_adjoint(lamN, list(Zlin), dm.host, wl.h, wl.cf, wl.levels, wl.iters,
                                               sh, mem, relax=relax)
@@ -112,8 +113,10 @@ def test_multilevel_vcycles_fp32(levels, cf, N):
     run_case(tiny(arch=wls.ARCH_CAUSAL, N=N, cf=cf, levels=levels, iters=2), weight_std=0.08, adjoint=True)
 
 
-def test_cross_attention_decoder_forward_fp32():
-    run_case(tiny(arch=wls.ARCH_CROSS, N=16, cf=4, levels=2, iters=2), weight_std=0.08)
+@pytest.mark.parametrize("levels", [2, 3])
+def test_cross_attention_decoder_forward_and_adjoint_fp32(levels):
+    run_case(tiny(arch=wls.ARCH_CROSS, N=16, cf=2 if levels == 3 else 4, levels=levels, iters=2), weight_std=0.08,
+             adjoint=True)
 
 
 @pytest.mark.parametrize("levels,cf", [(1, 4), (2, 1)])
@@ -191,3 +194,11 @@ def test_config5_mt_encoder_decoder_reduced_batch():
     Yr, rr, _ = omgrit.mgrit_forward(Y0, dm.host, dec.h, dec.cf, dec.levels, dec.iters, sh, Zr[-1])
     check_states(Yg, Yr, tol, "Z")
     check_resnorms(rg, rr, tol, float(np.linalg.norm(Yr[-1])))
+    # decoder adjoint, both sides linearised about the GPU's decoder states and encoder output
+    lamN = wls.terminal_adjoint(dec)
+    lg, ag = mb.mgrit_adjoint(dm.desc, opts, Yg, dm.blocks, dev(lamN), memory=Zg[-1].contiguous())
+    torch.cuda.synchronize()
+    lr, ar, _ = omgrit.mgrit_adjoint(lamN, list(Yg.cpu().numpy()), dm.host, dec.h, dec.cf, dec.levels, dec.iters,
+                                     sh, Zg[-1].cpu().numpy())
+    check_states(lg, lr, tol, "lambda")
+    check_resnorms(ag, ar, tol, float(np.linalg.norm(lr[0])))
