@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--no-adjoint", action="store_true", help="time mgrit_forward only")
     ap.add_argument("--max-groups", type=int, default=0, help="groups per kernel launch (0 = library default)")
     ap.add_argument("--lanes", type=int, default=0, help="1 = single stream, 2 = two lanes (0 = library default)")
+    ap.add_argument("--gemm-tile", type=int, default=0, help="tuning: force a GEMM tile configuration (0 = by shape)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not record per-kernel HIP events in the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -95,6 +96,8 @@ def main():
         mb.mgrit_set_max_groups_per_launch(args.max_groups)
     if args.lanes:
         mb.mgrit_set_lanes(args.lanes)
+    if args.gemm_tile:
+        mb.lib().mgrit_debug_gemm_tile_config(args.gemm_tile)
     desc = mb.model_desc(wl)
     opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters)
     T, d = wl.tokens, wl.d_model

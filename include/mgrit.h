@@ -196,6 +196,11 @@ int  mgrit_profile_read(int cls, double* total_ms, double* flops, double* bytes,
 /* Test hook: route GEMMs (first flag) / attention (second flag) to the generic kernels. */
 void mgrit_debug_force_simple_kernels(int gemm, int attn);
 
+/* Tuning hook: tile configuration of the MFMA grouped GEMM (0 = chosen by shape, the default;
+ * 1 = 256x256x64 and 3 = 256x192x64, one block per CU; 4 = 128x128x64 and 2 = 256x128x32, two
+ * blocks per CU).  A configuration that does not fit a shape falls back to configuration 2. */
+void mgrit_debug_gemm_tile_config(int cfg);
+
 #ifdef __cplusplus
 }
 #endif

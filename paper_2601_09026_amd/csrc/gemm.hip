@@ -84,6 +84,8 @@ __device__ __forceinline__ void epilogue4(const EpiPtrs& p, float hstep, int N, 
                   hstep, (long)m * N + n, acc);
 }
 
+constexpr int ce_gcd(int a, int b) { return b == 0 ? a : ce_gcd(b, a % b); }
+
 // Whole-tile epilogue of one wavefront of the MFMA kernel.  All operand pointers are
 // restrict-qualified parameters of this one function, so that the compiler may hoist the
 // loads of later rows above the stores of earlier ones (outputs never alias inputs).
@@ -99,11 +101,17 @@ __device__ __forceinline__ void tile_epilogue(
   if constexpr (STAGED) {
     constexpr int EP_LD = WTN * 4 + 16;                  // bytes per staged row (padded)
     constexpr int C4 = WTN / 4;                          // float4 per row
-    static_assert(64 % C4 == 0, "a lane keeps its column group over all iterations");
-    const int c4 = lane % C4, rsub = lane / C4;
-    const int n = ncol0 + 4 * c4;
-    f32x4 bv = {0.f, 0.f, 0.f, 0.f};
-    if (bias) bv = *reinterpret_cast<const f32x4*>(bias + n);   // one column group per lane for the whole tile
+    constexpr int NIT = 32 * C4 / 64;                    // float4 items per lane in a 32-row block
+    static_assert(32 * C4 % 64 == 0, "whole passes over a 32-row block");
+    // item e = it*64 + lane is float4 column e % C4 of row e / C4.  A lane's column group
+    // repeats with period NB in `it` (1 when C4 divides 64): one bias vector per phase.
+    constexpr int NB = C4 / ce_gcd(64, C4);
+    f32x4 bv[NB];
+#pragma unroll
+    for (int p = 0; p < NB; ++p) {
+      const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+      bv[p] = bias ? *reinterpret_cast<const f32x4*>(bias + ncol0 + 4 * ((p * 64 + lane) % C4)) : z;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -114,12 +122,14 @@ __device__ __forceinline__ void tile_epilogue(
           *reinterpret_cast<f32x4*>(ep + lr * EP_LD + (32 * j + 8 * q + 4 * lh) * 4) = v;
         }
 #pragma unroll
-      for (int it = 0; it < 32 * C4 / 64; ++it) {
-        const int row = it * (64 / C4) + rsub;
-        const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + c4 * 16) + bv;
+      for (int it = 0; it < NIT; ++it) {
+        const int e = it * 64 + lane;
+        const int row = e / C4, c4 = e % C4;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + c4 * 16) + bv[it % NB];
         const int m = mrow0 + 32 * i + row;
         if (m < M)
-          apply4<EPI, TO>(out_op, out_f32, z_out, z_in, base, X, ybar, RHS, OUT, hstep, (long)m * N + n, v);
+          apply4<EPI, TO>(out_op, out_f32, z_out, z_in, base, X, ybar, RHS, OUT, hstep,
+                          (long)m * N + ncol0 + 4 * c4, v);
       }
     }
   } else {
@@ -454,6 +464,44 @@ static double gemm_bytes(const GemmArgs& a, double esz) {
   return b;
 }
 
+// Compute units of the current device (256 if the query fails).
+static int compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
+      cus = 256;
+    n = cus;
+  }
+  return n;
+}
+
+// Tile configurations of the MFMA kernel (BK = 64, two stages, unless noted):
+//  1: 256x256, 8 wavefronts 2x4 (128x64 each, two per SIMD), one block per CU;
+//  3: 256x192, 8 wavefronts 4x2 (64x96 each), one block per CU;
+//  4: 128x128, 4 wavefronts (64x64 each), two blocks per CU;
+//  2: 256x128x32, three stages, 4 wavefronts (128x64 each), two blocks per CU: any N % 128 == 0.
+// A launch runs in rounds of (CUs x blocks per CU) tiles.  Measured on MI355X at 768..3072 wide
+// operands, the time of a round hardly depends on how full it is, and relative to a round of
+// 256x256 tiles a round of 256x192 tiles takes 0.9 and a (double) round of 128x128 tiles 0.62:
+// pick the configuration with the cheapest sum of rounds.
+static int choose_tile_config(int n_groups, int M, int N) {
+  struct Cand { int cfg, bm, bn, occ; double round_cost; };
+  static const Cand cands[] = {{1, 256, 256, 1, 1.0}, {3, 256, 192, 1, 0.9}, {4, 128, 128, 2, 0.62}};
+  const long cus = compute_units();
+  int best = 2;
+  double best_cost = 1e30;
+  for (const Cand& c : cands) {
+    if (N % c.bn != 0) continue;
+    const long tiles = (long)((M + c.bm - 1) / c.bm) * (N / c.bn) * n_groups;
+    const long rounds = (tiles + cus * c.occ - 1) / (cus * c.occ);
+    const double cost = rounds * c.round_cost;
+    if (cost < best_cost) { best_cost = cost; best = c.cfg; }
+  }
+  return best;
+}
+
 template <int EPI>
 static hipError_t launch_epi(const GemmArgs& a, bool is_bf16, hipStream_t st) {
   if (a.n_groups <= 0 || a.M <= 0) return hipSuccess;
@@ -464,23 +512,17 @@ static hipError_t launch_epi(const GemmArgs& a, bool is_bf16, hipStream_t st) {
   ProfScope ps(mfma_ok ? PC_GEMM_MFMA + EPI : PC_GEMM_SIMPLE, flops, gemm_bytes<EPI>(a, is_bf16 ? 2 : 4), st);
   if (!is_bf16) return launch_simple<float, EPI>(a, st);
   if (!mfma_ok) return launch_simple<bf16, EPI>(a, st);
-  // Tile choice (measured on MI355X at the benchmark shapes, 8 groups of 4096 rows):
-  //  1: 256x256x64, two stages, 8 wavefronts (2x4, 128x64 each, two per SIMD so that one can
-  //     issue memory instructions while the other feeds the MFMA pipe): best where N is a
-  //     multiple of 256;
-  //  2: 256x128x32, three stages, 4 wavefronts, two blocks per CU: for the other widths.
   int cfg = g_tile_cfg;
-  if (cfg == 0) cfg = (a.N % 256 == 0) ? 1 : 2;
+  if (cfg == 0) cfg = choose_tile_config(a.n_groups, a.M, a.N);
   switch (cfg) {
     case 1: if (a.N % 256 == 0) return launch_mfma<256, 256, 64, 2, 1, true, EPI, 2, 4>(a, st); break;
     case 2: return launch_mfma<256, 128, 32, 3, 2, true, EPI>(a, st);
+    case 3: if (a.N % 192 == 0) return launch_mfma<256, 192, 64, 2, 1, true, EPI, 4, 2>(a, st); break;
+    case 4: return launch_mfma<128, 128, 64, 2, 2, true, EPI>(a, st);
 #ifdef MG_GEMM_DEBUG
-    case 3: if (a.N % 256 == 0) return launch_mfma<256, 256, 64, 2, 1, true, EPI>(a, st); break;
-    case 4: return launch_mfma<128, 128, 64, 2, 2, false, EPI>(a, st);
     case 5: return launch_mfma<256, 128, 32, 2, 2, true, EPI>(a, st);
     case 6: if (a.N % 256 == 0) return launch_mfma<256, 256, 64, 2, 1, true, EPI, 2, 4>(a, st); break;
     case 7: if (a.N % 256 == 0) return launch_mfma<256, 256, 32, 4, 1, true, EPI, 2, 4>(a, st); break;
-    case 8: return launch_mfma<128, 128, 64, 2, 2, true, EPI>(a, st);
     case 9: return launch_mfma<256, 128, 64, 2, 1, true, EPI, 4, 2>(a, st);
     case 10: return launch_mfma<256, 128, 32, 3, 2, true, EPI, 4, 2>(a, st);
 #endif

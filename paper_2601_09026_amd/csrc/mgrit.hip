@@ -885,4 +885,6 @@ void mgrit_debug_force_simple_kernels(int gemm, int attn) {
   attn_force_simple(attn);
 }
 
+void mgrit_debug_gemm_tile_config(int cfg) { gemm_set_tile_config(cfg); }
+
 }  // extern "C"
