@@ -75,6 +75,29 @@ __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restric
   }
 }
 
+// 8 consecutive columns of a bf16 output (the epilogues whose operands are all bf16)
+__device__ __forceinline__ void store8(bf16* p, f32x4 a, f32x4 b) {
+  bf16x8 r = {(bf16)a[0], (bf16)a[1], (bf16)a[2], (bf16)a[3], (bf16)b[0], (bf16)b[1], (bf16)b[2], (bf16)b[3]};
+  *reinterpret_cast<bf16x8*>(p) = r;
+}
+template <int EPI>
+__device__ __forceinline__ void apply8(bf16* __restrict__ out, bf16* __restrict__ z_out,
+                                       const bf16* __restrict__ z_in, long idx, f32x4 a, f32x4 b) {
+  if constexpr (EPI == EPI_STORE) {
+    store8(out + idx, a, b);
+  } else if constexpr (EPI == EPI_GELU) {
+    if (z_out) store8(z_out + idx, a, b);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { a[r] = gelu_fast(a[r]); b[r] = gelu_fast(b[r]); }
+    store8(out + idx, a, b);
+  } else if constexpr (EPI == EPI_DGELU) {
+    const bf16x8 z = *reinterpret_cast<const bf16x8*>(z_in + idx);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { a[r] *= gelu_prime_fast((float)z[r]); b[r] *= gelu_prime_fast((float)z[4 + r]); }
+    store8(out + idx, a, b);
+  }
+}
+
 // one-off form for the generic kernel
 template <int EPI, typename TO>
 __device__ __forceinline__ void epilogue4(const EpiPtrs& p, float hstep, int N, int m, int n, f32x4 acc) {
@@ -100,18 +123,25 @@ __device__ __forceinline__ void tile_epilogue(
   const int lr = lane & 31, lh = lane >> 5;
   if constexpr (STAGED) {
     constexpr int EP_LD = WTN * 4 + 16;                  // bytes per staged row (padded)
-    constexpr int C4 = WTN / 4;                          // float4 per row
-    constexpr int NIT = 32 * C4 / 64;                    // float4 items per lane in a 32-row block
-    static_assert(32 * C4 % 64 == 0, "whole passes over a 32-row block");
-    // item e = it*64 + lane is float4 column e % C4 of row e / C4.  A lane's column group
-    // repeats with period NB in `it` (1 when C4 divides 64): one bias vector per phase.
-    constexpr int NB = C4 / ce_gcd(64, C4);
-    f32x4 bv[NB];
+    // A lane finishes CW consecutive columns at a time: 8 where the output is bf16 (16-byte
+    // stores: four lanes fill a 64-byte sector, so the memory side never has to read a sector
+    // back in order to merge a partial write), 4 where it is fp32.
+    constexpr bool WIDE = sizeof(TO) == 2 && (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_DGELU);
+    constexpr int CW = WIDE ? 8 : 4;
+    constexpr int CI = WTN / CW;                         // items per row
+    constexpr int NIT = 32 * CI / 64;                    // items per lane in a 32-row block
+    static_assert(32 * CI % 64 == 0, "whole passes over a 32-row block");
+    // item e = it*64 + lane is column group e % CI of row e / CI.  A lane's column group
+    // repeats with period NB in `it` (1 when CI divides 64): one bias vector per phase.
+    constexpr int NB = CI / ce_gcd(64, CI);
+    f32x4 bv[NB][CW / 4];
 #pragma unroll
-    for (int p = 0; p < NB; ++p) {
-      const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-      bv[p] = bias ? *reinterpret_cast<const f32x4*>(bias + ncol0 + 4 * ((p * 64 + lane) % C4)) : z;
-    }
+    for (int p = 0; p < NB; ++p)
+#pragma unroll
+      for (int h = 0; h < CW / 4; ++h) {
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        bv[p][h] = bias ? *reinterpret_cast<const f32x4*>(bias + ncol0 + CW * ((p * 64 + lane) % CI) + 4 * h) : z;
+      }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -124,12 +154,19 @@ __device__ __forceinline__ void tile_epilogue(
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
         const int e = it * 64 + lane;
-        const int row = e / C4, c4 = e % C4;
-        const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + c4 * 16) + bv[it % NB];
+        const int row = e / CI, ci = e % CI;
+        const unsigned char* src = ep + row * EP_LD + ci * CW * 4;
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(src) + bv[it % NB][0];
         const int m = mrow0 + 32 * i + row;
-        if (m < M)
-          apply4<EPI, TO>(out_op, out_f32, z_out, z_in, base, X, ybar, RHS, OUT, hstep,
-                          (long)m * N + ncol0 + 4 * c4, v);
+        const long idx = (long)m * N + ncol0 + CW * ci;
+        if constexpr (WIDE) {
+          const f32x4 v1 = *reinterpret_cast<const f32x4*>(src + 16) + bv[it % NB][1];
+          if (m < M)
+            apply8<EPI>(reinterpret_cast<bf16*>(out_op), reinterpret_cast<bf16*>(z_out),
+                        reinterpret_cast<const bf16*>(z_in), idx, v0, v1);
+        } else {
+          if (m < M) apply4<EPI, TO>(out_op, out_f32, z_out, z_in, base, X, ybar, RHS, OUT, hstep, idx, v0);
+        }
       }
     }
   } else {
@@ -206,7 +243,7 @@ template <int BK> __device__ __forceinline__ int swz(int row) {
 template <int BM, int BN, int BK, int STAGES, int OCC, bool STAGED, int EPI, typename TO, int DBG = 0,
           int WM = 2, int WN = 2>
 __global__ void __launch_bounds__(64 * WM * WN, OCC)
-gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd) {
+gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd, int pm, int pn) {
   constexpr int NW = WM * WN;                            // wavefronts per block
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -223,15 +260,27 @@ gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, in
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem2[];
 
   // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, so give each
-  // XCD one contiguous range of tiles (neighbouring tiles share an activation row panel and
-  // the group's weight matrix in that XCD's L2).
+  // XCD one contiguous range of tiles.  Inside a group's tile grid the order runs over
+  // pm x pn patches (pn = 0: plain row-major): the tiles an XCD runs at the same time then
+  // share pm activation row panels and a pn-tile-wide slice of the weight matrix, which fit
+  // that XCD's L2 together, and successive patches keep the row panels.
   const int pid = blockIdx.x;
   const int tile = (pid & 7) * per_xcd + (pid >> 3);
   if (tile >= total_tiles) return;
   const int tiles_per_group = tiles_m * tiles_n;
   const int g = tile / tiles_per_group;
   const int tg = tile - g * tiles_per_group;
-  const int tm = tg / tiles_n, tn = tg - tm * tiles_n;
+  int tm, tn;
+  if (pn > 0) {
+    const int patch = pm * pn, patches_n = tiles_n / pn;
+    const int b = tg / patch, w = tg - b * patch;
+    const int bm = b / patches_n, bn = b - bm * patches_n;
+    tm = bm * pm + w / pn;
+    tn = bn * pn + w % pn;
+  } else {
+    tm = tg / tiles_n;
+    tn = tg - tm * tiles_n;
+  }
   const int m0 = tm * BM, n0 = tn * BN;
 
   const bf16* A = reinterpret_cast<const bf16*>(a.A) + a.a_slots.of(g) * a.a_slot_stride;
@@ -411,6 +460,19 @@ void gemm_force_simple(int on) { g_force_simple = on; }
 void gemm_set_tile_config(int cfg) { g_tile_cfg = cfg; }
 void gemm_set_debug_mode(int m) { g_dbg_mode = m; }
 
+// Compute units of the current device (256 if the query fails).
+static int compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
+      cus = 256;
+    n = cus;
+  }
+  return n;
+}
+
 template <int BM, int BN, int BK, int STAGES, int OCC, bool STAGED, int EPI, int WM = 2, int WN = 2>
 static hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = a.N / BN;
@@ -419,6 +481,13 @@ static hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
   const size_t ring = (size_t)STAGES * (BM + BN) * BK * 2;
   const size_t staging = STAGED ? (size_t)WM * WN * ((32 * (BN / WN * 4 + 16) + 1023) / 1024 * 1024) : 0;
   const size_t smem = ring > staging ? ring : staging;
+  // patch shape of the tile order: as many tiles as one XCD runs at a time, pn wide
+  int pm = 0, pn = 0;
+  const int resident = compute_units() / 8 * OCC;
+  if (tiles_n > 4 && tiles_n % 4 == 0 && resident % 4 == 0 && tiles_m % (resident / 4) == 0) {
+    pn = 4;
+    pm = resident / 4;
+  }
   auto kern = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 0, WM, WN>;
   static bool attr_done = false;
   if (!attr_done) {
@@ -434,11 +503,12 @@ static hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
     auto k3 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 3, WM, WN>;
     auto kd = g_dbg_mode == 1 ? k1 : (g_dbg_mode == 2 ? k2 : k3);
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kd), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    hipLaunchKernelGGL(kd, dim3(per_xcd * 8), dim3(64 * WM * WN), smem, st, a, tiles_m, tiles_n, total, per_xcd);
+    hipLaunchKernelGGL(kd, dim3(per_xcd * 8), dim3(64 * WM * WN), smem, st, a, tiles_m, tiles_n, total, per_xcd, pm, pn);
     return hipGetLastError();
   }
 #endif
-  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(64 * WM * WN), smem, st, a, tiles_m, tiles_n, total, per_xcd);
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(64 * WM * WN), smem, st, a, tiles_m, tiles_n, total,
+                     per_xcd, pm, pn);
   return hipGetLastError();
 }
 
@@ -462,19 +532,6 @@ static double gemm_bytes(const GemmArgs& a, double esz) {
   if (EPI == EPI_RESID_INNER) b += G * MN * 4 * (a.base ? 2 : 1);
   if (EPI == EPI_RESID_OUTER) b += G * MN * 4 * (a.RHS.present() ? 4 : 3);
   return b;
-}
-
-// Compute units of the current device (256 if the query fails).
-static int compute_units() {
-  static int n = 0;
-  if (n == 0) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
-      cus = 256;
-    n = cus;
-  }
-  return n;
 }
 
 // Tile configurations of the MFMA kernel (BK = 64, two stages, unless noted):
