@@ -172,9 +172,10 @@ def main():
             ach = fl / (ms * 1e-3) / 1e12
             roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel (grouped projection GEMMs, all epilogues)",
                         "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                        "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                        "frac": ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(wl, adjoint),
                         "launches_per_step": n / args.steps, "avg_launch_us": ms * 1e3 / n,
                         "flop_per_launch": fl / n,
+                        "algorithmic_bytes_per_launch": sum(v["bytes"] for v in gemm) / n,
                         "share_of_instrumented_step_time": ms / args.steps / events_ms_per_step,
                         "instrumented_ms_per_step": events_ms_per_step}
         else:
@@ -220,6 +221,22 @@ def main():
         out["cpu_baseline"] = cpu_baseline(wl, n_phi, n_psi, args.cpu_seconds)
         out["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
     print(json.dumps(out))
+
+
+def measured_traffic(wl, adjoint):
+    """HBM bytes per grouped-GEMM launch (FETCH_SIZE + WRITE_SIZE, scaled by what the same counters
+    read for a plain copy) from the committed rocprofv3 --pmc summary of this workload, or None when
+    no summary covers it.  Counters cannot be read from inside this process."""
+    if not adjoint:
+        return None
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        f"{wl.name}_fwd_adjoint_pmc_summary.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_gemm_launch:"):
+            return float(line.split(":")[1])
+    return None
 
 
 def fold(mb, totals):
