@@ -201,6 +201,18 @@ def serial_adjoint(lamN, Z, theta, h, sh, mem=None):
     return mu[::-1]
 
 
+def parameter_gradients(lam, Z, theta, h, sh, mem=None):
+    """dtheta_n = h * (dF/dtheta_n (Z_n))^T lambda_{n+1} for n = 0..N-1 (paper section 3.1: with
+    lambda the adjoint states of the Euler network, this is the gradient of the loss with respect
+    to layer n's parameters; with MGRIT's inexact Z and lambda it is the paper's inexact
+    gradient).  lam and Z are indexed by n = 0..N.  Returns a list of dicts shaped like theta."""
+    out = []
+    for n, th in enumerate(theta):
+        g = tode.F_param_vjp(Z[n], th, lam[n + 1], sh, mem)
+        out.append({k: h * v for k, v in g.items()})
+    return out
+
+
 def mgrit_adjoint(lamN, Z, theta, h, cf, levels, iters, sh, mem=None, relax="FCF", init=None):
     """Returns (lambda_0..lambda_N, residual norms, evaluation counts per level)."""
     N = len(theta)

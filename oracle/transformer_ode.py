@@ -29,7 +29,9 @@ Q | K | V, head j owning rows j*d_h .. (j+1)*d_h of each third.
 
 Pins (tests/test_oracle_*.py): h=1 step == torch's pre-LN encoder / decoder
 layer in fp64; VJP == torch.autograd on an independent torch forward; central
-finite differences; <c, J v> == <J^T c, v>; zero weights => F == 0.
+finite differences; <c, J v> == <J^T c, v>; zero weights => F == 0; parameter
+cotangents == torch.autograd with respect to torch's own block parameters and
+central finite differences in single parameter entries.
 """
 from __future__ import annotations
 
@@ -248,6 +250,88 @@ def F_vjp(X, th, c, sh: Shape, mem=None):
     du1 = _self_attention_vjp(ds, u1, th, sh, causal)
     dX += _layer_norm_vjp(du1, X, g1, eps)
     return dX, dE
+
+
+def _layer_norm_param_vjp(dy, x, eps):
+    """Cotangents (dgamma, dbeta) of y = LN(x) * gamma + beta: sums over tokens."""
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    xhat = (x - mu) / np.sqrt(var + eps)
+    return (dy * xhat).sum(axis=0), dy.sum(axis=0)
+
+
+def F_param_vjp(X, th, c, sh: Shape, mem=None):
+    """(dF/dtheta)^T c at state X: one array per parameter of the block, shaped like it.
+
+    With c = lambda_{n+1} and X = Z_n this is, up to the factor h, the gradient of the loss with
+    respect to layer n's parameters (paper section 3.1: the adjoint variable is the
+    back-propagated gradient; theta enters the step only through h * F).  Every linear map
+    y = u W^T + b contributes dW = dy^T u and db = sum over tokens of dy; LayerNorm contributes
+    sums of dy * xhat and dy.  Written out operator by operator, no reuse of F_vjp.
+    """
+    X, c = _f64(X), _f64(c)
+    eps = sh.ln_eps
+    d, H, B, S = sh.d_model, sh.n_heads, sh.batch, sh.seq
+    causal = sh.arch != ARCH_ENCODER
+    g1, b1 = _f64(th["ln1_g"]), _f64(th["ln1_b"])
+    g2, b2 = _f64(th["ln2_g"]), _f64(th["ln2_b"])
+    Wqkv, Wo, W1, W2 = _f64(th["Wqkv"]), _f64(th["Wo"]), _f64(th["W1"]), _f64(th["W2"])
+    out = {}
+    # forward quantities
+    u1 = layer_norm(X, g1, b1, eps)
+    qkv = u1 @ Wqkv.T + _f64(th["bqkv"])
+    q = _split_heads(qkv[:, 0:d], B, S, H)
+    k = _split_heads(qkv[:, d:2 * d], B, S, H)
+    v = _split_heads(qkv[:, 2 * d:3 * d], B, S, H)
+    o = _merge_heads(attention_probs(q, k, causal) @ v)
+    s = o @ Wo.T + _f64(th["bo"])
+    if sh.arch == ARCH_CROSS:
+        g3, b3 = _f64(th["ln3_g"]), _f64(th["ln3_b"])
+        Wq, Wkv, Woc = _f64(th["Wq_c"]), _f64(th["Wkv_c"]), _f64(th["Wo_c"])
+        mem = _f64(mem)
+        Sm = sh.mem_seq
+        x3 = X + s
+        u3 = layer_norm(x3, g3, b3, eps)
+        qc = _split_heads(u3 @ Wq.T + _f64(th["bq_c"]), B, S, H)
+        kvc = mem @ Wkv.T + _f64(th["bkv_c"])
+        kc = _split_heads(kvc[:, 0:d], B, Sm, H)
+        vc = _split_heads(kvc[:, d:2 * d], B, Sm, H)
+        oc = _merge_heads(attention_probs(qc, kc, False) @ vc)
+        ybar = s + oc @ Woc.T + _f64(th["bo_c"])
+    else:
+        ybar = s
+    x2 = X + ybar
+    u2 = layer_norm(x2, g2, b2, eps)
+    z = u2 @ W1.T + _f64(th["b1"])
+    a = gelu(z)
+    # F = ybar + m,  m = a W2^T + b2
+    out["W2"], out["b2"] = c.T @ a, c.sum(axis=0)
+    dz = (c @ W2) * gelu_prime(z)
+    out["W1"], out["b1"] = dz.T @ u2, dz.sum(axis=0)
+    du2 = dz @ W1
+    out["ln2_g"], out["ln2_b"] = _layer_norm_param_vjp(du2, x2, eps)
+    dybar = c + _layer_norm_vjp(du2, x2, g2, eps)
+    if sh.arch == ARCH_CROSS:
+        out["Wo_c"], out["bo_c"] = dybar.T @ oc, dybar.sum(axis=0)
+        doc = _split_heads(dybar @ Woc, B, S, H)
+        dqc, dkc, dvc = _attention_core_vjp(doc, qc, kc, vc, causal=False)
+        dqc = _merge_heads(dqc)
+        dkvc = np.concatenate([_merge_heads(dkc), _merge_heads(dvc)], axis=1)
+        out["Wq_c"], out["bq_c"] = dqc.T @ u3, dqc.sum(axis=0)
+        out["Wkv_c"], out["bkv_c"] = dkvc.T @ mem, dkvc.sum(axis=0)
+        du3 = dqc @ Wq
+        out["ln3_g"], out["ln3_b"] = _layer_norm_param_vjp(du3, x3, eps)
+        ds = dybar + _layer_norm_vjp(du3, x3, g3, eps)
+    else:
+        ds = dybar
+    out["Wo"], out["bo"] = ds.T @ o, ds.sum(axis=0)
+    do = _split_heads(ds @ Wo, B, S, H)
+    dq, dk, dv = _attention_core_vjp(do, q, k, v, causal)
+    dqkv = np.concatenate([_merge_heads(dq), _merge_heads(dk), _merge_heads(dv)], axis=1)
+    out["Wqkv"], out["bqkv"] = dqkv.T @ u1, dqkv.sum(axis=0)
+    du1 = dqkv @ Wqkv
+    out["ln1_g"], out["ln1_b"] = _layer_norm_param_vjp(du1, X, eps)
+    return out
 
 
 def psi(lam, Z, th, hstep, sh: Shape, mem=None):

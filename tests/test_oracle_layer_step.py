@@ -197,3 +197,65 @@ def test_sequences_are_independent():
     for b in range(3):
         one = tode.phi(X[b * 4:(b + 1) * 4], th[0], 0.3, sh1)
         assert np.abs(one - full[b * 4:(b + 1) * 4]).max() < 1e-13
+
+
+# ---------------------------------------------------------------------------
+# parameter cotangents (dF/dtheta)^T c
+# ---------------------------------------------------------------------------
+def torch_param_grads(wl, L, grads_of):
+    """torch's gradients, renamed to the oracle's parameter names."""
+    g = {n: p.grad.numpy() for n, p in L.named_parameters()}
+    out = {"Wqkv": g["self_attn.in_proj_weight"], "bqkv": g["self_attn.in_proj_bias"],
+           "Wo": g["self_attn.out_proj.weight"], "bo": g["self_attn.out_proj.bias"],
+           "ln1_g": g["norm1.weight"], "ln1_b": g["norm1.bias"],
+           "W1": g["linear1.weight"], "b1": g["linear1.bias"],
+           "W2": g["linear2.weight"], "b2": g["linear2.bias"]}
+    if wl.arch == wls.ARCH_CROSS:
+        d = wl.d_model
+        out.update({"ln3_g": g["norm2.weight"], "ln3_b": g["norm2.bias"],
+                    "ln2_g": g["norm3.weight"], "ln2_b": g["norm3.bias"],
+                    "Wq_c": g["multihead_attn.in_proj_weight"][:d], "Wkv_c": g["multihead_attn.in_proj_weight"][d:],
+                    "bq_c": g["multihead_attn.in_proj_bias"][:d], "bkv_c": g["multihead_attn.in_proj_bias"][d:],
+                    "Wo_c": g["multihead_attn.out_proj.weight"], "bo_c": g["multihead_attn.out_proj.bias"]})
+    else:
+        out.update({"ln2_g": g["norm2.weight"], "ln2_b": g["norm2.bias"]})
+    return out
+
+
+@pytest.mark.parametrize("arch", ARCHS)
+def test_parameter_cotangents_equal_autograd(arch):
+    wl, sh, th = small(arch)
+    X = wls.initial_state(wl).astype(np.float64)
+    c = wls.terminal_adjoint(wl).astype(np.float64)
+    mem = wls.cross_memory(wl)
+    L = torch_layer(wl, th[0])
+    xt = torch.tensor(X)
+    mt = None if mem is None else torch.tensor(mem, dtype=torch.float64)
+    Fx = torch_step(wl, L, xt, mt, 1.0) - xt
+    (Fx * torch.tensor(c)).sum().backward()
+    ref = torch_param_grads(wl, L, None)
+    got = tode.F_param_vjp(X, th[0], c, sh, mem)
+    assert set(got) == set(wls.param_shapes(wl)) == set(ref)
+    for name, r in ref.items():
+        assert got[name].shape == tuple(wls.param_shapes(wl)[name]), name
+        assert np.abs(got[name] - r).max() < 1e-11 * max(1.0, np.abs(r).max()), name
+
+
+@pytest.mark.parametrize("arch", ARCHS)
+def test_parameter_cotangents_finite_differences(arch):
+    wl, sh, th = small(arch, d=16, H=2, f=24, B=2, S=4, Sm=3)
+    X = wls.initial_state(wl).astype(np.float64)
+    c = wls.terminal_adjoint(wl).astype(np.float64)
+    mem = wls.cross_memory(wl)
+    got = tode.F_param_vjp(X, th[0], c, sh, mem)
+    eps = 1e-6
+    rng = np.random.default_rng(11)
+    for name, shape in wls.param_shapes(wl).items():
+        for _ in range(2):
+            idx = tuple(int(rng.integers(0, n)) for n in shape)
+            tp = {k: np.array(v, dtype=np.float64) for k, v in th[0].items()}
+            tm = {k: np.array(v, dtype=np.float64) for k, v in th[0].items()}
+            tp[name][idx] += eps
+            tm[name][idx] -= eps
+            fd = ((c * tode.F(X, tp, sh, mem)).sum() - (c * tode.F(X, tm, sh, mem)).sum()) / (2 * eps)
+            assert abs(fd - got[name][idx]) < 1e-6 * max(1.0, abs(fd)), (name, idx)

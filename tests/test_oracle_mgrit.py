@@ -317,3 +317,32 @@ def test_coarse_level_is_first_order_approximation():
         coarse = mgrit.serial_forward(Z0, th[: N // 2], 2 * h, sh)[-1]
         gaps.append(np.linalg.norm(fine - coarse))
     assert 1.6 < gaps[0] / gaps[1] < 2.4 and 1.6 < gaps[1] / gaps[2] < 2.4
+
+
+def test_parameter_gradients_are_the_gradient_of_the_serial_network():
+    """dtheta_n = d<C, Z_N>/dtheta_n: central finite differences through the serial forward pass in
+    single entries of several layers' parameters, and exact linearity in the terminal adjoint."""
+    wl, sh, th = tiny(N=5, h=0.5, std=0.4)
+    Z0 = wls.initial_state(wl).astype(np.float64)
+    C = wls.terminal_adjoint(wl).astype(np.float64)
+    Z = mgrit.serial_forward(Z0, th, wl.h, sh)
+    lam = mgrit.serial_adjoint(C, Z, th, wl.h, sh)
+    grads = mgrit.parameter_gradients(lam, Z, th, wl.h, sh)
+    assert len(grads) == wl.N
+    rng = np.random.default_rng(5)
+    eps = 1e-6
+    for n in (0, 2, 4):
+        for name, shape in wls.param_shapes(wl).items():
+            idx = tuple(int(rng.integers(0, s)) for s in shape)
+            def loss(delta):
+                t = [dict(x) for x in th]
+                w = np.array(t[n][name], dtype=np.float64)
+                w[idx] += delta
+                t[n][name] = w
+                return (C * mgrit.serial_forward(Z0, t, wl.h, sh)[-1]).sum()
+            fd = (loss(eps) - loss(-eps)) / (2 * eps)
+            assert abs(fd - grads[n][name][idx]) < 2e-6 * max(1.0, abs(fd)), (n, name, idx)
+    lam2 = mgrit.serial_adjoint(-3.0 * C, Z, th, wl.h, sh)
+    g2 = mgrit.parameter_gradients(lam2, Z, th, wl.h, sh)
+    for name in grads[1]:
+        assert np.allclose(g2[1][name], -3.0 * grads[1][name], rtol=1e-12, atol=1e-14)
