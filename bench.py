@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--max-groups", type=int, default=0, help="groups per kernel launch (0 = library default)")
     ap.add_argument("--lanes", type=int, default=0, help="1 = single stream, 2 = two lanes (0 = library default)")
     ap.add_argument("--gemm-tile", type=int, default=0, help="tuning: force a GEMM tile configuration (0 = by shape)")
+    ap.add_argument("--param-grads", action="store_true",
+                    help="also produce the parameter gradients in every step (not part of the headline metric: "
+                         "the line then says so in `metric` and in config.param_grads)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not record per-kernel HIP events in the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -112,8 +115,15 @@ def main():
     lam_all = torch.empty_like(Z_all) if adjoint else None
     res_f = torch.zeros(max(wl.iters, 1), dtype=torch.float32, device="cuda")
     res_a = torch.zeros(max(wl.iters, 1), dtype=torch.float32, device="cuda")
-    ws_bytes = max(mb.mgrit_workspace_bytes(desc, opts, False),
-                   mb.mgrit_workspace_bytes(desc, opts, True) if adjoint else 0, 256)
+    grads = None
+    if args.param_grads:
+        if not adjoint or wl.arch == wls.ARCH_CROSS:
+            print("bench.py: --param-grads needs the adjoint and an encoder or causal workload", file=sys.stderr)
+            sys.exit(2)
+        gbytes = mb.grad_layout(desc).block_bytes
+        grads = [torch.empty(gbytes, dtype=torch.uint8, device="cuda") for _ in range(wl.N)]
+    ws_bytes = max(mb.mgrit_workspace_bytes(desc, opts, 0),
+                   mb.mgrit_workspace_bytes(desc, opts, 2 if grads else 1) if adjoint else 0, 256)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     n_phi = mb.mgrit_step_evaluations(opts)
     n_psi = n_phi if adjoint else 0
@@ -124,7 +134,7 @@ def main():
                          stream=stream)
         if adjoint:
             mb.mgrit_adjoint(desc, opts, Z_all, theta, lamN, memory=mem, lambda_all=lam_all, resnorm=res_a,
-                             workspace=ws, stream=stream)
+                             workspace=ws, stream=stream, dtheta=grads)
 
     for _ in range(args.warmup):
         step()
@@ -204,7 +214,8 @@ def main():
         print(f"{'wall, timed pass':28s} {'':13s} {ms_per_step:9.3f}", file=sys.stderr)
 
     out = {
-        "metric": "MGRIT fwd+adjoint layer-steps*tokens/sec" if adjoint else "MGRIT fwd layer-steps*tokens/sec",
+        "metric": ("MGRIT fwd+adjoint+param-grads layer-steps*tokens/sec" if grads else
+                   "MGRIT fwd+adjoint layer-steps*tokens/sec" if adjoint else "MGRIT fwd layer-steps*tokens/sec"),
         "value": value, "unit": "layer-steps*tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if wl.dtype == wls.DTYPE_BF16 else "f32", "data": "synthetic",
@@ -212,7 +223,8 @@ def main():
                    "batch": wl.batch, "seq": wl.seq, "N": wl.N, "h": wl.h, "cf": wl.cf, "levels": wl.levels,
                    "iters": wl.iters, "relax": "FCF", "adjoint": adjoint,
                    "phi_evaluations": n_phi, "psi_evaluations": n_psi,
-                   "max_groups_per_launch": args.max_groups or "default", "lanes": args.lanes or 2},
+                   "max_groups_per_launch": args.max_groups or "default", "lanes": args.lanes or 2,
+                   "param_grads": bool(grads)},
         "residual_norms": {"forward": [float(x) for x in res_f.cpu()[:wl.iters]],
                            "adjoint": [float(x) for x in res_a.cpu()[:wl.iters]] if adjoint else None},
         "roofline": roofline,

@@ -107,7 +107,9 @@ typedef struct mgrit_theta_layout_t {
 /* Fills *out for the given model.  Host only, no GPU needed. */
 int mgrit_theta_layout(const mgrit_model_desc* desc, mgrit_theta_layout_t* out);
 
-/* Workspace sizes in bytes (0 on invalid arguments).  Host only. */
+/* Workspace sizes in bytes (0 on invalid arguments).  Host only.
+ * mgrit_workspace_bytes: adjoint = 0 for mgrit_forward, 1 for mgrit_adjoint, 2 for
+ * mgrit_adjoint called with dtheta (parameter gradients need transposed operand copies). */
 size_t mgrit_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts, int adjoint);
 size_t mgrit_layer_step_workspace_bytes(const mgrit_model_desc* desc, int adjoint, int n_groups);
 
@@ -140,9 +142,18 @@ int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts,
  *   lambda_all device, [(N+1),T,d] fp32 out: row n = lambda_n; row N = copy of lambda_N,
  *              row 0 = dL/dZ_0
  *   memory     as in mgrit_forward (required for arch 2: the decoder is linearised with it)
- *   dmemory, dtheta  reserved, must be NULL in this build (MGRIT_UNSUPPORTED otherwise): the
- *              gradients with respect to the cross-attention memory and the parameters are
- *              not produced yet
+ *   dtheta     NULL, or HOST array of N device pointers to gradient blocks (out).  Block n
+ *              receives  h * (dF/dtheta_n (Z_n))^T lambda_{n+1}  (sec. 3.1: with the adjoint
+ *              states of the Euler network this is dL/dtheta_n; with MGRIT's inexact Z and
+ *              lambda, the paper's inexact gradient), computed from the final lambda in one
+ *              pass batched over all layers.  A gradient block is laid out like the fp32
+ *              parameter block of the same model (mgrit_theta_layout on a copy of desc with
+ *              dtype = MGRIT_DTYPE_F32), every entry fp32, whatever desc->dtype is; entries
+ *              are overwritten, not accumulated.  Needs the workspace of
+ *              mgrit_workspace_bytes(desc, opts, 2).  Encoder and causal blocks only:
+ *              MGRIT_UNSUPPORTED for arch 2.
+ *   dmemory    reserved, must be NULL (MGRIT_UNSUPPORTED otherwise): the gradient with respect
+ *              to the cross-attention memory is not produced yet
  */
 int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts,
                   const void* Z_all, const void* const* theta, const void* memory,

@@ -117,8 +117,30 @@ def mgrit_theta_layout(desc: ModelDesc) -> ThetaLayout:
     return out
 
 
-def mgrit_workspace_bytes(desc: ModelDesc, opts: Opts, adjoint: bool) -> int:
+def mgrit_workspace_bytes(desc: ModelDesc, opts: Opts, adjoint) -> int:
+    """adjoint: 0/False forward, 1/True adjoint, 2 adjoint with parameter gradients."""
     return int(lib().mgrit_workspace_bytes(C.byref(desc), C.byref(opts), int(adjoint)))
+
+
+def grad_layout(desc: ModelDesc) -> ThetaLayout:
+    """Layout of a gradient block: the fp32 parameter block of the same model."""
+    d32 = ModelDesc.from_buffer_copy(desc)
+    d32.dtype = 0
+    return mgrit_theta_layout(d32)
+
+
+def unpack_grad(desc: ModelDesc, block: torch.Tensor) -> Dict[str, np.ndarray]:
+    """Copies a gradient block (uint8 device tensor) back into named float32 arrays."""
+    lay = grad_layout(desc)
+    raw = block.cpu().numpy()
+    out = {}
+    for i, name in enumerate(P_NAMES):
+        if lay.offset[i] < 0:
+            continue
+        n = lay.rows[i] * lay.cols[i]
+        a = raw[lay.offset[i]:lay.offset[i] + 4 * n].view(np.float32)
+        out[name] = a.reshape(lay.rows[i], lay.cols[i]) if lay.cols[i] > 1 else a.copy()
+    return out
 
 
 def mgrit_layer_step_workspace_bytes(desc: ModelDesc, adjoint: bool, n_groups: int) -> int:
@@ -236,8 +258,10 @@ def mgrit_forward(desc: ModelDesc, opts: Opts, Z0: torch.Tensor, theta: List[tor
 def mgrit_adjoint(desc: ModelDesc, opts: Opts, Z_all: torch.Tensor, theta: List[torch.Tensor],
                   lambda_N: torch.Tensor, memory: Optional[torch.Tensor] = None,
                   lambda_all: Optional[torch.Tensor] = None, resnorm: Optional[torch.Tensor] = None,
-                  workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
-    """Returns (lambda_all [(N+1),T,d], resnorm [iters])."""
+                  workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
+                  dtheta: Optional[List[torch.Tensor]] = None):
+    """Returns (lambda_all [(N+1),T,d], resnorm [iters]).  dtheta: N uint8 device tensors of
+    grad_layout(desc).block_bytes each, filled with the parameter gradients."""
     T, d = desc.batch * desc.seq, desc.d_model
     _check_state(Z_all, (opts.N + 1, T, d), "Z_all")
     _check_state(lambda_N, (T, d), "lambda_N")
@@ -248,11 +272,14 @@ def mgrit_adjoint(desc: ModelDesc, opts: Opts, Z_all: torch.Tensor, theta: List[
     _check_state(lambda_all, (opts.N + 1, T, d), "lambda_all")
     if resnorm is None:
         resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z_all.device)
-    need = mgrit_workspace_bytes(desc, opts, True)
+    if dtheta is not None and len(dtheta) != opts.N:
+        raise ValueError("dtheta must hold N blocks")
+    need = mgrit_workspace_bytes(desc, opts, 2 if dtheta is not None else 1)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Z_all.device)
     st = lib().mgrit_adjoint(C.byref(desc), C.byref(opts), _ptr(Z_all), _ptr_array(theta), _ptr(memory),
-                             _ptr(lambda_N), _ptr(lambda_all), None, None, _ptr(resnorm), _ptr(workspace),
+                             _ptr(lambda_N), _ptr(lambda_all), None, _ptr_array(dtheta), _ptr(resnorm),
+                             _ptr(workspace),
                              workspace.numel(), _stream_handle(stream))
     if st != MGRIT_OK:
         raise MgritError(st, "mgrit_adjoint")

@@ -133,7 +133,7 @@ enum Epi : int {
   EPI_RESID_INNER = 2,  // ybar[m,n] (fp32, packed) = [base +] acc + bias      (sum of attention sublayers)
   EPI_RESID_OUTER = 3,  // OUT[m,n] = X + h*(ybar + acc + bias) + rhs          (the Euler update)
   EPI_DGELU = 4,        // out = acc * gelu'(z[m,n])                           (adjoint of the activation)
-  EPI_STORE_F32 = 5     // out (fp32 packed) = acc (+ bias)
+  EPI_STORE_F32 = 5     // out (fp32, packed or inside the group's output block) = hstep * (acc + bias)
 };
 
 struct GemmArgs {
@@ -154,6 +154,7 @@ struct GemmArgs {
   Rows OUT;                    // EPI_RESID_OUTER: the step's output state
   Rows RHS;                    // EPI_RESID_OUTER: optional right-hand side
   float hstep;
+  Params out_tab; long out_tab_off;    // EPI_STORE_F32: if set, group g writes at out_tab[g] + out_tab_off
 };
 
 }  // namespace mg

@@ -35,6 +35,7 @@ __device__ __forceinline__ EpiPtrs resolve_epi(const GemmArgs& a, int g, int epi
   const bool f32_out = epi == EPI_STORE_F32 || epi == EPI_RESID_INNER;
   const long osz = f32_out ? 4 : (long)sizeof(TO);
   p.out = a.out ? static_cast<char*>(a.out) + a.out_slots.of(g) * a.out_slot_stride * osz : nullptr;
+  if (a.out_tab.tab) p.out = const_cast<char*>(a.out_tab.at(g)) + a.out_tab_off;
   const long asz = epi == EPI_RESID_OUTER ? 4 : (long)sizeof(TO);
   p.aux = a.aux ? static_cast<char*>(a.aux) + a.aux_slots.of(g) * a.aux_slot_stride * asz : nullptr;
   p.base = a.base ? a.base + a.base_slots.of(g) * a.base_slot_stride : nullptr;
@@ -53,7 +54,7 @@ __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restric
   if constexpr (EPI == EPI_STORE) {
     store4<TO>(out_op + idx, acc);
   } else if constexpr (EPI == EPI_STORE_F32) {
-    store4<float>(out_f32 + idx, acc);
+    store4<float>(out_f32 + idx, hstep * acc);
   } else if constexpr (EPI == EPI_GELU) {
     if (z_out) store4<TO>(z_out + idx, acc);
     f32x4 y = {gelu_t<TO>(acc[0]), gelu_t<TO>(acc[1]), gelu_t<TO>(acc[2]), gelu_t<TO>(acc[3])};

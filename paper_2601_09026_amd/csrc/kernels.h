@@ -53,6 +53,27 @@ hipError_t upload_pointers(void** tab, const void* const* host_ptrs, int n, hipS
 hipError_t launch_transpose(int n_groups, Params in, Params out, long off, int rows, int cols, int elem_bytes,
                             hipStream_t st);
 
+// ---- grads.hip ---------------------------------------------------------------
+// dst_g[c, r] = src_g[r, c] (or GELU of it) on packed operand-type buffers, src [rows, cols].
+// With `partial` (n_groups * transpose_row_blocks(rows) * cols floats of scratch) also
+// sum_out_g[c] (fp32, at byte offset sum_off of the group's output block) = sum_scale * sum over rows of src_g[r, c].
+int transpose_row_blocks(int rows);
+hipError_t launch_transpose_slots(int n_groups, const void* src, long src_slot_stride, Slots src_slots, int rows,
+                                  int cols, void* dst, long dst_slot_stride, Slots dst_slots, bool gelu,
+                                  bool is_bf16, float* partial, Params sum_out, long sum_off, float sum_scale,
+                                  hipStream_t st);
+// LayerNorm gain / shift gradients: sums over tokens of dy * xhat and dy, scaled
+struct LnParamArgs {
+  int n_groups, T, d;
+  const void* dy; long dy_slot_stride; Slots dy_slots;    // packed operand type: cotangent of the LN output
+  Rows X;                                                 // LN input = X rows (optional) + addend (optional)
+  const float* xp; long xp_slot_stride; Slots xp_slots;
+  Params out; long gamma_off, beta_off;                   // fp32 outputs inside the group's output block
+  float scale, eps;
+};
+int ln_param_partial_rows();          // partial: n_groups * ln_param_partial_rows() * 2 * d floats
+hipError_t launch_ln_param_grad(const LnParamArgs& a, float* partial, bool is_bf16, hipStream_t st);
+
 // ---- attention.hip -----------------------------------------------------------
 struct AttnArgs {
   int n_groups, B, H, dh, Sq, Sk, causal;

@@ -153,6 +153,13 @@ struct Engine {
   float *c_lsec, *c_x3;
   void *cb, *dz, *du, *ds, *da, *dqkv;
   float *dxin, *Dbuf;
+  // parameter-gradient pass: transposed operands (Gc slots each), token-sum partials, table of tB slots
+  mgrit_theta_layout_t glay;       // layout of a gradient block: the fp32 parameter block of the model
+  void *tA = nullptr, *tB = nullptr;
+  float* gpart = nullptr;
+  void** tabTB = nullptr;
+  long tA_stride() const { return (long)(f > 3 * d ? f : 3 * d) * T; }   // elements per slot
+  long tB_stride() const { return (long)(f > d ? f : d) * T; }
 
   long Td() const { return (long)T * d; }
 
@@ -162,6 +169,9 @@ struct Engine {
     bf16 = m->dtype == MGRIT_DTYPE_BF16;
     T = m->batch * m->seq; Tm = m->batch * m->mem_seq; d = m->d_model; f = m->d_ff; H = m->n_heads;
     dh = d / H; esz = bf16 ? 2 : 4; st = s;
+    mgrit_model_desc m32 = *m;
+    m32.dtype = MGRIT_DTYPE_F32;
+    compute_layout(&m32, &glay);
   }
   // work buffers of one lane (a lane = a stream with its own intermediates)
   void carve_forward_work(Bump& b, int gc) {
@@ -215,6 +225,15 @@ struct Engine {
     dxin = b.take<float>(G * T * d);
     Dbuf = b.take<float>(G * md.batch * H * md.seq);
     qkv = o = act = nullptr; xin = nullptr;
+  }
+  void carve_grad_work(Bump& b) {
+    const size_t G = Gc;
+    tA = b.take_bytes(G * tA_stride() * esz);
+    tB = b.take_bytes(G * tB_stride() * esz);
+    const size_t widest = f > 3 * d ? f : 3 * d;
+    const size_t p1 = G * transpose_row_blocks(T) * widest, p2 = G * ln_param_partial_rows() * 2 * (size_t)d;
+    gpart = b.take<float>(p1 > p2 ? p1 : p2);
+    tabTB = b.take<void*>(G);
   }
 };
 
@@ -359,27 +378,80 @@ int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, floa
   return MGRIT_OK;
 }
 
+// Weight and bias gradient of one linear map y = u W^T + b of the chunk's layers:
+//   dW[out,in] = scale * dY^T U,  db[out] = scale * sum over tokens of dY,
+// dY [T,out] and U [T,in] packed operand-type buffers.  The product runs on the same
+// "both operands reduction-contiguous" GEMM, on transposed copies of dY and U (reduction over
+// the T tokens); gelu_u: U = GELU(given buffer).  Results go into the layers' gradient blocks.
+int linear_param_grads(Engine& E, int n, const void* dY, long dy_stride, Slots dy_slots, int out_dim,
+                       const void* U, long u_stride, Slots u_slots, int in_dim, bool gelu_u, Params DT,
+                       int w_id, int b_id, float scale) {
+  const Slots loc = {0, 1};
+  const int T = E.T;
+  const Params none = {nullptr, 0, 0};
+  HIPCHK(launch_transpose_slots(n, dY, dy_stride, dy_slots, T, out_dim, E.tA, E.tA_stride(), loc, false, E.bf16,
+                                E.gpart, DT, E.glay.offset[b_id], scale, E.st));
+  HIPCHK(launch_transpose_slots(n, U, u_stride, u_slots, T, in_dim, E.tB, E.tB_stride(), loc, gelu_u, E.bf16,
+                                nullptr, none, 0, 0.f, E.st));
+  GemmArgs g = gemm_base(n, out_dim, in_dim, T, E.tA, E.tA_stride(), loc, Params{(const void* const*)E.tabTB, 0, 1},
+                         0, -1);
+  g.out_tab = DT; g.out_tab_off = E.glay.offset[w_id]; g.hstep = scale;
+  HIPCHK(launch_gemm(g, EPI_STORE_F32, E.bf16, E.st));
+  return MGRIT_OK;
+}
+
 // One chunk of the adjoint step:  OUT = IN + hstep * J(LIN; theta)^T IN (+ RHS), from the cache.
 // THT: parameter blocks whose matrices are stored transposed; TH: the original blocks.
+// With DT (gradient blocks of the chunk's layers) the chunk is a parameter-gradient pass instead:
+// the same backward chain with IN = lambda_{n+1}, every linear map and LayerNorm also emitting
+// hstep * (its parameter cotangent), and no state written (paper section 3.1: theta enters the
+// step only through h F, so dtheta_n = h (dF/dtheta_n (Z_n))^T lambda_{n+1}).
 int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Params THT, Rows LIN, Slots cs,
-                  float hstep) {
+                  float hstep, const Params* DT = nullptr) {
   const int T = E.T, d = E.d, f = E.f;
   const auto& L = E.lay;
   const Slots loc = {0, 1};
   const size_t esz = E.esz;
 
   HIPCHK(launch_cast_rows(n, E.Td(), IN, E.cb, E.Td(), loc, E.bf16, E.st));
+  LnFwdArgs lf;
+  LnParamArgs lp;
+  if (DT) {
+    // m = GELU(z) W2^T + b2
+    STCHK(linear_param_grads(E, n, E.cb, E.Td(), loc, d, E.c_z, (long)T * f, cs, f, true, *DT, MGRIT_P_W2,
+                             MGRIT_P_B2, hstep));
+    memset(&lf, 0, sizeof(lf));
+    lf.n_groups = n; lf.T = T; lf.d = d; lf.X = LIN; lf.P = TH; lf.eps = E.md.ln_eps;
+    lf.out = E.u; lf.out_slot_stride = E.Td(); lf.out_slots = loc;
+    memset(&lp, 0, sizeof(lp));
+    lp.n_groups = n; lp.T = T; lp.d = d; lp.X = LIN; lp.out = *DT; lp.scale = hstep; lp.eps = E.md.ln_eps;
+    lp.dy = E.du; lp.dy_slot_stride = E.Td(); lp.dy_slots = loc;
+  }
 
   // dz = (c W2) * gelu'(z)        [T,d] x [d,f]: transposed W2 is [f,d]
   GemmArgs g = gemm_base(n, T, f, d, E.cb, E.Td(), loc, THT, L.offset[MGRIT_P_W2], -1);
   g.out = E.dz; g.out_slot_stride = (long)T * f; g.out_slots = loc;
   g.aux = E.c_z; g.aux_slot_stride = (long)T * f; g.aux_slots = cs;
   HIPCHK(launch_gemm(g, EPI_DGELU, E.bf16, E.st));
+  if (DT) {
+    // z = LN2(X + ybar) W1^T + b1
+    lf.xp = E.c_xin; lf.xp_slot_stride = E.Td(); lf.xp_slots = cs;
+    lf.gamma_off = L.offset[MGRIT_P_LN2_G]; lf.beta_off = L.offset[MGRIT_P_LN2_B];
+    HIPCHK(launch_ln_fwd(lf, E.bf16, E.st));
+    STCHK(linear_param_grads(E, n, E.dz, (long)T * f, loc, f, E.u, E.Td(), loc, d, false, *DT, MGRIT_P_W1,
+                             MGRIT_P_B1, hstep));
+  }
 
   // du2 = dz W1                   [T,f] x [f,d]: transposed W1 is [d,f]
   g = gemm_base(n, T, d, f, E.dz, (long)T * f, loc, THT, L.offset[MGRIT_P_W1], -1);
   g.out = E.du; g.out_slot_stride = E.Td(); g.out_slots = loc;
   HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+
+  if (DT) {
+    lp.xp = E.c_xin; lp.xp_slot_stride = E.Td(); lp.xp_slots = cs;
+    lp.gamma_off = E.glay.offset[MGRIT_P_LN2_G]; lp.beta_off = E.glay.offset[MGRIT_P_LN2_B];
+    HIPCHK(launch_ln_param_grad(lp, E.gpart, E.bf16, E.st));
+  }
 
   // dX' = LN2^T du2 ;  ds = c + dX'
   LnBwdArgs lb;
@@ -430,6 +502,11 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
     HIPCHK(launch_ln_bwd(lb, E.bf16, E.st));
   }
 
+  // s = o Wo^T + bo
+  if (DT)
+    STCHK(linear_param_grads(E, n, E.ds, E.Td(), loc, d, E.c_o, E.Td(), cs, d, false, *DT, MGRIT_P_WO,
+                             MGRIT_P_BO, hstep));
+
   // da = ds Wo
   g = gemm_base(n, T, d, d, E.ds, E.Td(), loc, THT, L.offset[MGRIT_P_WO], -1);
   g.out = E.da; g.out_slot_stride = E.Td(); g.out_slots = loc;
@@ -452,10 +529,26 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
   at.D = E.Dbuf; at.D_slot_stride = (long)E.md.batch * E.H * E.md.seq; at.D_slots = loc;
   HIPCHK(launch_attn_bwd(at, E.bf16, E.st));
 
+  if (DT) {
+    // qkv = LN1(X) Wqkv^T + bqkv
+    lf.xp = nullptr;
+    lf.gamma_off = L.offset[MGRIT_P_LN1_G]; lf.beta_off = L.offset[MGRIT_P_LN1_B];
+    HIPCHK(launch_ln_fwd(lf, E.bf16, E.st));
+    STCHK(linear_param_grads(E, n, E.dqkv, (long)T * 3 * d, loc, 3 * d, E.u, E.Td(), loc, d, false, *DT,
+                             MGRIT_P_WQKV, MGRIT_P_BQKV, hstep));
+  }
+
   // du1 = dqkv Wqkv               [T,3d] x [3d,d]: transposed Wqkv is [d,3d]
   g = gemm_base(n, T, d, 3 * d, E.dqkv, (long)T * 3 * d, loc, THT, L.offset[MGRIT_P_WQKV], -1);
   g.out = E.du; g.out_slot_stride = E.Td(); g.out_slots = loc;
   HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+
+  if (DT) {
+    lp.xp = nullptr;
+    lp.gamma_off = E.glay.offset[MGRIT_P_LN1_G]; lp.beta_off = E.glay.offset[MGRIT_P_LN1_B];
+    HIPCHK(launch_ln_param_grad(lp, E.gpart, E.bf16, E.st));
+    return MGRIT_OK;
+  }
 
   // dX = dX' + LN1^T du1 ;  OUT = c + hstep dX (+ RHS)
   memset(&lb, 0, sizeof(lb));
@@ -504,6 +597,16 @@ int adjoint_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Pa
   return run_chunks(E, E2, G, [&](Engine& L, int c0, int n) {
     return adjoint_chunk(L, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), shift(THT, c0),
                          shift(LIN, c0), shift(cs, c0), hstep);
+  });
+}
+
+// parameter gradients of G layers: group g has IN = lambda_{n+1}, LIN = Z_n, gradient block DT[g]
+int gradient_groups(Engine& E, Engine* E2, int G, Rows IN, Params TH, Params THT, Rows LIN, Slots cs, Params DT,
+                    float hstep) {
+  return run_chunks(E, E2, G, [&](Engine& L, int c0, int n) {
+    const Params dt = shift(DT, c0);
+    return adjoint_chunk(L, n, shift(IN, c0), NO_ROWS, NO_ROWS, shift(TH, c0), shift(THT, c0), shift(LIN, c0),
+                         shift(cs, c0), hstep, &dt);
   });
 }
 
@@ -613,10 +716,13 @@ struct Plan {                       // workspace of mgrit_forward / mgrit_adjoin
   bool two_lanes = false;
   Driver D;
   void* thT_blocks = nullptr;
+  void** tabDT = nullptr;           // layer n -> gradient block (adjoint with parameter gradients)
   size_t bytes = 0;
 };
 
-int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, bool adjoint, void* ws, hipStream_t st) {
+// mode: 0 forward, 1 adjoint, 2 adjoint followed by the parameter-gradient pass
+int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, int mode, void* ws, hipStream_t st) {
+  const bool adjoint = mode != 0;
   Bump b(ws);
   Engine& E = P.E;
   E.init(md, st);
@@ -637,6 +743,16 @@ int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, bool ad
     D.tabZ = b.take<void*>(N + 1);
     D.tabThT = b.take<void*>(N);
     P.thT_blocks = b.take_bytes((size_t)N * E.lay.block_bytes);
+  }
+  if (mode == 2) {
+    P.tabDT = b.take<void*>(N);
+    for (Engine* L : {&E, P.two_lanes ? &P.E2 : nullptr}) {
+      if (!L) continue;
+      L->carve_grad_work(b);
+      if (ws && launch_fill_table(L->tabTB, static_cast<char*>(L->tB), L->tB_stride() * (long)L->esz, L->Gc, st) !=
+                    hipSuccess)
+        return MGRIT_HIP_ERROR;
+    }
   }
   D.tabG.assign(D.L, nullptr);
   if (!serial) {
@@ -685,8 +801,10 @@ int mgrit_theta_layout(const mgrit_model_desc* desc, mgrit_theta_layout_t* out) 
 
 size_t mgrit_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts, int adjoint) {
   if (validate_desc(desc) != MGRIT_OK || validate_opts(opts) != MGRIT_OK) return 0;
+  if (adjoint < 0 || adjoint > 2) return 0;
+  if (adjoint == 2 && desc->arch == MGRIT_ARCH_CROSS) return 0;
   Plan P;
-  if (make_plan(P, desc, opts, adjoint != 0, nullptr, nullptr) != MGRIT_OK) return 0;
+  if (make_plan(P, desc, opts, adjoint, nullptr, nullptr) != MGRIT_OK) return 0;
   return P.bytes;
 }
 
@@ -733,7 +851,7 @@ int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   Plan P;
-  STCHK(make_plan(P, desc, opts, false, workspace, st));
+  STCHK(make_plan(P, desc, opts, 0, workspace, st));
   Engine& E = P.E;
   Driver& D = P.D;
   const int N = opts->N;
@@ -759,17 +877,20 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
                   void* stream) {
   STCHK(validate_desc(desc));
   STCHK(validate_opts(opts));
-  if (dmemory || dtheta) return MGRIT_UNSUPPORTED;
+  if (dmemory) return MGRIT_UNSUPPORTED;
+  if (dtheta && desc->arch == MGRIT_ARCH_CROSS) return MGRIT_UNSUPPORTED;
   if (desc->arch == MGRIT_ARCH_CROSS && !memory) return MGRIT_INVALID_ARG;
   if (!Z_all || !lambda_N || !lambda_all || !workspace) return MGRIT_INVALID_ARG;
   STCHK(check_ptr_array(theta, opts->N));
-  const size_t need = mgrit_workspace_bytes(desc, opts, 1);
+  if (dtheta) STCHK(check_ptr_array((const void* const*)dtheta, opts->N));
+  const int mode = dtheta ? 2 : 1;
+  const size_t need = mgrit_workspace_bytes(desc, opts, mode);
   if (need == 0) return MGRIT_INVALID_ARG;
   if (workspace_bytes < need) return MGRIT_WORKSPACE_TOO_SMALL;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   Plan P;
-  STCHK(make_plan(P, desc, opts, true, workspace, st));
+  STCHK(make_plan(P, desc, opts, mode, workspace, st));
   Engine& E = P.E;
   Driver& D = P.D;
   const int N = opts->N;
@@ -796,7 +917,15 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
                             hipMemcpyDeviceToDevice, st));
   }
   D.resnorm = resnorm;
-  return D.run(opts->iters);
+  STCHK(D.run(opts->iters));
+  if (dtheta) {
+    // one batched pass over all layers: layer n takes lambda_{n+1} (point N-1-n of the reversed grid)
+    HIPCHK(upload_pointers(P.tabDT, (const void* const*)dtheta, N, st));
+    Rows LamNext = {(const void* const*)D.tabW, N - 1, -1};
+    Params DT = {(const void* const*)P.tabDT, 0, 1};
+    STCHK(gradient_groups(E, D.E2, N, LamNext, TH, THT, Zrows, Slots{0, 1}, DT, opts->h));
+  }
+  return MGRIT_OK;
 }
 
 int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups, const void* const* in,

@@ -98,6 +98,22 @@ def test_invalid_arguments_are_rejected_without_a_device():
         mb.mgrit_workspace_bytes(dec, mb.mgrit_opts(32, 1 / 32, 4, 2, 2), False) > 0
 
 
+def test_parameter_gradient_workspace_and_support():
+    desc = mb.model_desc(wls.named_workloads()["bert_base"])
+    opts = mb.mgrit_opts(64, 1 / 64, 4, 2, 2)
+    assert mb.mgrit_workspace_bytes(desc, opts, 2) > mb.mgrit_workspace_bytes(desc, opts, 1) > 0
+    assert mb.mgrit_workspace_bytes(desc, opts, 3) == 0
+    dec = mb.model_desc(wls.named_workloads()["mt_decoder"])
+    assert mb.mgrit_workspace_bytes(dec, mb.mgrit_opts(32, 1 / 32, 4, 2, 2), 2) == 0     # no dtheta for arch 2
+    # a gradient block is the fp32 parameter block: same tensors, 4-byte entries, in order
+    lay, glay = mb.mgrit_theta_layout(desc), mb.grad_layout(desc)
+    for i in range(mb.P_COUNT):
+        assert (lay.offset[i] < 0) == (glay.offset[i] < 0)
+        if glay.offset[i] >= 0:
+            assert (glay.rows[i], glay.cols[i], glay.elem_bytes[i]) == (lay.rows[i], lay.cols[i], 4)
+    assert glay.block_bytes > lay.block_bytes
+
+
 def test_workspace_grows_with_groups_and_levels():
     desc = mb.model_desc(wls.named_workloads()["bert_base"])
     a = mb.mgrit_layer_step_workspace_bytes(desc, False, 1)

@@ -1,0 +1,118 @@
+"""GPU parity of the parameter gradients  dtheta_n = h (dF/dtheta_n (Z_n))^T lambda_{n+1}
+(mgrit_adjoint with gradient blocks) against the CPU oracle.
+
+Both sides linearise about the same forward states (the GPU's own MGRIT iterate).  The small
+cases compare the whole chain (oracle adjoint MGRIT, then oracle gradients) for every parameter
+of every layer.  At the benchmark's full size the gradient of layer n is a local function of
+Z_n and lambda_{n+1}: the oracle recomputes sampled layers on the full batch from the GPU's
+states."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mgrit as omgrit, transformer_ode as tode
+from paper_2601_09026_amd import binding as mb
+from paper_2601_09026_amd import workloads as wls
+
+from gpu_util import TOL, DeviceModel, dev, relerr, shape_of
+
+pytestmark = pytest.mark.gpu
+
+
+def grad_blocks(desc, N):
+    nbytes = mb.grad_layout(desc).block_bytes
+    # poisoned: every entry the library does not overwrite would show up as NaN
+    return [torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda").view(torch.uint8)
+            for _ in range(N)]
+
+
+def compare_layer(got, ref, tol, what):
+    assert set(got) == set(ref), what
+    worst = 0.0
+    for name, r in ref.items():
+        g = got[name].astype(np.float64)
+        assert np.isfinite(g).all(), f"{what} {name}: non-finite"
+        assert g.shape == r.shape, f"{what} {name}: shape {g.shape} vs {r.shape}"
+        e = relerr(g, r)
+        assert e <= tol, f"{what} {name}: error {e:.3e} > {tol}"
+        worst = max(worst, e)
+    return worst
+
+
+def run_case(wl, weight_std=0.08, max_groups=0):
+    print(f"[case] dtheta {wl.name} arch={wl.arch} dtype={wl.dtype} d={wl.d_model} B={wl.batch} S={wl.seq} "
+          f"N={wl.N} cf={wl.cf} L={wl.levels} it={wl.iters} mg={max_groups}", flush=True)
+    mb.mgrit_set_max_groups_per_launch(max_groups)
+    try:
+        dm = DeviceModel(wl, weight_std=weight_std)
+        sh = shape_of(wl)
+        tol = TOL[wl.dtype]
+        opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters)
+        Zg, _ = mb.mgrit_forward(dm.desc, opts, dev(wls.initial_state(wl)), dm.blocks)
+        lamN = wls.terminal_adjoint(wl)
+        blocks = grad_blocks(dm.desc, wl.N)
+        lg, _ = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN), dtheta=blocks)
+        torch.cuda.synchronize()
+        # the adjoint states must not depend on whether gradients were asked for
+        lg2, _ = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN))
+        torch.cuda.synchronize()
+        assert torch.equal(lg, lg2)
+        Zlin = list(Zg.cpu().numpy().astype(np.float64))
+        lr, _, _ = omgrit.mgrit_adjoint(lamN, Zlin, dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh)
+        ref = omgrit.parameter_gradients(lr, Zlin, dm.host, wl.h, sh)
+        worst = 0.0
+        for n in range(wl.N):
+            worst = max(worst, compare_layer(mb.unpack_grad(dm.desc, blocks[n]), ref[n], tol, f"layer {n}"))
+        print(f"  worst relative error over all parameters and layers: {worst:.2e} (bar {tol})")
+    finally:
+        mb.mgrit_set_max_groups_per_launch(0)
+
+
+def tiny(arch=wls.ARCH_ENCODER, dtype=wls.DTYPE_F32, N=16, cf=4, levels=2, iters=2, h=1.0, d=64, H=4, f=128,
+         B=2, S=24, seed=43):
+    return wls.Workload("tiny", arch, d, H, f, B, S, 0, N, h, cf, levels, iters, dtype, seed)
+
+
+@pytest.mark.parametrize("max_groups", [0, 3])
+def test_two_level_encoder_fp32(max_groups):
+    run_case(tiny(), max_groups=max_groups)
+
+
+def test_three_level_causal_fp32():
+    run_case(tiny(arch=wls.ARCH_CAUSAL, N=16, cf=2, levels=3))
+
+
+def test_serial_limit_fp32():
+    run_case(tiny(N=6, cf=4, levels=1, iters=1))
+
+
+def test_bert_shape_reduced_bf16():
+    # model shape of the benchmark (MFMA kernels, 256 tokens = 4 k-tiles of the weight-gradient products)
+    run_case(wls.named_workloads()["bert_base"].scaled(batch=2, N=8, h=1.0 / 8), weight_std=0.02)
+
+
+def test_gpt2_shape_reduced_bf16():
+    run_case(wls.named_workloads()["gpt2_small"].scaled(batch=1, N=8, h=1.0 / 8, levels=2), weight_std=0.02)
+
+
+def test_full_size_bert_sampled_layers():
+    """Full batch, the launch configuration the benchmark times; layers 0, 37 and 63 recomputed by the
+    oracle from the GPU's Z_n and lambda_{n+1} (the gradient of a layer is local to them)."""
+    wl = wls.named_workloads()["bert_base"]
+    print(f"[case] dtheta full size {wl.name}", flush=True)
+    dm = DeviceModel(wl)
+    sh = shape_of(wl)
+    tol = TOL[wl.dtype]
+    opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters)
+    Zg, _ = mb.mgrit_forward(dm.desc, opts, dev(wls.initial_state(wl)), dm.blocks)
+    blocks = grad_blocks(dm.desc, wl.N)
+    lg, _ = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(wls.terminal_adjoint(wl)), dtheta=blocks)
+    torch.cuda.synchronize()
+    for n in (0, 37, 63):
+        c = lg[n + 1].cpu().numpy().astype(np.float64)
+        ref = tode.F_param_vjp(Zg[n].cpu().numpy().astype(np.float64), dm.host[n], c, sh)
+        ref = {k: wl.h * v for k, v in ref.items()}
+        worst = compare_layer(mb.unpack_grad(dm.desc, blocks[n]), ref, tol, f"layer {n}")
+        print(f"  layer {n}: worst relative error {worst:.2e} (bar {tol})", flush=True)
+    for n in range(wl.N):       # every block was written
+        assert torch.isfinite(blocks[n].view(torch.float32)).all(), n
