@@ -175,6 +175,46 @@ int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups,
                              const void* const* rhs, const void* memory, float hstep,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- adaptive control of the inexactness (sec. 3.2.3), host only ---------------------------
+ * The convergence factor of MGRIT iteration k is ||r^(k+1)|| / ||r^(k)||, the ratio of consecutive
+ * entries of the `resnorm` output above.  Policy of the paper: every `probe_every` batches run one
+ * batch with twice the iterations and look at the factor of its final iteration; above `threshold`
+ * (1 in the paper) the iteration count is no longer effective, and either the count is raised or
+ * training switches to serial propagation.  The caller owns the struct (plain data, may be copied
+ * or checkpointed) and drives it around its own calls of mgrit_forward / mgrit_adjoint (one
+ * indicator per direction, as in the paper's Fig. 5):
+ *     it = mgrit_indicator_begin_batch(&ind);     // iterations for this batch; 0 = run serial
+ *     opts.iters = it; opts.levels = it ? L : 1;  mgrit_forward(..., resnorm_dev, ...);
+ *     copy resnorm to the host if ind.probing;    mgrit_indicator_end_batch(&ind, resnorm_host, it);
+ * Where the paper leaves the policy open: batches are counted from 0 and batch b is a probe when
+ * (b + 1) is a multiple of probe_every; MGRIT_MITIGATE_MORE_ITERATIONS doubles `iters` (the count
+ * the probe just ran) while that stays <= max_iters and falls back to serial beyond;
+ * MGRIT_MITIGATE_SERIAL switches at the first failing probe; serial is final.  A probe whose last
+ * residual is not finite fails; one whose residuals are both zero passes. */
+enum { MGRIT_MITIGATE_SERIAL = 0, MGRIT_MITIGATE_MORE_ITERATIONS = 1 };
+typedef struct {
+  int32_t iters;          /* iterations on ordinary batches (doubled on probes)                 */
+  int32_t probe_every;    /* probe period in batches, 0 = never probe                           */
+  int32_t mitigation;     /* MGRIT_MITIGATE_*                                                   */
+  int32_t max_iters;      /* ceiling of `iters` under MGRIT_MITIGATE_MORE_ITERATIONS            */
+  float   threshold;      /* failing convergence factor                                         */
+  float   last_factor;    /* factor seen by the last probe, -1 before the first                 */
+  int64_t batch;          /* batches finished                                                   */
+  int32_t serial;         /* 1 once switched to serial propagation                              */
+  int32_t probing;        /* 1 between begin_batch and end_batch of a probe batch               */
+  int32_t failures;       /* probes that failed so far                                          */
+  int32_t reserved;
+} mgrit_indicator;
+/* Returns MGRIT_OK or MGRIT_INVALID_ARG (iters < 1, negative period or ceiling, threshold <= 0). */
+int mgrit_indicator_init(mgrit_indicator* ind, int iters, int probe_every, int mitigation, int max_iters,
+                         float threshold);
+/* Iterations to run for the coming batch: 2*iters on a probe, iters otherwise, 0 = serial. */
+int mgrit_indicator_begin_batch(mgrit_indicator* ind);
+/* resnorm: HOST array of the n residual norms of the batch just run (ignored unless it was a
+ * probe).  Returns 1 if the policy changed (iters raised or switched to serial), 0 if not,
+ * MGRIT_INVALID_ARG on bad arguments. */
+int mgrit_indicator_end_batch(mgrit_indicator* ind, const float* resnorm, int n);
+
 const char* mgrit_status_string(int status);
 int         mgrit_last_hip_error(void);          /* hipError_t of the last MGRIT_HIP_ERROR */
 

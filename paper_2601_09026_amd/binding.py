@@ -22,6 +22,17 @@ P_NAMES = ["ln1_g", "ln1_b", "bqkv", "bo", "ln2_g", "ln2_b", "b1", "b2", "ln3_g"
 P_COUNT = len(P_NAMES)
 
 
+class Indicator(C.Structure):
+    """mgrit_indicator: the host-side inexactness controller (plain data)."""
+    _fields_ = [("iters", C.c_int32), ("probe_every", C.c_int32), ("mitigation", C.c_int32),
+                ("max_iters", C.c_int32), ("threshold", C.c_float), ("last_factor", C.c_float),
+                ("batch", C.c_int64), ("serial", C.c_int32), ("probing", C.c_int32), ("failures", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+MITIGATE_SERIAL, MITIGATE_MORE_ITERATIONS = 0, 1
+
+
 class ModelDesc(C.Structure):
     _fields_ = [("arch", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ff", C.c_int32),
                 ("batch", C.c_int32), ("seq", C.c_int32), ("mem_seq", C.c_int32), ("dtype", C.c_int32),
@@ -75,6 +86,12 @@ def lib() -> C.CDLL:
         L.layer_step_batched.argtypes = [C.POINTER(ModelDesc), C.c_int, C.c_int, vpp, vpp, vpp, vpp, vpp, vp,
                                          C.c_float, vp, C.c_size_t, vp]
         L.layer_step_batched.restype = C.c_int
+        L.mgrit_indicator_init.argtypes = [C.POINTER(Indicator), C.c_int, C.c_int, C.c_int, C.c_int, C.c_float]
+        L.mgrit_indicator_init.restype = C.c_int
+        L.mgrit_indicator_begin_batch.argtypes = [C.POINTER(Indicator)]
+        L.mgrit_indicator_begin_batch.restype = C.c_int
+        L.mgrit_indicator_end_batch.argtypes = [C.POINTER(Indicator), C.POINTER(C.c_float), C.c_int]
+        L.mgrit_indicator_end_batch.restype = C.c_int
         L.mgrit_status_string.argtypes = [C.c_int]
         L.mgrit_status_string.restype = C.c_char_p
         L.mgrit_last_hip_error.argtypes = []
@@ -149,6 +166,24 @@ def mgrit_layer_step_workspace_bytes(desc: ModelDesc, adjoint: bool, n_groups: i
 
 def mgrit_step_evaluations(opts: Opts) -> int:
     return int(lib().mgrit_step_evaluations(C.byref(opts)))
+
+
+def mgrit_indicator_init(iters: int, probe_every: int, mitigation: int = MITIGATE_SERIAL, max_iters: int = 0,
+                         threshold: float = 1.0) -> Indicator:
+    ind = Indicator()
+    st = lib().mgrit_indicator_init(C.byref(ind), iters, probe_every, mitigation, max_iters, threshold)
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_indicator_init")
+    return ind
+
+
+def mgrit_indicator_begin_batch(ind: Indicator) -> int:
+    return int(lib().mgrit_indicator_begin_batch(C.byref(ind)))
+
+
+def mgrit_indicator_end_batch(ind: Indicator, resnorm) -> int:
+    r = np.ascontiguousarray(resnorm, dtype=np.float32)
+    return int(lib().mgrit_indicator_end_batch(C.byref(ind), r.ctypes.data_as(C.POINTER(C.c_float)), r.size))
 
 
 def mgrit_set_max_groups_per_launch(n: int) -> None:

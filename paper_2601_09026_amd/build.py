@@ -12,7 +12,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmgrit_hip.so")
-SOURCES = ["gemm.hip", "rowwise.hip", "grads.hip", "attention.hip", "attention_mfma.hip", "mgrit.hip", "prof.hip"]
+SOURCES = ["gemm.hip", "rowwise.hip", "grads.hip", "attention.hip", "attention_mfma.hip", "mgrit.hip", "prof.hip", "indicator.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
