@@ -109,7 +109,8 @@ int mgrit_theta_layout(const mgrit_model_desc* desc, mgrit_theta_layout_t* out);
 
 /* Workspace sizes in bytes (0 on invalid arguments).  Host only.
  * mgrit_workspace_bytes: adjoint = 0 for mgrit_forward, 1 for mgrit_adjoint, 2 for
- * mgrit_adjoint called with dtheta (parameter gradients need transposed operand copies). */
+ * mgrit_adjoint called with dtheta or dmemory (the gradient pass needs transposed operand
+ * copies and per-layer terms). */
 size_t mgrit_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts, int adjoint);
 size_t mgrit_layer_step_workspace_bytes(const mgrit_model_desc* desc, int adjoint, int n_groups);
 
@@ -149,11 +150,12 @@ int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts,
  *              pass batched over all layers.  A gradient block is laid out like the fp32
  *              parameter block of the same model (mgrit_theta_layout on a copy of desc with
  *              dtype = MGRIT_DTYPE_F32), every entry fp32, whatever desc->dtype is; entries
- *              are overwritten, not accumulated.  Needs the workspace of
- *              mgrit_workspace_bytes(desc, opts, 2).  Encoder and causal blocks only:
- *              MGRIT_UNSUPPORTED for arch 2.
- *   dmemory    reserved, must be NULL (MGRIT_UNSUPPORTED otherwise): the gradient with respect
- *              to the cross-attention memory is not produced yet
+ *              are overwritten, not accumulated.
+ *   dmemory    NULL, or device [batch*mem_seq, d] fp32 out (arch 2 only, MGRIT_INVALID_ARG for
+ *              the other block types): dL/dE = sum over layers of h * (dF/dE (Y_n))^T lambda_{n+1},
+ *              the gradient with respect to the cross-attention memory (the encoder output),
+ *              from the same pass; overwritten.
+ *              Either output needs the workspace of mgrit_workspace_bytes(desc, opts, 2).
  */
 int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts,
                   const void* Z_all, const void* const* theta, const void* memory,

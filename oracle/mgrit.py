@@ -213,6 +213,16 @@ def parameter_gradients(lam, Z, theta, h, sh, mem=None):
     return out
 
 
+def memory_gradient(lam, Z, theta, h, sh, mem):
+    """dL/dE = sum over layers of h * (dF_dec/dE (Y_n))^T lambda_{n+1}: the encoder output E enters
+    every decoder layer's cross-attention, so its gradient collects one term per layer."""
+    out = np.zeros_like(np.asarray(mem, dtype=np.float64))
+    for n, th in enumerate(theta):
+        _, dE = tode.F_vjp(Z[n], th, lam[n + 1], sh, mem)
+        out += h * dE
+    return out
+
+
 def mgrit_adjoint(lamN, Z, theta, h, cf, levels, iters, sh, mem=None, relax="FCF", init=None):
     """Returns (lambda_0..lambda_N, residual norms, evaluation counts per level)."""
     N = len(theta)

@@ -294,9 +294,10 @@ def mgrit_adjoint(desc: ModelDesc, opts: Opts, Z_all: torch.Tensor, theta: List[
                   lambda_N: torch.Tensor, memory: Optional[torch.Tensor] = None,
                   lambda_all: Optional[torch.Tensor] = None, resnorm: Optional[torch.Tensor] = None,
                   workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
-                  dtheta: Optional[List[torch.Tensor]] = None):
+                  dtheta: Optional[List[torch.Tensor]] = None, dmemory: Optional[torch.Tensor] = None):
     """Returns (lambda_all [(N+1),T,d], resnorm [iters]).  dtheta: N uint8 device tensors of
-    grad_layout(desc).block_bytes each, filled with the parameter gradients."""
+    grad_layout(desc).block_bytes each, filled with the parameter gradients; dmemory: fp32
+    [batch*mem_seq, d] device tensor filled with the gradient of the cross-attention memory."""
     T, d = desc.batch * desc.seq, desc.d_model
     _check_state(Z_all, (opts.N + 1, T, d), "Z_all")
     _check_state(lambda_N, (T, d), "lambda_N")
@@ -309,11 +310,13 @@ def mgrit_adjoint(desc: ModelDesc, opts: Opts, Z_all: torch.Tensor, theta: List[
         resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z_all.device)
     if dtheta is not None and len(dtheta) != opts.N:
         raise ValueError("dtheta must hold N blocks")
-    need = mgrit_workspace_bytes(desc, opts, 2 if dtheta is not None else 1)
+    if dmemory is not None:
+        _check_state(dmemory, (desc.batch * desc.mem_seq, d), "dmemory")
+    need = mgrit_workspace_bytes(desc, opts, 2 if (dtheta is not None or dmemory is not None) else 1)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Z_all.device)
     st = lib().mgrit_adjoint(C.byref(desc), C.byref(opts), _ptr(Z_all), _ptr_array(theta), _ptr(memory),
-                             _ptr(lambda_N), _ptr(lambda_all), None, _ptr_array(dtheta), _ptr(resnorm),
+                             _ptr(lambda_N), _ptr(lambda_all), _ptr(dmemory), _ptr_array(dtheta), _ptr(resnorm),
                              _ptr(workspace),
                              workspace.numel(), _stream_handle(stream))
     if st != MGRIT_OK:

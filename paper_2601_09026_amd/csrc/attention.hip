@@ -306,21 +306,21 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_simple_kernel(const AttnArgs
       }
     }
   }
-  T* dK = reinterpret_cast<T*>(a.dk) + a.dqkv_slots.of(g) * a.dqkv_slot_stride +
-          (long)b * a.Sk * a.dqkv_row_stride + h * dh;
-  T* dV = reinterpret_cast<T*>(a.dv) + a.dqkv_slots.of(g) * a.dqkv_slot_stride +
-          (long)b * a.Sk * a.dqkv_row_stride + h * dh;
+  const long kv_rs = a.dkv_row_stride ? a.dkv_row_stride : a.dqkv_row_stride;
+  const long kv_ss = a.dkv_slot_stride ? a.dkv_slot_stride : a.dqkv_slot_stride;
+  T* dK = reinterpret_cast<T*>(a.dk) + a.dqkv_slots.of(g) * kv_ss + (long)b * a.Sk * kv_rs + h * dh;
+  T* dV = reinterpret_cast<T*>(a.dv) + a.dqkv_slots.of(g) * kv_ss + (long)b * a.Sk * kv_rs + h * dh;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int kj = j0 + wave * 4 + r;
     if (kj >= a.Sk) continue;
     if (lane < dh) {
-      dK[(long)kj * a.dqkv_row_stride + lane] = from_f<T>(dk[r][0]);
-      dV[(long)kj * a.dqkv_row_stride + lane] = from_f<T>(dv[r][0]);
+      dK[(long)kj * kv_rs + lane] = from_f<T>(dk[r][0]);
+      dV[(long)kj * kv_rs + lane] = from_f<T>(dv[r][0]);
     }
     if (lane + 64 < dh) {
-      dK[(long)kj * a.dqkv_row_stride + lane + 64] = from_f<T>(dk[r][1]);
-      dV[(long)kj * a.dqkv_row_stride + lane + 64] = from_f<T>(dv[r][1]);
+      dK[(long)kj * kv_rs + lane + 64] = from_f<T>(dk[r][1]);
+      dV[(long)kj * kv_rs + lane + 64] = from_f<T>(dv[r][1]);
     }
   }
 }

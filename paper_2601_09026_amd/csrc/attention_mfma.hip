@@ -110,8 +110,10 @@ __device__ __forceinline__ HeadPtrs head_ptrs(const AttnArgs& a, int g, int b, i
     const long base = a.dqkv_slots.of(g) * a.dqkv_slot_stride;
     p.dQ = reinterpret_cast<bf16*>(a.dq) + base + (long)b * a.Sq * a.dqkv_row_stride + h * dh;
     if (a.dk) {
-      p.dK = reinterpret_cast<bf16*>(a.dk) + base + (long)b * a.Sk * a.dqkv_row_stride + h * dh;
-      p.dV = reinterpret_cast<bf16*>(a.dv) + base + (long)b * a.Sk * a.dqkv_row_stride + h * dh;
+      const long kv_rs = a.dkv_row_stride ? a.dkv_row_stride : a.dqkv_row_stride;
+      const long kv_base = a.dqkv_slots.of(g) * (a.dkv_slot_stride ? a.dkv_slot_stride : a.dqkv_slot_stride);
+      p.dK = reinterpret_cast<bf16*>(a.dk) + kv_base + (long)b * a.Sk * kv_rs + h * dh;
+      p.dV = reinterpret_cast<bf16*>(a.dv) + kv_base + (long)b * a.Sk * kv_rs + h * dh;
     }
     p.D = a.D + a.D_slots.of(g) * a.D_slot_stride + ((long)b * a.H + h) * a.Sq;
   }
@@ -347,8 +349,9 @@ __global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dkv_mfma_kernel(const Att
     }
   }
   if (kj < a.Sk) {
-    store_rows_T(P.dK, a.dqkv_row_stride, kj, dk, rsqrtf(64.f), lh);
-    store_rows_T(P.dV, a.dqkv_row_stride, kj, dv, 1.0f, lh);
+    const long kv_rs = a.dkv_row_stride ? a.dkv_row_stride : a.dqkv_row_stride;
+    store_rows_T(P.dK, kv_rs, kj, dk, rsqrtf(64.f), lh);
+    store_rows_T(P.dV, kv_rs, kj, dv, 1.0f, lh);
   }
 }
 

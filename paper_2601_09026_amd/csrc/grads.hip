@@ -125,6 +125,23 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* parti
   }
 }
 
+__global__ void __launch_bounds__(256) sum_slots_kernel(const float* in, int n, long elems, float* out, float scale) {
+  const long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= elems) return;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < n; ++s) acc += *reinterpret_cast<const f32x4*>(in + (long)s * elems + i);
+  *reinterpret_cast<f32x4*>(out + i) = scale * acc;
+}
+
+hipError_t launch_sum_slots(const float* in, int n, long elems, float* out, float scale, hipStream_t st) {
+  if (n <= 0 || elems <= 0) return hipSuccess;
+  if (elems % 4 != 0) return hipErrorInvalidValue;
+  ProfScope ps(PC_ELEMENTWISE, 0.0, (double)(n + 1) * elems * 4, st);
+  hipLaunchKernelGGL(sum_slots_kernel, dim3((unsigned)((elems / 4 + 255) / 256)), dim3(256), 0, st, in, n, elems, out,
+                     scale);
+  return hipGetLastError();
+}
+
 int transpose_row_blocks(int rows) { return (rows + TR - 1) / TR; }
 
 hipError_t launch_transpose_slots(int n_groups, const void* src, long src_slot_stride, Slots src_slots, int rows,

@@ -71,6 +71,8 @@ struct LnParamArgs {
   Params out; long gamma_off, beta_off;                   // fp32 outputs inside the group's output block
   float scale, eps;
 };
+// out[i] = scale * sum over s < n of in[s * elems + i]   (fixed order)
+hipError_t launch_sum_slots(const float* in, int n, long elems, float* out, float scale, hipStream_t st);
 int ln_param_partial_rows();          // partial: n_groups * ln_param_partial_rows() * 2 * d floats
 hipError_t launch_ln_param_grad(const LnParamArgs& a, float* partial, bool is_bf16, hipStream_t st);
 
@@ -85,6 +87,7 @@ struct AttnArgs {
   // backward only
   const void* dO; long do_row_stride, do_slot_stride; Slots do_slots;
   void* dq; void* dk; void* dv; long dqkv_row_stride, dqkv_slot_stride; Slots dqkv_slots;
+  long dkv_row_stride, dkv_slot_stride;                              // dk, dv if laid out unlike dq (0: same)
   float* D; long D_slot_stride; Slots D_slots;                       // [B,H,Sq] scratch: rowsum(dO*O)
 };
 hipError_t launch_attn_fwd(const AttnArgs& a, bool is_bf16, hipStream_t st);

@@ -158,8 +158,10 @@ struct Engine {
   void *tA = nullptr, *tB = nullptr;
   float* gpart = nullptr;
   void** tabTB = nullptr;
-  long tA_stride() const { return (long)(f > 3 * d ? f : 3 * d) * T; }   // elements per slot
-  long tB_stride() const { return (long)(f > d ? f : d) * T; }
+  void* dkvc = nullptr;            // cross-attention decoder: dK | dV of the cross attention, [Tm, 2d] per slot
+  int Tmax() const { return T > Tm ? T : Tm; }
+  long tA_stride() const { return (long)(f > 3 * d ? f : 3 * d) * Tmax(); }   // elements per slot
+  long tB_stride() const { return (long)(f > d ? f : d) * Tmax(); }
 
   long Td() const { return (long)T * d; }
 
@@ -231,9 +233,10 @@ struct Engine {
     tA = b.take_bytes(G * tA_stride() * esz);
     tB = b.take_bytes(G * tB_stride() * esz);
     const size_t widest = f > 3 * d ? f : 3 * d;
-    const size_t p1 = G * transpose_row_blocks(T) * widest, p2 = G * ln_param_partial_rows() * 2 * (size_t)d;
+    const size_t p1 = G * transpose_row_blocks(Tmax()) * widest, p2 = G * ln_param_partial_rows() * 2 * (size_t)d;
     gpart = b.take<float>(p1 > p2 ? p1 : p2);
     tabTB = b.take<void*>(G);
+    dkvc = md.arch == MGRIT_ARCH_CROSS ? b.take_bytes(G * Tm * 2 * d * esz) : nullptr;
   }
 };
 
@@ -385,9 +388,9 @@ int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, floa
 // the T tokens); gelu_u: U = GELU(given buffer).  Results go into the layers' gradient blocks.
 int linear_param_grads(Engine& E, int n, const void* dY, long dy_stride, Slots dy_slots, int out_dim,
                        const void* U, long u_stride, Slots u_slots, int in_dim, bool gelu_u, Params DT,
-                       int w_id, int b_id, float scale) {
+                       int w_id, int b_id, float scale, int tokens = 0) {
   const Slots loc = {0, 1};
-  const int T = E.T;
+  const int T = tokens ? tokens : E.T;
   const Params none = {nullptr, 0, 0};
   HIPCHK(launch_transpose_slots(n, dY, dy_stride, dy_slots, T, out_dim, E.tA, E.tA_stride(), loc, false, E.bf16,
                                 E.gpart, DT, E.glay.offset[b_id], scale, E.st));
@@ -406,8 +409,14 @@ int linear_param_grads(Engine& E, int n, const void* dY, long dy_stride, Slots d
 // the same backward chain with IN = lambda_{n+1}, every linear map and LayerNorm also emitting
 // hstep * (its parameter cotangent), and no state written (paper section 3.1: theta enters the
 // step only through h F, so dtheta_n = h (dF/dtheta_n (Z_n))^T lambda_{n+1}).
+struct GradPass {
+  const Params* DT = nullptr;      // gradient blocks of the chunk's layers, or null
+  float* dE_all = nullptr;         // cross-attention decoder: [layer slot, Tm, d] fp32 memory-gradient terms, or null
+};
+
 int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Params THT, Rows LIN, Slots cs,
-                  float hstep, const Params* DT = nullptr) {
+                  float hstep, const GradPass* gp = nullptr) {
+  const Params* DT = gp ? gp->DT : nullptr;
   const int T = E.T, d = E.d, f = E.f;
   const auto& L = E.lay;
   const Slots loc = {0, 1};
@@ -416,14 +425,14 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
   HIPCHK(launch_cast_rows(n, E.Td(), IN, E.cb, E.Td(), loc, E.bf16, E.st));
   LnFwdArgs lf;
   LnParamArgs lp;
+  memset(&lf, 0, sizeof(lf));
+  memset(&lp, 0, sizeof(lp));
   if (DT) {
     // m = GELU(z) W2^T + b2
     STCHK(linear_param_grads(E, n, E.cb, E.Td(), loc, d, E.c_z, (long)T * f, cs, f, true, *DT, MGRIT_P_W2,
                              MGRIT_P_B2, hstep));
-    memset(&lf, 0, sizeof(lf));
     lf.n_groups = n; lf.T = T; lf.d = d; lf.X = LIN; lf.P = TH; lf.eps = E.md.ln_eps;
     lf.out = E.u; lf.out_slot_stride = E.Td(); lf.out_slots = loc;
-    memset(&lp, 0, sizeof(lp));
     lp.n_groups = n; lp.T = T; lp.d = d; lp.X = LIN; lp.out = *DT; lp.scale = hstep; lp.eps = E.md.ln_eps;
     lp.dy = E.du; lp.dy_slot_stride = E.Td(); lp.dy_slots = loc;
   }
@@ -466,11 +475,15 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
 
   if (E.md.arch == MGRIT_ARCH_CROSS) {
     // Here ds = c + dx2 is the cotangent of ybar = s + CA(LN3(Y + s), E); dxin = dx2.
+    // c = o_c Wo_c^T + bo_c
+    if (DT)
+      STCHK(linear_param_grads(E, n, E.ds, E.Td(), loc, d, E.c_oc, E.Td(), cs, d, false, *DT, MGRIT_P_WO_C,
+                               MGRIT_P_BO_C, hstep));
     // do_c = ds Wo_c
     g = gemm_base(n, T, d, d, E.ds, E.Td(), loc, THT, L.offset[MGRIT_P_WO_C], -1);
     g.out = E.da; g.out_slot_stride = E.Td(); g.out_slots = loc;
     HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
-    // cross-attention backward: only dQ is needed (dK, dV feed the gradient of the memory only)
+    // cross-attention backward: lambda needs dQ only; dK, dV feed the gradients of Wkv_c and of the memory
     AttnArgs ac;
     memset(&ac, 0, sizeof(ac));
     ac.n_groups = n; ac.B = E.md.batch; ac.H = E.H; ac.dh = E.dh; ac.Sq = E.md.seq; ac.Sk = E.md.mem_seq;
@@ -484,12 +497,37 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
     ac.dO = E.da; ac.do_row_stride = d; ac.do_slot_stride = E.Td(); ac.do_slots = loc;
     ac.dq = E.dqkv; ac.dk = nullptr; ac.dv = nullptr;
     ac.dqkv_row_stride = d; ac.dqkv_slot_stride = (long)T * 3 * d; ac.dqkv_slots = loc;
+    if (gp) {
+      ac.dk = E.dkvc; ac.dv = (char*)E.dkvc + (size_t)d * esz;
+      ac.dkv_row_stride = 2 * d; ac.dkv_slot_stride = (long)E.Tm * 2 * d;
+    }
     ac.D = E.Dbuf; ac.D_slot_stride = (long)E.md.batch * E.H * E.md.seq; ac.D_slots = loc;
     HIPCHK(launch_attn_bwd(ac, E.bf16, E.st));
+    if (DT) {
+      // q_c = LN3(Y + s) Wq_c^T + bq_c ;  [k_c | v_c] = E Wkv_c^T + bkv_c
+      lf.xp = E.c_x3; lf.xp_slot_stride = E.Td(); lf.xp_slots = cs;
+      lf.gamma_off = L.offset[MGRIT_P_LN3_G]; lf.beta_off = L.offset[MGRIT_P_LN3_B];
+      HIPCHK(launch_ln_fwd(lf, E.bf16, E.st));
+      STCHK(linear_param_grads(E, n, E.dqkv, (long)T * 3 * d, loc, d, E.u, E.Td(), loc, d, false, *DT,
+                               MGRIT_P_WQ_C, MGRIT_P_BQ_C, hstep));
+      STCHK(linear_param_grads(E, n, E.dkvc, (long)E.Tm * 2 * d, loc, 2 * d, E.memb, 0, loc, d, false, *DT,
+                               MGRIT_P_WKV_C, MGRIT_P_BKV_C, hstep, E.Tm));
+    }
+    if (gp && gp->dE_all) {
+      // this layer's term of dL/dE:  hstep * [dK | dV] Wkv_c       [Tm,2d] x [2d,d]: transposed Wkv_c is [d,2d]
+      g = gemm_base(n, E.Tm, d, 2 * d, E.dkvc, (long)E.Tm * 2 * d, loc, THT, L.offset[MGRIT_P_WKV_C], -1);
+      g.out = gp->dE_all; g.out_slot_stride = (long)E.Tm * d; g.out_slots = cs; g.hstep = hstep;
+      HIPCHK(launch_gemm(g, EPI_STORE_F32, E.bf16, E.st));
+    }
     // du3 = dq_c Wq_c
     g = gemm_base(n, T, d, d, E.dqkv, (long)T * 3 * d, loc, THT, L.offset[MGRIT_P_WQ_C], -1);
     g.out = E.du; g.out_slot_stride = E.Td(); g.out_slots = loc;
     HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+    if (DT) {
+      lp.xp = E.c_x3; lp.xp_slot_stride = E.Td(); lp.xp_slots = cs;
+      lp.gamma_off = E.glay.offset[MGRIT_P_LN3_G]; lp.beta_off = E.glay.offset[MGRIT_P_LN3_B];
+      HIPCHK(launch_ln_param_grad(lp, E.gpart, E.bf16, E.st));
+    }
     // dx3 = LN3^T du3 at Y + s;  dxin <- dx2 + dx3 (in place);  ds <- c + dx2 + dx3
     memset(&lb, 0, sizeof(lb));
     lb.n_groups = n; lb.T = T; lb.d = d; lb.eps = E.md.ln_eps;
@@ -547,8 +585,8 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
     lp.xp = nullptr;
     lp.gamma_off = E.glay.offset[MGRIT_P_LN1_G]; lp.beta_off = E.glay.offset[MGRIT_P_LN1_B];
     HIPCHK(launch_ln_param_grad(lp, E.gpart, E.bf16, E.st));
-    return MGRIT_OK;
   }
+  if (gp) return MGRIT_OK;           // a gradient pass writes no state
 
   // dX = dX' + LN1^T du1 ;  OUT = c + hstep dX (+ RHS)
   memset(&lb, 0, sizeof(lb));
@@ -601,17 +639,21 @@ int adjoint_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Pa
 }
 
 // parameter gradients of G layers: group g has IN = lambda_{n+1}, LIN = Z_n, gradient block DT[g]
-int gradient_groups(Engine& E, Engine* E2, int G, Rows IN, Params TH, Params THT, Rows LIN, Slots cs, Params DT,
-                    float hstep) {
+int gradient_groups(Engine& E, Engine* E2, int G, Rows IN, Params TH, Params THT, Rows LIN, Slots cs,
+                    const Params* DT, float* dE_all, float hstep) {
   return run_chunks(E, E2, G, [&](Engine& L, int c0, int n) {
-    const Params dt = shift(DT, c0);
+    Params dt = {nullptr, 0, 0};
+    GradPass gp;
+    if (DT) { dt = shift(*DT, c0); gp.DT = &dt; }
+    gp.dE_all = dE_all;
     return adjoint_chunk(L, n, shift(IN, c0), NO_ROWS, NO_ROWS, shift(TH, c0), shift(THT, c0), shift(LIN, c0),
-                         shift(cs, c0), hstep, &dt);
+                         shift(cs, c0), hstep, &gp);
   });
 }
 
 int transpose_blocks(Engine& E, int n, Params TH, Params THT) {
-  static const int mats[] = {MGRIT_P_WQKV, MGRIT_P_WO, MGRIT_P_W1, MGRIT_P_W2, MGRIT_P_WQ_C, MGRIT_P_WO_C};
+  static const int mats[] = {MGRIT_P_WQKV, MGRIT_P_WO, MGRIT_P_W1, MGRIT_P_W2, MGRIT_P_WQ_C, MGRIT_P_WO_C,
+                             MGRIT_P_WKV_C};
   for (int id : mats) {
     if (E.lay.offset[id] < 0) continue;
     HIPCHK(launch_transpose(n, TH, THT, E.lay.offset[id], E.lay.rows[id], E.lay.cols[id], E.lay.elem_bytes[id],
@@ -717,6 +759,7 @@ struct Plan {                       // workspace of mgrit_forward / mgrit_adjoin
   Driver D;
   void* thT_blocks = nullptr;
   void** tabDT = nullptr;           // layer n -> gradient block (adjoint with parameter gradients)
+  float* dE_all = nullptr;          // cross-attention decoder: per-layer terms of the memory gradient
   size_t bytes = 0;
 };
 
@@ -746,6 +789,7 @@ int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, int mod
   }
   if (mode == 2) {
     P.tabDT = b.take<void*>(N);
+    if (md->arch == MGRIT_ARCH_CROSS) P.dE_all = b.take<float>((size_t)N * E.Tm * E.d);
     for (Engine* L : {&E, P.two_lanes ? &P.E2 : nullptr}) {
       if (!L) continue;
       L->carve_grad_work(b);
@@ -802,7 +846,6 @@ int mgrit_theta_layout(const mgrit_model_desc* desc, mgrit_theta_layout_t* out) 
 size_t mgrit_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts, int adjoint) {
   if (validate_desc(desc) != MGRIT_OK || validate_opts(opts) != MGRIT_OK) return 0;
   if (adjoint < 0 || adjoint > 2) return 0;
-  if (adjoint == 2 && desc->arch == MGRIT_ARCH_CROSS) return 0;
   Plan P;
   if (make_plan(P, desc, opts, adjoint, nullptr, nullptr) != MGRIT_OK) return 0;
   return P.bytes;
@@ -877,13 +920,12 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
                   void* stream) {
   STCHK(validate_desc(desc));
   STCHK(validate_opts(opts));
-  if (dmemory) return MGRIT_UNSUPPORTED;
-  if (dtheta && desc->arch == MGRIT_ARCH_CROSS) return MGRIT_UNSUPPORTED;
+  if (dmemory && desc->arch != MGRIT_ARCH_CROSS) return MGRIT_INVALID_ARG;
   if (desc->arch == MGRIT_ARCH_CROSS && !memory) return MGRIT_INVALID_ARG;
   if (!Z_all || !lambda_N || !lambda_all || !workspace) return MGRIT_INVALID_ARG;
   STCHK(check_ptr_array(theta, opts->N));
   if (dtheta) STCHK(check_ptr_array((const void* const*)dtheta, opts->N));
-  const int mode = dtheta ? 2 : 1;
+  const int mode = (dtheta || dmemory) ? 2 : 1;
   const size_t need = mgrit_workspace_bytes(desc, opts, mode);
   if (need == 0) return MGRIT_INVALID_ARG;
   if (workspace_bytes < need) return MGRIT_WORKSPACE_TOO_SMALL;
@@ -918,12 +960,16 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
   }
   D.resnorm = resnorm;
   STCHK(D.run(opts->iters));
-  if (dtheta) {
+  if (dtheta || dmemory) {
     // one batched pass over all layers: layer n takes lambda_{n+1} (point N-1-n of the reversed grid)
-    HIPCHK(upload_pointers(P.tabDT, (const void* const*)dtheta, N, st));
+    if (dtheta) HIPCHK(upload_pointers(P.tabDT, (const void* const*)dtheta, N, st));
     Rows LamNext = {(const void* const*)D.tabW, N - 1, -1};
     Params DT = {(const void* const*)P.tabDT, 0, 1};
-    STCHK(gradient_groups(E, D.E2, N, LamNext, TH, THT, Zrows, Slots{0, 1}, DT, opts->h));
+    STCHK(gradient_groups(E, D.E2, N, LamNext, TH, THT, Zrows, Slots{0, 1}, dtheta ? &DT : nullptr,
+                          dmemory ? P.dE_all : nullptr, opts->h));
+    // dL/dE = sum over layers of the per-layer terms, in layer order
+    if (dmemory)
+      HIPCHK(launch_sum_slots(P.dE_all, N, (long)E.Tm * E.d, static_cast<float*>(dmemory), 1.0f, st));
   }
   return MGRIT_OK;
 }

@@ -104,7 +104,8 @@ def test_parameter_gradient_workspace_and_support():
     assert mb.mgrit_workspace_bytes(desc, opts, 2) > mb.mgrit_workspace_bytes(desc, opts, 1) > 0
     assert mb.mgrit_workspace_bytes(desc, opts, 3) == 0
     dec = mb.model_desc(wls.named_workloads()["mt_decoder"])
-    assert mb.mgrit_workspace_bytes(dec, mb.mgrit_opts(32, 1 / 32, 4, 2, 2), 2) == 0     # no dtheta for arch 2
+    dopts = mb.mgrit_opts(32, 1 / 32, 4, 2, 2)
+    assert mb.mgrit_workspace_bytes(dec, dopts, 2) > mb.mgrit_workspace_bytes(dec, dopts, 1) > 0
     # a gradient block is the fp32 parameter block: same tensors, 4-byte entries, in order
     lay, glay = mb.mgrit_theta_layout(desc), mb.grad_layout(desc)
     for i in range(mb.P_COUNT):

@@ -39,7 +39,7 @@ def compare_layer(got, ref, tol, what):
     return worst
 
 
-def run_case(wl, weight_std=0.08, max_groups=0):
+def run_case(wl, weight_std=0.08, max_groups=0, memory=None):
     print(f"[case] dtheta {wl.name} arch={wl.arch} dtype={wl.dtype} d={wl.d_model} B={wl.batch} S={wl.seq} "
           f"N={wl.N} cf={wl.cf} L={wl.levels} it={wl.iters} mg={max_groups}", flush=True)
     mb.mgrit_set_max_groups_per_launch(max_groups)
@@ -48,29 +48,44 @@ def run_case(wl, weight_std=0.08, max_groups=0):
         sh = shape_of(wl)
         tol = TOL[wl.dtype]
         opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters)
-        Zg, _ = mb.mgrit_forward(dm.desc, opts, dev(wls.initial_state(wl)), dm.blocks)
+        cross = wl.arch == wls.ARCH_CROSS
+        mem = (wls.cross_memory(wl) if memory is None else memory) if cross else None
+        dmem = None if mem is None else dev(mem)
+        Zg, _ = mb.mgrit_forward(dm.desc, opts, dev(wls.initial_state(wl)), dm.blocks, memory=dmem)
         lamN = wls.terminal_adjoint(wl)
         blocks = grad_blocks(dm.desc, wl.N)
-        lg, _ = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN), dtheta=blocks)
+        dE = torch.full((wl.batch * wl.mem_seq, wl.d_model), float("nan"), device="cuda") if cross else None
+        lg, _ = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN), memory=dmem, dtheta=blocks, dmemory=dE)
         torch.cuda.synchronize()
         # the adjoint states must not depend on whether gradients were asked for
-        lg2, _ = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN))
+        lg2, _ = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN), memory=dmem)
         torch.cuda.synchronize()
         assert torch.equal(lg, lg2)
         Zlin = list(Zg.cpu().numpy().astype(np.float64))
-        lr, _, _ = omgrit.mgrit_adjoint(lamN, Zlin, dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh)
-        ref = omgrit.parameter_gradients(lr, Zlin, dm.host, wl.h, sh)
+        lr, _, _ = omgrit.mgrit_adjoint(lamN, Zlin, dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh, mem)
+        ref = omgrit.parameter_gradients(lr, Zlin, dm.host, wl.h, sh, mem)
         worst = 0.0
         for n in range(wl.N):
             worst = max(worst, compare_layer(mb.unpack_grad(dm.desc, blocks[n]), ref[n], tol, f"layer {n}"))
         print(f"  worst relative error over all parameters and layers: {worst:.2e} (bar {tol})")
+        if cross:
+            dE_ref = omgrit.memory_gradient(lr, Zlin, dm.host, wl.h, sh, mem)
+            e = relerr(dE.cpu().numpy(), dE_ref)
+            print(f"  memory gradient: relative error {e:.2e} (bar {tol})")
+            assert e <= tol
+            # asking for the memory gradient alone gives the same numbers
+            dE2 = torch.full_like(dE, float("nan"))
+            mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN), memory=dmem, dmemory=dE2)
+            torch.cuda.synchronize()
+            assert torch.equal(dE, dE2)
     finally:
         mb.mgrit_set_max_groups_per_launch(0)
 
 
 def tiny(arch=wls.ARCH_ENCODER, dtype=wls.DTYPE_F32, N=16, cf=4, levels=2, iters=2, h=1.0, d=64, H=4, f=128,
          B=2, S=24, seed=43):
-    return wls.Workload("tiny", arch, d, H, f, B, S, 0, N, h, cf, levels, iters, dtype, seed)
+    return wls.Workload("tiny", arch, d, H, f, B, S, 20 if arch == wls.ARCH_CROSS else 0, N, h, cf, levels, iters,
+                        dtype, seed)
 
 
 @pytest.mark.parametrize("max_groups", [0, 3])
@@ -80,6 +95,15 @@ def test_two_level_encoder_fp32(max_groups):
 
 def test_three_level_causal_fp32():
     run_case(tiny(arch=wls.ARCH_CAUSAL, N=16, cf=2, levels=3))
+
+
+def test_cross_attention_decoder_fp32():
+    run_case(tiny(arch=wls.ARCH_CROSS, N=8, cf=4, levels=2))
+
+
+def test_mt_decoder_shape_reduced_bf16():
+    # model shape of the translation decoder; the memory is a seeded stand-in for the encoder output
+    run_case(wls.named_workloads()["mt_decoder"].scaled(batch=4, N=8, h=1.0 / 8), weight_std=0.02)
 
 
 def test_serial_limit_fp32():
@@ -116,3 +140,32 @@ def test_full_size_bert_sampled_layers():
         print(f"  layer {n}: worst relative error {worst:.2e} (bar {tol})", flush=True)
     for n in range(wl.N):       # every block was written
         assert torch.isfinite(blocks[n].view(torch.float32)).all(), n
+
+
+def test_full_size_mt_decoder_sampled_layers_and_memory_gradient():
+    """Translation decoder at full batch: parameter gradients of layers 0, 17, 31 and the memory gradient
+    (all 32 per-layer terms) recomputed by the oracle from the GPU's Y_n and lambda_{n+1}.  The memory is
+    a seeded stand-in for the encoder output."""
+    wl = wls.named_workloads()["mt_decoder"]
+    print(f"[case] dtheta + dmemory full size {wl.name}", flush=True)
+    dm = DeviceModel(wl)
+    sh = shape_of(wl)
+    tol = TOL[wl.dtype]
+    opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters)
+    mem = wls.cross_memory(wl)
+    dmem = dev(mem)
+    Yg, _ = mb.mgrit_forward(dm.desc, opts, dev(wls.initial_state(wl)), dm.blocks, memory=dmem)
+    blocks = grad_blocks(dm.desc, wl.N)
+    dE = torch.full((wl.batch * wl.mem_seq, wl.d_model), float("nan"), device="cuda")
+    lg, _ = mb.mgrit_adjoint(dm.desc, opts, Yg, dm.blocks, dev(wls.terminal_adjoint(wl)), memory=dmem, dtheta=blocks,
+                             dmemory=dE)
+    torch.cuda.synchronize()
+    Y = Yg.cpu().numpy().astype(np.float64)
+    lam = lg.cpu().numpy().astype(np.float64)
+    for n in (0, 17, 31):
+        ref = {k: wl.h * v for k, v in tode.F_param_vjp(Y[n], dm.host[n], lam[n + 1], sh, mem).items()}
+        worst = compare_layer(mb.unpack_grad(dm.desc, blocks[n]), ref, tol, f"layer {n}")
+        print(f"  layer {n}: worst relative error {worst:.2e} (bar {tol})", flush=True)
+    e = relerr(dE.cpu().numpy(), omgrit.memory_gradient(list(lam), list(Y), dm.host, wl.h, sh, mem))
+    print(f"  memory gradient: relative error {e:.2e} (bar {tol})", flush=True)
+    assert e <= tol

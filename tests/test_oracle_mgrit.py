@@ -346,3 +346,35 @@ def test_parameter_gradients_are_the_gradient_of_the_serial_network():
     g2 = mgrit.parameter_gradients(lam2, Z, th, wl.h, sh)
     for name in grads[1]:
         assert np.allclose(g2[1][name], -3.0 * grads[1][name], rtol=1e-12, atol=1e-14)
+
+
+def test_decoder_memory_and_parameter_gradients_by_finite_differences():
+    """Cross-attention decoder: dL/dE (sum of one term per layer) and the cross-attention parameters'
+    gradients equal central finite differences of <C, Y_N> through the serial decoder network."""
+    wl, sh, th = tiny(arch=wls.ARCH_CROSS, N=4, h=0.5, std=0.4, B=2)
+    Y0 = wls.initial_state(wl).astype(np.float64)
+    C = wls.terminal_adjoint(wl).astype(np.float64)
+    E = wls.cross_memory(wl).astype(np.float64)
+    Y = mgrit.serial_forward(Y0, th, wl.h, sh, E)
+    lam = mgrit.serial_adjoint(C, Y, th, wl.h, sh, E)
+    dE = mgrit.memory_gradient(lam, Y, th, wl.h, sh, E)
+    grads = mgrit.parameter_gradients(lam, Y, th, wl.h, sh, E)
+    rng = np.random.default_rng(8)
+    eps = 1e-6
+    for _ in range(4):
+        v = rng.standard_normal(E.shape)
+        fd = ((C * mgrit.serial_forward(Y0, th, wl.h, sh, E + eps * v)[-1]).sum() -
+              (C * mgrit.serial_forward(Y0, th, wl.h, sh, E - eps * v)[-1]).sum()) / (2 * eps)
+        assert abs(fd - (dE * v).sum()) < 1e-7 * max(1.0, abs(fd))
+    for n in (0, 3):
+        for name in ("Wkv_c", "bkv_c", "Wq_c", "bq_c", "Wo_c", "bo_c", "ln3_g", "ln3_b"):
+            shape = wls.param_shapes(wl)[name]
+            idx = tuple(int(rng.integers(0, s)) for s in shape)
+            def loss(delta):
+                t = [dict(x) for x in th]
+                w = np.array(t[n][name], dtype=np.float64)
+                w[idx] += delta
+                t[n][name] = w
+                return (C * mgrit.serial_forward(Y0, t, wl.h, sh, E)[-1]).sum()
+            fd = (loss(eps) - loss(-eps)) / (2 * eps)
+            assert abs(fd - grads[n][name][idx]) < 2e-6 * max(1.0, abs(fd)), (n, name, idx)
