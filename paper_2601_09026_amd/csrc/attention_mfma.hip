@@ -217,11 +217,17 @@ __global__ void __launch_bounds__(NW * 64, 4) attn_fwd_mfma_kernel(const AttnArg
 // ---------------------------------------------------------------------------
 // backward pass 1: D and dQ, one wavefront per 32 query rows
 // ---------------------------------------------------------------------------
+// LDS of the two backward passes (bf16 elements): pass 1 stages K, V row-major and K transposed;
+// pass 2 stages Q, dO both ways.  The fused kernel runs them one after the other in the same buffer.
+constexpr int BWD_DQ_LDS = 2 * 64 * FA_LD + 64 * FA_LDT;
+constexpr int BWD_DKV_LDS = 2 * 64 * FA_LD + 2 * 64 * FA_LDT;
+
+// d_local: if not null, D of the block's query rows is also left there (index = row - q0)
 template <int NW>
-__global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dq_mfma_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * FA_LD];     // [key][d]
-  __shared__ __attribute__((aligned(16))) bf16 Vs[64 * FA_LD];     // [key][d]
-  __shared__ __attribute__((aligned(16))) bf16 Kt[64 * FA_LDT];     // [d][key]
+__device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, float* d_local) {
+  bf16* Ks = lds;                        // [key][d]
+  bf16* Vs = Ks + 64 * FA_LD;            // [key][d]
+  bf16* Kt = Vs + 64 * FA_LD;            // [d][key]
   const int g = blockIdx.z;
   const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
   const int q0 = blockIdx.x * (NW * 32);
@@ -242,6 +248,7 @@ __global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dq_mfma_kernel(const Attn
   Dq += __shfl_xor(Dq, 32, 64);
   const float lse2 = P.lse[qc] * LOG2E;
   if (qi < a.Sq && lh == 0) P.D[qi] = Dq;
+  if (d_local && lh == 0) d_local[wave * 32 + lr] = Dq;
 
   const float c = rsqrtf(64.f) * LOG2E;
   f32x16 dq[2] = {zero16(), zero16()};
@@ -280,16 +287,23 @@ __global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dq_mfma_kernel(const Attn
   if (qi < a.Sq) store_rows_T(P.dQ, a.dqkv_row_stride, qi, dq, rsqrtf(64.f), lh);
 }
 
+template <int NW>
+__global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dq_mfma_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16 lds[BWD_DQ_LDS];
+  attn_bwd_dq_body<NW>(a, lds, nullptr);
+}
+
 // ---------------------------------------------------------------------------
 // backward pass 2: dK and dV, one wavefront per 32 key rows
 // ---------------------------------------------------------------------------
+// d_src: D of query row i at d_src[i] (the global array of pass 1, or the fused kernel's LDS copy)
 template <int NW>
-__global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dkv_mfma_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16 Qs[64 * FA_LD];     // [query][d]
-  __shared__ __attribute__((aligned(16))) bf16 dOs[64 * FA_LD];    // [query][d]
-  __shared__ __attribute__((aligned(16))) bf16 Qt[64 * FA_LDT];     // [d][query]
-  __shared__ __attribute__((aligned(16))) bf16 dOt[64 * FA_LDT];    // [d][query]
-  __shared__ float Ls[64], Ds[64];
+__device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, float* Ls, float* Ds,
+                                                  const float* d_src) {
+  bf16* Qs = lds;                        // [query][d]
+  bf16* dOs = Qs + 64 * FA_LD;           // [query][d]
+  bf16* Qt = dOs + 64 * FA_LD;           // [d][query]
+  bf16* dOt = Qt + 64 * FA_LDT;          // [d][query]
   const int g = blockIdx.z;
   const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
   const int j0 = blockIdx.x * (NW * 32);
@@ -316,7 +330,7 @@ __global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dkv_mfma_kernel(const Att
       const int qq = i0 + threadIdx.x;
       const int qcl = qq < a.Sq ? qq : a.Sq - 1;
       Ls[threadIdx.x] = P.lse[qcl] * LOG2E;
-      Ds[threadIdx.x] = P.D[qcl];
+      Ds[threadIdx.x] = d_src ? d_src[qcl] : P.D[qcl];
     }
     __syncthreads();
     if (a.causal && i0 + 63 < k_wave_first) continue;      // every query of the tile precedes this wave's keys
@@ -355,6 +369,25 @@ __global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dkv_mfma_kernel(const Att
   }
 }
 
+template <int NW>
+__global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dkv_mfma_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16 lds[BWD_DKV_LDS];
+  __shared__ float Ls[64], Ds[64];
+  attn_bwd_dkv_body<NW>(a, lds, Ls, Ds, nullptr);
+}
+
+// Sequences that fit one block (Sq, Sk <= 32 NW): both passes in one launch.  The head's Q, K, V,
+// dO are then read from HBM once (pass 2 finds them in L2) and D never leaves the CU.
+template <int NW>
+__global__ void __launch_bounds__(NW * 64, 3) attn_bwd_fused_mfma_kernel(const AttnArgs a) {
+  constexpr int LDS = BWD_DQ_LDS > BWD_DKV_LDS ? BWD_DQ_LDS : BWD_DKV_LDS;
+  __shared__ __attribute__((aligned(16))) bf16 lds[LDS];
+  __shared__ float Ls[64], Ds[64], Dall[NW * 32];
+  attn_bwd_dq_body<NW>(a, lds, Dall);
+  __syncthreads();
+  attn_bwd_dkv_body<NW>(a, lds, Ls, Ds, Dall);
+}
+
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
@@ -375,6 +408,12 @@ hipError_t attn_fwd_mfma(const AttnArgs& a, hipStream_t st) {
 }
 
 hipError_t attn_bwd_mfma(const AttnArgs& a, hipStream_t st) {
+  if (a.dk && a.Sq <= 128 && a.Sk <= 128) {
+    dim3 grid(1, a.B * a.H, a.n_groups);
+    if (a.Sq <= 64 && a.Sk <= 64) hipLaunchKernelGGL(attn_bwd_fused_mfma_kernel<2>, grid, dim3(128), 0, st, a);
+    else hipLaunchKernelGGL(attn_bwd_fused_mfma_kernel<4>, grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+  }
   if (a.Sq <= 64) {
     dim3 grid((a.Sq + 63) / 64, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel<2>, grid, dim3(128), 0, st, a);
