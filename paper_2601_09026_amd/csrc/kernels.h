@@ -17,6 +17,10 @@ struct LnFwdArgs {
   Params P; long gamma_off, beta_off;
   void* out; long out_slot_stride; Slots out_slots;       // packed, operand type
   float eps;
+  // optional (linearisation cache): the normalised row xhat = (x - mean) * rstd, packed operand type with
+  // the same row layout as `out`, and rstd, one float per row ([slot][T])
+  void* xhat; long xhat_slot_stride; Slots xhat_slots;
+  float* rstd;
 };
 hipError_t launch_ln_fwd(const LnFwdArgs& a, bool is_bf16, hipStream_t st);
 
@@ -32,6 +36,11 @@ struct LnBwdArgs {
   void* out_op; long oo_slot_stride; Slots oo_slots;         // optional packed operand type: c + v
   Rows OUT; Rows RHS; float hstep;                           // optional: OUT = c + hstep*v (+ RHS)
   float eps;
+  // optional: the LN input given as cached xhat (packed operand type) and rstd ([slot][T]) instead of X / xp
+  const void* xhat; long xhat_slot_stride; Slots xhat_slots;
+  const float* rstd;
+  // optional: c as a packed operand-type copy, used for out_op in place of the fp32 rows C
+  const void* cop; long cop_slot_stride; Slots cop_slots;
 };
 hipError_t launch_ln_bwd(const LnBwdArgs& a, bool is_bf16, hipStream_t st);
 

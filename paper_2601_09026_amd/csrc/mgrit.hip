@@ -149,6 +149,8 @@ struct Engine {
   int n_cache;
   void *c_qkv, *c_o, *c_z;
   float *c_lse, *c_xin;
+  void *c_xh1, *c_xh2;             // normalised LN1 / LN2 inputs (operand type) ...
+  float *c_rs1, *c_rs2;            // ... and their 1/std, one per token
   void *c_qc, *c_kvc, *c_oc;       // cross-attention decoder only
   float *c_lsec, *c_x3;
   void *cb, *dz, *du, *ds, *da, *dqkv;
@@ -203,6 +205,10 @@ struct Engine {
     c_z = b.take_bytes(C * T * f * esz);
     c_lse = b.take<float>(C * md.batch * H * md.seq);
     c_xin = b.take<float>(C * T * d);
+    c_xh1 = b.take_bytes(C * T * d * esz);
+    c_xh2 = b.take_bytes(C * T * d * esz);
+    c_rs1 = b.take<float>(C * T);
+    c_rs2 = b.take<float>(C * T);
     memb = nullptr; c_qc = c_kvc = c_oc = nullptr; c_lsec = c_x3 = nullptr;
     if (md.arch == MGRIT_ARCH_CROSS) {
       c_qc = b.take_bytes(C * T * d * esz);
@@ -307,7 +313,9 @@ int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, floa
   ln.n_groups = n; ln.T = T; ln.d = d; ln.X = IN; ln.P = TH;
   ln.gamma_off = L.offset[MGRIT_P_LN1_G]; ln.beta_off = L.offset[MGRIT_P_LN1_B];
   ln.out = E.u; ln.out_slot_stride = E.Td(); ln.out_slots = loc; ln.eps = E.md.ln_eps;
+  if (cache) { ln.xhat = E.c_xh1; ln.xhat_slot_stride = E.Td(); ln.xhat_slots = cs; ln.rstd = E.c_rs1; }
   HIPCHK(launch_ln_fwd(ln, E.bf16, E.st));
+  ln.xhat = nullptr; ln.rstd = nullptr;
 
   GemmArgs g = gemm_base(n, T, 3 * d, d, E.u, E.Td(), loc, TH, L.offset[MGRIT_P_WQKV], L.offset[MGRIT_P_BQKV]);
   g.out = qkv; g.out_slot_stride = (long)T * 3 * d; g.out_slots = cs;
@@ -363,6 +371,7 @@ int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, floa
 
   ln.X = IN; ln.xp = xin; ln.xp_slot_stride = E.Td(); ln.xp_slots = cs;          // LN2(X + ybar)
   ln.gamma_off = L.offset[MGRIT_P_LN2_G]; ln.beta_off = L.offset[MGRIT_P_LN2_B];
+  if (cache) { ln.xhat = E.c_xh2; ln.xhat_slot_stride = E.Td(); ln.xhat_slots = cs; ln.rstd = E.c_rs2; }
   HIPCHK(launch_ln_fwd(ln, E.bf16, E.st));
 
   g = gemm_base(n, T, f, d, E.u, E.Td(), loc, TH, L.offset[MGRIT_P_W1], L.offset[MGRIT_P_B1]);
@@ -467,10 +476,11 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
   memset(&lb, 0, sizeof(lb));
   lb.n_groups = n; lb.T = T; lb.d = d; lb.eps = E.md.ln_eps;
   lb.dy = E.du; lb.dy_slot_stride = E.Td(); lb.dy_slots = loc;
-  lb.X = LIN; lb.xp = E.c_xin; lb.xp_slot_stride = E.Td(); lb.xp_slots = cs;    // LN2 input X + s
+  lb.xhat = E.c_xh2; lb.xhat_slot_stride = E.Td(); lb.xhat_slots = cs; lb.rstd = E.c_rs2;   // LN2 input X + ybar
   lb.P = TH; lb.gamma_off = L.offset[MGRIT_P_LN2_G];
   lb.out_f32 = E.dxin; lb.of_slot_stride = E.Td(); lb.of_slots = loc;
-  lb.C = IN; lb.out_op = E.ds; lb.oo_slot_stride = E.Td(); lb.oo_slots = loc;
+  lb.cop = E.cb; lb.cop_slot_stride = E.Td(); lb.cop_slots = loc;
+  lb.out_op = E.ds; lb.oo_slot_stride = E.Td(); lb.oo_slots = loc;
   HIPCHK(launch_ln_bwd(lb, E.bf16, E.st));
 
   if (E.md.arch == MGRIT_ARCH_CROSS) {
@@ -592,7 +602,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
   memset(&lb, 0, sizeof(lb));
   lb.n_groups = n; lb.T = T; lb.d = d; lb.eps = E.md.ln_eps;
   lb.dy = E.du; lb.dy_slot_stride = E.Td(); lb.dy_slots = loc;
-  lb.X = LIN;
+  lb.xhat = E.c_xh1; lb.xhat_slot_stride = E.Td(); lb.xhat_slots = cs; lb.rstd = E.c_rs1;
   lb.P = TH; lb.gamma_off = L.offset[MGRIT_P_LN1_G];
   lb.add = E.dxin; lb.add_slot_stride = E.Td(); lb.add_slots = loc;
   lb.C = IN; lb.OUT = OUT; lb.RHS = RHS; lb.hstep = hstep;

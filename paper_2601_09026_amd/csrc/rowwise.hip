@@ -69,12 +69,16 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const LnFwdArgs a) {
     const float* gamma = reinterpret_cast<const float*>(pb + a.gamma_off);
     const float* beta = reinterpret_cast<const float*>(pb + a.beta_off);
     TO* out = reinterpret_cast<TO*>(a.out) + a.out_slots.of(g) * a.out_slot_stride + (long)t * d;
+    TO* xh = a.xhat ? reinterpret_cast<TO*>(a.xhat) + a.xhat_slots.of(g) * a.xhat_slot_stride + (long)t * d : nullptr;
+    if (xh && lane == 0) a.rstd[a.xhat_slots.of(g) * a.T + t] = rstd;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int c = (i * 64 + lane) * 4;
-      if (c < d)
-        store4<TO>(out + c, cur[i] * rstd * *reinterpret_cast<const f32x4*>(gamma + c) +
-                                *reinterpret_cast<const f32x4*>(beta + c));
+      if (c < d) {
+        const f32x4 xn = cur[i] * rstd;
+        if (xh) store4<TO>(xh + c, xn);
+        store4<TO>(out + c, xn * *reinterpret_cast<const f32x4*>(gamma + c) + *reinterpret_cast<const f32x4*>(beta + c));
+      }
     }
     if (next >= total) break;
     if constexpr (PREFETCH) {
@@ -122,7 +126,7 @@ hipError_t launch_ln_fwd(const LnFwdArgs& a, bool is_bf16, hipStream_t st) {
 //   vjp  = rstd*(dxhat - mean(dxhat) - xhat*mean(dxhat*xhat))
 //   v = add + vjp;  out_f32 = v;  out_op = c + v;  OUT = c + hstep*v + RHS
 // ---------------------------------------------------------------------------
-template <typename TO, int NV>
+template <typename TO, int NV, bool XH>
 __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
   const int lane = threadIdx.x & 63;
   const int total = a.n_groups * a.T;
@@ -131,43 +135,58 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
   int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= total) return;
 
-  auto load = [&](int r, f32x4* v, f32x4* w) {
+  // XH: the row arrives normalised (cached xhat, rs = its rstd); otherwise as X (+ addend)
+  auto load = [&](int r, f32x4* v, f32x4* w, float& rs) {
     const int g = r / a.T, t = r - g * a.T;
     const long ro = (long)t * d;
-    const float* x = a.X.present() ? a.X.at(g) + ro : nullptr;
-    const float* xa = a.xp ? a.xp + a.xp_slots.of(g) * a.xp_slot_stride + ro : nullptr;
     const TO* dy = reinterpret_cast<const TO*>(a.dy) + a.dy_slots.of(g) * a.dy_slot_stride + ro;
+    if constexpr (XH) {
+      const TO* xh = reinterpret_cast<const TO*>(a.xhat) + a.xhat_slots.of(g) * a.xhat_slot_stride + ro;
+      rs = a.rstd[a.xhat_slots.of(g) * a.T + t];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = (i * 64 + lane) * 4;
-      if (c < d) { v[i] = load_sum(x, xa, c); w[i] = load4<TO>(dy + c); }
+      for (int i = 0; i < NV; ++i) {
+        const int c = (i * 64 + lane) * 4;
+        if (c < d) { v[i] = load4<TO>(xh + c); w[i] = load4<TO>(dy + c); }
+      }
+    } else {
+      const float* x = a.X.present() ? a.X.at(g) + ro : nullptr;
+      const float* xa = a.xp ? a.xp + a.xp_slots.of(g) * a.xp_slot_stride + ro : nullptr;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int c = (i * 64 + lane) * 4;
+        if (c < d) { v[i] = load_sum(x, xa, c); w[i] = load4<TO>(dy + c); }
+      }
     }
   };
   constexpr bool PREFETCH = NV <= 4;                 // wider rows would spill: load in place instead
   f32x4 v[NV], w[NV], nv_[PREFETCH ? NV : 1], nw_[PREFETCH ? NV : 1];
-  load(row, v, w);
+  float rs_cur = 0.f, rs_next = 0.f;
+  load(row, v, w, rs_cur);
   while (true) {
     const int next = row + nwaves;
-    if (PREFETCH && next < total) load(next, nv_, nw_);
+    if (PREFETCH && next < total) load(next, nv_, nw_, rs_next);
     const int g = row / a.T, t = row - g * a.T;
     const long ro = (long)t * d;
     const float* gamma = reinterpret_cast<const float*>(a.P.at(g) + a.gamma_off);
-    float s = 0.f;
+    float rstd = rs_cur;
+    if constexpr (!XH) {
+      float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < NV; ++i)
-      if ((i * 64 + lane) * 4 < d) s += sum4(v[i]);
-    const float mu = wave_sum(s) / d;
-    float q = 0.f;
+      for (int i = 0; i < NV; ++i)
+        if ((i * 64 + lane) * 4 < d) s += sum4(v[i]);
+      const float mu = wave_sum(s) / d;
+      float q = 0.f;
 #pragma unroll
-    for (int i = 0; i < NV; ++i)
-      if ((i * 64 + lane) * 4 < d) { v[i] = v[i] - mu; q += dot4(v[i], v[i]); }
-    const float rstd = 1.0f / sqrtf(wave_sum(q) / d + a.eps);
+      for (int i = 0; i < NV; ++i)
+        if ((i * 64 + lane) * 4 < d) { v[i] = v[i] - mu; q += dot4(v[i], v[i]); }
+      rstd = 1.0f / sqrtf(wave_sum(q) / d + a.eps);
+    }
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int c = (i * 64 + lane) * 4;
       if (c < d) {
-        v[i] = v[i] * rstd;                                              // xhat
+        if constexpr (!XH) v[i] = v[i] * rstd;                           // xhat
         w[i] = w[i] * *reinterpret_cast<const f32x4*>(gamma + c);        // dxhat
         s1 += sum4(w[i]);
         s2 += dot4(w[i], v[i]);
@@ -177,7 +196,8 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
     const float* add = a.add ? a.add + a.add_slots.of(g) * a.add_slot_stride + ro : nullptr;
     float* of = a.out_f32 ? a.out_f32 + a.of_slots.of(g) * a.of_slot_stride + ro : nullptr;
     TO* oo = a.out_op ? reinterpret_cast<TO*>(a.out_op) + a.oo_slots.of(g) * a.oo_slot_stride + ro : nullptr;
-    const bool need_c = oo != nullptr || a.OUT.present();
+    const TO* cop = a.cop ? reinterpret_cast<const TO*>(a.cop) + a.cop_slots.of(g) * a.cop_slot_stride + ro : nullptr;
+    const bool need_c = (oo != nullptr && !cop) || a.OUT.present();
     const float* cvec = need_c ? a.C.at(g) + ro : nullptr;
     float* OUT = a.OUT.present() ? a.OUT.at(g) + ro : nullptr;
     const float* RHS = a.RHS.present() ? a.RHS.at(g) + ro : nullptr;
@@ -188,9 +208,10 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
         f32x4 r = rstd * (w[i] - m1 - v[i] * m2);
         if (add) r += *reinterpret_cast<const f32x4*>(add + c);
         if (of) *reinterpret_cast<f32x4*>(of + c) = r;
+        if (oo && cop) store4<TO>(oo + c, load4<TO>(cop + c) + r);
         if (need_c) {
           f32x4 cc = *reinterpret_cast<const f32x4*>(cvec + c);
-          if (oo) store4<TO>(oo + c, cc + r);
+          if (oo && !cop) store4<TO>(oo + c, cc + r);
           if (OUT) {
             f32x4 res = cc + a.hstep * r;
             if (RHS) res += *reinterpret_cast<const f32x4*>(RHS + c);
@@ -203,21 +224,22 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
     if constexpr (PREFETCH) {
 #pragma unroll
       for (int i = 0; i < NV; ++i) { v[i] = nv_[i]; w[i] = nw_[i]; }
+      rs_cur = rs_next;
     } else {
-      load(next, v, w);
+      load(next, v, w, rs_cur);
     }
     row = next;
   }
 }
 
-template <typename TO>
+template <typename TO, bool XH>
 static void ln_bwd_dispatch(const LnBwdArgs& a, unsigned blocks, hipStream_t st) {
   const int nv = (a.d + 255) / 256;
-  if (nv <= 1) hipLaunchKernelGGL((ln_bwd_kernel<TO, 1>), dim3(blocks), dim3(256), 0, st, a);
-  else if (nv == 2) hipLaunchKernelGGL((ln_bwd_kernel<TO, 2>), dim3(blocks), dim3(256), 0, st, a);
-  else if (nv == 3) hipLaunchKernelGGL((ln_bwd_kernel<TO, 3>), dim3(blocks), dim3(256), 0, st, a);
-  else if (nv == 4) hipLaunchKernelGGL((ln_bwd_kernel<TO, 4>), dim3(blocks), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((ln_bwd_kernel<TO, 8>), dim3(blocks), dim3(256), 0, st, a);
+  if (nv <= 1) hipLaunchKernelGGL((ln_bwd_kernel<TO, 1, XH>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 2) hipLaunchKernelGGL((ln_bwd_kernel<TO, 2, XH>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 3) hipLaunchKernelGGL((ln_bwd_kernel<TO, 3, XH>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 4) hipLaunchKernelGGL((ln_bwd_kernel<TO, 4, XH>), dim3(blocks), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((ln_bwd_kernel<TO, 8, XH>), dim3(blocks), dim3(256), 0, st, a);
 }
 
 hipError_t launch_ln_bwd(const LnBwdArgs& a, bool is_bf16, hipStream_t st) {
@@ -226,12 +248,15 @@ hipError_t launch_ln_bwd(const LnBwdArgs& a, bool is_bf16, hipStream_t st) {
   if (rows > 0x7fffffffL || a.d > 256 * LN_MAXV) return hipErrorInvalidValue;
   const unsigned blocks = ln_grid(rows);
   const double esz = is_bf16 ? 2 : 4;
-  const double per_elem = esz + (a.X.present() ? 4 : 0) + (a.xp ? 4 : 0) + (a.add ? 4 : 0) + (a.out_f32 ? 4 : 0) +
-                          ((a.out_op || a.OUT.present()) ? 4 : 0) + (a.out_op ? esz : 0) +
-                          (a.OUT.present() ? 4 : 0) + (a.RHS.present() ? 4 : 0);
+  const bool xh = a.xhat != nullptr;
+  if (xh && !a.rstd) return hipErrorInvalidValue;
+  const bool c_rows = (a.out_op && !a.cop) || a.OUT.present();
+  const double per_elem = esz + (xh ? esz : (a.X.present() ? 4 : 0) + (a.xp ? 4 : 0)) + (a.add ? 4 : 0) +
+                          (a.out_f32 ? 4 : 0) + (c_rows ? 4 : 0) + (a.out_op && a.cop ? esz : 0) +
+                          (a.out_op ? esz : 0) + (a.OUT.present() ? 4 : 0) + (a.RHS.present() ? 4 : 0);
   ProfScope ps(PC_LN_BWD, 16.0 * rows * a.d, (double)rows * a.d * per_elem, st);
-  if (is_bf16) ln_bwd_dispatch<bf16>(a, blocks, st);
-  else ln_bwd_dispatch<float>(a, blocks, st);
+  if (is_bf16) { if (xh) ln_bwd_dispatch<bf16, true>(a, blocks, st); else ln_bwd_dispatch<bf16, false>(a, blocks, st); }
+  else { if (xh) ln_bwd_dispatch<float, true>(a, blocks, st); else ln_bwd_dispatch<float, false>(a, blocks, st); }
   return hipGetLastError();
 }
 
