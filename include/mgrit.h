@@ -163,6 +163,29 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts,
                   void* dmemory, void* const* dtheta, float* resnorm,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* Buffer layers (Appendix "Buffer layers"): the first n_open and the last n_close layers of the
+ * network are propagated serially (exactly) with their own step size h_buffer (the paper uses 1),
+ * and only the N = opts->N layers in between by MGRIT with step opts->h (the paper: 1 / N).
+ * theta, dtheta: n_open + N + n_close blocks in network order; Z_all, lambda_all:
+ * [(n_open + N + n_close + 1), T, d] fp32, row n = state after n layers; resnorm: the MGRIT part's
+ * residual norms.  Everything else as in mgrit_forward / mgrit_adjoint; n_open = n_close = 0
+ * reduces to them.  Workspace: mgrit_buffered_workspace_bytes (adjoint as in mgrit_workspace_bytes). */
+typedef struct {
+  int32_t n_open, n_close;
+  float   h_buffer;
+} mgrit_buffer_opts;
+size_t mgrit_buffered_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                                      const mgrit_buffer_opts* buf, int adjoint);
+int mgrit_forward_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
+                           const void* Z0, const void* const* theta, const void* memory,
+                           void* Z_all, float* resnorm,
+                           void* workspace, size_t workspace_bytes, void* stream);
+int mgrit_adjoint_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
+                           const void* Z_all, const void* const* theta, const void* memory,
+                           const void* lambda_N, void* lambda_all,
+                           void* dmemory, void* const* dtheta, float* resnorm,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* One batched layer step over n_groups independent (state, layer) pairs -- the
  * launch that F-/C-relaxation of Algorithm 1 is made of.
  *   adjoint == 0:  out[g] = in[g] + hstep * F(in[g]; theta[g])            (+ rhs[g])

@@ -231,3 +231,29 @@ def mgrit_adjoint(lamN, Z, theta, h, cf, levels, iters, sh, mem=None, relax="FCF
     mu, res, counts = mgrit_solve(adjoint_propagator(theta, Z, h, cf, sh, mem), lamN, N,
                                   cf, levels, iters, relax, init)
     return mu[::-1], res, counts
+
+
+# ----------------------------------------------------------------------------
+# buffer layers (paper appendix "Buffer layers"): the first n_open and last n_close layers are
+# propagated serially with their own step size (1 in the paper), the layers in between by MGRIT
+# ----------------------------------------------------------------------------
+def buffered_forward(Z0, theta, h, cf, levels, iters, sh, n_open, n_close, h_buffer, mem=None, relax="FCF"):
+    """States after every layer of the whole network (n_open + N + n_close + 1 of them) and the
+    residual norms of the MGRIT part."""
+    N = len(theta) - n_open - n_close
+    Z = serial_forward(Z0, theta[:n_open], h_buffer, sh, mem) if n_open else [np.asarray(Z0, dtype=np.float64)]
+    mid, res, _ = mgrit_forward(Z[-1], theta[n_open:n_open + N], h, cf, levels, iters, sh, mem, relax)
+    Z = Z + mid[1:]
+    if n_close:
+        Z = Z + serial_forward(Z[-1], theta[n_open + N:], h_buffer, sh, mem)[1:]
+    return Z, res
+
+
+def buffered_adjoint(lamN, Z, theta, h, cf, levels, iters, sh, n_open, n_close, h_buffer, mem=None, relax="FCF"):
+    """Adjoint states lambda_n, n = 0..n_open+N+n_close, and the MGRIT part's residual norms."""
+    N = len(theta) - n_open - n_close
+    a, b = n_open, n_open + N
+    tail = serial_adjoint(lamN, Z[b:], theta[b:], h_buffer, sh, mem) if n_close else [np.asarray(lamN, np.float64)]
+    mid, res, _ = mgrit_adjoint(tail[0], Z[a:b + 1], theta[a:b], h, cf, levels, iters, sh, mem, relax)
+    head = serial_adjoint(mid[0], Z[:a + 1], theta[:a], h_buffer, sh, mem) if n_open else [mid[0]]
+    return head[:-1] + mid + tail[1:], res

@@ -33,6 +33,10 @@ class Indicator(C.Structure):
 MITIGATE_SERIAL, MITIGATE_MORE_ITERATIONS = 0, 1
 
 
+class BufferOpts(C.Structure):
+    _fields_ = [("n_open", C.c_int32), ("n_close", C.c_int32), ("h_buffer", C.c_float)]
+
+
 class ModelDesc(C.Structure):
     _fields_ = [("arch", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ff", C.c_int32),
                 ("batch", C.c_int32), ("seq", C.c_int32), ("mem_seq", C.c_int32), ("dtype", C.c_int32),
@@ -86,6 +90,15 @@ def lib() -> C.CDLL:
         L.layer_step_batched.argtypes = [C.POINTER(ModelDesc), C.c_int, C.c_int, vpp, vpp, vpp, vpp, vpp, vp,
                                          C.c_float, vp, C.c_size_t, vp]
         L.layer_step_batched.restype = C.c_int
+        L.mgrit_buffered_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.POINTER(BufferOpts),
+                                                     C.c_int]
+        L.mgrit_buffered_workspace_bytes.restype = C.c_size_t
+        L.mgrit_forward_buffered.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.POINTER(BufferOpts), vp, vpp,
+                                             vp, vp, vp, vp, C.c_size_t, vp]
+        L.mgrit_forward_buffered.restype = C.c_int
+        L.mgrit_adjoint_buffered.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.POINTER(BufferOpts), vp, vpp,
+                                             vp, vp, vp, vp, vpp, vp, vp, C.c_size_t, vp]
+        L.mgrit_adjoint_buffered.restype = C.c_int
         L.mgrit_indicator_init.argtypes = [C.POINTER(Indicator), C.c_int, C.c_int, C.c_int, C.c_int, C.c_float]
         L.mgrit_indicator_init.restype = C.c_int
         L.mgrit_indicator_begin_batch.argtypes = [C.POINTER(Indicator)]
@@ -343,3 +356,50 @@ def layer_step_batched(desc: ModelDesc, adjoint: bool, inputs: List[torch.Tensor
     if st != MGRIT_OK:
         raise MgritError(st, "layer_step_batched")
     return outputs
+
+
+def mgrit_buffered_workspace_bytes(desc: ModelDesc, opts: Opts, buf: BufferOpts, adjoint) -> int:
+    return int(lib().mgrit_buffered_workspace_bytes(C.byref(desc), C.byref(opts), C.byref(buf), int(adjoint)))
+
+
+def mgrit_forward_buffered(desc: ModelDesc, opts: Opts, buf: BufferOpts, Z0: torch.Tensor,
+                           theta: List[torch.Tensor], memory: Optional[torch.Tensor] = None,
+                           stream: Optional[torch.cuda.Stream] = None):
+    """Serial open / close layers around the MGRIT middle.  Returns (Z_all, resnorm)."""
+    T, d = desc.batch * desc.seq, desc.d_model
+    n = buf.n_open + opts.N + buf.n_close
+    _check_state(Z0, (T, d), "Z0")
+    if len(theta) != n:
+        raise ValueError("theta must hold n_open + N + n_close blocks")
+    Z_all = torch.empty((n + 1, T, d), dtype=torch.float32, device=Z0.device)
+    resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z0.device)
+    ws = torch.empty(max(mgrit_buffered_workspace_bytes(desc, opts, buf, 0), 256), dtype=torch.uint8, device=Z0.device)
+    st = lib().mgrit_forward_buffered(C.byref(desc), C.byref(opts), C.byref(buf), _ptr(Z0), _ptr_array(theta),
+                                      _ptr(memory), _ptr(Z_all), _ptr(resnorm), _ptr(ws), ws.numel(),
+                                      _stream_handle(stream))
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_forward_buffered")
+    return Z_all, resnorm
+
+
+def mgrit_adjoint_buffered(desc: ModelDesc, opts: Opts, buf: BufferOpts, Z_all: torch.Tensor,
+                           theta: List[torch.Tensor], lambda_N: torch.Tensor, memory: Optional[torch.Tensor] = None,
+                           dtheta: Optional[List[torch.Tensor]] = None,
+                           stream: Optional[torch.cuda.Stream] = None):
+    """Returns (lambda_all, resnorm) of the buffered network; dtheta as in mgrit_adjoint."""
+    T, d = desc.batch * desc.seq, desc.d_model
+    n = buf.n_open + opts.N + buf.n_close
+    _check_state(Z_all, (n + 1, T, d), "Z_all")
+    _check_state(lambda_N, (T, d), "lambda_N")
+    if len(theta) != n or (dtheta is not None and len(dtheta) != n):
+        raise ValueError("theta / dtheta must hold n_open + N + n_close blocks")
+    lambda_all = torch.empty_like(Z_all)
+    resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z_all.device)
+    need = mgrit_buffered_workspace_bytes(desc, opts, buf, 2 if dtheta is not None else 1)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=Z_all.device)
+    st = lib().mgrit_adjoint_buffered(C.byref(desc), C.byref(opts), C.byref(buf), _ptr(Z_all), _ptr_array(theta),
+                                      _ptr(memory), _ptr(lambda_N), _ptr(lambda_all), None, _ptr_array(dtheta),
+                                      _ptr(resnorm), _ptr(ws), ws.numel(), _stream_handle(stream))
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_adjoint_buffered")
+    return lambda_all, resnorm

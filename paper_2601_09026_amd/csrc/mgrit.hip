@@ -913,8 +913,8 @@ int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
   HIPCHK(upload_pointers(D.tabTh, theta, N, st));
   if (desc->arch == MGRIT_ARCH_CROSS)
     HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
-  // initial values
-  HIPCHK(hipMemcpyAsync(Z_all, Z0, state, hipMemcpyDeviceToDevice, st));
+  // initial values (Z0 may be row 0 of Z_all itself)
+  if (Z0 != Z_all) HIPCHK(hipMemcpyAsync(Z_all, Z0, state, hipMemcpyDeviceToDevice, st));
   if (!serial_run(opts) && opts->init_guess == 0) {
     for (int k = 1; k <= N / opts->cf; ++k)
       HIPCHK(hipMemcpyAsync(static_cast<char*>(Z_all) + (size_t)k * opts->cf * state, Z0, state,
@@ -961,8 +961,9 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
   Rows Zrows = {(const void* const*)D.tabZ, 0, 1};
   STCHK(forward_groups(E, D.E2, N, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
   // initial values
-  HIPCHK(hipMemcpyAsync(static_cast<char*>(lambda_all) + (size_t)N * state, lambda_N, state,
-                        hipMemcpyDeviceToDevice, st));
+  if (lambda_N != static_cast<char*>(lambda_all) + (size_t)N * state)     // may be row N of lambda_all itself
+    HIPCHK(hipMemcpyAsync(static_cast<char*>(lambda_all) + (size_t)N * state, lambda_N, state,
+                          hipMemcpyDeviceToDevice, st));
   if (!serial_run(opts) && opts->init_guess == 0) {
     for (int k = 1; k <= N / opts->cf; ++k)
       HIPCHK(hipMemcpyAsync(static_cast<char*>(lambda_all) + (size_t)(N - k * opts->cf) * state, lambda_N, state,
@@ -980,6 +981,103 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
     // dL/dE = sum over layers of the per-layer terms, in layer order
     if (dmemory)
       HIPCHK(launch_sum_slots(P.dE_all, N, (long)E.Tm * E.d, static_cast<float*>(dmemory), 1.0f, st));
+  }
+  return MGRIT_OK;
+}
+
+// ---- buffer layers: serial open / close segments around the MGRIT middle ----------------------
+namespace {
+int validate_buffer(const mgrit_buffer_opts* b) {
+  if (!b || b->n_open < 0 || b->n_close < 0 || !isfinite(b->h_buffer)) return MGRIT_INVALID_ARG;
+  return MGRIT_OK;
+}
+mgrit_opts serial_opts(int n, float h) {
+  mgrit_opts o;
+  memset(&o, 0, sizeof(o));
+  o.N = n; o.h = h; o.cf = 1; o.levels = 1; o.iters = 1; o.relax = MGRIT_RELAX_FCF; o.init_guess = 0;
+  return o;
+}
+}  // namespace
+
+size_t mgrit_buffered_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                                      const mgrit_buffer_opts* buf, int adjoint) {
+  if (validate_buffer(buf) != MGRIT_OK) return 0;
+  size_t need = mgrit_workspace_bytes(desc, opts, adjoint);
+  if (need == 0) return 0;
+  for (int n : {buf->n_open, buf->n_close}) {
+    if (n == 0) continue;
+    const mgrit_opts so = serial_opts(n, buf->h_buffer);
+    const size_t w = mgrit_workspace_bytes(desc, &so, adjoint);
+    if (w == 0) return 0;
+    if (w > need) need = w;
+  }
+  return need;
+}
+
+int mgrit_forward_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
+                           const void* Z0, const void* const* theta, const void* memory, void* Z_all,
+                           float* resnorm, void* workspace, size_t workspace_bytes, void* stream) {
+  STCHK(validate_desc(desc));
+  STCHK(validate_opts(opts));
+  STCHK(validate_buffer(buf));
+  if (!Z0 || !Z_all || !theta) return MGRIT_INVALID_ARG;
+  const size_t need = mgrit_buffered_workspace_bytes(desc, opts, buf, 0);
+  if (need == 0) return MGRIT_INVALID_ARG;
+  if (!workspace || workspace_bytes < need) return workspace ? MGRIT_WORKSPACE_TOO_SMALL : MGRIT_INVALID_ARG;
+  const size_t state = (size_t)desc->batch * desc->seq * desc->d_model * sizeof(float);
+  char* Z = static_cast<char*>(Z_all);
+  const int no = buf->n_open, nc = buf->n_close, N = opts->N;
+  STCHK(check_ptr_array(theta, no + N + nc));
+  const void* z_in = Z0;
+  if (no > 0) {
+    const mgrit_opts so = serial_opts(no, buf->h_buffer);
+    STCHK(mgrit_forward(desc, &so, z_in, theta, memory, Z, nullptr, workspace, workspace_bytes, stream));
+    z_in = Z + (size_t)no * state;
+  }
+  STCHK(mgrit_forward(desc, opts, z_in, theta + no, memory, Z + (size_t)no * state, resnorm, workspace,
+                      workspace_bytes, stream));
+  if (nc > 0) {
+    const mgrit_opts so = serial_opts(nc, buf->h_buffer);
+    char* row = Z + (size_t)(no + N) * state;
+    STCHK(mgrit_forward(desc, &so, row, theta + no + N, memory, row, nullptr, workspace, workspace_bytes, stream));
+  }
+  return MGRIT_OK;
+}
+
+int mgrit_adjoint_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
+                           const void* Z_all, const void* const* theta, const void* memory, const void* lambda_N,
+                           void* lambda_all, void* dmemory, void* const* dtheta, float* resnorm, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  STCHK(validate_desc(desc));
+  STCHK(validate_opts(opts));
+  STCHK(validate_buffer(buf));
+  if (!Z_all || !lambda_N || !lambda_all || !theta) return MGRIT_INVALID_ARG;
+  // the memory gradient would have to be accumulated over the three segments: not offered here
+  if (dmemory) return MGRIT_UNSUPPORTED;
+  const int mode = dtheta ? 2 : 1;
+  const size_t need = mgrit_buffered_workspace_bytes(desc, opts, buf, mode);
+  if (need == 0) return MGRIT_INVALID_ARG;
+  if (!workspace || workspace_bytes < need) return workspace ? MGRIT_WORKSPACE_TOO_SMALL : MGRIT_INVALID_ARG;
+  const size_t state = (size_t)desc->batch * desc->seq * desc->d_model * sizeof(float);
+  const char* Z = static_cast<const char*>(Z_all);
+  char* Lm = static_cast<char*>(lambda_all);
+  const int no = buf->n_open, nc = buf->n_close, N = opts->N;
+  STCHK(check_ptr_array(theta, no + N + nc));
+  if (dtheta) STCHK(check_ptr_array((const void* const*)dtheta, no + N + nc));
+  const void* lam_in = lambda_N;
+  if (nc > 0) {
+    const mgrit_opts so = serial_opts(nc, buf->h_buffer);
+    const size_t off = (size_t)(no + N) * state;
+    STCHK(mgrit_adjoint(desc, &so, Z + off, theta + no + N, memory, lam_in, Lm + off, nullptr,
+                        dtheta ? dtheta + no + N : nullptr, nullptr, workspace, workspace_bytes, stream));
+    lam_in = Lm + off;
+  }
+  STCHK(mgrit_adjoint(desc, opts, Z + (size_t)no * state, theta + no, memory, lam_in, Lm + (size_t)no * state,
+                      nullptr, dtheta ? dtheta + no : nullptr, resnorm, workspace, workspace_bytes, stream));
+  if (no > 0) {
+    const mgrit_opts so = serial_opts(no, buf->h_buffer);
+    STCHK(mgrit_adjoint(desc, &so, Z, theta, memory, Lm + (size_t)no * state, Lm, nullptr, dtheta, nullptr,
+                        workspace, workspace_bytes, stream));
   }
   return MGRIT_OK;
 }

@@ -115,6 +115,22 @@ def test_parameter_gradient_workspace_and_support():
     assert glay.block_bytes > lay.block_bytes
 
 
+def test_buffered_workspace_and_argument_checks():
+    desc = mb.model_desc(wls.named_workloads()["gpt2_small"])
+    opts = mb.mgrit_opts(16, 1 / 16, 4, 2, 1)
+    plain = mb.mgrit_workspace_bytes(desc, opts, 1)
+    assert mb.mgrit_buffered_workspace_bytes(desc, opts, mb.BufferOpts(0, 0, 1.0), 1) == plain
+    assert mb.mgrit_buffered_workspace_bytes(desc, opts, mb.BufferOpts(2, 2, 1.0), 1) >= plain
+    assert mb.mgrit_buffered_workspace_bytes(desc, opts, mb.BufferOpts(-1, 2, 1.0), 1) == 0
+    L = mb.lib()
+    bad = mb.BufferOpts(1, -2, 1.0)
+    assert L.mgrit_forward_buffered(C.byref(desc), C.byref(opts), C.byref(bad), None, None, None, None, None, None,
+                                    0, None) == -1
+    ok = mb.BufferOpts(1, 1, 1.0)
+    assert L.mgrit_forward_buffered(C.byref(desc), C.byref(opts), C.byref(ok), None, None, None, None, None, None,
+                                    0, None) == -1
+
+
 def test_workspace_grows_with_groups_and_levels():
     desc = mb.model_desc(wls.named_workloads()["bert_base"])
     a = mb.mgrit_layer_step_workspace_bytes(desc, False, 1)

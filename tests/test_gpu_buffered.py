@@ -1,0 +1,66 @@
+"""Buffer layers on the GPU (serial open / close layers with their own step size around the MGRIT
+middle) against the oracle's composition: states, adjoint states, residual norms, parameter
+gradients."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mgrit as omgrit
+from paper_2601_09026_amd import binding as mb
+from paper_2601_09026_amd import workloads as wls
+
+from gpu_util import TOL, DeviceModel, dev, relerr, shape_of
+from test_gpu_mgrit import check_states, check_resnorms
+from test_gpu_param_grads import grad_blocks, compare_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(wl, n_open, n_close, h_buffer=1.0, weight_std=0.08, grads=False):
+    n_total = n_open + wl.N + n_close
+    print(f"[case] buffered {wl.name} arch={wl.arch} dtype={wl.dtype} open={n_open} N={wl.N} close={n_close} "
+          f"cf={wl.cf} L={wl.levels} it={wl.iters} grads={grads}", flush=True)
+    dm = DeviceModel(wl, n_layers=n_total, weight_std=weight_std)
+    sh = shape_of(wl)
+    tol = TOL[wl.dtype]
+    opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters)
+    buf = mb.BufferOpts(n_open, n_close, h_buffer)
+    Z0 = wls.initial_state(wl)
+    Zg, rg = mb.mgrit_forward_buffered(dm.desc, opts, buf, dev(Z0), dm.blocks)
+    torch.cuda.synchronize()
+    Zr, rr = omgrit.buffered_forward(Z0, dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh, n_open, n_close, h_buffer)
+    check_states(Zg, Zr, tol, "Z")
+    check_resnorms(rg, rr, tol, float(np.linalg.norm(Zr[-1])))
+    lamN = wls.terminal_adjoint(wl)
+    blocks = grad_blocks(dm.desc, n_total) if grads else None
+    lg, ag = mb.mgrit_adjoint_buffered(dm.desc, opts, buf, Zg, dm.blocks, dev(lamN), dtheta=blocks)
+    torch.cuda.synchronize()
+    Zlin = list(Zg.cpu().numpy().astype(np.float64))
+    lr, ar = omgrit.buffered_adjoint(lamN, Zlin, dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh, n_open, n_close,
+                                     h_buffer)
+    check_states(lg, lr, tol, "lambda")
+    check_resnorms(ag, ar, tol, float(np.linalg.norm(lr[0])))
+    if grads:
+        steps = [h_buffer] * n_open + [wl.h] * wl.N + [h_buffer] * n_close
+        from oracle import transformer_ode as tode
+        for n in range(n_total):
+            ref = {k: steps[n] * v for k, v in tode.F_param_vjp(Zlin[n], dm.host[n], lr[n + 1], sh).items()}
+            compare_layer(mb.unpack_grad(dm.desc, blocks[n]), ref, tol, f"layer {n}")
+
+
+def tiny(arch=wls.ARCH_CAUSAL, dtype=wls.DTYPE_F32, N=16, cf=4, levels=2, iters=1, d=64, H=4, f=128, B=2, S=24):
+    return wls.Workload("tiny", arch, d, H, f, B, S, 0, N, 1.0 / N, cf, levels, iters, dtype, 47)
+
+
+def test_two_open_two_close_fp32():
+    # the paper's decoder-only set-up in small: 2 + 16 + 2 layers, step 1 outside, 1/16 inside
+    run_case(tiny(), 2, 2, grads=True)
+
+
+@pytest.mark.parametrize("n_open,n_close", [(0, 0), (3, 0), (0, 1)])
+def test_one_sided_buffers_fp32(n_open, n_close):
+    run_case(tiny(iters=2), n_open, n_close)
+
+
+def test_gpt2_shape_reduced_bf16():
+    run_case(wls.named_workloads()["gpt2_small"].scaled(batch=1, N=16, h=1.0 / 16, levels=2), 2, 2, weight_std=0.02)

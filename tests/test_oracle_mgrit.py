@@ -378,3 +378,38 @@ def test_decoder_memory_and_parameter_gradients_by_finite_differences():
                 return (C * mgrit.serial_forward(Y0, t, wl.h, sh, E)[-1]).sum()
             fd = (loss(eps) - loss(-eps)) / (2 * eps)
             assert abs(fd - grads[n][name][idx]) < 2e-6 * max(1.0, abs(fd)), (n, name, idx)
+
+
+def test_buffered_network_reduces_to_per_layer_step_sizes():
+    """With a serial middle the buffered network is the plain recursion with step 1 on the open and
+    close layers and h in between; with MGRIT in the middle, enough iterations reproduce it; and its
+    adjoint is the gradient of that network (finite differences)."""
+    wl, sh, th = tiny(N=12, cf=2, h=0.25, std=0.4)
+    no, nc, hb = 2, 2, 1.0
+    Z0 = wls.initial_state(wl).astype(np.float64)
+    C = wls.terminal_adjoint(wl).astype(np.float64)
+    steps = [hb] * no + [wl.h] * (wl.N - no - nc) + [hb] * nc
+    def plain(z0):
+        Z = [z0]
+        for n, hs in enumerate(steps):
+            Z.append(tode.phi(Z[-1], th[n], hs, sh))
+        return Z
+    ref = plain(Z0)
+    Z, res = mgrit.buffered_forward(Z0, th, wl.h, 2, 1, 1, sh, no, nc, hb)
+    assert len(Z) == wl.N + 1 and res == []
+    for a, b in zip(Z, ref):
+        assert np.allclose(a, b, rtol=0, atol=1e-13)
+    Zm, res = mgrit.buffered_forward(Z0, th, wl.h, 2, 2, 4, sh, no, nc, hb)      # M = 4 intervals: exact after 4
+    assert len(res) == 4
+    assert np.allclose(Zm[-1], ref[-1], rtol=0, atol=1e-12)
+    Zi, _ = mgrit.buffered_forward(Z0, th, wl.h, 2, 2, 1, sh, no, nc, hb)        # one iteration: inexact middle ...
+    assert np.abs(Zi[-1] - ref[-1]).max() > 1e-6
+    assert np.allclose(Zi[no], ref[no], rtol=0, atol=1e-13)                      # ... but exact open layers
+    lam, _ = mgrit.buffered_adjoint(C, ref, th, wl.h, 2, 2, 4, sh, no, nc, hb)
+    assert len(lam) == wl.N + 1
+    rng = np.random.default_rng(2)
+    eps = 1e-6
+    for _ in range(3):
+        v = rng.standard_normal(Z0.shape)
+        fd = ((C * plain(Z0 + eps * v)[-1]).sum() - (C * plain(Z0 - eps * v)[-1]).sum()) / (2 * eps)
+        assert abs(fd - (lam[0] * v).sum()) < 1e-7 * max(1.0, abs(fd))
