@@ -102,7 +102,7 @@ def main():
     if args.gemm_tile:
         mb.lib().mgrit_debug_gemm_tile_config(args.gemm_tile)
     desc = mb.model_desc(wl)
-    opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters)
+    opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters, wl.relax)
     T, d = wl.tokens, wl.d_model
 
     # inputs resident in HBM before anything is timed
@@ -221,7 +221,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if wl.dtype == wls.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "d_model": wl.d_model, "n_heads": wl.n_heads, "d_ff": wl.d_ff,
                    "batch": wl.batch, "seq": wl.seq, "N": wl.N, "h": wl.h, "cf": wl.cf, "levels": wl.levels,
-                   "iters": wl.iters, "relax": "FCF", "adjoint": adjoint,
+                   "iters": wl.iters, "relax": "FCF" if wl.relax else "F", "adjoint": adjoint,
                    "phi_evaluations": n_phi, "psi_evaluations": n_psi,
                    "max_groups_per_launch": args.max_groups or "default", "lanes": args.lanes or 2,
                    "param_grads": bool(grads)},

@@ -1,4 +1,4 @@
-// Fused softmax attention on the 32x32x16 bf16 MFMA (d_head = 64), forward and backward.
+// Fused softmax attention on the 32x32x16 bf16 MFMA (d_head = 64 or 128), forward and backward.
 //
 // Every product is arranged as  D[i][j] = sum_k A[i][k] B[k][j]  with the wavefront's own 32
 // rows (queries in the forward and dQ kernels, keys in the dK/dV kernel) on the j axis.  In
@@ -26,23 +26,25 @@ namespace mg {
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
 // LDS has 64 four-byte banks.  Row-major tiles are read 16 bytes per lane (16 lanes per
-// clock): 144-byte rows put 16 consecutive rows on 16 distinct 16-byte slots.  Transposed
-// tiles are read 8 bytes per lane (32 lanes per clock): 136-byte rows (an odd number of
-// 8-byte units) put 32 consecutive rows on 32 distinct 8-byte slots.
-constexpr int FA_LD = 72;                 // row-major tile: 64 bf16 + 8 pad
-constexpr int FA_LDT = 68;                // transposed tile: 64 bf16 + 4 pad
+// clock): rows of DH + 8 bf16 (144 or 272 bytes, an odd number of 16-byte units) put 16
+// consecutive rows on 16 distinct 16-byte slots.  Transposed tiles are read 8 bytes per lane
+// (32 lanes per clock): 136-byte rows (an odd number of 8-byte units) put 32 consecutive rows
+// on 32 distinct 8-byte slots.
+template <int DH> constexpr int fa_ld() { return DH + 8; }     // row-major tile [64][DH + 8 pad]
+constexpr int FA_LDT = 68;                // transposed tile [DH][64 + 4 pad]
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-// 64 rows x 64 cols of bf16 from global (rows clamped to nrows-1) into a row-major LDS tile
+// 64 rows x DH cols of bf16 from global (rows clamped to nrows-1) into a row-major LDS tile
 // and/or its transpose.  Work item = (row pair, 8-column chunk); the chunk varies fastest so
-// that 8 consecutive lanes fetch one whole 128-byte row (coalesced global reads matter more
+// that DH/8 consecutive lanes fetch one whole row (coalesced global reads matter more
 // here than the two-way bank conflict the transposed 4-byte stores then have).
-template <int NT, bool PLAIN, bool TRANS>
+template <int NT, int DH, bool PLAIN, bool TRANS>
 __device__ __forceinline__ void stage64(bf16* plain, bf16* trans, const bf16* src, long rs, int row0, int nrows) {
+  constexpr int FA_LD = fa_ld<DH>(), CH = DH / 8;
 #pragma unroll
-  for (int item = threadIdx.x; item < 256; item += NT) {
-    const int cc = item & 7, rp = item >> 3;
+  for (int item = threadIdx.x; item < 32 * CH; item += NT) {
+    const int cc = item % CH, rp = item / CH;
     int r0 = row0 + 2 * rp, r1 = r0 + 1;
     r0 = r0 < nrows ? r0 : nrows - 1;
     r1 = r1 < nrows ? r1 : nrows - 1;
@@ -63,8 +65,9 @@ __device__ __forceinline__ void stage64(bf16* plain, bf16* trans, const bf16* sr
 }
 
 // A operand from a row-major tile: row `row`, reduction chunk of k-step ks
+template <int DH>
 __device__ __forceinline__ bf16x8 frag_plain(const bf16* tile, int row, int ks, int lh) {
-  return *reinterpret_cast<const bf16x8*>(tile + row * FA_LD + 16 * ks + 8 * lh);
+  return *reinterpret_cast<const bf16x8*>(tile + row * fa_ld<DH>() + 16 * ks + 8 * lh);
 }
 // A operand from a transposed tile: row `row` (a feature), reduction over the tile's 64
 // staged rows, k-step t of 32-row tile rt, in the register-order enumeration
@@ -97,7 +100,7 @@ struct HeadPtrs {
 
 __device__ __forceinline__ HeadPtrs head_ptrs(const AttnArgs& a, int g, int b, int h) {
   HeadPtrs p;
-  const int dh = 64;
+  const int dh = a.dh;
   p.Q = reinterpret_cast<const bf16*>(a.q) + a.q_slots.of(g) * a.q_slot_stride + (long)b * a.Sq * a.q_row_stride + h * dh;
   p.K = reinterpret_cast<const bf16*>(a.k) + a.k_slots.of(g) * a.k_slot_stride + (long)b * a.Sk * a.k_row_stride + h * dh;
   p.V = reinterpret_cast<const bf16*>(a.v) + a.k_slots.of(g) * a.v_slot_stride + (long)b * a.Sk * a.v_row_stride + h * dh;
@@ -120,11 +123,12 @@ __device__ __forceinline__ HeadPtrs head_ptrs(const AttnArgs& a, int g, int b, i
   return p;
 }
 
-// store a [64 features][32 rows] accumulator pair (transposed result) as rows of 64 bf16
+// store [DH features][32 rows] accumulators (transposed result) as rows of DH bf16
+template <int DH>
 __device__ __forceinline__ void store_rows_T(bf16* dst, long row_stride, int row, const f32x16* acc, float mul,
                                              int lh) {
 #pragma unroll
-  for (int dt = 0; dt < 2; ++dt)
+  for (int dt = 0; dt < DH / 32; ++dt)
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       f32x4 v = {acc[dt][4 * q] * mul, acc[dt][4 * q + 1] * mul, acc[dt][4 * q + 2] * mul, acc[dt][4 * q + 3] * mul};
@@ -135,10 +139,15 @@ __device__ __forceinline__ void store_rows_T(bf16* dst, long row_stride, int row
 // ---------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------
-template <int NW>
-__global__ void __launch_bounds__(NW * 64, 4) attn_fwd_mfma_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * FA_LD];     // [key][d]
-  __shared__ __attribute__((aligned(16))) bf16 Vt[64 * FA_LDT];     // [d][key]
+// Resident blocks per CU the register budget is set for: the accumulators grow with DH.
+template <int DH> constexpr int fa_fwd_blocks() { return DH == 64 ? 4 : 2; }
+template <int DH> constexpr int fa_bwd_blocks() { return DH == 64 ? 3 : 2; }
+
+template <int NW, int DH>
+__global__ void __launch_bounds__(NW * 64, fa_fwd_blocks<DH>()) attn_fwd_mfma_kernel(const AttnArgs a) {
+  constexpr int KS = DH / 16, DT = DH / 32;
+  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * fa_ld<DH>()];    // [key][d]
+  __shared__ __attribute__((aligned(16))) bf16 Vt[DH * FA_LDT];          // [d][key]
   const int g = blockIdx.z;
   const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
   const int q0 = blockIdx.x * (NW * 32);
@@ -146,28 +155,30 @@ __global__ void __launch_bounds__(NW * 64, 4) attn_fwd_mfma_kernel(const AttnArg
   const HeadPtrs P = head_ptrs(a, g, b, h);
   const int qi = q0 + wave * 32 + lr;
   const int qc = qi < a.Sq ? qi : a.Sq - 1;
-  bf16x8 qf[4];
+  bf16x8 qf[KS];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks)
+  for (int ks = 0; ks < KS; ++ks)
     qf[ks] = *reinterpret_cast<const bf16x8*>(P.Q + (long)qc * a.q_row_stride + 16 * ks + 8 * lh);
 
-  const float c = rsqrtf(64.f) * LOG2E;
+  const float c = rsqrtf((float)DH) * LOG2E;
   float m = -INFINITY, l = 0.f;
-  f32x16 o[2] = {zero16(), zero16()};
+  f32x16 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = zero16();
   const int q_blk_last = min(q0 + NW * 32, a.Sq) - 1;
   const int k_end = a.causal ? min(a.Sk, q_blk_last + 1) : a.Sk;
   const int q_wave_last = q0 + wave * 32 + 31;
   for (int k0 = 0; k0 < k_end; k0 += 64) {
     __syncthreads();
-    stage64<NW * 64, true, false>(Ks, nullptr, P.K, a.k_row_stride, k0, a.Sk);
-    stage64<NW * 64, false, true>(nullptr, Vt, P.V, a.v_row_stride, k0, a.Sk);
+    stage64<NW * 64, DH, true, false>(Ks, nullptr, P.K, a.k_row_stride, k0, a.Sk);
+    stage64<NW * 64, DH, false, true>(nullptr, Vt, P.V, a.v_row_stride, k0, a.Sk);
     __syncthreads();
     if (a.causal && k0 > q_wave_last) continue;          // wave-uniform; barriers are above
     f32x16 s[2] = {zero16(), zero16()};
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) s[kt] = MFMA(frag_plain(Ks, 32 * kt + lr, ks, lh), qf[ks], s[kt]);
+      for (int ks = 0; ks < KS; ++ks) s[kt] = MFMA(frag_plain<DH>(Ks, 32 * kt + lr, ks, lh), qf[ks], s[kt]);
     float mloc = -INFINITY;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
@@ -196,7 +207,7 @@ __global__ void __launch_bounds__(NW * 64, 4) attn_fwd_mfma_kernel(const AttnArg
     l = l * corr + lsum;
     m = mn;
 #pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[dt][i] *= corr;
 #pragma unroll
@@ -205,11 +216,11 @@ __global__ void __launch_bounds__(NW * 64, 4) attn_fwd_mfma_kernel(const AttnArg
       for (int t = 0; t < 2; ++t) {
         const bf16x8 pb = regs_to_b(s[kt], t);
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt) o[dt] = MFMA(frag_trans(Vt, 32 * dt + lr, kt, t, lh), pb, o[dt]);
+        for (int dt = 0; dt < DT; ++dt) o[dt] = MFMA(frag_trans(Vt, 32 * dt + lr, kt, t, lh), pb, o[dt]);
       }
   }
   if (qi < a.Sq) {
-    store_rows_T(P.Ow, a.o_row_stride, qi, o, 1.0f / l, lh);
+    store_rows_T<DH>(P.Ow, a.o_row_stride, qi, o, 1.0f / l, lh);
     if (P.lse && lh == 0) P.lse[qi] = (m + log2f(l)) * LN2;
   }
 }
@@ -219,12 +230,13 @@ __global__ void __launch_bounds__(NW * 64, 4) attn_fwd_mfma_kernel(const AttnArg
 // ---------------------------------------------------------------------------
 // LDS of the two backward passes (bf16 elements): pass 1 stages K, V row-major and K transposed;
 // pass 2 stages Q, dO both ways.  The fused kernel runs them one after the other in the same buffer.
-constexpr int BWD_DQ_LDS = 2 * 64 * FA_LD + 64 * FA_LDT;
-constexpr int BWD_DKV_LDS = 2 * 64 * FA_LD + 2 * 64 * FA_LDT;
+template <int DH> constexpr int bwd_dq_lds() { return 2 * 64 * fa_ld<DH>() + DH * FA_LDT; }
+template <int DH> constexpr int bwd_dkv_lds() { return 2 * 64 * fa_ld<DH>() + 2 * DH * FA_LDT; }
 
 // d_local: if not null, D of the block's query rows is also left there (index = row - q0)
-template <int NW>
+template <int NW, int DH>
 __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, float* d_local) {
+  constexpr int KS = DH / 16, DT = DH / 32, FA_LD = fa_ld<DH>();
   bf16* Ks = lds;                        // [key][d]
   bf16* Vs = Ks + 64 * FA_LD;            // [key][d]
   bf16* Kt = Vs + 64 * FA_LD;            // [d][key]
@@ -235,10 +247,10 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, f
   const HeadPtrs P = head_ptrs(a, g, b, h);
   const int qi = q0 + wave * 32 + lr;
   const int qc = qi < a.Sq ? qi : a.Sq - 1;
-  bf16x8 qf[4], dof[4];
+  bf16x8 qf[KS], dof[KS];
   float Dq = 0.f;
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
+  for (int ks = 0; ks < KS; ++ks) {
     qf[ks] = *reinterpret_cast<const bf16x8*>(P.Q + (long)qc * a.q_row_stride + 16 * ks + 8 * lh);
     dof[ks] = *reinterpret_cast<const bf16x8*>(P.dO + (long)qc * a.do_row_stride + 16 * ks + 8 * lh);
     const bf16x8 of = *reinterpret_cast<const bf16x8*>(P.O + (long)qc * a.o_row_stride + 16 * ks + 8 * lh);
@@ -250,24 +262,26 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, f
   if (qi < a.Sq && lh == 0) P.D[qi] = Dq;
   if (d_local && lh == 0) d_local[wave * 32 + lr] = Dq;
 
-  const float c = rsqrtf(64.f) * LOG2E;
-  f32x16 dq[2] = {zero16(), zero16()};
+  const float c = rsqrtf((float)DH) * LOG2E;
+  f32x16 dq[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) dq[dt] = zero16();
   const int q_blk_last = min(q0 + NW * 32, a.Sq) - 1;
   const int k_end = a.causal ? min(a.Sk, q_blk_last + 1) : a.Sk;
   const int q_wave_last = q0 + wave * 32 + 31;
   for (int k0 = 0; k0 < k_end; k0 += 64) {
     __syncthreads();
-    stage64<NW * 64, true, true>(Ks, Kt, P.K, a.k_row_stride, k0, a.Sk);
-    stage64<NW * 64, true, false>(Vs, nullptr, P.V, a.v_row_stride, k0, a.Sk);
+    stage64<NW * 64, DH, true, true>(Ks, Kt, P.K, a.k_row_stride, k0, a.Sk);
+    stage64<NW * 64, DH, true, false>(Vs, nullptr, P.V, a.v_row_stride, k0, a.Sk);
     __syncthreads();
     if (a.causal && k0 > q_wave_last) continue;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
       f32x16 s = zero16(), dp = zero16();
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        s = MFMA(frag_plain(Ks, 32 * kt + lr, ks, lh), qf[ks], s);
-        dp = MFMA(frag_plain(Vs, 32 * kt + lr, ks, lh), dof[ks], dp);
+      for (int ks = 0; ks < KS; ++ks) {
+        s = MFMA(frag_plain<DH>(Ks, 32 * kt + lr, ks, lh), qf[ks], s);
+        dp = MFMA(frag_plain<DH>(Vs, 32 * kt + lr, ks, lh), dof[ks], dp);
       }
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
@@ -280,30 +294,31 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, f
       for (int t = 0; t < 2; ++t) {
         const bf16x8 ab = regs_to_b(s, t);
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt) dq[dt] = MFMA(frag_trans(Kt, 32 * dt + lr, kt, t, lh), ab, dq[dt]);
+        for (int dt = 0; dt < DT; ++dt) dq[dt] = MFMA(frag_trans(Kt, 32 * dt + lr, kt, t, lh), ab, dq[dt]);
       }
     }
   }
-  if (qi < a.Sq) store_rows_T(P.dQ, a.dqkv_row_stride, qi, dq, rsqrtf(64.f), lh);
+  if (qi < a.Sq) store_rows_T<DH>(P.dQ, a.dqkv_row_stride, qi, dq, rsqrtf((float)DH), lh);
 }
 
-template <int NW>
-__global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dq_mfma_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16 lds[BWD_DQ_LDS];
-  attn_bwd_dq_body<NW>(a, lds, nullptr);
+template <int NW, int DH>
+__global__ void __launch_bounds__(NW * 64, fa_bwd_blocks<DH>()) attn_bwd_dq_mfma_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16 lds[bwd_dq_lds<DH>()];
+  attn_bwd_dq_body<NW, DH>(a, lds, nullptr);
 }
 
 // ---------------------------------------------------------------------------
 // backward pass 2: dK and dV, one wavefront per 32 key rows
 // ---------------------------------------------------------------------------
 // d_src: D of query row i at d_src[i] (the global array of pass 1, or the fused kernel's LDS copy)
-template <int NW>
+template <int NW, int DH>
 __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, float* Ls, float* Ds,
                                                   const float* d_src) {
+  constexpr int KS = DH / 16, DT = DH / 32, FA_LD = fa_ld<DH>();
   bf16* Qs = lds;                        // [query][d]
   bf16* dOs = Qs + 64 * FA_LD;           // [query][d]
   bf16* Qt = dOs + 64 * FA_LD;           // [d][query]
-  bf16* dOt = Qt + 64 * FA_LDT;          // [d][query]
+  bf16* dOt = Qt + DH * FA_LDT;          // [d][query]
   const int g = blockIdx.z;
   const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
   const int j0 = blockIdx.x * (NW * 32);
@@ -311,21 +326,23 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
   const HeadPtrs P = head_ptrs(a, g, b, h);
   const int kj = j0 + wave * 32 + lr;
   const int kc = kj < a.Sk ? kj : a.Sk - 1;
-  bf16x8 kf[4], vf[4];
+  bf16x8 kf[KS], vf[KS];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
+  for (int ks = 0; ks < KS; ++ks) {
     kf[ks] = *reinterpret_cast<const bf16x8*>(P.K + (long)kc * a.k_row_stride + 16 * ks + 8 * lh);
     vf[ks] = *reinterpret_cast<const bf16x8*>(P.V + (long)kc * a.v_row_stride + 16 * ks + 8 * lh);
   }
-  const float c = rsqrtf(64.f) * LOG2E;
-  f32x16 dk[2] = {zero16(), zero16()}, dv[2] = {zero16(), zero16()};
+  const float c = rsqrtf((float)DH) * LOG2E;
+  f32x16 dk[DT], dv[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) { dk[dt] = zero16(); dv[dt] = zero16(); }
   // causal: key j only receives from queries i >= j
   const int i_begin = a.causal ? (j0 / 64) * 64 : 0;
   const int k_wave_first = j0 + wave * 32;
   for (int i0 = i_begin; i0 < a.Sq; i0 += 64) {
     __syncthreads();
-    stage64<NW * 64, true, true>(Qs, Qt, P.Q, a.q_row_stride, i0, a.Sq);
-    stage64<NW * 64, true, true>(dOs, dOt, P.dO, a.do_row_stride, i0, a.Sq);
+    stage64<NW * 64, DH, true, true>(Qs, Qt, P.Q, a.q_row_stride, i0, a.Sq);
+    stage64<NW * 64, DH, true, true>(dOs, dOt, P.dO, a.do_row_stride, i0, a.Sq);
     if (threadIdx.x < 64) {
       const int qq = i0 + threadIdx.x;
       const int qcl = qq < a.Sq ? qq : a.Sq - 1;
@@ -338,9 +355,9 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
     for (int qt = 0; qt < 2; ++qt) {
       f32x16 s = zero16(), dp = zero16();
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        s = MFMA(frag_plain(Qs, 32 * qt + lr, ks, lh), kf[ks], s);
-        dp = MFMA(frag_plain(dOs, 32 * qt + lr, ks, lh), vf[ks], dp);
+      for (int ks = 0; ks < KS; ++ks) {
+        s = MFMA(frag_plain<DH>(Qs, 32 * qt + lr, ks, lh), kf[ks], s);
+        dp = MFMA(frag_plain<DH>(dOs, 32 * qt + lr, ks, lh), vf[ks], dp);
       }
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
@@ -355,7 +372,7 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
       for (int t = 0; t < 2; ++t) {
         const bf16x8 pb = regs_to_b(s, t), ab = regs_to_b(dp, t);
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
+        for (int dt = 0; dt < DT; ++dt) {
           dv[dt] = MFMA(frag_trans(dOt, 32 * dt + lr, qt, t, lh), pb, dv[dt]);
           dk[dt] = MFMA(frag_trans(Qt, 32 * dt + lr, qt, t, lh), ab, dk[dt]);
         }
@@ -364,72 +381,82 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
   }
   if (kj < a.Sk) {
     const long kv_rs = a.dkv_row_stride ? a.dkv_row_stride : a.dqkv_row_stride;
-    store_rows_T(P.dK, kv_rs, kj, dk, rsqrtf(64.f), lh);
-    store_rows_T(P.dV, kv_rs, kj, dv, 1.0f, lh);
+    store_rows_T<DH>(P.dK, kv_rs, kj, dk, rsqrtf((float)DH), lh);
+    store_rows_T<DH>(P.dV, kv_rs, kj, dv, 1.0f, lh);
   }
 }
 
-template <int NW>
-__global__ void __launch_bounds__(NW * 64, 3) attn_bwd_dkv_mfma_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16 lds[BWD_DKV_LDS];
+template <int NW, int DH>
+__global__ void __launch_bounds__(NW * 64, fa_bwd_blocks<DH>()) attn_bwd_dkv_mfma_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16 lds[bwd_dkv_lds<DH>()];
   __shared__ float Ls[64], Ds[64];
-  attn_bwd_dkv_body<NW>(a, lds, Ls, Ds, nullptr);
+  attn_bwd_dkv_body<NW, DH>(a, lds, Ls, Ds, nullptr);
 }
 
 // Sequences that fit one block (Sq, Sk <= 32 NW): both passes in one launch.  The head's Q, K, V,
 // dO are then read from HBM once (pass 2 finds them in L2) and D never leaves the CU.
-template <int NW>
-__global__ void __launch_bounds__(NW * 64, 3) attn_bwd_fused_mfma_kernel(const AttnArgs a) {
-  constexpr int LDS = BWD_DQ_LDS > BWD_DKV_LDS ? BWD_DQ_LDS : BWD_DKV_LDS;
+template <int NW, int DH>
+__global__ void __launch_bounds__(NW * 64, fa_bwd_blocks<DH>()) attn_bwd_fused_mfma_kernel(const AttnArgs a) {
+  constexpr int LDS = bwd_dq_lds<DH>() > bwd_dkv_lds<DH>() ? bwd_dq_lds<DH>() : bwd_dkv_lds<DH>();
   __shared__ __attribute__((aligned(16))) bf16 lds[LDS];
   __shared__ float Ls[64], Ds[64], Dall[NW * 32];
-  attn_bwd_dq_body<NW>(a, lds, Dall);
+  attn_bwd_dq_body<NW, DH>(a, lds, Dall);
   __syncthreads();
-  attn_bwd_dkv_body<NW>(a, lds, Ls, Ds, Dall);
+  attn_bwd_dkv_body<NW, DH>(a, lds, Ls, Ds, Dall);
 }
 
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 bool attn_mfma_supported(const AttnArgs& a) {
-  return a.dh == 64 && (a.q_row_stride % 8 == 0) && (a.k_row_stride % 8 == 0) && (a.v_row_stride % 8 == 0) &&
-         (a.o_row_stride % 8 == 0);
+  return (a.dh == 64 || a.dh == 128) && (a.q_row_stride % 8 == 0) && (a.k_row_stride % 8 == 0) &&
+         (a.v_row_stride % 8 == 0) && (a.o_row_stride % 8 == 0);
+}
+
+template <int DH>
+static hipError_t attn_fwd_mfma_dh(const AttnArgs& a, hipStream_t st) {
+  if (a.Sq <= 64) {
+    dim3 grid((a.Sq + 63) / 64, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<2, DH>), grid, dim3(128), 0, st, a);
+  } else {
+    dim3 grid((a.Sq + 127) / 128, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<4, DH>), grid, dim3(256), 0, st, a);
+  }
+  return hipGetLastError();
 }
 
 hipError_t attn_fwd_mfma(const AttnArgs& a, hipStream_t st) {
+  return a.dh == 64 ? attn_fwd_mfma_dh<64>(a, st) : attn_fwd_mfma_dh<128>(a, st);
+}
+
+template <int DH>
+static hipError_t attn_bwd_mfma_dh(const AttnArgs& a, hipStream_t st) {
+  if (a.dk && a.Sq <= 128 && a.Sk <= 128) {
+    dim3 grid(1, a.B * a.H, a.n_groups);
+    if (a.Sq <= 64 && a.Sk <= 64) hipLaunchKernelGGL((attn_bwd_fused_mfma_kernel<2, DH>), grid, dim3(128), 0, st, a);
+    else hipLaunchKernelGGL((attn_bwd_fused_mfma_kernel<4, DH>), grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+  }
   if (a.Sq <= 64) {
     dim3 grid((a.Sq + 63) / 64, a.B * a.H, a.n_groups);
-    hipLaunchKernelGGL(attn_fwd_mfma_kernel<2>, grid, dim3(128), 0, st, a);
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<2, DH>), grid, dim3(128), 0, st, a);
   } else {
     dim3 grid((a.Sq + 127) / 128, a.B * a.H, a.n_groups);
-    hipLaunchKernelGGL(attn_fwd_mfma_kernel<4>, grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<4, DH>), grid, dim3(256), 0, st, a);
+  }
+  if (!a.dk) return hipGetLastError();           // only dQ wanted (cross-attention: dK, dV feed the memory gradient)
+  if (a.Sk <= 64) {
+    dim3 grid((a.Sk + 63) / 64, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<2, DH>), grid, dim3(128), 0, st, a);
+  } else {
+    dim3 grid((a.Sk + 127) / 128, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<4, DH>), grid, dim3(256), 0, st, a);
   }
   return hipGetLastError();
 }
 
 hipError_t attn_bwd_mfma(const AttnArgs& a, hipStream_t st) {
-  if (a.dk && a.Sq <= 128 && a.Sk <= 128) {
-    dim3 grid(1, a.B * a.H, a.n_groups);
-    if (a.Sq <= 64 && a.Sk <= 64) hipLaunchKernelGGL(attn_bwd_fused_mfma_kernel<2>, grid, dim3(128), 0, st, a);
-    else hipLaunchKernelGGL(attn_bwd_fused_mfma_kernel<4>, grid, dim3(256), 0, st, a);
-    return hipGetLastError();
-  }
-  if (a.Sq <= 64) {
-    dim3 grid((a.Sq + 63) / 64, a.B * a.H, a.n_groups);
-    hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel<2>, grid, dim3(128), 0, st, a);
-  } else {
-    dim3 grid((a.Sq + 127) / 128, a.B * a.H, a.n_groups);
-    hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel<4>, grid, dim3(256), 0, st, a);
-  }
-  if (!a.dk) return hipGetLastError();           // only dQ wanted (cross-attention: dK, dV feed the memory gradient)
-  if (a.Sk <= 64) {
-    dim3 grid((a.Sk + 63) / 64, a.B * a.H, a.n_groups);
-    hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel<2>, grid, dim3(128), 0, st, a);
-  } else {
-    dim3 grid((a.Sk + 127) / 128, a.B * a.H, a.n_groups);
-    hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel<4>, grid, dim3(256), 0, st, a);
-  }
-  return hipGetLastError();
+  return a.dh == 64 ? attn_bwd_mfma_dh<64>(a, st) : attn_bwd_mfma_dh<128>(a, st);
 }
 
 }  // namespace mg

@@ -50,6 +50,7 @@ class Workload:
     seed: int
     adjoint: bool = False
     ln_eps: float = 1e-5
+    relax: int = 1        # 0 = F-relaxation, 1 = FCF-relaxation
 
     @property
     def tokens(self) -> int:
@@ -61,7 +62,9 @@ class Workload:
 
 
 def named_workloads() -> Dict[str, Workload]:
-    """The five benchmark configurations (index i of the list = ``configs[i]``)."""
+    """The five benchmark configurations (index i of the list = ``configs[i]``), followed by the
+    deep-narrow shape of the paper's own scaling study (its "MC" example: one head of width 128,
+    sequences of 2048 tokens, hundreds of layers, F-relaxation, more levels)."""
     w = [
         Workload("tiny_encoder", ARCH_ENCODER, 64, 4, 256, 2, 32, 0, 16, 1.0 / 16, 4, 2, 2,
                  DTYPE_F32, seed=0, adjoint=True),
@@ -75,6 +78,8 @@ def named_workloads() -> Dict[str, Workload]:
                  DTYPE_BF16, seed=4),
         Workload("mt_decoder", ARCH_CROSS, 512, 8, 2048, 64, 64, 64, 32, 1.0 / 32, 4, 2, 2,
                  DTYPE_BF16, seed=5),
+        Workload("mc_deep_narrow", ARCH_ENCODER, 128, 1, 128, 8, 2048, 0, 256, 1.0 / 256, 4, 3, 2,
+                 DTYPE_BF16, seed=6, relax=0),
     ]
     return {x.name: x for x in w}
 

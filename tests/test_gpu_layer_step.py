@@ -80,6 +80,17 @@ def test_small_head_dimension_uses_generic_attention_bf16():
     run_adjoint_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.05, force_simple=0)
 
 
+@pytest.mark.parametrize("arch,S", [(wls.ARCH_ENCODER, 200), (wls.ARCH_CAUSAL, 200), (wls.ARCH_CROSS, 50),
+                                    (wls.ARCH_ENCODER, 40), (wls.ARCH_CAUSAL, 100)])
+def test_head_dimension_128_bf16(arch, S):
+    """d_head = 128 (the deep-narrow configuration has one head of 128): matrix-core attention with
+    four feature tiles; S = 200 spans several key blocks with a ragged tail, S <= 128 takes the
+    fused backward."""
+    wl = make(arch, wls.DTYPE_BF16, d=256, H=2, B=2, S=S, Sm=70)
+    run_forward_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.05, force_simple=0)
+    run_adjoint_case(wl, G=2, hstep=0.5, with_rhs=True, weight_std=0.05, force_simple=0)
+
+
 def test_forward_step_tiny_config_shape_fp32():
     """d=64, 4 heads of 16, f=256, S=32: the shape of the smallest benchmark configuration."""
     wl = wls.named_workloads()["tiny_encoder"]

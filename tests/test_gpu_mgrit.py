@@ -40,13 +40,23 @@ def check_states(got_all, ref_list, tol, what):
     return worst
 
 
-def check_resnorms(got, ref, tol, scale):
+def check_resnorms(got, ref, tol, states):
+    """Residual norms of the GPU run against the oracle's; `states` are the oracle's states.
+
+    A residual is the difference of two propagator evaluations at nearly equal inputs, and
+    parity grants each evaluation an error of `tol` times its increment.  So the residual norm
+    is only resolved down to about tol * |w_N - w_0| (bf16: a few 1e-2 of the total increment;
+    perturbing the oracle's increments by that much moves its late residuals by this amount):
+    the bar is 10 * tol relative plus that absolute floor, and norms at the fp32 rounding level
+    of the state only have to be small."""
     got = got.cpu().numpy()
+    scale = float(np.linalg.norm(states[-1]))
+    floor = tol * float(np.linalg.norm(np.asarray(states[-1], np.float64) - np.asarray(states[0], np.float64)))
     for i, r in enumerate(ref):
         if r < 100 * np.finfo(np.float32).eps * scale:      # at rounding level: only require smallness
-            assert got[i] < 1000 * np.finfo(np.float32).eps * scale, (i, got[i], r)
+            assert got[i] < 1000 * np.finfo(np.float32).eps * scale + floor, (i, got[i], r)
         else:
-            assert abs(got[i] - r) <= 10 * tol * r, f"resnorm[{i}]: {got[i]} vs {r}"
+            assert abs(got[i] - r) <= 10 * tol * r + floor, f"resnorm[{i}]: {got[i]} vs {r} (floor {floor})"
 
 
 def run_case(wl, weight_std=0.02, relax="FCF", adjoint=False, init_from_serial=False, max_groups=0):
@@ -72,8 +82,7 @@ def run_case(wl, weight_std=0.02, relax="FCF", adjoint=False, init_from_serial=F
         Zr, rr, counts = omgrit.mgrit_forward(Z0, dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh, mem,
                                               relax=relax, init=init)
         check_states(Zg, Zr, tol, "Z")
-        scale = float(np.linalg.norm(Zr[-1]))
-        check_resnorms(rg, rr, tol, scale)
+        check_resnorms(rg, rr, tol, Zr)
         if adjoint:
             lamN = wls.terminal_adjoint(wl)
             # linearise both sides about the same states: the GPU's own forward result
@@ -84,7 +93,7 @@ def run_case(wl, weight_std=0.02, relax="FCF", adjoint=False, init_from_serial=F
             lr, arr, _ = omgrit.mgrit_adjoint(lamN, list(Zlin), dm.host, wl.h, wl.cf, wl.levels, wl.iters,
                                               sh, mem, relax=relax)
             check_states(lg, lr, tol, "lambda")
-            check_resnorms(arg, arr, tol, float(np.linalg.norm(lr[0])))
+            check_resnorms(arg, arr, tol, lr[::-1])
         return Zg, Zr, rr
     finally:
         mb.mgrit_set_max_groups_per_launch(0)
@@ -193,7 +202,7 @@ def test_config5_mt_encoder_decoder_reduced_batch():
     torch.cuda.synchronize()
     Yr, rr, _ = omgrit.mgrit_forward(Y0, dm.host, dec.h, dec.cf, dec.levels, dec.iters, sh, Zr[-1])
     check_states(Yg, Yr, tol, "Z")
-    check_resnorms(rg, rr, tol, float(np.linalg.norm(Yr[-1])))
+    check_resnorms(rg, rr, tol, Yr)
     # decoder adjoint, both sides linearised about the GPU's decoder states and encoder output
     lamN = wls.terminal_adjoint(dec)
     lg, ag = mb.mgrit_adjoint(dm.desc, opts, Yg, dm.blocks, dev(lamN), memory=Zg[-1].contiguous())
@@ -201,4 +210,13 @@ def test_config5_mt_encoder_decoder_reduced_batch():
     lr, ar, _ = omgrit.mgrit_adjoint(lamN, list(Yg.cpu().numpy()), dm.host, dec.h, dec.cf, dec.levels, dec.iters,
                                      sh, Zg[-1].cpu().numpy())
     check_states(lg, lr, tol, "lambda")
-    check_resnorms(ag, ar, tol, float(np.linalg.norm(lr[0])))
+    check_resnorms(ag, ar, tol, lr[::-1])
+
+
+# ----------------------------------------------------------------- deep-narrow shape of the scaling study
+@pytest.mark.parametrize("levels,cf,N", [(4, 2, 32), (3, 4, 64)])
+def test_deep_narrow_shape_reduced_f_relaxation(levels, cf, N):
+    """One head of width 128 (the generic attention kernels), F-relaxation, three and four levels;
+    sequence length and batch cut to what the oracle finishes in seconds."""
+    wl = wls.named_workloads()["mc_deep_narrow"].scaled(batch=2, seq=192, N=N, h=1.0 / N, cf=cf, levels=levels)
+    run_case(wl, relax="F", adjoint=True)
