@@ -195,6 +195,24 @@ def main():
                 roofline = {"bound": "alu", "kernel": "gemm_simple_kernel (fp32 FMA)", "achieved": ach,
                             "peak": 157.3, "unit": "TFLOP/s", "frac": ach / 157.3, "traffic": None,
                             "avg_launch_us": gen["ms"] * 1e3 / gen["launches"]}
+        # long sequences with few features (the deep-narrow workload): the fused attention kernels
+        # outweigh the GEMMs and are the dominant kernel instead (algorithmic flops: 2 products
+        # forward, 5 backward; the two-pass backward recomputes two of them)
+        att = [totals[k] for k in ("attn_fwd", "attn_bwd") if k in totals]
+        if att and roofline is not None and roofline["bound"] == "mfma" and wl.d_model // wl.n_heads in (64, 128):
+            a_ms = sum(v["ms"] for v in att)
+            if a_ms > sum(v["ms"] for v in gemm):
+                a_fl = sum(v["flops"] for v in att); a_n = sum(v["launches"] for v in att)
+                ach = a_fl / (a_ms * 1e-3) / 1e12
+                roofline = {"bound": "mfma", "kernel": "attn_fwd_mfma_kernel + attn_bwd_*_mfma_kernel (fused softmax attention)",
+                            "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                            "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                            "launches_per_step": a_n / args.steps, "avg_launch_us": a_ms * 1e3 / a_n,
+                            "flop_per_launch": a_fl / a_n,
+                            "algorithmic_bytes_per_launch": sum(v["bytes"] for v in att) / a_n,
+                            "share_of_instrumented_step_time": a_ms / args.steps / events_ms_per_step,
+                            "instrumented_ms_per_step": events_ms_per_step,
+                            "grouped_gemm_TFLOPs": roofline["achieved"]}
         hbm = {}
         for k in ("ln_fwd", "ln_vjp", "elementwise"):
             if k in totals and totals[k]["ms"] > 0:

@@ -43,7 +43,11 @@ the coarse forward step that starts at layer n.
 Pins (tests/test_oracle_mgrit.py): one level or cf = 1 == serial; exactness
 front of two-level MGRIT (k C-points per F-iteration, 2k per FCF-iteration);
 serial solution is a fixed point with zero residual; closed-form recurrences
-for a scalar linear F; three-level fixed point and limit.
+for a scalar linear F; three-level fixed point and limit.  Stacked
+encoder-decoder grid: serial pass == encoder stack then decoder stack run by
+the single-network functions; lambda_0 and parameter gradients against central
+differences of the stacked network; the hand-over lambda_X(N_enc) == terminal
+value + the decoder's memory gradient; exactness front across the switch.
 """
 from __future__ import annotations
 
@@ -257,3 +261,83 @@ def buffered_adjoint(lamN, Z, theta, h, cf, levels, iters, sh, n_open, n_close, 
     mid, res, _ = mgrit_adjoint(tail[0], Z[a:b + 1], theta[a:b], h, cf, levels, iters, sh, mem, relax)
     head = serial_adjoint(mid[0], Z[:a + 1], theta[:a], h_buffer, sh, mem) if n_open else [mid[0]]
     return head[:-1] + mid + tail[1:], res
+
+
+# ----------------------------------------------------------------------------
+# stacked encoder-decoder system (paper section 3.1, eq. "fp_transformer"): one state
+# Z_n = [X_n ; Y_n] on one time axis of N = N_enc + N_dec steps.  For n < N_enc the encoder layer
+# advances X and leaves Y alone; from N_enc on the decoder layer advances Y, reading the X part
+# of the same state as its cross-attention memory, and leaves X alone.  Rows of a state array:
+# the B*S_x encoder tokens first, then the B*S_y decoder tokens.
+# ----------------------------------------------------------------------------
+def _split_xy(w, sh_enc: tode.Shape):
+    tx = sh_enc.batch * sh_enc.seq
+    w = np.asarray(w, dtype=np.float64)
+    return w[:tx], w[tx:]
+
+
+def stacked_forward_propagator(theta: Sequence[dict], n_enc: int, h: float, cf: int, sh_enc: tode.Shape,
+                               sh_dec: tode.Shape) -> Propagator:
+    """Phi^l_j([X;Y]) = [X;Y] + cf^l h F(t_n, [X;Y]), n = j cf^l: the piecewise F of the stacked
+    system, taken at the step's starting time like theta."""
+    def step(lvl, j, w):
+        s = cf ** lvl
+        n = j * s
+        X, Y = _split_xy(w, sh_enc)
+        if n < n_enc:
+            return np.concatenate([tode.phi(X, theta[n], s * h, sh_enc), Y])
+        return np.concatenate([X, tode.phi(Y, theta[n], s * h, sh_dec, X)])
+    return step
+
+
+def stacked_adjoint_propagator(theta: Sequence[dict], Z: Sequence[np.ndarray], n_enc: int, h: float, cf: int,
+                               sh_enc: tode.Shape, sh_dec: tode.Shape) -> Propagator:
+    """Transpose of the stacked step that starts at layer n = N - (j+1) cf^l, linearised at Z_n.
+    A decoder step depends on X through the cross-attention memory, so its transpose adds the
+    memory cotangent to the X part of the adjoint state."""
+    N = len(Z) - 1
+
+    def step(lvl, j, mu):
+        s = cf ** lvl
+        n = N - (j + 1) * s
+        mx, my = _split_xy(mu, sh_enc)
+        Xn, Yn = _split_xy(Z[n], sh_enc)
+        if n < n_enc:
+            return np.concatenate([tode.psi(mx, Xn, theta[n], s * h, sh_enc), my])
+        dY, dX = tode.F_vjp(Yn, theta[n], my, sh_dec, Xn)
+        return np.concatenate([mx + s * h * dX, my + s * h * dY])
+    return step
+
+
+def stacked_serial_forward(Z0, theta, n_enc, h, sh_enc, sh_dec):
+    return serial_solve(stacked_forward_propagator(theta, n_enc, h, 1, sh_enc, sh_dec), Z0, len(theta))
+
+
+def stacked_mgrit_forward(Z0, theta, n_enc, h, cf, levels, iters, sh_enc, sh_dec, relax="FCF"):
+    """Returns (Z_0..Z_N, residual norms, evaluation counts per level)."""
+    return mgrit_solve(stacked_forward_propagator(theta, n_enc, h, cf, sh_enc, sh_dec), Z0, len(theta),
+                       cf, levels, iters, relax, None)
+
+
+def stacked_serial_adjoint(lamN, Z, theta, n_enc, h, sh_enc, sh_dec):
+    mu = serial_solve(stacked_adjoint_propagator(theta, Z, n_enc, h, 1, sh_enc, sh_dec), lamN, len(theta))
+    return mu[::-1]
+
+
+def stacked_mgrit_adjoint(lamN, Z, theta, n_enc, h, cf, levels, iters, sh_enc, sh_dec, relax="FCF"):
+    """Returns (lambda_0..lambda_N, residual norms, evaluation counts per level)."""
+    mu, res, counts = mgrit_solve(stacked_adjoint_propagator(theta, Z, n_enc, h, cf, sh_enc, sh_dec), lamN,
+                                  len(theta), cf, levels, iters, relax, None)
+    return mu[::-1], res, counts
+
+
+def stacked_parameter_gradients(lam, Z, theta, n_enc, h, sh_enc, sh_dec):
+    """dtheta_n = h (dF/dtheta_n (t_n, Z_n))^T lambda_{n+1}: an encoder layer sees the X parts, a
+    decoder layer the Y parts with the X part of Z_n as memory."""
+    out = []
+    for n, th in enumerate(theta):
+        lx, ly = _split_xy(lam[n + 1], sh_enc)
+        Xn, Yn = _split_xy(Z[n], sh_enc)
+        g = tode.F_param_vjp(Xn, th, lx, sh_enc) if n < n_enc else tode.F_param_vjp(Yn, th, ly, sh_dec, Xn)
+        out.append({k: h * v for k, v in g.items()})
+    return out

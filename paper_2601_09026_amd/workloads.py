@@ -162,3 +162,58 @@ def select_sequences(wl: Workload, x: np.ndarray, seqs, seq_len: Optional[int] =
     s = wl.seq if seq_len is None else seq_len
     idx = np.concatenate([np.arange(b * s, (b + 1) * s) for b in seqs])
     return x[idx]
+
+
+# ----------------------------------------------------------------------------
+# stacked encoder-decoder system: one time axis, encoder layers first (paper section 3.1)
+# ----------------------------------------------------------------------------
+@dataclass(frozen=True)
+class StackedWorkload:
+    """An encoder and a cross-attention decoder of the same width and batch on one grid of
+    enc.N + dec.N layers.  State rows: the encoder's tokens, then the decoder's.  The decoder
+    workload carries the grid's step size and MGRIT knobs; dec.mem_seq == enc.seq."""
+    name: str
+    enc: Workload
+    dec: Workload
+
+    def __post_init__(self):
+        e, d = self.enc, self.dec
+        assert e.arch == ARCH_ENCODER and d.arch == ARCH_CROSS
+        assert (e.d_model, e.n_heads, e.d_ff, e.batch, e.dtype) == (d.d_model, d.n_heads, d.d_ff, d.batch, d.dtype)
+        assert d.mem_seq == e.seq
+
+    @property
+    def N(self) -> int:
+        return self.enc.N + self.dec.N
+
+    @property
+    def n_enc(self) -> int:
+        return self.enc.N
+
+    @property
+    def tokens(self) -> int:
+        return self.enc.tokens + self.dec.tokens
+
+
+def stacked_workloads() -> Dict[str, StackedWorkload]:
+    """The machine-translation configuration as one grid: 32 encoder + 32 decoder layers."""
+    w = named_workloads()
+    dec = w["mt_decoder"].scaled(h=1.0 / 64)
+    return {"mt_stacked": StackedWorkload("mt_stacked", w["mt_encoder"].scaled(h=1.0 / 64), dec)}
+
+
+def stacked_layer_params(sw: StackedWorkload, layer: int, weight_std: float = 0.02) -> Dict[str, np.ndarray]:
+    """Layer `layer` of the stacked grid: an encoder layer below n_enc, a decoder layer from there."""
+    if layer < sw.n_enc:
+        return layer_params(sw.enc, layer, weight_std)
+    return layer_params(sw.dec, layer - sw.n_enc, weight_std)
+
+
+def stacked_initial_state(sw: StackedWorkload) -> np.ndarray:
+    """[X_0 ; Y_0]: source embeddings, then target embeddings."""
+    return np.concatenate([initial_state(sw.enc), initial_state(sw.dec)])
+
+
+def stacked_terminal_adjoint(sw: StackedWorkload) -> np.ndarray:
+    """lambda_N for L = <C, Z_N> over both parts of the final state."""
+    return np.concatenate([terminal_adjoint(sw.enc), terminal_adjoint(sw.dec)])

@@ -413,3 +413,119 @@ def test_buffered_network_reduces_to_per_layer_step_sizes():
         v = rng.standard_normal(Z0.shape)
         fd = ((C * plain(Z0 + eps * v)[-1]).sum() - (C * plain(Z0 - eps * v)[-1]).sum()) / (2 * eps)
         assert abs(fd - (lam[0] * v).sum()) < 1e-7 * max(1.0, abs(fd))
+
+
+# ------------------------------------------------------------------ stacked encoder-decoder grid
+def stacked_tiny(n_enc=6, n_dec=6, cf=2, levels=2, d=16, H=2, f=32, B=2, Sx=5, Sy=4, std=0.5, h=0.5):
+    enc = wls.Workload("e", wls.ARCH_ENCODER, d, H, f, B, Sx, 0, n_enc, h, cf, levels, 1, wls.DTYPE_F32, 51)
+    dec = wls.Workload("d", wls.ARCH_CROSS, d, H, f, B, Sy, Sx, n_dec, h, cf, levels, 1, wls.DTYPE_F32, 52)
+    sw = wls.StackedWorkload("s", enc, dec)
+    she = tode.Shape(enc.arch, d, H, B, Sx, 0)
+    shd = tode.Shape(dec.arch, d, H, B, Sy, Sx)
+    th = [wls.stacked_layer_params(sw, n, std) for n in range(sw.N)]
+    return sw, she, shd, th
+
+
+def test_stacked_serial_forward_is_encoder_then_decoder():
+    """Eq. "fp_transformer": X is frozen after the last encoder step and Y before it, so the
+    serial stacked pass is the encoder stack followed by the decoder stack that attends to the
+    encoder's output.  The two stacks are run here by the single-network functions."""
+    sw, she, shd, th = stacked_tiny()
+    Z0 = wls.stacked_initial_state(sw)
+    Z = mgrit.stacked_serial_forward(Z0, th, sw.n_enc, sw.dec.h, she, shd)
+    tx = sw.enc.tokens
+    X = mgrit.serial_forward(Z0[:tx], th[:sw.n_enc], sw.dec.h, she)
+    Y = mgrit.serial_forward(Z0[tx:], th[sw.n_enc:], sw.dec.h, shd, X[-1])
+    for n in range(sw.N + 1):
+        assert np.array_equal(Z[n][:tx], X[min(n, sw.n_enc)])
+        assert np.array_equal(Z[n][tx:], Y[max(n - sw.n_enc, 0)])
+
+
+def test_stacked_serial_adjoint_is_the_gradient_of_the_stacked_network():
+    """lambda_0 = d<C, Z_N>/dZ_0 by central differences, for perturbations of source and target
+    embeddings: the source direction only reaches the loss through every decoder layer's
+    cross-attention, so it checks the memory cotangent that the decoder steps add to lambda_X."""
+    sw, she, shd, th = stacked_tiny(n_enc=3, n_dec=3)
+    Z0 = wls.stacked_initial_state(sw).astype(np.float64)
+    C = wls.stacked_terminal_adjoint(sw).astype(np.float64)
+    C[:sw.enc.tokens] *= 0.3          # the final X enters the loss too, with another weight
+    Z = mgrit.stacked_serial_forward(Z0, th, sw.n_enc, sw.dec.h, she, shd)
+    lam = mgrit.stacked_serial_adjoint(C, Z, th, sw.n_enc, sw.dec.h, she, shd)
+    rng = np.random.default_rng(3)
+    for part in ("x", "y", "both"):
+        D = rng.standard_normal(Z0.shape)
+        if part == "x":
+            D[sw.enc.tokens:] = 0.0
+        if part == "y":
+            D[:sw.enc.tokens] = 0.0
+        eps = 1e-6
+        Lp = np.sum(C * mgrit.stacked_serial_forward(Z0 + eps * D, th, sw.n_enc, sw.dec.h, she, shd)[-1])
+        Lm = np.sum(C * mgrit.stacked_serial_forward(Z0 - eps * D, th, sw.n_enc, sw.dec.h, she, shd)[-1])
+        fd = (Lp - Lm) / (2 * eps)
+        assert abs(fd - np.sum(lam[0] * D)) <= 1e-7 * max(1.0, abs(fd)), (part, fd, np.sum(lam[0] * D))
+
+
+def test_stacked_adjoint_handover_is_terminal_plus_memory_gradient():
+    """At the encoder's end lambda_X equals its terminal value plus the decoder's gradient with
+    respect to its memory (one term per decoder layer), and lambda_Y does not change over the
+    encoder steps."""
+    sw, she, shd, th = stacked_tiny(n_enc=4, n_dec=5)
+    Z0 = wls.stacked_initial_state(sw)
+    C = wls.stacked_terminal_adjoint(sw).astype(np.float64)
+    Z = mgrit.stacked_serial_forward(Z0, th, sw.n_enc, sw.dec.h, she, shd)
+    lam = mgrit.stacked_serial_adjoint(C, Z, th, sw.n_enc, sw.dec.h, she, shd)
+    tx = sw.enc.tokens
+    Y = [z[tx:] for z in Z[sw.n_enc:]]
+    lamY = mgrit.serial_adjoint(C[tx:], Y, th[sw.n_enc:], sw.dec.h, shd, Z[-1][:tx])
+    dE = mgrit.memory_gradient(lamY, Y, th[sw.n_enc:], sw.dec.h, shd, Z[-1][:tx])
+    assert relerr(lam[sw.n_enc][:tx], C[:tx] + dE) < 1e-13
+    for n in range(sw.n_enc + 1):
+        assert np.array_equal(lam[n][tx:], lam[sw.n_enc][tx:])
+    assert relerr(lam[sw.n_enc][tx:], lamY[0]) < 1e-13
+
+
+@pytest.mark.parametrize("relax,speed", [("F", 1), ("FCF", 2)])
+def test_stacked_mgrit_exactness_front_and_limit(relax, speed):
+    """Two-level MGRIT on the stacked grid: exact on `speed` more C-points per iteration, across
+    the encoder/decoder switch (n_enc = 5 is not a C-point), and equal to the serial pass after
+    enough iterations; forward and adjoint."""
+    sw, she, shd, th = stacked_tiny(n_enc=5, n_dec=7, cf=2, levels=2)
+    Z0 = wls.stacked_initial_state(sw)
+    C = wls.stacked_terminal_adjoint(sw)
+    ser = mgrit.stacked_serial_forward(Z0, th, sw.n_enc, sw.dec.h, she, shd)
+    lser = mgrit.stacked_serial_adjoint(C, ser, th, sw.n_enc, sw.dec.h, she, shd)
+    M = sw.N // 2
+    for it in (1, 2, 3):
+        W, res, _ = mgrit.stacked_mgrit_forward(Z0, th, sw.n_enc, sw.dec.h, 2, 2, it, she, shd, relax)
+        lam, lres, _ = mgrit.stacked_mgrit_adjoint(C, ser, th, sw.n_enc, sw.dec.h, 2, 2, it, she, shd, relax)
+        front = min(speed * it, M)
+        for k in range(front + 1):
+            assert relerr(W[2 * k], ser[2 * k]) < 1e-12
+            assert relerr(lam[sw.N - 2 * k], lser[sw.N - 2 * k]) < 1e-12
+        if front < M:
+            assert relerr(W[-1], ser[-1]) > 1e-8
+            assert relerr(lam[0], lser[0]) > 1e-8
+    W, res, _ = mgrit.stacked_mgrit_forward(Z0, th, sw.n_enc, sw.dec.h, 2, 2, M, she, shd, relax)
+    assert max(relerr(a, b) for a, b in zip(W, ser)) < 1e-12
+
+
+def test_stacked_parameter_gradients_by_finite_differences():
+    """One encoder matrix (reaches the loss only through the decoder's memory), one decoder
+    cross-attention matrix and one decoder LayerNorm gain."""
+    sw, she, shd, th = stacked_tiny(n_enc=3, n_dec=3)
+    Z0 = wls.stacked_initial_state(sw)
+    C = wls.stacked_terminal_adjoint(sw).astype(np.float64)
+    C[:sw.enc.tokens] = 0.0           # loss on the decoder output only
+    Z = mgrit.stacked_serial_forward(Z0, th, sw.n_enc, sw.dec.h, she, shd)
+    lam = mgrit.stacked_serial_adjoint(C, Z, th, sw.n_enc, sw.dec.h, she, shd)
+    g = mgrit.stacked_parameter_gradients(lam, Z, th, sw.n_enc, sw.dec.h, she, shd)
+    rng = np.random.default_rng(5)
+    for n, name in ((1, "W1"), (4, "Wkv_c"), (5, "ln3_g"), (0, "bqkv")):
+        D = rng.standard_normal(th[n][name].shape)
+        vals = []
+        for sgn in (+1, -1):
+            th2 = [dict(t) for t in th]
+            th2[n][name] = th[n][name].astype(np.float64) + sgn * 1e-6 * D
+            vals.append(np.sum(C * mgrit.stacked_serial_forward(Z0, th2, sw.n_enc, sw.dec.h, she, shd)[-1]))
+        fd = (vals[0] - vals[1]) / 2e-6
+        assert abs(fd - np.sum(g[n][name] * D)) <= 2e-7 * max(1.0, abs(fd)), (n, name, fd, np.sum(g[n][name] * D))
