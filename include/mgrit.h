@@ -186,6 +186,36 @@ int mgrit_adjoint_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts,
                            void* dmemory, void* const* dtheta, float* resnorm,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* Stacked encoder-decoder system (sec. 3.1, eq. "fp_transformer"): one MGRIT grid over the
+ * N = opts->N = N_enc + N_dec layers of an encoder followed by a cross-attention decoder.  The
+ * state of a grid point is Z_n = [X_n ; Y_n]: the batch*mem_seq encoder tokens, then the
+ * batch*seq decoder tokens, each d_model wide.  For n < n_enc the step is the encoder block on
+ * the X rows (Y rows copied); from n_enc on it is the decoder block on the Y rows, whose
+ * cross-attention reads the X rows of the same input state (X rows copied).  A coarse step takes
+ * the type and the parameters of the fine layer it starts at.  The transposed decoder step also
+ * adds the memory cotangent to the X rows of the adjoint state.
+ *   desc       the decoder's description: arch must be MGRIT_ARCH_CROSS; the encoder is the
+ *              arch-0 block of the same d_model, n_heads, d_ff, batch, dtype with seq = mem_seq
+ *   n_enc      1 <= n_enc < opts->N
+ *   theta      host array of N device pointers: the first n_enc blocks in the encoder's layout
+ *              (mgrit_theta_layout of the encoder description), the others in the decoder's
+ *   Z0, lambda_N           device [batch*(mem_seq+seq), d] fp32
+ *   Z_all, lambda_all      device [(N+1), batch*(mem_seq+seq), d] fp32, row n = grid point n
+ *   dtheta     NULL, or host array of N device pointers to fp32 gradient blocks (layouts of the
+ *              fp32 encoder / decoder descriptions), as in mgrit_adjoint
+ * Everything else (resnorm, workspace, stream, errors, ownership) as in mgrit_forward /
+ * mgrit_adjoint.  Workspace: mgrit_stacked_workspace_bytes (adjoint as in mgrit_workspace_bytes). */
+size_t mgrit_stacked_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, int adjoint);
+int mgrit_forward_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc,
+                          const void* Z0, const void* const* theta,
+                          void* Z_all, float* resnorm,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int mgrit_adjoint_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc,
+                          const void* Z_all, const void* const* theta,
+                          const void* lambda_N, void* lambda_all,
+                          void* const* dtheta, float* resnorm,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
 /* One batched layer step over n_groups independent (state, layer) pairs -- the
  * launch that F-/C-relaxation of Algorithm 1 is made of.
  *   adjoint == 0:  out[g] = in[g] + hstep * F(in[g]; theta[g])            (+ rhs[g])

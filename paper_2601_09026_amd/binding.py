@@ -99,6 +99,14 @@ def lib() -> C.CDLL:
         L.mgrit_adjoint_buffered.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.POINTER(BufferOpts), vp, vpp,
                                              vp, vp, vp, vp, vpp, vp, vp, C.c_size_t, vp]
         L.mgrit_adjoint_buffered.restype = C.c_int
+        L.mgrit_stacked_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.c_int, C.c_int]
+        L.mgrit_stacked_workspace_bytes.restype = C.c_size_t
+        L.mgrit_forward_stacked.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.c_int, vp, vpp, vp, vp, vp,
+                                            C.c_size_t, vp]
+        L.mgrit_forward_stacked.restype = C.c_int
+        L.mgrit_adjoint_stacked.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.c_int, vp, vpp, vp, vp, vpp, vp,
+                                            vp, C.c_size_t, vp]
+        L.mgrit_adjoint_stacked.restype = C.c_int
         L.mgrit_indicator_init.argtypes = [C.POINTER(Indicator), C.c_int, C.c_int, C.c_int, C.c_int, C.c_float]
         L.mgrit_indicator_init.restype = C.c_int
         L.mgrit_indicator_begin_batch.argtypes = [C.POINTER(Indicator)]
@@ -402,4 +410,55 @@ def mgrit_adjoint_buffered(desc: ModelDesc, opts: Opts, buf: BufferOpts, Z_all: 
                                       _ptr(resnorm), _ptr(ws), ws.numel(), _stream_handle(stream))
     if st != MGRIT_OK:
         raise MgritError(st, "mgrit_adjoint_buffered")
+    return lambda_all, resnorm
+
+
+# ---- stacked encoder-decoder grid -------------------------------------------------------------
+def encoder_desc(desc: ModelDesc) -> ModelDesc:
+    """The encoder half of a stacked grid described by its decoder `desc`."""
+    return ModelDesc(0, desc.d_model, desc.n_heads, desc.d_ff, desc.batch, desc.mem_seq, 0, desc.dtype, desc.ln_eps)
+
+
+def mgrit_stacked_workspace_bytes(desc: ModelDesc, opts: Opts, n_enc: int, adjoint: int) -> int:
+    return int(lib().mgrit_stacked_workspace_bytes(C.byref(desc), C.byref(opts), int(n_enc), int(adjoint)))
+
+
+def mgrit_forward_stacked(desc: ModelDesc, opts: Opts, n_enc: int, Z0: torch.Tensor, theta: List[torch.Tensor],
+                          stream: Optional[torch.cuda.Stream] = None):
+    """One MGRIT grid over n_enc encoder layers followed by decoder layers; state rows = encoder
+    tokens then decoder tokens.  Returns (Z_all, resnorm)."""
+    T, d = desc.batch * (desc.mem_seq + desc.seq), desc.d_model
+    _check_state(Z0, (T, d), "Z0")
+    if len(theta) != opts.N:
+        raise ValueError("theta must hold N blocks")
+    Z_all = torch.empty((opts.N + 1, T, d), dtype=torch.float32, device=Z0.device)
+    resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z0.device)
+    ws = torch.empty(max(mgrit_stacked_workspace_bytes(desc, opts, n_enc, 0), 256), dtype=torch.uint8,
+                     device=Z0.device)
+    st = lib().mgrit_forward_stacked(C.byref(desc), C.byref(opts), int(n_enc), _ptr(Z0), _ptr_array(theta),
+                                     _ptr(Z_all), _ptr(resnorm), _ptr(ws), ws.numel(), _stream_handle(stream))
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_forward_stacked")
+    return Z_all, resnorm
+
+
+def mgrit_adjoint_stacked(desc: ModelDesc, opts: Opts, n_enc: int, Z_all: torch.Tensor, theta: List[torch.Tensor],
+                          lambda_N: torch.Tensor, dtheta: Optional[List[torch.Tensor]] = None,
+                          stream: Optional[torch.cuda.Stream] = None):
+    """Returns (lambda_all, resnorm) of the stacked grid; dtheta as in mgrit_adjoint (encoder
+    layers' blocks in the encoder's fp32 layout, decoder layers' in the decoder's)."""
+    T, d = desc.batch * (desc.mem_seq + desc.seq), desc.d_model
+    _check_state(Z_all, (opts.N + 1, T, d), "Z_all")
+    _check_state(lambda_N, (T, d), "lambda_N")
+    if len(theta) != opts.N or (dtheta is not None and len(dtheta) != opts.N):
+        raise ValueError("theta / dtheta must hold N blocks")
+    lambda_all = torch.empty_like(Z_all)
+    resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z_all.device)
+    need = mgrit_stacked_workspace_bytes(desc, opts, n_enc, 2 if dtheta is not None else 1)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=Z_all.device)
+    st = lib().mgrit_adjoint_stacked(C.byref(desc), C.byref(opts), int(n_enc), _ptr(Z_all), _ptr_array(theta),
+                                     _ptr(lambda_N), _ptr(lambda_all), _ptr_array(dtheta), _ptr(resnorm), _ptr(ws),
+                                     ws.numel(), _stream_handle(stream))
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_adjoint_stacked")
     return lambda_all, resnorm

@@ -24,8 +24,9 @@ constexpr int WAVE = 64;
 struct Rows {                       // fp32 [T,d] states reached through a table
   const void* const* tab;           // device array of device pointers (may be null)
   int i0, is;
+  long off;                         // element offset inside every state (a row range of a stacked state)
   __device__ __forceinline__ float* at(int g) const {
-    return (float*)const_cast<void*>(tab[i0 + (long)g * is]);
+    return (float*)const_cast<void*>(tab[i0 + (long)g * is]) + off;
   }
   __host__ __device__ bool present() const { return tab != nullptr; }
 };

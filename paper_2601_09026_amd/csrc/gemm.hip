@@ -69,8 +69,8 @@ __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restric
     store4<float>(out_f32 + idx, acc);
   } else if constexpr (EPI == EPI_RESID_OUTER) {
     f32x4 x = *reinterpret_cast<const f32x4*>(X + idx);
-    f32x4 yb = *reinterpret_cast<const f32x4*>(ybar + idx);
-    f32x4 r = x + hstep * (yb + acc);
+    if (ybar) acc += *reinterpret_cast<const f32x4*>(ybar + idx);
+    f32x4 r = x + hstep * acc;
     if (RHS) r += *reinterpret_cast<const f32x4*>(RHS + idx);
     store4<float>(OUT + idx, r);
   }

@@ -51,6 +51,7 @@ hipError_t launch_cast_rows(int n_groups, long elems, Rows X, void* out, long ou
 hipError_t launch_cast_flat(const float* in, void* out, long elems, bool is_bf16, hipStream_t st);
 // dst[g] = a[g] - b[g]  on fp32 rows
 hipError_t launch_sub_rows(int n_groups, long elems, Rows A, Rows B, Rows D, hipStream_t st);
+hipError_t launch_add_rows(int n_groups, long elems, Rows A, Rows B, Rows D, hipStream_t st);   // D = A (+ B)
 // partial[block] = sum over the block's elements of (a-b)^2 in double; then out[0] = sqrt(sum partial)
 hipError_t launch_resnorm(int n_groups, long elems, Rows A, Rows B, double* partial, int max_partial,
                           float* out, hipStream_t st);

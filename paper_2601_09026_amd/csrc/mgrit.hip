@@ -161,6 +161,10 @@ struct Engine {
   float* gpart = nullptr;
   void** tabTB = nullptr;
   void* dkvc = nullptr;            // cross-attention decoder: dK | dV of the cross attention, [Tm, 2d] per slot
+  // decoder half of a stacked encoder-decoder grid: every group attends to the X part of its own
+  // input state, so the operand-type copy of the memory is per launch slot ([Tm, d] each)
+  bool per_group_mem = false;
+  void* membG = nullptr;
   int Tmax() const { return T > Tm ? T : Tm; }
   long tA_stride() const { return (long)(f > 3 * d ? f : 3 * d) * Tmax(); }   // elements per slot
   long tB_stride() const { return (long)(f > d ? f : d) * Tmax(); }
@@ -191,6 +195,7 @@ struct Engine {
       x3 = b.take<float>(G * T * d);
       qc = b.take_bytes(G * T * d * esz);
       kvc = b.take_bytes(G * Tm * 2 * d * esz);
+      if (per_group_mem) membG = b.take_bytes(G * Tm * d * esz);
     }
   }
   void carve_forward(Bump& b, int gc) {
@@ -233,6 +238,10 @@ struct Engine {
     dxin = b.take<float>(G * T * d);
     Dbuf = b.take<float>(G * md.batch * H * md.seq);
     qkv = o = act = nullptr; xin = nullptr;
+    if (per_group_mem) {
+      membG = b.take_bytes(G * Tm * d * esz);
+      dkvc = b.take_bytes(G * Tm * 2 * d * esz);
+    }
   }
   void carve_grad_work(Bump& b) {
     const size_t G = Gc;
@@ -242,7 +251,7 @@ struct Engine {
     const size_t p1 = G * transpose_row_blocks(Tmax()) * widest, p2 = G * ln_param_partial_rows() * 2 * (size_t)d;
     gpart = b.take<float>(p1 > p2 ? p1 : p2);
     tabTB = b.take<void*>(G);
-    dkvc = md.arch == MGRIT_ARCH_CROSS ? b.take_bytes(G * Tm * 2 * d * esz) : nullptr;
+    if (!per_group_mem) dkvc = md.arch == MGRIT_ARCH_CROSS ? b.take_bytes(G * Tm * 2 * d * esz) : nullptr;
   }
 };
 
@@ -296,8 +305,9 @@ GemmArgs gemm_base(int n, int M, int N, int K, const void* A, long a_stride, Slo
 
 // One chunk (n <= Gc groups) of the forward layer step.  `cache`: write the linearisation
 // cache at `cslots` instead of advancing the state (stops before FFN2).
+// MEM (decoder of a stacked grid): group g's cross-attention memory is the fp32 rows MEM.at(g).
 int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, float hstep, bool cache,
-                  Slots cslots) {
+                  Slots cslots, Rows MEM = NO_ROWS) {
   const int T = E.T, d = E.d, f = E.f;
   const auto& L = E.lay;
   const Slots loc = {0, 1};
@@ -350,7 +360,9 @@ int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, floa
     g = gemm_base(n, T, d, d, E.u, E.Td(), loc, TH, L.offset[MGRIT_P_WQ_C], L.offset[MGRIT_P_BQ_C]);
     g.out = qc; g.out_slot_stride = E.Td(); g.out_slots = cs;
     HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
-    g = gemm_base(n, E.Tm, 2 * d, d, E.memb, 0, loc, TH, L.offset[MGRIT_P_WKV_C], L.offset[MGRIT_P_BKV_C]);
+    if (MEM.present()) HIPCHK(launch_cast_rows(n, (long)E.Tm * d, MEM, E.membG, (long)E.Tm * d, loc, E.bf16, E.st));
+    g = gemm_base(n, E.Tm, 2 * d, d, MEM.present() ? E.membG : E.memb, MEM.present() ? (long)E.Tm * d : 0, loc, TH,
+                  L.offset[MGRIT_P_WKV_C], L.offset[MGRIT_P_BKV_C]);
     g.out = kvc; g.out_slot_stride = (long)E.Tm * 2 * d; g.out_slots = cs;
     HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
     memset(&at, 0, sizeof(at));
@@ -422,9 +434,19 @@ struct GradPass {
   const Params* DT = nullptr;      // gradient blocks of the chunk's layers, or null
   float* dE_all = nullptr;         // cross-attention decoder: [layer slot, Tm, d] fp32 memory-gradient terms, or null
 };
+// Decoder step of a stacked encoder-decoder grid (paper section 3.1, eq. "fp_transformer"): the
+// memory of group g is the X part of its linearisation state, and the transposed step adds the
+// memory cotangent to the X part of the adjoint state:  OUTX = INX + hstep * dE (+ RHSX).
+struct StackedDec {
+  Rows MEM, INX, OUTX, RHSX;
+};
+inline StackedDec shift(StackedDec s, int c0) {
+  s.MEM = shift(s.MEM, c0); s.INX = shift(s.INX, c0); s.OUTX = shift(s.OUTX, c0); s.RHSX = shift(s.RHSX, c0);
+  return s;
+}
 
 int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Params THT, Rows LIN, Slots cs,
-                  float hstep, const GradPass* gp = nullptr) {
+                  float hstep, const GradPass* gp = nullptr, const StackedDec* sd = nullptr) {
   const Params* DT = gp ? gp->DT : nullptr;
   const int T = E.T, d = E.d, f = E.f;
   const auto& L = E.lay;
@@ -507,7 +529,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
     ac.dO = E.da; ac.do_row_stride = d; ac.do_slot_stride = E.Td(); ac.do_slots = loc;
     ac.dq = E.dqkv; ac.dk = nullptr; ac.dv = nullptr;
     ac.dqkv_row_stride = d; ac.dqkv_slot_stride = (long)T * 3 * d; ac.dqkv_slots = loc;
-    if (gp) {
+    if (gp || sd) {
       ac.dk = E.dkvc; ac.dv = (char*)E.dkvc + (size_t)d * esz;
       ac.dkv_row_stride = 2 * d; ac.dkv_slot_stride = (long)E.Tm * 2 * d;
     }
@@ -520,8 +542,15 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
       HIPCHK(launch_ln_fwd(lf, E.bf16, E.st));
       STCHK(linear_param_grads(E, n, E.dqkv, (long)T * 3 * d, loc, d, E.u, E.Td(), loc, d, false, *DT,
                                MGRIT_P_WQ_C, MGRIT_P_BQ_C, hstep));
-      STCHK(linear_param_grads(E, n, E.dkvc, (long)E.Tm * 2 * d, loc, 2 * d, E.memb, 0, loc, d, false, *DT,
-                               MGRIT_P_WKV_C, MGRIT_P_BKV_C, hstep, E.Tm));
+      if (sd) HIPCHK(launch_cast_rows(n, (long)E.Tm * d, sd->MEM, E.membG, (long)E.Tm * d, loc, E.bf16, E.st));
+      STCHK(linear_param_grads(E, n, E.dkvc, (long)E.Tm * 2 * d, loc, 2 * d, sd ? E.membG : E.memb,
+                               sd ? (long)E.Tm * d : 0, loc, d, false, *DT, MGRIT_P_WKV_C, MGRIT_P_BKV_C, hstep, E.Tm));
+    }
+    if (sd && !gp) {
+      // lambda_X <- lambda_X + hstep * [dK | dV] Wkv_c (+ rhs)    [Tm,2d] x [2d,d]: transposed Wkv_c is [d,2d]
+      g = gemm_base(n, E.Tm, d, 2 * d, E.dkvc, (long)E.Tm * 2 * d, loc, THT, L.offset[MGRIT_P_WKV_C], -1);
+      g.X = sd->INX; g.OUT = sd->OUTX; g.RHS = sd->RHSX; g.hstep = hstep;
+      HIPCHK(launch_gemm(g, EPI_RESID_OUTER, E.bf16, E.st));
     }
     if (gp && gp->dE_all) {
       // this layer's term of dL/dE:  hstep * [dK | dV] Wkv_c       [Tm,2d] x [2d,d]: transposed Wkv_c is [d,2d]
@@ -633,31 +662,35 @@ int run_chunks(Engine& E, Engine* E2, int G, F fn) {
 }
 
 int forward_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Params TH, float hstep, bool cache,
-                   Slots cslots) {
+                   Slots cslots, Rows MEM = NO_ROWS) {
   return run_chunks(E, E2, G, [&](Engine& L, int c0, int n) {
     return forward_chunk(L, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), hstep, cache,
-                         shift(cslots, c0));
+                         shift(cslots, c0), shift(MEM, c0));
   });
 }
 
 int adjoint_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Params TH, Params THT, Rows LIN,
-                   Slots cs, float hstep) {
+                   Slots cs, float hstep, const StackedDec* sd = nullptr) {
   return run_chunks(E, E2, G, [&](Engine& L, int c0, int n) {
+    StackedDec s;
+    if (sd) s = shift(*sd, c0);
     return adjoint_chunk(L, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), shift(THT, c0),
-                         shift(LIN, c0), shift(cs, c0), hstep);
+                         shift(LIN, c0), shift(cs, c0), hstep, nullptr, sd ? &s : nullptr);
   });
 }
 
 // parameter gradients of G layers: group g has IN = lambda_{n+1}, LIN = Z_n, gradient block DT[g]
 int gradient_groups(Engine& E, Engine* E2, int G, Rows IN, Params TH, Params THT, Rows LIN, Slots cs,
-                    const Params* DT, float* dE_all, float hstep) {
+                    const Params* DT, float* dE_all, float hstep, const StackedDec* sd = nullptr) {
   return run_chunks(E, E2, G, [&](Engine& L, int c0, int n) {
     Params dt = {nullptr, 0, 0};
     GradPass gp;
     if (DT) { dt = shift(*DT, c0); gp.DT = &dt; }
     gp.dE_all = dE_all;
+    StackedDec s;
+    if (sd) s = shift(*sd, c0);
     return adjoint_chunk(L, n, shift(IN, c0), NO_ROWS, NO_ROWS, shift(TH, c0), shift(THT, c0), shift(LIN, c0),
-                         shift(cs, c0), hstep, &gp);
+                         shift(cs, c0), hstep, &gp, sd ? &s : nullptr);
   });
 }
 
@@ -692,8 +725,69 @@ struct Driver {
   int max_partial = 0;
   float* resnorm = nullptr;
   int64_t evals = 0;
+  // stacked encoder-decoder grid (paper section 3.1, eq. "fp_transformer"): E, E2 are the encoder's
+  // engines, Ed, Ed2 the decoder's; layers below n_enc are encoder layers.  A state is the X rows
+  // (x_elems floats) followed by the Y rows (y_elems floats).
+  Engine* Ed = nullptr;
+  Engine* Ed2 = nullptr;
+  int n_enc = 0;
+  long x_elems = 0, y_elems = 0;
+  long state_elems() const { return Ed ? x_elems + y_elems : E->Td(); }
 
   static int ipow(int b, int e) { int r = 1; while (e-- > 0) r *= b; return r; }
+  static Rows part(Rows r, long off) { if (r.tab) r.off += off; return r; }
+
+  // Stacked grid: the groups of a sweep start at increasing (forward) or decreasing (adjoint)
+  // layers, so they split into one run of encoder steps and one run of decoder steps.  An
+  // encoder step advances the X rows and copies the Y rows (+ right-hand side), a decoder step
+  // the other way round, reading the X rows of its input (forward) or of its linearisation
+  // state (adjoint) as cross-attention memory.
+  int step_stacked(int cnt, int n0, int ns, Rows IN, Rows OUT, Rows RHS, float hstep) {
+    // groups k = 0..cnt-1 act on layer n0 + k*ns
+    int n_first = 0;                                 // groups of the first run
+    const bool first_is_enc = adjoint ? false : true;
+    if (!adjoint) {                                  // ns >= 0: encoder while n0 + k ns < n_enc
+      if (n0 >= n_enc) n_first = 0;
+      else if (ns <= 0) n_first = cnt;
+      else n_first = (n_enc - 1 - n0) / ns + 1;
+    } else {                                         // ns <= 0: decoder while n0 + k ns >= n_enc
+      if (n0 < n_enc) n_first = 0;
+      else if (ns >= 0) n_first = cnt;
+      else n_first = (n0 - n_enc) / (-ns) + 1;
+    }
+    if (n_first > cnt) n_first = cnt;
+    for (int run = 0; run < 2; ++run) {
+      const int c0 = run == 0 ? 0 : n_first, n = run == 0 ? n_first : cnt - n_first;
+      if (n <= 0) continue;
+      const bool enc = (run == 0) == first_is_enc;
+      const int nl = n0 + c0 * ns;
+      const Rows in = shift(IN, c0), out = shift(OUT, c0), rhs = shift(RHS, c0);
+      const Rows inx = in, outx = out, rhsx = rhs;
+      const Rows iny = part(in, x_elems), outy = part(out, x_elems), rhsy = part(rhs, x_elems);
+      Params TH = {(const void* const*)tabTh, nl, ns};
+      if (!adjoint) {
+        if (enc) {
+          STCHK(forward_groups(*E, E2, n, inx, outx, rhsx, TH, hstep, false, Slots{0, 0}));
+          HIPCHK(launch_add_rows(n, y_elems, iny, rhsy, outy, E->st));
+        } else {
+          STCHK(forward_groups(*Ed, Ed2, n, iny, outy, rhsy, TH, hstep, false, Slots{0, 0}, inx));
+          HIPCHK(launch_add_rows(n, x_elems, inx, rhsx, outx, E->st));
+        }
+        continue;
+      }
+      Params THT = {(const void* const*)tabThT, nl, ns};
+      Rows LIN = {(const void* const*)tabZ, nl, ns};
+      if (enc) {
+        STCHK(adjoint_groups(*E, E2, n, inx, outx, rhsx, TH, THT, LIN, Slots{nl, ns}, hstep));
+        HIPCHK(launch_add_rows(n, y_elems, iny, rhsy, outy, E->st));
+      } else {
+        StackedDec sd = {LIN, inx, outx, rhsx};
+        STCHK(adjoint_groups(*Ed, Ed2, n, iny, outy, rhsy, TH, THT, part(LIN, x_elems), Slots{nl - n_enc, ns}, hstep,
+                             &sd));
+      }
+    }
+    return MGRIT_OK;
+  }
 
   // cnt steps of level `lvl`, group k starting at point j = j0 + k*js
   int step(int lvl, int j0, int js, int cnt, Rows OUT, Rows RHS) {
@@ -702,6 +796,10 @@ struct Driver {
     const int s = ipow(cf, lvl);
     const float hstep = (float)((double)s * (double)h);
     Rows IN = {(const void* const*)tabW, j0 * s, js * s};
+    if (Ed) {
+      if (!adjoint) return step_stacked(cnt, j0 * s, js * s, IN, OUT, RHS, hstep);
+      return step_stacked(cnt, N - (j0 + 1) * s, -js * s, IN, OUT, RHS, hstep);
+    }
     if (!adjoint) {
       Params TH = {(const void* const*)tabTh, j0 * s, js * s};
       return forward_groups(*E, E2, cnt, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
@@ -743,11 +841,11 @@ struct Driver {
     Rows R = {(const void* const*)tabR, 0, 1};
     STCHK(step(lvl, cf - 1, cf, M, R, Gr(lvl, cf, cf)));
     if (E && lvl == 0 && resnorm)
-      HIPCHK(launch_resnorm(M, E->Td(), R, W(lvl, cf, cf), partial, max_partial, resnorm + iter, E->st));
+      HIPCHK(launch_resnorm(M, state_elems(), R, W(lvl, cf, cf), partial, max_partial, resnorm + iter, E->st));
     // g'_k = R_k - Phi'(w_{(k-1) cf}),  k = 1..M
     Rows Gn = {(const void* const*)(E ? tabG[lvl + 1] : nullptr), 1, 1};
     STCHK(step(lvl + 1, 0, 1, M, Gn, NO_ROWS));
-    if (E) HIPCHK(launch_sub_rows(M, E->Td(), R, Gn, Gn, E->st));
+    if (E) HIPCHK(launch_sub_rows(M, state_elems(), R, Gn, Gn, E->st));
     STCHK(vcycle(lvl + 1, iter, false));
     STCHK(f_relax(lvl, M));
     return MGRIT_OK;
@@ -981,6 +1079,197 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
     // dL/dE = sum over layers of the per-layer terms, in layer order
     if (dmemory)
       HIPCHK(launch_sum_slots(P.dE_all, N, (long)E.Tm * E.d, static_cast<float*>(dmemory), 1.0f, st));
+  }
+  return MGRIT_OK;
+}
+
+// ---- stacked encoder-decoder grid (paper section 3.1, eq. "fp_transformer") --------------------
+namespace {
+struct StackedPlan {
+  Engine Ee, Ee2, Ed, Ed2;          // encoder / decoder engines of the two lanes
+  bool two_lanes = false;
+  Driver D;
+  void* thT_blocks = nullptr;
+  void** tabDT = nullptr;
+  size_t enc_block = 0, dec_block = 0;
+  size_t bytes = 0;
+};
+
+mgrit_model_desc encoder_of(const mgrit_model_desc* dec) {
+  mgrit_model_desc m = *dec;
+  m.arch = MGRIT_ARCH_ENCODER;
+  m.seq = dec->mem_seq;
+  m.mem_seq = 0;
+  return m;
+}
+
+int validate_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc) {
+  STCHK(validate_desc(desc));
+  STCHK(validate_opts(opts));
+  if (desc->arch != MGRIT_ARCH_CROSS) return MGRIT_INVALID_ARG;
+  const mgrit_model_desc me = encoder_of(desc);
+  STCHK(validate_desc(&me));
+  if (n_enc < 1 || n_enc >= opts->N) return MGRIT_INVALID_ARG;
+  return MGRIT_OK;
+}
+
+// mode: 0 forward, 1 adjoint, 2 adjoint followed by the parameter-gradient pass
+int make_stacked_plan(StackedPlan& P, const mgrit_model_desc* md, const mgrit_opts* op, int n_enc, int mode,
+                      void* ws, hipStream_t st) {
+  const bool adjoint = mode != 0;
+  Bump b(ws);
+  const mgrit_model_desc me = encoder_of(md);
+  P.Ee.init(&me, st);
+  P.Ed.init(md, st);
+  P.Ed.per_group_mem = true;
+  P.enc_block = P.Ee.lay.block_bytes;
+  P.dec_block = P.Ed.lay.block_bytes;
+  const int N = op->N, n_dec = N - n_enc;
+  const bool serial = serial_run(op);
+  const int M0 = serial ? 1 : N / op->cf;
+  int gc = max_groups();
+  const int widest = adjoint ? (N > M0 ? N : M0) : M0;
+  if (gc > widest) gc = widest;
+  if (adjoint) { P.Ee.carve_adjoint(b, gc, n_enc); P.Ed.carve_adjoint(b, gc, n_dec); }
+  else { P.Ee.carve_forward(b, gc); P.Ed.carve_forward(b, gc); }
+  P.two_lanes = widest >= 2 && make_lane(P.Ee2, P.Ee, b, adjoint, ws == nullptr);
+  if (P.two_lanes && !make_lane(P.Ed2, P.Ed, b, adjoint, ws == nullptr)) return MGRIT_HIP_ERROR;
+  Driver& D = P.D;
+  D.E = &P.Ee; D.E2 = P.two_lanes ? &P.Ee2 : nullptr;
+  D.Ed = &P.Ed; D.Ed2 = P.two_lanes ? &P.Ed2 : nullptr;
+  D.n_enc = n_enc; D.x_elems = P.Ee.Td(); D.y_elems = P.Ed.Td();
+  D.adjoint = adjoint; D.N = N; D.cf = op->cf; D.L = serial ? 1 : op->levels; D.relax = op->relax; D.h = op->h;
+  D.tabW = b.take<void*>(N + 1);
+  D.tabTh = b.take<void*>(N);
+  if (adjoint) {
+    D.tabZ = b.take<void*>(N + 1);
+    D.tabThT = b.take<void*>(N);
+    P.thT_blocks = b.take_bytes((size_t)n_enc * P.enc_block + (size_t)n_dec * P.dec_block);
+  }
+  if (mode == 2) {
+    P.tabDT = b.take<void*>(N);
+    for (Engine* L : {&P.Ee, &P.Ed, P.two_lanes ? &P.Ee2 : nullptr, P.two_lanes ? &P.Ed2 : nullptr}) {
+      if (!L) continue;
+      L->carve_grad_work(b);
+      if (ws && launch_fill_table(L->tabTB, static_cast<char*>(L->tB), L->tB_stride() * (long)L->esz, L->Gc, st) !=
+                    hipSuccess)
+        return MGRIT_HIP_ERROR;
+    }
+  }
+  D.tabG.assign(D.L, nullptr);
+  if (!serial) {
+    D.tabR = b.take<void*>(M0);
+    D.max_partial = M0 * resnorm_partials_per_group();
+    D.partial = b.take<double>(D.max_partial);
+    const size_t state = (size_t)D.state_elems() * sizeof(float);
+    char* Rbuf = static_cast<char*>(b.take_bytes(M0 * state));
+    std::vector<char*> Gbuf(D.L, nullptr);
+    for (int l = 1; l < D.L; ++l) {
+      const int Nl = N / Driver::ipow(op->cf, l);
+      D.tabG[l] = b.take<void*>(Nl + 1);
+      Gbuf[l] = static_cast<char*>(b.take_bytes((size_t)(Nl + 1) * state));
+    }
+    if (ws) {
+      if (launch_fill_table(D.tabR, Rbuf, (long)state, M0, st) != hipSuccess) return MGRIT_HIP_ERROR;
+      for (int l = 1; l < D.L; ++l) {
+        const int Nl = N / Driver::ipow(op->cf, l);
+        if (launch_fill_table(D.tabG[l], Gbuf[l], (long)state, Nl + 1, st) != hipSuccess) return MGRIT_HIP_ERROR;
+      }
+    }
+  }
+  P.bytes = (b.off + 255) / 256 * 256;
+  return MGRIT_OK;
+}
+}  // namespace
+
+size_t mgrit_stacked_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, int adjoint) {
+  if (validate_stacked(desc, opts, n_enc) != MGRIT_OK || adjoint < 0 || adjoint > 2) return 0;
+  StackedPlan P;
+  if (make_stacked_plan(P, desc, opts, n_enc, adjoint, nullptr, nullptr) != MGRIT_OK) return 0;
+  return P.bytes;
+}
+
+int mgrit_forward_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, const void* Z0,
+                          const void* const* theta, void* Z_all, float* resnorm, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  STCHK(validate_stacked(desc, opts, n_enc));
+  if (!Z0 || !Z_all || !workspace) return MGRIT_INVALID_ARG;
+  STCHK(check_ptr_array(theta, opts->N));
+  const size_t need = mgrit_stacked_workspace_bytes(desc, opts, n_enc, 0);
+  if (need == 0) return MGRIT_INVALID_ARG;
+  if (workspace_bytes < need) return MGRIT_WORKSPACE_TOO_SMALL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  StackedPlan P;
+  STCHK(make_stacked_plan(P, desc, opts, n_enc, 0, workspace, st));
+  Driver& D = P.D;
+  const int N = opts->N;
+  const size_t state = (size_t)D.state_elems() * sizeof(float);
+  HIPCHK(launch_fill_table(D.tabW, static_cast<char*>(Z_all), (long)state, N + 1, st));
+  HIPCHK(upload_pointers(D.tabTh, theta, N, st));
+  if (Z0 != Z_all) HIPCHK(hipMemcpyAsync(Z_all, Z0, state, hipMemcpyDeviceToDevice, st));
+  if (!serial_run(opts) && opts->init_guess == 0) {
+    for (int k = 1; k <= N / opts->cf; ++k)
+      HIPCHK(hipMemcpyAsync(static_cast<char*>(Z_all) + (size_t)k * opts->cf * state, Z0, state,
+                            hipMemcpyDeviceToDevice, st));
+  }
+  D.resnorm = resnorm;
+  return D.run(opts->iters);
+}
+
+int mgrit_adjoint_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, const void* Z_all,
+                          const void* const* theta, const void* lambda_N, void* lambda_all, void* const* dtheta,
+                          float* resnorm, void* workspace, size_t workspace_bytes, void* stream) {
+  STCHK(validate_stacked(desc, opts, n_enc));
+  if (!Z_all || !lambda_N || !lambda_all || !workspace) return MGRIT_INVALID_ARG;
+  STCHK(check_ptr_array(theta, opts->N));
+  if (dtheta) STCHK(check_ptr_array((const void* const*)dtheta, opts->N));
+  const int mode = dtheta ? 2 : 1;
+  const size_t need = mgrit_stacked_workspace_bytes(desc, opts, n_enc, mode);
+  if (need == 0) return MGRIT_INVALID_ARG;
+  if (workspace_bytes < need) return MGRIT_WORKSPACE_TOO_SMALL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  StackedPlan P;
+  STCHK(make_stacked_plan(P, desc, opts, n_enc, mode, workspace, st));
+  Driver& D = P.D;
+  const int N = opts->N, n_dec = N - n_enc;
+  const size_t state = (size_t)D.state_elems() * sizeof(float);
+  HIPCHK(launch_fill_table(D.tabW, static_cast<char*>(lambda_all) + (size_t)N * state, -(long)state, N + 1, st));
+  HIPCHK(launch_fill_table(D.tabZ, static_cast<char*>(const_cast<void*>(Z_all)), (long)state, N + 1, st));
+  HIPCHK(upload_pointers(D.tabTh, theta, N, st));
+  char* tblocks = static_cast<char*>(P.thT_blocks);
+  HIPCHK(launch_fill_table(D.tabThT, tblocks, (long)P.enc_block, n_enc, st));
+  HIPCHK(launch_fill_table(D.tabThT + n_enc, tblocks + (size_t)n_enc * P.enc_block, (long)P.dec_block, n_dec, st));
+  const Params TH = {(const void* const*)D.tabTh, 0, 1};
+  const Params THT = {(const void* const*)D.tabThT, 0, 1};
+  STCHK(transpose_blocks(P.Ee, n_enc, TH, THT));
+  STCHK(transpose_blocks(P.Ed, n_dec, shift(TH, n_enc), shift(THT, n_enc)));
+  // linearisation cache, batched over layers: encoder layers at the X rows of Z_n, decoder layers at
+  // the Y rows with the X rows of the same state as memory
+  const Rows Zrows = {(const void* const*)D.tabZ, 0, 1};
+  const Rows ZdecX = shift(Zrows, n_enc), ZdecY = Driver::part(ZdecX, D.x_elems);
+  STCHK(forward_groups(P.Ee, D.E2, n_enc, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
+  STCHK(forward_groups(P.Ed, D.Ed2, n_dec, ZdecY, NO_ROWS, NO_ROWS, shift(TH, n_enc), 0.f, true, Slots{0, 1}, ZdecX));
+  char* lamN_row = static_cast<char*>(lambda_all) + (size_t)N * state;
+  if (lambda_N != lamN_row) HIPCHK(hipMemcpyAsync(lamN_row, lambda_N, state, hipMemcpyDeviceToDevice, st));
+  if (!serial_run(opts) && opts->init_guess == 0) {
+    for (int k = 1; k <= N / opts->cf; ++k)
+      HIPCHK(hipMemcpyAsync(static_cast<char*>(lambda_all) + (size_t)(N - k * opts->cf) * state, lambda_N, state,
+                            hipMemcpyDeviceToDevice, st));
+  }
+  D.resnorm = resnorm;
+  STCHK(D.run(opts->iters));
+  if (dtheta) {
+    // layer n takes lambda_{n+1}: point N-1-n of the reversed grid
+    HIPCHK(upload_pointers(P.tabDT, (const void* const*)dtheta, N, st));
+    const Rows LamNext = {(const void* const*)D.tabW, N - 1, -1};
+    const Params DT = {(const void* const*)P.tabDT, 0, 1};
+    STCHK(gradient_groups(P.Ee, D.E2, n_enc, LamNext, TH, THT, Zrows, Slots{0, 1}, &DT, nullptr, opts->h));
+    const Params DTd = shift(DT, n_enc);
+    StackedDec sd = {ZdecX, NO_ROWS, NO_ROWS, NO_ROWS};
+    STCHK(gradient_groups(P.Ed, D.Ed2, n_dec, Driver::part(shift(LamNext, n_enc), D.x_elems), shift(TH, n_enc),
+                          shift(THT, n_enc), ZdecY, Slots{0, 1}, &DTd, nullptr, opts->h, &sd));
   }
   return MGRIT_OK;
 }

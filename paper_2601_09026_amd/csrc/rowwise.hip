@@ -325,6 +325,29 @@ hipError_t launch_sub_rows(int n_groups, long elems, Rows A, Rows B, Rows D, hip
   return hipGetLastError();
 }
 
+// D = A (+ B): the part of a stacked state that a step leaves alone, plus the right-hand side
+__global__ void __launch_bounds__(256) add_rows_kernel(long elems, Rows A, Rows B, Rows D) {
+  const int g = blockIdx.y;
+  const float* pa = A.at(g);
+  const float* pb = B.present() ? B.at(g) : nullptr;
+  float* pd = D.at(g);
+  for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (long)gridDim.x * 256 * 4) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(pa + i);
+    if (pb) v += *reinterpret_cast<const f32x4*>(pb + i);
+    *reinterpret_cast<f32x4*>(pd + i) = v;
+  }
+}
+
+hipError_t launch_add_rows(int n_groups, long elems, Rows A, Rows B, Rows D, hipStream_t st) {
+  if (n_groups <= 0 || elems <= 0) return hipSuccess;
+  long want = (elems / 4 + 255) / 256;
+  const unsigned bx = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+  ProfScope ps(PC_ELEMENTWISE, B.present() ? (double)n_groups * elems : 0.0,
+               (double)n_groups * elems * (B.present() ? 12 : 8), st);
+  hipLaunchKernelGGL(add_rows_kernel, dim3(bx, n_groups), dim3(256), 0, st, elems, A, B, D);
+  return hipGetLastError();
+}
+
 constexpr int RN_BLOCKS = 32;       // partial sums per group
 
 __global__ void __launch_bounds__(256) resnorm_partial_kernel(long elems, Rows A, Rows B, double* partial) {
