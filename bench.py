@@ -34,7 +34,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="bert_base",
-                    help="tiny_encoder | bert_base | gpt2_small | vit_small | mt_encoder | mt_decoder")
+                    help="tiny_encoder | bert_base | gpt2_small | vit_small | mt_encoder | mt_decoder | "
+                         "mc_deep_narrow | mt_stacked (encoder and decoder on one grid)")
     ap.add_argument("--no-adjoint", action="store_true", help="time mgrit_forward only")
     ap.add_argument("--max-groups", type=int, default=0, help="groups per kernel launch (0 = library default)")
     ap.add_argument("--lanes", type=int, default=0, help="1 = single stream, 2 = two lanes (0 = library default)")
@@ -92,7 +93,8 @@ def main():
     from paper_2601_09026_amd import binding as mb
     from paper_2601_09026_amd import workloads as wls
 
-    wl = wls.named_workloads()[args.workload]
+    sw = wls.stacked_workloads().get(args.workload)        # encoder + decoder on one grid, or None
+    wl = sw.dec.scaled(name=sw.name, N=sw.N) if sw else wls.named_workloads()[args.workload]
     adjoint = not args.no_adjoint
     torch.cuda.set_device(0)
     if args.max_groups:
@@ -103,13 +105,24 @@ def main():
         mb.lib().mgrit_debug_gemm_tile_config(args.gemm_tile)
     desc = mb.model_desc(wl)
     opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters, wl.relax)
-    T, d = wl.tokens, wl.d_model
+    # stacked grid: a state holds the encoder's and the decoder's tokens, an evaluation advances one
+    # of the two parts (equally many tokens in this workload), which is what the metric counts
+    T, d = (sw.tokens if sw else wl.tokens), wl.d_model
+    if sw:
+        assert sw.enc.tokens == sw.dec.tokens
+    T_eval = wl.tokens
 
     # inputs resident in HBM before anything is timed
-    theta = [mb.pack_theta(desc, wls.layer_params(wl, n)) for n in range(wl.N)]
-    Z0 = torch.from_numpy(wls.initial_state(wl)).cuda()
-    lamN = torch.from_numpy(wls.terminal_adjoint(wl)).cuda()
-    mem = wls.cross_memory(wl)
+    if sw:
+        desc_e = mb.encoder_desc(desc)
+        theta = [mb.pack_theta(desc_e if n < sw.n_enc else desc, wls.stacked_layer_params(sw, n)) for n in range(sw.N)]
+        Z0 = torch.from_numpy(wls.stacked_initial_state(sw)).cuda()
+        lamN = torch.from_numpy(wls.stacked_terminal_adjoint(sw)).cuda()
+    else:
+        theta = [mb.pack_theta(desc, wls.layer_params(wl, n)) for n in range(wl.N)]
+        Z0 = torch.from_numpy(wls.initial_state(wl)).cuda()
+        lamN = torch.from_numpy(wls.terminal_adjoint(wl)).cuda()
+    mem = None if sw else wls.cross_memory(wl)
     mem = None if mem is None else torch.from_numpy(mem).cuda()
     Z_all = torch.empty((wl.N + 1, T, d), dtype=torch.float32, device="cuda")
     lam_all = torch.empty_like(Z_all) if adjoint else None
@@ -117,19 +130,32 @@ def main():
     res_a = torch.zeros(max(wl.iters, 1), dtype=torch.float32, device="cuda")
     grads = None
     if args.param_grads:
-        if not adjoint or wl.arch == wls.ARCH_CROSS:
+        if not adjoint or (wl.arch == wls.ARCH_CROSS and not sw):
             print("bench.py: --param-grads needs the adjoint and an encoder or causal workload", file=sys.stderr)
             sys.exit(2)
-        gbytes = mb.grad_layout(desc).block_bytes
-        grads = [torch.empty(gbytes, dtype=torch.uint8, device="cuda") for _ in range(wl.N)]
-    ws_bytes = max(mb.mgrit_workspace_bytes(desc, opts, 0),
-                   mb.mgrit_workspace_bytes(desc, opts, 2 if grads else 1) if adjoint else 0, 256)
+        gbytes = [mb.grad_layout(desc_e if sw and n < sw.n_enc else desc).block_bytes for n in range(wl.N)]
+        grads = [torch.empty(b, dtype=torch.uint8, device="cuda") for b in gbytes]
+    if sw:
+        ws_bytes = max(mb.mgrit_stacked_workspace_bytes(desc, opts, sw.n_enc, 0),
+                       mb.mgrit_stacked_workspace_bytes(desc, opts, sw.n_enc, 2 if grads else 1) if adjoint else 0, 256)
+    else:
+        ws_bytes = max(mb.mgrit_workspace_bytes(desc, opts, 0),
+                       mb.mgrit_workspace_bytes(desc, opts, 2 if grads else 1) if adjoint else 0, 256)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     n_phi = mb.mgrit_step_evaluations(opts)
     n_psi = n_phi if adjoint else 0
     stream = torch.cuda.current_stream()
 
+    def step_stacked():
+        mb.mgrit_forward_stacked(desc, opts, sw.n_enc, Z0, theta, Z_all=Z_all, resnorm=res_f, workspace=ws,
+                                 stream=stream)
+        if adjoint:
+            mb.mgrit_adjoint_stacked(desc, opts, sw.n_enc, Z_all, theta, lamN, dtheta=grads, lambda_all=lam_all,
+                                     resnorm=res_a, workspace=ws, stream=stream)
+
     def step():
+        if sw:
+            return step_stacked()
         mb.mgrit_forward(desc, opts, Z0, theta, memory=mem, Z_all=Z_all, resnorm=res_f, workspace=ws,
                          stream=stream)
         if adjoint:
@@ -146,7 +172,7 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    value = (n_phi + n_psi) * T / (ms_per_step * 1e-3)
+    value = (n_phi + n_psi) * T_eval / (ms_per_step * 1e-3)
 
     # second pass over the same K steps with a HIP event pair around every kernel launch (recorded
     # by the library on the launch stream).  Recording ~2500 event pairs per step costs several
@@ -242,13 +268,24 @@ def main():
                    "iters": wl.iters, "relax": "FCF" if wl.relax else "F", "adjoint": adjoint,
                    "phi_evaluations": n_phi, "psi_evaluations": n_psi,
                    "max_groups_per_launch": args.max_groups or "default", "lanes": args.lanes or 2,
-                   "param_grads": bool(grads)},
+                   "param_grads": bool(grads),
+                   **({"stacked": True, "n_enc": sw.n_enc, "src_seq": sw.enc.seq} if sw else {})},
         "residual_norms": {"forward": [float(x) for x in res_f.cpu()[:wl.iters]],
                            "adjoint": [float(x) for x in res_a.cpu()[:wl.iters]] if adjoint else None},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, n_phi, n_psi, args.cpu_seconds)
+        if sw:
+            # about half of the evaluations are encoder steps, half decoder steps (n_enc = N / 2)
+            ce = cpu_baseline(sw.enc, n_phi // 2, n_psi // 2, args.cpu_seconds / 2)
+            cd = cpu_baseline(sw.dec, n_phi - n_phi // 2, n_psi - n_psi // 2, args.cpu_seconds / 2)
+            work_e = (n_phi // 2 + n_psi // 2) * sw.enc.tokens
+            work_d = (n_phi + n_psi) * T_eval - work_e
+            cd["value"] = (work_e + work_d) / (work_e / ce["value"] + work_d / cd["value"])
+            cd["sample"] = "encoder half: " + ce["sample"] + "; decoder half: " + cd["sample"]
+            out["cpu_baseline"] = cd
+        else:
+            out["cpu_baseline"] = cpu_baseline(wl, n_phi, n_psi, args.cpu_seconds)
         out["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
     print(json.dumps(out))
 

@@ -424,19 +424,25 @@ def mgrit_stacked_workspace_bytes(desc: ModelDesc, opts: Opts, n_enc: int, adjoi
 
 
 def mgrit_forward_stacked(desc: ModelDesc, opts: Opts, n_enc: int, Z0: torch.Tensor, theta: List[torch.Tensor],
-                          stream: Optional[torch.cuda.Stream] = None):
+                          Z_all: Optional[torch.Tensor] = None, resnorm: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
     """One MGRIT grid over n_enc encoder layers followed by decoder layers; state rows = encoder
-    tokens then decoder tokens.  Returns (Z_all, resnorm)."""
+    tokens then decoder tokens.  Returns (Z_all, resnorm).  Buffers are allocated here if not given."""
     T, d = desc.batch * (desc.mem_seq + desc.seq), desc.d_model
     _check_state(Z0, (T, d), "Z0")
     if len(theta) != opts.N:
         raise ValueError("theta must hold N blocks")
-    Z_all = torch.empty((opts.N + 1, T, d), dtype=torch.float32, device=Z0.device)
-    resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z0.device)
-    ws = torch.empty(max(mgrit_stacked_workspace_bytes(desc, opts, n_enc, 0), 256), dtype=torch.uint8,
-                     device=Z0.device)
+    if Z_all is None:
+        Z_all = torch.empty((opts.N + 1, T, d), dtype=torch.float32, device=Z0.device)
+    _check_state(Z_all, (opts.N + 1, T, d), "Z_all")
+    if resnorm is None:
+        resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z0.device)
+    if workspace is None:
+        workspace = torch.empty(max(mgrit_stacked_workspace_bytes(desc, opts, n_enc, 0), 256), dtype=torch.uint8,
+                                device=Z0.device)
     st = lib().mgrit_forward_stacked(C.byref(desc), C.byref(opts), int(n_enc), _ptr(Z0), _ptr_array(theta),
-                                     _ptr(Z_all), _ptr(resnorm), _ptr(ws), ws.numel(), _stream_handle(stream))
+                                     _ptr(Z_all), _ptr(resnorm), _ptr(workspace), workspace.numel(),
+                                     _stream_handle(stream))
     if st != MGRIT_OK:
         raise MgritError(st, "mgrit_forward_stacked")
     return Z_all, resnorm
@@ -444,7 +450,8 @@ def mgrit_forward_stacked(desc: ModelDesc, opts: Opts, n_enc: int, Z0: torch.Ten
 
 def mgrit_adjoint_stacked(desc: ModelDesc, opts: Opts, n_enc: int, Z_all: torch.Tensor, theta: List[torch.Tensor],
                           lambda_N: torch.Tensor, dtheta: Optional[List[torch.Tensor]] = None,
-                          stream: Optional[torch.cuda.Stream] = None):
+                          lambda_all: Optional[torch.Tensor] = None, resnorm: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
     """Returns (lambda_all, resnorm) of the stacked grid; dtheta as in mgrit_adjoint (encoder
     layers' blocks in the encoder's fp32 layout, decoder layers' in the decoder's)."""
     T, d = desc.batch * (desc.mem_seq + desc.seq), desc.d_model
@@ -452,13 +459,17 @@ def mgrit_adjoint_stacked(desc: ModelDesc, opts: Opts, n_enc: int, Z_all: torch.
     _check_state(lambda_N, (T, d), "lambda_N")
     if len(theta) != opts.N or (dtheta is not None and len(dtheta) != opts.N):
         raise ValueError("theta / dtheta must hold N blocks")
-    lambda_all = torch.empty_like(Z_all)
-    resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z_all.device)
-    need = mgrit_stacked_workspace_bytes(desc, opts, n_enc, 2 if dtheta is not None else 1)
-    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=Z_all.device)
+    if lambda_all is None:
+        lambda_all = torch.empty_like(Z_all)
+    _check_state(lambda_all, (opts.N + 1, T, d), "lambda_all")
+    if resnorm is None:
+        resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z_all.device)
+    if workspace is None:
+        need = mgrit_stacked_workspace_bytes(desc, opts, n_enc, 2 if dtheta is not None else 1)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Z_all.device)
     st = lib().mgrit_adjoint_stacked(C.byref(desc), C.byref(opts), int(n_enc), _ptr(Z_all), _ptr_array(theta),
-                                     _ptr(lambda_N), _ptr(lambda_all), _ptr_array(dtheta), _ptr(resnorm), _ptr(ws),
-                                     ws.numel(), _stream_handle(stream))
+                                     _ptr(lambda_N), _ptr(lambda_all), _ptr_array(dtheta), _ptr(resnorm),
+                                     _ptr(workspace), workspace.numel(), _stream_handle(stream))
     if st != MGRIT_OK:
         raise MgritError(st, "mgrit_adjoint_stacked")
     return lambda_all, resnorm

@@ -131,6 +131,32 @@ def test_buffered_workspace_and_argument_checks():
                                     0, None) == -1
 
 
+def test_stacked_grid_workspace_and_argument_checks():
+    """The stacked encoder-decoder entry points take the decoder's description: any other block type,
+    a switch layer outside 1..N-1 or a missing buffer is refused before the device is touched."""
+    dec = mb.model_desc(wls.named_workloads()["mt_decoder"])
+    enc = mb.model_desc(wls.named_workloads()["mt_encoder"])
+    opts = mb.mgrit_opts(64, 1 / 64, 4, 2, 2)
+    fwd = mb.mgrit_stacked_workspace_bytes(dec, opts, 32, 0)
+    adj = mb.mgrit_stacked_workspace_bytes(dec, opts, 32, 1)
+    grad = mb.mgrit_stacked_workspace_bytes(dec, opts, 32, 2)
+    assert 0 < fwd < adj < grad
+    # both halves' work buffers are in it
+    assert fwd > mb.mgrit_workspace_bytes(dec, opts, 0)
+    for bad_n_enc in (0, 64, -3, 65):
+        assert mb.mgrit_stacked_workspace_bytes(dec, opts, bad_n_enc, 0) == 0
+    assert mb.mgrit_stacked_workspace_bytes(enc, opts, 32, 0) == 0
+    assert mb.mgrit_stacked_workspace_bytes(dec, opts, 32, 3) == 0
+    e = mb.encoder_desc(dec)
+    assert (e.arch, e.seq, e.mem_seq, e.d_model) == (0, dec.mem_seq, 0, dec.d_model)
+    L = mb.lib()
+    assert L.mgrit_forward_stacked(C.byref(enc), C.byref(opts), 32, None, None, None, None, None, 0, None) == -1
+    assert L.mgrit_forward_stacked(C.byref(dec), C.byref(opts), 0, None, None, None, None, None, 0, None) == -1
+    assert L.mgrit_forward_stacked(C.byref(dec), C.byref(opts), 32, None, None, None, None, None, 0, None) == -1
+    assert L.mgrit_adjoint_stacked(C.byref(dec), C.byref(opts), 32, None, None, None, None, None, None, None, 0,
+                                   None) == -1
+
+
 def test_workspace_grows_with_groups_and_levels():
     desc = mb.model_desc(wls.named_workloads()["bert_base"])
     a = mb.mgrit_layer_step_workspace_bytes(desc, False, 1)

@@ -128,3 +128,52 @@ def test_mt_shape_reduced_bf16():
     sw = wls.stacked_workloads()["mt_stacked"]
     sw = wls.StackedWorkload("mt_small", sw.enc.scaled(batch=4, N=8, h=1.0 / 16), sw.dec.scaled(batch=4, N=8, h=1.0 / 16))
     run_case(sw, weight_std=0.02, grads=True)
+
+
+def test_full_size_mt_stacked_sampled_sentence_pairs():
+    """The translation configuration on one grid at its full size (64 sentence pairs, 32 + 32 layers), in
+    the launch configuration bench.py times.  Sentence pairs are independent through the whole method, so
+    the oracle recomputes sampled pairs alone (the complete MGRIT iteration, forward and adjoint) and every
+    state of those pairs is compared.  The residual norms couple the batch: no oracle value is stored for
+    them at this size (parity unpinned for the norm itself; it must decrease)."""
+    from gpu_util import increment_tolerance
+    sw = wls.stacked_workloads()["mt_stacked"]
+    e, d = sw.enc, sw.dec
+    print(f"[case] full size mt_stacked: B={d.batch} Sx={e.seq} Sy={d.seq} d={d.d_model} N={sw.N} cf={d.cf} "
+          f"L={d.levels} it={d.iters}", flush=True)
+    desc_d = mb.model_desc(d)
+    desc_e = mb.encoder_desc(desc_d)
+    host = [wls.stacked_layer_params(sw, n) for n in range(sw.N)]
+    blocks = [mb.pack_theta(desc_e if n < sw.n_enc else desc_d, host[n]) for n in range(sw.N)]
+    tol = TOL[d.dtype]
+    opts = mb.mgrit_opts(sw.N, d.h, d.cf, d.levels, d.iters, d.relax)
+    Z0 = wls.stacked_initial_state(sw)
+    lamN = wls.stacked_terminal_adjoint(sw)
+    Zg, rg = mb.mgrit_forward_stacked(desc_d, opts, sw.n_enc, dev(Z0), blocks)
+    lg, ag = mb.mgrit_adjoint_stacked(desc_d, opts, sw.n_enc, Zg, blocks, dev(lamN))
+    torch.cuda.synchronize()
+    she = tode.Shape(e.arch, e.d_model, e.n_heads, 1, e.seq, 0, e.ln_eps)
+    shd = tode.Shape(d.arch, d.d_model, d.n_heads, 1, d.seq, d.mem_seq, d.ln_eps)
+    tx = e.tokens
+    for b in (7, 62):
+        rows = np.concatenate([np.arange(b * e.seq, (b + 1) * e.seq), tx + np.arange(b * d.seq, (b + 1) * d.seq)])
+        Zr, _, _ = omgrit.stacked_mgrit_forward(Z0[rows], host, sw.n_enc, d.h, d.cf, d.levels, d.iters, she, shd)
+        got = Zg[:, rows, :].cpu().numpy().astype(np.float64)
+        lr, _, _ = omgrit.stacked_mgrit_adjoint(lamN[rows], list(got), host, sw.n_enc, d.h, d.cf, d.levels, d.iters,
+                                                she, shd)
+        lgot = lg[:, rows, :].cpu().numpy().astype(np.float64)
+        for what, g, r, base_row, far in (("Z", got, Zr, 0, sw.N), ("lambda", lgot, lr, sw.N, 0)):
+            for n in range(sw.N + 1):
+                err = relerr(g[n], r[n])
+                assert err <= tol, f"{what}(pair {b})[{n}]: value error {err:.3e} > {tol}"
+            # increments over the start value, for the encoder rows and the decoder rows separately
+            for part, sl in (("X", slice(0, e.seq)), ("Y", slice(e.seq, None))):
+                for n in (far, sw.n_enc):
+                    base = r[base_row][sl]
+                    if np.linalg.norm(r[n][sl] - base) > 0:
+                        err = relerr(g[n][sl] - base, r[n][sl] - base)
+                        bar = increment_tolerance(tol, r[n][sl], base, abs(n - base_row))
+                        print(f"  {what}_{part}(pair {b})[{n}] increment err {err:.2e} (bar {bar:.2e})")
+                        assert err <= bar, f"{what}_{part}(pair {b})[{n}]: increment error {err:.3e} > {bar:.3e}"
+    for norms in (rg.cpu().numpy(), ag.cpu().numpy()):
+        assert np.isfinite(norms).all() and all(norms[i + 1] < norms[i] for i in range(d.iters - 1)), norms
