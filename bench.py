@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--param-grads", action="store_true",
                     help="also produce the parameter gradients in every step (not part of the headline metric: "
                          "the line then says so in `metric` and in config.param_grads)")
+    ap.add_argument("--attn-wide", type=int, default=-1,
+                    help="tuning: mask of d_head=128 attention kernels with 256-row blocks (1 fwd, 2 dQ, 4 dK/dV)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not record per-kernel HIP events in the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -101,6 +103,8 @@ def main():
         mb.mgrit_set_max_groups_per_launch(args.max_groups)
     if args.lanes:
         mb.mgrit_set_lanes(args.lanes)
+    if args.attn_wide >= 0:
+        mb.lib().mgrit_debug_attention_wide_blocks(args.attn_wide)
     if args.gemm_tile:
         mb.lib().mgrit_debug_gemm_tile_config(args.gemm_tile)
     desc = mb.model_desc(wl)

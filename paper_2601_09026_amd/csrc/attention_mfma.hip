@@ -140,11 +140,11 @@ __device__ __forceinline__ void store_rows_T(bf16* dst, long row_stride, int row
 // forward
 // ---------------------------------------------------------------------------
 // Resident blocks per CU the register budget is set for: the accumulators grow with DH.
-template <int DH> constexpr int fa_fwd_blocks() { return DH == 64 ? 4 : 2; }
-template <int DH> constexpr int fa_bwd_blocks() { return DH == 64 ? 3 : 2; }
+template <int DH, int NW = 4> constexpr int fa_fwd_blocks() { return NW == 8 ? 1 : DH == 64 ? 4 : 2; }
+template <int DH, int NW = 4> constexpr int fa_bwd_blocks() { return NW == 8 ? 1 : DH == 64 ? 3 : 2; }
 
 template <int NW, int DH>
-__global__ void __launch_bounds__(NW * 64, fa_fwd_blocks<DH>()) attn_fwd_mfma_kernel(const AttnArgs a) {
+__global__ void __launch_bounds__(NW * 64, (fa_fwd_blocks<DH, NW>())) attn_fwd_mfma_kernel(const AttnArgs a) {
   constexpr int KS = DH / 16, DT = DH / 32;
   __shared__ __attribute__((aligned(16))) bf16 Ks[64 * fa_ld<DH>()];    // [key][d]
   __shared__ __attribute__((aligned(16))) bf16 Vt[DH * FA_LDT];          // [d][key]
@@ -302,7 +302,7 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, f
 }
 
 template <int NW, int DH>
-__global__ void __launch_bounds__(NW * 64, fa_bwd_blocks<DH>()) attn_bwd_dq_mfma_kernel(const AttnArgs a) {
+__global__ void __launch_bounds__(NW * 64, (fa_bwd_blocks<DH, NW>())) attn_bwd_dq_mfma_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) bf16 lds[bwd_dq_lds<DH>()];
   attn_bwd_dq_body<NW, DH>(a, lds, nullptr);
 }
@@ -387,7 +387,7 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
 }
 
 template <int NW, int DH>
-__global__ void __launch_bounds__(NW * 64, fa_bwd_blocks<DH>()) attn_bwd_dkv_mfma_kernel(const AttnArgs a) {
+__global__ void __launch_bounds__(NW * 64, (fa_bwd_blocks<DH, NW>())) attn_bwd_dkv_mfma_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) bf16 lds[bwd_dkv_lds<DH>()];
   __shared__ float Ls[64], Ds[64];
   attn_bwd_dkv_body<NW, DH>(a, lds, Ls, Ds, nullptr);
@@ -396,7 +396,7 @@ __global__ void __launch_bounds__(NW * 64, fa_bwd_blocks<DH>()) attn_bwd_dkv_mfm
 // Sequences that fit one block (Sq, Sk <= 32 NW): both passes in one launch.  The head's Q, K, V,
 // dO are then read from HBM once (pass 2 finds them in L2) and D never leaves the CU.
 template <int NW, int DH>
-__global__ void __launch_bounds__(NW * 64, fa_bwd_blocks<DH>()) attn_bwd_fused_mfma_kernel(const AttnArgs a) {
+__global__ void __launch_bounds__(NW * 64, (fa_bwd_blocks<DH, NW>())) attn_bwd_fused_mfma_kernel(const AttnArgs a) {
   constexpr int LDS = bwd_dq_lds<DH>() > bwd_dkv_lds<DH>() ? bwd_dq_lds<DH>() : bwd_dkv_lds<DH>();
   __shared__ __attribute__((aligned(16))) bf16 lds[LDS];
   __shared__ float Ls[64], Ds[64], Dall[NW * 32];
@@ -413,11 +413,20 @@ bool attn_mfma_supported(const AttnArgs& a) {
          (a.v_row_stride % 8 == 0) && (a.o_row_stride % 8 == 0);
 }
 
+// Long sequences: blocks of 256 rows halve the K/V (Q/dO) bytes staged from L2 per flop, which is
+// what bounds these kernels once a head no longer fits a block or two.
+constexpr int FA_LONG = 1024;
+int g_attn_wide = 5;            // bit 0: forward, bit 1: dQ pass (measured: no gain), bit 2: dK/dV pass
+void attn_set_wide_blocks(int mask) { g_attn_wide = mask & 7; }
+
 template <int DH>
 static hipError_t attn_fwd_mfma_dh(const AttnArgs& a, hipStream_t st) {
   if (a.Sq <= 64) {
     dim3 grid((a.Sq + 63) / 64, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_fwd_mfma_kernel<2, DH>), grid, dim3(128), 0, st, a);
+  } else if (DH == 128 && a.Sq >= FA_LONG && (g_attn_wide & 1)) {
+    dim3 grid((a.Sq + 255) / 256, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<8, DH>), grid, dim3(512), 0, st, a);
   } else {
     dim3 grid((a.Sq + 127) / 128, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_fwd_mfma_kernel<4, DH>), grid, dim3(256), 0, st, a);
@@ -440,6 +449,9 @@ static hipError_t attn_bwd_mfma_dh(const AttnArgs& a, hipStream_t st) {
   if (a.Sq <= 64) {
     dim3 grid((a.Sq + 63) / 64, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<2, DH>), grid, dim3(128), 0, st, a);
+  } else if (DH == 128 && a.Sq >= FA_LONG && (g_attn_wide & 2)) {
+    dim3 grid((a.Sq + 255) / 256, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<8, DH>), grid, dim3(512), 0, st, a);
   } else {
     dim3 grid((a.Sq + 127) / 128, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<4, DH>), grid, dim3(256), 0, st, a);
@@ -448,6 +460,9 @@ static hipError_t attn_bwd_mfma_dh(const AttnArgs& a, hipStream_t st) {
   if (a.Sk <= 64) {
     dim3 grid((a.Sk + 63) / 64, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<2, DH>), grid, dim3(128), 0, st, a);
+  } else if (DH == 128 && a.Sk >= FA_LONG && (g_attn_wide & 4)) {
+    dim3 grid((a.Sk + 255) / 256, a.B * a.H, a.n_groups);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<8, DH>), grid, dim3(512), 0, st, a);
   } else {
     dim3 grid((a.Sk + 127) / 128, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<4, DH>), grid, dim3(256), 0, st, a);

@@ -1458,5 +1458,6 @@ void mgrit_debug_force_simple_kernels(int gemm, int attn) {
 }
 
 void mgrit_debug_gemm_tile_config(int cfg) { gemm_set_tile_config(cfg); }
+void mgrit_debug_attention_wide_blocks(int mask) { attn_set_wide_blocks(mask); }
 
 }  // extern "C"

@@ -25,13 +25,23 @@ __device__ __forceinline__ f32x4 load_sum(const float* x, const float* xa, int c
 __device__ __forceinline__ float sum4(f32x4 v) { return (v[0] + v[1]) + (v[2] + v[3]); }
 __device__ __forceinline__ float dot4(f32x4 a, f32x4 b) { return (a[0] * b[0] + a[1] * b[1]) + (a[2] * b[2] + a[3] * b[3]); }
 
-template <typename TO, int NV>
+// sum over the LPR consecutive lanes that share a row
+template <int LPR> __device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// LPR lanes per row: 64 (one row per wavefront, NV vectors of 4 per lane), or 32 / 16 for rows of at
+// most 128 / 64 elements (NV = 1), where a wavefront works on 2 / 4 rows at once.
+template <typename TO, int NV, int LPR>
 __global__ void __launch_bounds__(256) ln_fwd_kernel(const LnFwdArgs a) {
-  const int lane = threadIdx.x & 63;
+  constexpr int RPW = 64 / LPR;
+  const int lane = threadIdx.x & (LPR - 1);
   const int total = a.n_groups * a.T;
-  const int nwaves = gridDim.x * 4;
+  const int nwaves = gridDim.x * 4 * RPW;
   const int d = a.d;
-  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int row = (blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + ((threadIdx.x & 63) / LPR);
   if (row >= total) return;
 
   auto src = [&](int r, const float*& x, const float*& xa, int& g, int& t) {
@@ -44,7 +54,7 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const LnFwdArgs a) {
     src(r, x, xa, g, t);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int c = (i * 64 + lane) * 4;
+      const int c = (i * LPR + lane) * 4;
       if (c < d) v[i] = load_sum(x, xa, c);
     }
   };
@@ -58,13 +68,13 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const LnFwdArgs a) {
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i)
-      if ((i * 64 + lane) * 4 < d) s += sum4(cur[i]);
-    const float mu = wave_sum(s) / d;
+      if ((i * LPR + lane) * 4 < d) s += sum4(cur[i]);
+    const float mu = group_sum<LPR>(s) / d;
     float q = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i)
-      if ((i * 64 + lane) * 4 < d) { cur[i] = cur[i] - mu; q += dot4(cur[i], cur[i]); }
-    const float rstd = 1.0f / sqrtf(wave_sum(q) / d + a.eps);
+      if ((i * LPR + lane) * 4 < d) { cur[i] = cur[i] - mu; q += dot4(cur[i], cur[i]); }
+    const float rstd = 1.0f / sqrtf(group_sum<LPR>(q) / d + a.eps);
     const char* pb = a.P.at(g);
     const float* gamma = reinterpret_cast<const float*>(pb + a.gamma_off);
     const float* beta = reinterpret_cast<const float*>(pb + a.beta_off);
@@ -73,7 +83,7 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const LnFwdArgs a) {
     if (xh && lane == 0) a.rstd[a.xhat_slots.of(g) * a.T + t] = rstd;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int c = (i * 64 + lane) * 4;
+      const int c = (i * LPR + lane) * 4;
       if (c < d) {
         const f32x4 xn = cur[i] * rstd;
         if (xh) store4<TO>(xh + c, xn);
@@ -91,27 +101,32 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const LnFwdArgs a) {
   }
 }
 
-static unsigned ln_grid(long rows) {
-  long want = (rows + 3) / 4;
+static int ln_lanes_per_row(int d) { return d <= 64 ? 16 : d <= 128 ? 32 : 64; }
+
+static unsigned ln_grid(long rows, int d) {
+  const long per_block = 4 * (64 / ln_lanes_per_row(d));
+  long want = (rows + per_block - 1) / per_block;
   const long cap = 256L * LN_BLOCKS_PER_CU;
   return (unsigned)(want < cap ? want : cap);
 }
 
 template <typename TO>
 static void ln_fwd_dispatch(const LnFwdArgs& a, unsigned blocks, hipStream_t st) {
-  const int nv = (a.d + 255) / 256;
-  if (nv <= 1) hipLaunchKernelGGL((ln_fwd_kernel<TO, 1>), dim3(blocks), dim3(256), 0, st, a);
-  else if (nv == 2) hipLaunchKernelGGL((ln_fwd_kernel<TO, 2>), dim3(blocks), dim3(256), 0, st, a);
-  else if (nv == 3) hipLaunchKernelGGL((ln_fwd_kernel<TO, 3>), dim3(blocks), dim3(256), 0, st, a);
-  else if (nv == 4) hipLaunchKernelGGL((ln_fwd_kernel<TO, 4>), dim3(blocks), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((ln_fwd_kernel<TO, 8>), dim3(blocks), dim3(256), 0, st, a);
+  const int nv = (a.d + 255) / 256, lpr = ln_lanes_per_row(a.d);
+  if (lpr == 16) hipLaunchKernelGGL((ln_fwd_kernel<TO, 1, 16>), dim3(blocks), dim3(256), 0, st, a);
+  else if (lpr == 32) hipLaunchKernelGGL((ln_fwd_kernel<TO, 1, 32>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv <= 1) hipLaunchKernelGGL((ln_fwd_kernel<TO, 1, 64>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 2) hipLaunchKernelGGL((ln_fwd_kernel<TO, 2, 64>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 3) hipLaunchKernelGGL((ln_fwd_kernel<TO, 3, 64>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 4) hipLaunchKernelGGL((ln_fwd_kernel<TO, 4, 64>), dim3(blocks), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((ln_fwd_kernel<TO, 8, 64>), dim3(blocks), dim3(256), 0, st, a);
 }
 
 hipError_t launch_ln_fwd(const LnFwdArgs& a, bool is_bf16, hipStream_t st) {
   const long rows = (long)a.n_groups * a.T;
   if (rows <= 0) return hipSuccess;
   if (rows > 0x7fffffffL || a.d > 256 * LN_MAXV) return hipErrorInvalidValue;
-  const unsigned blocks = ln_grid(rows);
+  const unsigned blocks = ln_grid(rows, a.d);
   const double esz = is_bf16 ? 2 : 4;
   ProfScope ps(PC_LN_FWD, 8.0 * rows * a.d,
                (double)rows * a.d * ((a.X.present() ? 4 : 0) + (a.xp ? 4 : 0) + esz), st);
@@ -126,13 +141,14 @@ hipError_t launch_ln_fwd(const LnFwdArgs& a, bool is_bf16, hipStream_t st) {
 //   vjp  = rstd*(dxhat - mean(dxhat) - xhat*mean(dxhat*xhat))
 //   v = add + vjp;  out_f32 = v;  out_op = c + v;  OUT = c + hstep*v + RHS
 // ---------------------------------------------------------------------------
-template <typename TO, int NV, bool XH>
+template <typename TO, int NV, bool XH, int LPR>
 __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
-  const int lane = threadIdx.x & 63;
+  constexpr int RPW = 64 / LPR;                      // rows per wavefront, as in ln_fwd_kernel
+  const int lane = threadIdx.x & (LPR - 1);
   const int total = a.n_groups * a.T;
-  const int nwaves = gridDim.x * 4;
+  const int nwaves = gridDim.x * 4 * RPW;
   const int d = a.d;
-  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int row = (blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + ((threadIdx.x & 63) / LPR);
   if (row >= total) return;
 
   // XH: the row arrives normalised (cached xhat, rs = its rstd); otherwise as X (+ addend)
@@ -145,7 +161,7 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
       rs = a.rstd[a.xhat_slots.of(g) * a.T + t];
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
-        const int c = (i * 64 + lane) * 4;
+        const int c = (i * LPR + lane) * 4;
         if (c < d) { v[i] = load4<TO>(xh + c); w[i] = load4<TO>(dy + c); }
       }
     } else {
@@ -153,7 +169,7 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
       const float* xa = a.xp ? a.xp + a.xp_slots.of(g) * a.xp_slot_stride + ro : nullptr;
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
-        const int c = (i * 64 + lane) * 4;
+        const int c = (i * LPR + lane) * 4;
         if (c < d) { v[i] = load_sum(x, xa, c); w[i] = load4<TO>(dy + c); }
       }
     }
@@ -173,18 +189,18 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
       float s = 0.f;
 #pragma unroll
       for (int i = 0; i < NV; ++i)
-        if ((i * 64 + lane) * 4 < d) s += sum4(v[i]);
-      const float mu = wave_sum(s) / d;
+        if ((i * LPR + lane) * 4 < d) s += sum4(v[i]);
+      const float mu = group_sum<LPR>(s) / d;
       float q = 0.f;
 #pragma unroll
       for (int i = 0; i < NV; ++i)
-        if ((i * 64 + lane) * 4 < d) { v[i] = v[i] - mu; q += dot4(v[i], v[i]); }
-      rstd = 1.0f / sqrtf(wave_sum(q) / d + a.eps);
+        if ((i * LPR + lane) * 4 < d) { v[i] = v[i] - mu; q += dot4(v[i], v[i]); }
+      rstd = 1.0f / sqrtf(group_sum<LPR>(q) / d + a.eps);
     }
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int c = (i * 64 + lane) * 4;
+      const int c = (i * LPR + lane) * 4;
       if (c < d) {
         if constexpr (!XH) v[i] = v[i] * rstd;                           // xhat
         w[i] = w[i] * *reinterpret_cast<const f32x4*>(gamma + c);        // dxhat
@@ -192,7 +208,7 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
         s2 += dot4(w[i], v[i]);
       }
     }
-    const float m1 = wave_sum(s1) / d, m2 = wave_sum(s2) / d;
+    const float m1 = group_sum<LPR>(s1) / d, m2 = group_sum<LPR>(s2) / d;
     const float* add = a.add ? a.add + a.add_slots.of(g) * a.add_slot_stride + ro : nullptr;
     float* of = a.out_f32 ? a.out_f32 + a.of_slots.of(g) * a.of_slot_stride + ro : nullptr;
     TO* oo = a.out_op ? reinterpret_cast<TO*>(a.out_op) + a.oo_slots.of(g) * a.oo_slot_stride + ro : nullptr;
@@ -203,7 +219,7 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
     const float* RHS = a.RHS.present() ? a.RHS.at(g) + ro : nullptr;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int c = (i * 64 + lane) * 4;
+      const int c = (i * LPR + lane) * 4;
       if (c < d) {
         f32x4 r = rstd * (w[i] - m1 - v[i] * m2);
         if (add) r += *reinterpret_cast<const f32x4*>(add + c);
@@ -234,19 +250,21 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
 
 template <typename TO, bool XH>
 static void ln_bwd_dispatch(const LnBwdArgs& a, unsigned blocks, hipStream_t st) {
-  const int nv = (a.d + 255) / 256;
-  if (nv <= 1) hipLaunchKernelGGL((ln_bwd_kernel<TO, 1, XH>), dim3(blocks), dim3(256), 0, st, a);
-  else if (nv == 2) hipLaunchKernelGGL((ln_bwd_kernel<TO, 2, XH>), dim3(blocks), dim3(256), 0, st, a);
-  else if (nv == 3) hipLaunchKernelGGL((ln_bwd_kernel<TO, 3, XH>), dim3(blocks), dim3(256), 0, st, a);
-  else if (nv == 4) hipLaunchKernelGGL((ln_bwd_kernel<TO, 4, XH>), dim3(blocks), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((ln_bwd_kernel<TO, 8, XH>), dim3(blocks), dim3(256), 0, st, a);
+  const int nv = (a.d + 255) / 256, lpr = ln_lanes_per_row(a.d);
+  if (lpr == 16) hipLaunchKernelGGL((ln_bwd_kernel<TO, 1, XH, 16>), dim3(blocks), dim3(256), 0, st, a);
+  else if (lpr == 32) hipLaunchKernelGGL((ln_bwd_kernel<TO, 1, XH, 32>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv <= 1) hipLaunchKernelGGL((ln_bwd_kernel<TO, 1, XH, 64>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 2) hipLaunchKernelGGL((ln_bwd_kernel<TO, 2, XH, 64>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 3) hipLaunchKernelGGL((ln_bwd_kernel<TO, 3, XH, 64>), dim3(blocks), dim3(256), 0, st, a);
+  else if (nv == 4) hipLaunchKernelGGL((ln_bwd_kernel<TO, 4, XH, 64>), dim3(blocks), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((ln_bwd_kernel<TO, 8, XH, 64>), dim3(blocks), dim3(256), 0, st, a);
 }
 
 hipError_t launch_ln_bwd(const LnBwdArgs& a, bool is_bf16, hipStream_t st) {
   const long rows = (long)a.n_groups * a.T;
   if (rows <= 0) return hipSuccess;
   if (rows > 0x7fffffffL || a.d > 256 * LN_MAXV) return hipErrorInvalidValue;
-  const unsigned blocks = ln_grid(rows);
+  const unsigned blocks = ln_grid(rows, a.d);
   const double esz = is_bf16 ? 2 : 4;
   const bool xh = a.xhat != nullptr;
   if (xh && !a.rstd) return hipErrorInvalidValue;

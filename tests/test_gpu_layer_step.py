@@ -91,6 +91,22 @@ def test_head_dimension_128_bf16(arch, S):
     run_adjoint_case(wl, G=2, hstep=0.5, with_rhs=True, weight_std=0.05, force_simple=0)
 
 
+@pytest.mark.parametrize("arch", [wls.ARCH_ENCODER, wls.ARCH_CAUSAL])
+def test_long_sequence_head_dimension_128_wide_blocks_bf16(arch):
+    """S = 1100 with one head of 128: the 256-row attention blocks (five blocks, the last one ragged; 18
+    key tiles, the last one ragged), forward and adjoint, against the 128-row blocks as well."""
+    wl = make(arch, wls.DTYPE_BF16, d=128, H=1, f=128, B=1, S=1100)
+    run_forward_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.05, force_simple=0)
+    run_adjoint_case(wl, G=2, hstep=0.5, with_rhs=True, weight_std=0.05, force_simple=0)
+    try:
+        for mask in (0, 7):        # 128-row blocks everywhere; 256-row blocks in all three kernels
+            mb.lib().mgrit_debug_attention_wide_blocks(mask)
+            run_forward_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.05, force_simple=0)
+            run_adjoint_case(wl, G=2, hstep=0.5, with_rhs=True, weight_std=0.05, force_simple=0)
+    finally:
+        mb.lib().mgrit_debug_attention_wide_blocks(5)
+
+
 def test_forward_step_tiny_config_shape_fp32():
     """d=64, 4 heads of 16, f=256, S=32: the shape of the smallest benchmark configuration."""
     wl = wls.named_workloads()["tiny_encoder"]
