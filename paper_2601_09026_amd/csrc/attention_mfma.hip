@@ -167,7 +167,7 @@ __global__ void __launch_bounds__(NW * 64, (fa_fwd_blocks<DH, NW>())) attn_fwd_m
   for (int dt = 0; dt < DT; ++dt) o[dt] = zero16();
   const int q_blk_last = min(q0 + NW * 32, a.Sq) - 1;
   const int k_end = a.causal ? min(a.Sk, q_blk_last + 1) : a.Sk;
-  const int q_wave_last = q0 + wave * 32 + 31;
+  const int q_wave_first = q0 + wave * 32, q_wave_last = q_wave_first + 31;
   for (int k0 = 0; k0 < k_end; k0 += 64) {
     __syncthreads();
     stage64<NW * 64, DH, true, false>(Ks, nullptr, P.K, a.k_row_stride, k0, a.Sk);
@@ -179,19 +179,26 @@ __global__ void __launch_bounds__(NW * 64, (fa_fwd_blocks<DH, NW>())) attn_fwd_m
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) s[kt] = MFMA(frag_plain<DH>(Ks, 32 * kt + lr, ks, lh), qf[ks], s[kt]);
-    float mloc = -INFINITY;
+    // a tile whose 64 keys all exist and precede every query of the wavefront needs no mask
+    // (wave-uniform test); masked scores become -inf, whose exp2 is 0
+    const bool full = k0 + 64 <= a.Sk && (!a.causal || k0 + 63 <= q_wave_first);
+    if (!full) {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = k0 + 32 * kt + 8 * (i >> 2) + 4 * lh + (i & 3);
+          const bool valid = key < a.Sk && (!a.causal || key <= qi);
+          s[kt][i] = valid ? s[kt][i] : -INFINITY;
+        }
+    }
+    float mloc = -INFINITY;                                // of the raw scores; the scale c is positive
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = k0 + 32 * kt + 8 * (i >> 2) + 4 * lh + (i & 3);
-        const bool valid = key < a.Sk && (!a.causal || key <= qi);
-        const float v = valid ? s[kt][i] * c : -INFINITY;
-        s[kt][i] = v;
-        mloc = fmaxf(mloc, v);
-      }
+      for (int i = 0; i < 16; ++i) mloc = fmaxf(mloc, s[kt][i]);
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-    const float mn = fmaxf(m, mloc);
+    const float mn = fmaxf(m, mloc * c);
     const float ms = mn == -INFINITY ? 0.f : mn;         // fully masked so far: keep exp2 finite
     const float corr = exp2f(m - ms);
     float lsum = 0.f;
@@ -199,7 +206,7 @@ __global__ void __launch_bounds__(NW * 64, (fa_fwd_blocks<DH, NW>())) attn_fwd_m
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const float p = exp2f(s[kt][i] - ms);
+        const float p = exp2f(fmaf(s[kt][i], c, -ms));
         s[kt][i] = p;
         lsum += p;
       }
@@ -268,13 +275,14 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, f
   for (int dt = 0; dt < DT; ++dt) dq[dt] = zero16();
   const int q_blk_last = min(q0 + NW * 32, a.Sq) - 1;
   const int k_end = a.causal ? min(a.Sk, q_blk_last + 1) : a.Sk;
-  const int q_wave_last = q0 + wave * 32 + 31;
+  const int q_wave_first = q0 + wave * 32, q_wave_last = q_wave_first + 31;
   for (int k0 = 0; k0 < k_end; k0 += 64) {
     __syncthreads();
     stage64<NW * 64, DH, true, true>(Ks, Kt, P.K, a.k_row_stride, k0, a.Sk);
     stage64<NW * 64, DH, true, false>(Vs, nullptr, P.V, a.v_row_stride, k0, a.Sk);
     __syncthreads();
     if (a.causal && k0 > q_wave_last) continue;
+    const bool full = k0 + 64 <= a.Sk && (!a.causal || k0 + 63 <= q_wave_first);   // no mask needed
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
       f32x16 s = zero16(), dp = zero16();
@@ -283,12 +291,17 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, f
         s = MFMA(frag_plain<DH>(Ks, 32 * kt + lr, ks, lh), qf[ks], s);
         dp = MFMA(frag_plain<DH>(Vs, 32 * kt + lr, ks, lh), dof[ks], dp);
       }
+      if (full) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = k0 + 32 * kt + 8 * (i >> 2) + 4 * lh + (i & 3);
-        const bool valid = key < a.Sk && (!a.causal || key <= qi);
-        const float p = valid ? exp2f(s[i] * c - lse2) : 0.f;
-        s[i] = p * (dp[i] - Dq);                            // dA^T
+        for (int i = 0; i < 16; ++i) s[i] = exp2f(fmaf(s[i], c, -lse2)) * (dp[i] - Dq);      // dA^T
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = k0 + 32 * kt + 8 * (i >> 2) + 4 * lh + (i & 3);
+          const bool valid = key < a.Sk && (!a.causal || key <= qi);
+          const float p = valid ? exp2f(fmaf(s[i], c, -lse2)) : 0.f;
+          s[i] = p * (dp[i] - Dq);
+        }
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
@@ -351,6 +364,8 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
     }
     __syncthreads();
     if (a.causal && i0 + 63 < k_wave_first) continue;      // every query of the tile precedes this wave's keys
+    // no mask needed: all 64 queries exist, the wavefront's keys exist and (causal) precede them all
+    const bool full = i0 + 64 <= a.Sq && k_wave_first + 32 <= a.Sk && (!a.causal || k_wave_first + 31 <= i0);
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
       f32x16 s = zero16(), dp = zero16();
@@ -359,14 +374,24 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
         s = MFMA(frag_plain<DH>(Qs, 32 * qt + lr, ks, lh), kf[ks], s);
         dp = MFMA(frag_plain<DH>(dOs, 32 * qt + lr, ks, lh), vf[ks], dp);
       }
+      if (full) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int ql = 32 * qt + 8 * (i >> 2) + 4 * lh + (i & 3);
-        const int qq = i0 + ql;
-        const bool valid = qq < a.Sq && kj < a.Sk && (!a.causal || kj <= qq);
-        const float p = valid ? exp2f(s[i] * c - Ls[ql]) : 0.f;
-        s[i] = p;
-        dp[i] = p * (dp[i] - Ds[ql]);
+        for (int i = 0; i < 16; ++i) {
+          const int ql = 32 * qt + 8 * (i >> 2) + 4 * lh + (i & 3);
+          const float p = exp2f(fmaf(s[i], c, -Ls[ql]));
+          s[i] = p;
+          dp[i] = p * (dp[i] - Ds[ql]);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int ql = 32 * qt + 8 * (i >> 2) + 4 * lh + (i & 3);
+          const int qq = i0 + ql;
+          const bool valid = qq < a.Sq && kj < a.Sk && (!a.causal || kj <= qq);
+          const float p = valid ? exp2f(fmaf(s[i], c, -Ls[ql])) : 0.f;
+          s[i] = p;
+          dp[i] = p * (dp[i] - Ds[ql]);
+        }
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
