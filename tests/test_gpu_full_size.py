@@ -156,3 +156,44 @@ def test_full_gpt2_small_adjoint_residuals_and_samples():
         bar = increment_tolerance(tol, ref, base, 1)
         print(f"  F-point {n}: increment err {e:.2e} (bar {bar:.2e})")
         assert e <= bar
+
+
+def test_full_mc_deep_narrow_relations_on_a_sampled_sequence():
+    """The deep-narrow configuration at its full size (8 sequences of 2048 tokens, one head of 128, 256
+    layers, 3 levels, F-relaxation), as bench.py launches it.  The oracle's complete iteration for one such
+    sequence takes many minutes, so the check uses what holds at any size: Z_0 and lambda_N are copied
+    exactly, residual norms decrease, and after the closing F-relaxation every F-point satisfies
+    Z_{n+1} = Phi(Z_n) and lambda_n = Psi(lambda_{n+1}; Z_n), recomputed by the oracle on one sequence
+    (this is where the 256-row attention blocks and the 2-rows-per-wavefront LayerNorm run at full length)."""
+    wl = wls.named_workloads()["mc_deep_narrow"]
+    tol = TOL[wl.dtype]
+    print(f"[case] full size {wl.name}: B={wl.batch} S={wl.seq} d={wl.d_model} N={wl.N} cf={wl.cf} L={wl.levels} "
+          f"it={wl.iters} relax={wl.relax}", flush=True)
+    dm = DeviceModel(wl)
+    opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters, wl.relax)
+    Z0, lamN = wls.initial_state(wl), wls.terminal_adjoint(wl)
+    Zg, rg = mb.mgrit_forward(dm.desc, opts, dev(Z0), dm.blocks)
+    lg, ag = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN))
+    torch.cuda.synchronize()
+    assert torch.equal(Zg[0].cpu(), torch.from_numpy(Z0))
+    assert torch.equal(lg[wl.N].cpu(), torch.from_numpy(lamN))
+    for norms in (rg.cpu().numpy(), ag.cpu().numpy()):
+        assert np.isfinite(norms).all() and norms[1] < norms[0], norms
+    sh1 = tode.Shape(wl.arch, wl.d_model, wl.n_heads, 1, wl.seq, 0, wl.ln_eps)
+    r = rows_of(wl, 5)
+    for n in (0, 129, 254):                     # Z_{n+1} is an F-point: n + 1 not a multiple of cf
+        assert (n + 1) % wl.cf != 0
+        base = Zg[n, r, :].cpu().numpy().astype(np.float64)
+        ref = tode.phi(base, dm.host[n], wl.h, sh1)
+        e = relerr(Zg[n + 1, r, :].cpu().numpy() - base, ref - base)
+        bar = increment_tolerance(tol, ref, base, 1)
+        print(f"  Z F-point {n + 1}: increment err {e:.2e} (bar {bar:.2e})")
+        assert e <= bar
+    for n in (wl.N - 2, 130, 1):                # lambda_n is an F-point of the reversed grid
+        assert (wl.N - n) % wl.cf != 0
+        base = lg[n + 1, r, :].cpu().numpy().astype(np.float64)
+        ref = tode.psi(base, Zg[n, r, :].cpu().numpy(), dm.host[n], wl.h, sh1)
+        e = relerr(lg[n, r, :].cpu().numpy() - base, ref - base)
+        bar = increment_tolerance(tol, ref, base, 1)
+        print(f"  lambda F-point {n}: increment err {e:.2e} (bar {bar:.2e})")
+        assert e <= bar
