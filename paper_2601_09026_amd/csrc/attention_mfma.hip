@@ -141,7 +141,7 @@ __device__ __forceinline__ void store_rows_T(bf16* dst, long row_stride, int row
 // ---------------------------------------------------------------------------
 // Resident blocks per CU the register budget is set for: the accumulators grow with DH.
 template <int DH, int NW = 4> constexpr int fa_fwd_blocks() { return NW == 8 ? 1 : DH == 64 ? 4 : 2; }
-template <int DH, int NW = 4> constexpr int fa_bwd_blocks() { return NW == 8 ? 1 : DH == 64 ? 3 : 2; }
+template <int DH, int NW = 4> constexpr int fa_bwd_blocks() { return NW == 8 ? 1 : 2; }
 
 template <int NW, int DH>
 __global__ void __launch_bounds__(NW * 64, (fa_fwd_blocks<DH, NW>())) attn_fwd_mfma_kernel(const AttnArgs a) {
@@ -439,17 +439,21 @@ bool attn_mfma_supported(const AttnArgs& a) {
 }
 
 // Long sequences: blocks of 256 rows halve the K/V (Q/dO) bytes staged from L2 per flop, which is
-// what bounds these kernels once a head no longer fits a block or two.
-constexpr int FA_LONG = 1024;
-int g_attn_wide = 5;            // bit 0: forward, bit 1: dQ pass (measured: no gain), bit 2: dK/dV pass
-void attn_set_wide_blocks(int mask) { g_attn_wide = mask & 7; }
+// what bounds these kernels once a head no longer fits a block or two.  Mask bits 0-2: forward,
+// dQ pass, dK/dV pass at d_head = 128 (sequences from 1024 tokens); bits 4-6: the same at
+// d_head = 64 (from 512 tokens).
+int g_attn_wide = 5;
+void attn_set_wide_blocks(int mask) { g_attn_wide = mask & 0x77; }
+template <int DH> static bool attn_wide(int pass, int seq) {
+  return DH == 128 ? (seq >= 1024 && ((g_attn_wide >> pass) & 1)) : (seq >= 512 && ((g_attn_wide >> (4 + pass)) & 1));
+}
 
 template <int DH>
 static hipError_t attn_fwd_mfma_dh(const AttnArgs& a, hipStream_t st) {
   if (a.Sq <= 64) {
     dim3 grid((a.Sq + 63) / 64, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_fwd_mfma_kernel<2, DH>), grid, dim3(128), 0, st, a);
-  } else if (DH == 128 && a.Sq >= FA_LONG && (g_attn_wide & 1)) {
+  } else if (attn_wide<DH>(0, a.Sq)) {
     dim3 grid((a.Sq + 255) / 256, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_fwd_mfma_kernel<8, DH>), grid, dim3(512), 0, st, a);
   } else {
@@ -474,7 +478,7 @@ static hipError_t attn_bwd_mfma_dh(const AttnArgs& a, hipStream_t st) {
   if (a.Sq <= 64) {
     dim3 grid((a.Sq + 63) / 64, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<2, DH>), grid, dim3(128), 0, st, a);
-  } else if (DH == 128 && a.Sq >= FA_LONG && (g_attn_wide & 2)) {
+  } else if (attn_wide<DH>(1, a.Sq)) {
     dim3 grid((a.Sq + 255) / 256, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<8, DH>), grid, dim3(512), 0, st, a);
   } else {
@@ -485,7 +489,7 @@ static hipError_t attn_bwd_mfma_dh(const AttnArgs& a, hipStream_t st) {
   if (a.Sk <= 64) {
     dim3 grid((a.Sk + 63) / 64, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<2, DH>), grid, dim3(128), 0, st, a);
-  } else if (DH == 128 && a.Sk >= FA_LONG && (g_attn_wide & 4)) {
+  } else if (attn_wide<DH>(2, a.Sk)) {
     dim3 grid((a.Sk + 255) / 256, a.B * a.H, a.n_groups);
     hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<8, DH>), grid, dim3(512), 0, st, a);
   } else {
