@@ -12,7 +12,8 @@ namespace mg {
 // in flight while it reduces and writes the current one (few long-lived waves instead of one
 // short-lived wave per row).  NV = float4 per lane (row kept in registers), d <= 256*NV.
 constexpr int LN_MAXV = 8;          // d <= 64*4*8 = 2048
-constexpr int LN_BLOCKS_PER_CU = 8;
+constexpr int LN_FWD_BLOCKS_PER_CU = 16;   // grid caps (measured: the forward kernel gains from the larger one,
+constexpr int LN_BWD_BLOCKS_PER_CU = 8;    // the VJP, with twice the registers, loses)
 
 // LN input = state row (optional) + packed fp32 addend (optional); at least one is present
 __device__ __forceinline__ f32x4 load_sum(const float* x, const float* xa, int c) {
@@ -103,10 +104,10 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const LnFwdArgs a) {
 
 static int ln_lanes_per_row(int d) { return d <= 64 ? 16 : d <= 128 ? 32 : 64; }
 
-static unsigned ln_grid(long rows, int d) {
+static unsigned ln_grid(long rows, int d, int blocks_per_cu) {
   const long per_block = 4 * (64 / ln_lanes_per_row(d));
   long want = (rows + per_block - 1) / per_block;
-  const long cap = 256L * LN_BLOCKS_PER_CU;
+  const long cap = 256L * blocks_per_cu;
   return (unsigned)(want < cap ? want : cap);
 }
 
@@ -126,7 +127,7 @@ hipError_t launch_ln_fwd(const LnFwdArgs& a, bool is_bf16, hipStream_t st) {
   const long rows = (long)a.n_groups * a.T;
   if (rows <= 0) return hipSuccess;
   if (rows > 0x7fffffffL || a.d > 256 * LN_MAXV) return hipErrorInvalidValue;
-  const unsigned blocks = ln_grid(rows, a.d);
+  const unsigned blocks = ln_grid(rows, a.d, LN_FWD_BLOCKS_PER_CU);
   const double esz = is_bf16 ? 2 : 4;
   ProfScope ps(PC_LN_FWD, 8.0 * rows * a.d,
                (double)rows * a.d * ((a.X.present() ? 4 : 0) + (a.xp ? 4 : 0) + esz), st);
@@ -264,7 +265,7 @@ hipError_t launch_ln_bwd(const LnBwdArgs& a, bool is_bf16, hipStream_t st) {
   const long rows = (long)a.n_groups * a.T;
   if (rows <= 0) return hipSuccess;
   if (rows > 0x7fffffffL || a.d > 256 * LN_MAXV) return hipErrorInvalidValue;
-  const unsigned blocks = ln_grid(rows, a.d);
+  const unsigned blocks = ln_grid(rows, a.d, LN_BWD_BLOCKS_PER_CU);
   const double esz = is_bf16 ? 2 : 4;
   const bool xh = a.xhat != nullptr;
   if (xh && !a.rstd) return hipErrorInvalidValue;
