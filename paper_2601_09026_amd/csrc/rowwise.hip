@@ -13,7 +13,7 @@ namespace mg {
 // short-lived wave per row).  NV = float4 per lane (row kept in registers), d <= 256*NV.
 constexpr int LN_MAXV = 8;          // d <= 64*4*8 = 2048
 constexpr int LN_FWD_BLOCKS_PER_CU = 16;   // grid caps (measured: the forward kernel gains from the larger one,
-constexpr int LN_BWD_BLOCKS_PER_CU = 8;    // the VJP, with twice the registers, loses)
+constexpr int LN_BWD_BLOCKS_PER_CU = 16;   // the VJP likewise once it no longer prefetches rows of more than 512 elements)
 
 // LN input = state row (optional) + packed fp32 addend (optional); at least one is present
 __device__ __forceinline__ f32x4 load_sum(const float* x, const float* xa, int c) {
@@ -175,7 +175,7 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
       }
     }
   };
-  constexpr bool PREFETCH = NV <= 4;                 // wider rows would spill: load in place instead
+  constexpr bool PREFETCH = NV <= 2;                 // wider rows would spill: load in place instead
   f32x4 v[NV], w[NV], nv_[PREFETCH ? NV : 1], nw_[PREFETCH ? NV : 1];
   float rs_cur = 0.f, rs_next = 0.f;
   load(row, v, w, rs_cur);
