@@ -45,6 +45,8 @@ def parse():
                          "the line then says so in `metric` and in config.param_grads)")
     ap.add_argument("--attn-wide", type=int, default=-1,
                     help="tuning: mask of d_head=128 attention kernels with 256-row blocks (1 fwd, 2 dQ, 4 dK/dV)")
+    ap.add_argument("--no-pipeline", action="store_true",
+                    help="tuning: serial coarse solve and the following F-relaxation one after the other")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not record per-kernel HIP events in the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -105,6 +107,8 @@ def main():
         mb.mgrit_set_lanes(args.lanes)
     if args.attn_wide >= 0:
         mb.lib().mgrit_debug_attention_wide_blocks(args.attn_wide)
+    if args.no_pipeline:
+        mb.lib().mgrit_debug_pipeline_coarse_solve(0)
     if args.gemm_tile:
         mb.lib().mgrit_debug_gemm_tile_config(args.gemm_tile)
     desc = mb.model_desc(wl)

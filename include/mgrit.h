@@ -313,6 +313,10 @@ void mgrit_debug_gemm_tile_config(int cfg);
  * blocks everywhere. */
 void mgrit_debug_attention_wide_blocks(int mask);
 
+/* Tuning hook: 1 (default) overlaps the serial solve on the coarsest level with the F-relaxation
+ * that follows it (needs the two lanes); 0 runs them one after the other.  Results are identical. */
+void mgrit_debug_pipeline_coarse_solve(int on);
+
 #ifdef __cplusplus
 }
 #endif

@@ -127,6 +127,8 @@ def lib() -> C.CDLL:
         L.mgrit_debug_gemm_tile_config.restype = None
         L.mgrit_debug_attention_wide_blocks.argtypes = [C.c_int]
         L.mgrit_debug_attention_wide_blocks.restype = None
+        L.mgrit_debug_pipeline_coarse_solve.argtypes = [C.c_int]
+        L.mgrit_debug_pipeline_coarse_solve.restype = None
         L.mgrit_profile_enable.argtypes = [C.c_int]
         L.mgrit_profile_enable.restype = C.c_int
         L.mgrit_profile_reset.argtypes = []

@@ -259,9 +259,11 @@ struct Engine {
 // helper stream (forked from and joined back into the caller's stream with events), so that
 // the bandwidth-bound kernels of one chunk overlap the matrix kernels of the other.  The
 // helper stream and its two events are created once per process, on first use.
+constexpr int PIPE_EVENTS = 32;
 struct AuxStream {
   hipStream_t s = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
+  hipEvent_t pipe[PIPE_EVENTS] = {};     // hand-overs from the serial coarse solve to the helper lane
   bool tried = false, ok = false;
 };
 AuxStream& aux_stream() {
@@ -271,10 +273,13 @@ AuxStream& aux_stream() {
     a.ok = hipStreamCreateWithFlags(&a.s, hipStreamNonBlocking) == hipSuccess &&
            hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) == hipSuccess &&
            hipEventCreateWithFlags(&a.join, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; a.ok && i < PIPE_EVENTS; ++i)
+      a.ok = hipEventCreateWithFlags(&a.pipe[i], hipEventDisableTiming) == hipSuccess;
   }
   return a;
 }
 int g_lanes = 2;                            // 1 = everything on the caller's stream
+int g_pipeline = 1;                         // overlap the serial coarse solve with the F-relaxation that follows it
 
 // Engine of the second lane: same model and shared buffers, own work buffers and stream.
 inline bool make_lane(Engine& E2, const Engine& E, Bump& b, bool adjoint, bool measure_only) {
@@ -789,10 +794,14 @@ struct Driver {
     return MGRIT_OK;
   }
 
+  Engine* only = nullptr;          // when set, step() enqueues on this engine's stream alone (no fork / join)
+
   // cnt steps of level `lvl`, group k starting at point j = j0 + k*js
   int step(int lvl, int j0, int js, int cnt, Rows OUT, Rows RHS) {
     evals += cnt;
     if (!E) return MGRIT_OK;
+    Engine& L1 = only ? *only : *E;
+    Engine* L2 = only ? nullptr : E2;
     const int s = ipow(cf, lvl);
     const float hstep = (float)((double)s * (double)h);
     Rows IN = {(const void* const*)tabW, j0 * s, js * s};
@@ -802,13 +811,48 @@ struct Driver {
     }
     if (!adjoint) {
       Params TH = {(const void* const*)tabTh, j0 * s, js * s};
-      return forward_groups(*E, E2, cnt, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
+      return forward_groups(L1, L2, cnt, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
     }
     const int n0 = N - (j0 + 1) * s, ns = -js * s;       // layer the coarse step lands on
     Params TH = {(const void* const*)tabTh, n0, ns};
     Params THT = {(const void* const*)tabThT, n0, ns};
     Rows LIN = {(const void* const*)tabZ, n0, ns};
-    return adjoint_groups(*E, E2, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep);
+    return adjoint_groups(L1, L2, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep);
+  }
+
+  // The serial solve on the coarsest level (level lvl + 1, M steps) and the F-relaxation of level
+  // lvl that follows it, overlapped: interval k of level lvl may relax as soon as its C-point v_k
+  // is final, i.e. after coarse step k.  The coarse steps stay on the caller's stream (single
+  // groups, which leave much of the chip idle); after every `chunk` of them an event hands the
+  // finished intervals to the helper lane, which runs their cf-1 dependent F-steps meanwhile.
+  // Same kernels on the same data as the sequential order: results are identical.
+  int coarse_solve_with_relaxation(int lvl, int M) {
+    AuxStream& a = aux_stream();
+    const int chunk = E2->Gc;
+    int k0 = 0, ev = 0;
+    auto relax = [&](Engine* lane, int ka, int kb) {      // F-relaxation of intervals ka .. kb-1 on one lane
+      only = lane;
+      int st = MGRIT_OK;
+      for (int i = 0; i + 1 < cf && st == MGRIT_OK; ++i)
+        st = step(lvl, ka * cf + i, cf, kb - ka, W(lvl, ka * cf + i + 1, cf), Gr(lvl, ka * cf + i + 1, cf));
+      only = nullptr;
+      return st;
+    };
+    for (int j = 0; j <= M; ++j) {                       // j coarse steps done: v_0 .. v_j are final
+      if (j >= 1) STCHK(step(lvl + 1, j - 1, 1, 1, W(lvl + 1, j, 1), Gr(lvl + 1, j, 1)));
+      const int k1 = j + 1;                              // intervals k0 .. k1-1 can relax now
+      if (k1 >= M || k1 % chunk != 0) continue;          // the last chunk stays on this lane, see below
+      hipEvent_t e = a.pipe[ev++ % PIPE_EVENTS];
+      HIPCHK(hipEventRecord(e, E->st));
+      HIPCHK(hipStreamWaitEvent(E2->st, e, 0));
+      STCHK(relax(E2, k0, k1));
+      k0 = k1;
+    }
+    // the helper lane still has its chunks to finish: the remaining intervals relax on this lane
+    STCHK(relax(E, k0, M));
+    HIPCHK(hipEventRecord(a.join, E2->st));
+    HIPCHK(hipStreamWaitEvent(E->st, a.join, 0));
+    return MGRIT_OK;
   }
 
   Rows W(int lvl, int j0, int js) const {
@@ -846,6 +890,8 @@ struct Driver {
     Rows Gn = {(const void* const*)(E ? tabG[lvl + 1] : nullptr), 1, 1};
     STCHK(step(lvl + 1, 0, 1, M, Gn, NO_ROWS));
     if (E) HIPCHK(launch_sub_rows(M, state_elems(), R, Gn, Gn, E->st));
+    if (E && E2 && !Ed && g_pipeline && lvl + 1 == L - 1 && M >= 2 && cf >= 2)
+      return coarse_solve_with_relaxation(lvl, M);
     STCHK(vcycle(lvl + 1, iter, false));
     STCHK(f_relax(lvl, M));
     return MGRIT_OK;
@@ -1459,5 +1505,6 @@ void mgrit_debug_force_simple_kernels(int gemm, int attn) {
 
 void mgrit_debug_gemm_tile_config(int cfg) { gemm_set_tile_config(cfg); }
 void mgrit_debug_attention_wide_blocks(int mask) { attn_set_wide_blocks(mask); }
+void mgrit_debug_pipeline_coarse_solve(int on) { g_pipeline = on ? 1 : 0; }
 
 }  // extern "C"

@@ -165,6 +165,31 @@ def test_run_to_run_bit_identical():
     assert torch.equal(a, b) and torch.equal(ra, rb)
 
 
+@pytest.mark.parametrize("levels,cf,N", [(2, 4, 32), (3, 2, 16), (2, 4, 12)])
+def test_overlapped_coarse_solve_is_bit_identical_to_the_sequential_order(levels, cf, N):
+    """The serial coarse solve hands finished intervals to the helper lane, which F-relaxes them while
+    the remaining coarse steps run: the same kernels on the same data as one after the other, so every
+    state, adjoint state and residual norm must agree bit for bit (M = 8, 4 and 3 intervals on the level
+    above the coarsest; 3 is not a multiple of the launch chunk)."""
+    wl = tiny(arch=wls.ARCH_CAUSAL, dtype=wls.DTYPE_BF16, N=N, cf=cf, levels=levels, iters=2, d=128, f=256)
+    dm = DeviceModel(wl, weight_std=0.05)
+    Z0, lamN = dev(wls.initial_state(wl)), dev(wls.terminal_adjoint(wl))
+    opts = mb.mgrit_opts(N, 1.0, cf, levels, 2)
+    out = []
+    try:
+        for on in (1, 0, 1):
+            mb.lib().mgrit_debug_pipeline_coarse_solve(on)
+            Z, rz = mb.mgrit_forward(dm.desc, opts, Z0, dm.blocks)
+            lam, rl = mb.mgrit_adjoint(dm.desc, opts, Z, dm.blocks, lamN)
+            torch.cuda.synchronize()
+            out.append((Z, rz, lam, rl))
+    finally:
+        mb.lib().mgrit_debug_pipeline_coarse_solve(1)
+    for a, b in ((out[0], out[1]), (out[0], out[2])):
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+
+
 # ----------------------------------------------------------------- benchmark configurations
 def test_config1_tiny_encoder_full():
     wl = wls.named_workloads()["tiny_encoder"]
