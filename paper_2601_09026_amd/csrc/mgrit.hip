@@ -761,6 +761,12 @@ struct Driver {
       else n_first = (n0 - n_enc) / (-ns) + 1;
     }
     if (n_first > cnt) n_first = cnt;
+    // engines of this call: both lanes with fork / join, or one lane alone (see `only`)
+    const bool helper = only != nullptr && only == E2;
+    Engine& Le = helper ? *E2 : *E;
+    Engine& Ld = helper ? *Ed2 : *Ed;
+    Engine* Le2 = only ? nullptr : E2;
+    Engine* Ld2 = only ? nullptr : Ed2;
     for (int run = 0; run < 2; ++run) {
       const int c0 = run == 0 ? 0 : n_first, n = run == 0 ? n_first : cnt - n_first;
       if (n <= 0) continue;
@@ -772,22 +778,22 @@ struct Driver {
       Params TH = {(const void* const*)tabTh, nl, ns};
       if (!adjoint) {
         if (enc) {
-          STCHK(forward_groups(*E, E2, n, inx, outx, rhsx, TH, hstep, false, Slots{0, 0}));
-          HIPCHK(launch_add_rows(n, y_elems, iny, rhsy, outy, E->st));
+          STCHK(forward_groups(Le, Le2, n, inx, outx, rhsx, TH, hstep, false, Slots{0, 0}));
+          HIPCHK(launch_add_rows(n, y_elems, iny, rhsy, outy, Le.st));
         } else {
-          STCHK(forward_groups(*Ed, Ed2, n, iny, outy, rhsy, TH, hstep, false, Slots{0, 0}, inx));
-          HIPCHK(launch_add_rows(n, x_elems, inx, rhsx, outx, E->st));
+          STCHK(forward_groups(Ld, Ld2, n, iny, outy, rhsy, TH, hstep, false, Slots{0, 0}, inx));
+          HIPCHK(launch_add_rows(n, x_elems, inx, rhsx, outx, Le.st));
         }
         continue;
       }
       Params THT = {(const void* const*)tabThT, nl, ns};
       Rows LIN = {(const void* const*)tabZ, nl, ns};
       if (enc) {
-        STCHK(adjoint_groups(*E, E2, n, inx, outx, rhsx, TH, THT, LIN, Slots{nl, ns}, hstep));
-        HIPCHK(launch_add_rows(n, y_elems, iny, rhsy, outy, E->st));
+        STCHK(adjoint_groups(Le, Le2, n, inx, outx, rhsx, TH, THT, LIN, Slots{nl, ns}, hstep));
+        HIPCHK(launch_add_rows(n, y_elems, iny, rhsy, outy, Le.st));
       } else {
         StackedDec sd = {LIN, inx, outx, rhsx};
-        STCHK(adjoint_groups(*Ed, Ed2, n, iny, outy, rhsy, TH, THT, part(LIN, x_elems), Slots{nl - n_enc, ns}, hstep,
+        STCHK(adjoint_groups(Ld, Ld2, n, iny, outy, rhsy, TH, THT, part(LIN, x_elems), Slots{nl - n_enc, ns}, hstep,
                              &sd));
       }
     }
@@ -890,7 +896,7 @@ struct Driver {
     Rows Gn = {(const void* const*)(E ? tabG[lvl + 1] : nullptr), 1, 1};
     STCHK(step(lvl + 1, 0, 1, M, Gn, NO_ROWS));
     if (E) HIPCHK(launch_sub_rows(M, state_elems(), R, Gn, Gn, E->st));
-    if (E && E2 && !Ed && g_pipeline && lvl + 1 == L - 1 && M >= 2 && cf >= 2)
+    if (E && E2 && g_pipeline && lvl + 1 == L - 1 && M >= 2 && cf >= 2)
       return coarse_solve_with_relaxation(lvl, M);
     STCHK(vcycle(lvl + 1, iter, false));
     STCHK(f_relax(lvl, M));

@@ -177,3 +177,28 @@ def test_full_size_mt_stacked_sampled_sentence_pairs():
                         assert err <= bar, f"{what}_{part}(pair {b})[{n}]: increment error {err:.3e} > {bar:.3e}"
     for norms in (rg.cpu().numpy(), ag.cpu().numpy()):
         assert np.isfinite(norms).all() and all(norms[i + 1] < norms[i] for i in range(d.iters - 1)), norms
+
+
+def test_overlapped_coarse_solve_is_bit_identical_on_the_stacked_grid():
+    """Coarse steps of both kinds (encoder, then decoder) hand finished intervals to the helper lane:
+    same states, adjoint states and norms as the sequential order, bit for bit."""
+    sw = stacked(dtype=wls.DTYPE_BF16, d=128, H=2, f=256, n_enc=12, n_dec=20, cf=4, levels=2, h=0.5)
+    d = sw.dec
+    desc_d = mb.model_desc(d)
+    desc_e = mb.encoder_desc(desc_d)
+    blocks = [mb.pack_theta(desc_e if n < sw.n_enc else desc_d, wls.stacked_layer_params(sw, n, 0.05))
+              for n in range(sw.N)]
+    opts = mb.mgrit_opts(sw.N, d.h, d.cf, d.levels, d.iters, d.relax)
+    Z0, lamN = dev(wls.stacked_initial_state(sw)), dev(wls.stacked_terminal_adjoint(sw))
+    out = []
+    try:
+        for on in (1, 0):
+            mb.lib().mgrit_debug_pipeline_coarse_solve(on)
+            Z, rz = mb.mgrit_forward_stacked(desc_d, opts, sw.n_enc, Z0, blocks)
+            lam, rl = mb.mgrit_adjoint_stacked(desc_d, opts, sw.n_enc, Z, blocks, lamN)
+            torch.cuda.synchronize()
+            out.append((Z, rz, lam, rl))
+    finally:
+        mb.lib().mgrit_debug_pipeline_coarse_solve(1)
+    for x, y in zip(out[0], out[1]):
+        assert torch.equal(x, y)
