@@ -133,8 +133,10 @@ enum Epi : int {
   EPI_GELU = 1,         // out = gelu(acc + bias); optionally z = acc + bias kept for the adjoint
   EPI_RESID_INNER = 2,  // ybar[m,n] (fp32, packed) = [base +] acc + bias      (sum of attention sublayers)
   EPI_RESID_OUTER = 3,  // OUT[m,n] = X + h*(ybar + acc + bias) + rhs          (the Euler update)
-  EPI_DGELU = 4,        // out = acc * gelu'(z[m,n])                           (adjoint of the activation)
-  EPI_STORE_F32 = 5     // out (fp32, packed or inside the group's output block) = hstep * (acc + bias)
+  EPI_DGELU = 4,        // out = acc * g[m,n], g = the cached gelu'(z)          (adjoint of the activation)
+  EPI_STORE_F32 = 5,    // out (fp32, packed or inside the group's output block) = hstep * (acc + bias)
+  EPI_GELU_PRIME = 6    // out = gelu'(acc + bias) (operand type); optionally z = acc + bias kept as well:
+                        // the linearisation cache holds the derivative, evaluated once per layer
 };
 
 struct GemmArgs {
@@ -148,7 +150,7 @@ struct GemmArgs {
   Params bias;
   // outputs / epilogue operands
   void* out; long out_slot_stride; Slots out_slots;      // packed output (operand type or fp32)
-  void* aux; long aux_slot_stride; Slots aux_slots;      // EPI_GELU: z out (may be null); EPI_DGELU: z in;
+  void* aux; long aux_slot_stride; Slots aux_slots;      // EPI_GELU, EPI_GELU_PRIME: z out (may be null); EPI_DGELU: g in;
                                                          // EPI_RESID_OUTER: ybar (fp32 packed)
   Rows X;                      // EPI_RESID_OUTER: the step's input state
   const float* base; long base_slot_stride; Slots base_slots;   // EPI_RESID_INNER: optional packed fp32 addend

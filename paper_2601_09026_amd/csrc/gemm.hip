@@ -59,11 +59,13 @@ __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restric
     if (z_out) store4<TO>(z_out + idx, acc);
     f32x4 y = {gelu_t<TO>(acc[0]), gelu_t<TO>(acc[1]), gelu_t<TO>(acc[2]), gelu_t<TO>(acc[3])};
     store4<TO>(out_op + idx, y);
-  } else if constexpr (EPI == EPI_DGELU) {
-    f32x4 zz = load4<TO>(z_in + idx);
-    f32x4 y = {acc[0] * gelu_prime_t<TO>(zz[0]), acc[1] * gelu_prime_t<TO>(zz[1]),
-               acc[2] * gelu_prime_t<TO>(zz[2]), acc[3] * gelu_prime_t<TO>(zz[3])};
+  } else if constexpr (EPI == EPI_GELU_PRIME) {
+    if (z_out) store4<TO>(z_out + idx, acc);
+    f32x4 y = {gelu_prime_t<TO>(acc[0]), gelu_prime_t<TO>(acc[1]), gelu_prime_t<TO>(acc[2]),
+               gelu_prime_t<TO>(acc[3])};
     store4<TO>(out_op + idx, y);
+  } else if constexpr (EPI == EPI_DGELU) {
+    store4<TO>(out_op + idx, acc * load4<TO>(z_in + idx));
   } else if constexpr (EPI == EPI_RESID_INNER) {
     if (base) acc += *reinterpret_cast<const f32x4*>(base + idx);
     store4<float>(out_f32 + idx, acc);
@@ -91,10 +93,15 @@ __device__ __forceinline__ void apply8(bf16* __restrict__ out, bf16* __restrict_
 #pragma unroll
     for (int r = 0; r < 4; ++r) { a[r] = gelu_fast(a[r]); b[r] = gelu_fast(b[r]); }
     store8(out + idx, a, b);
-  } else if constexpr (EPI == EPI_DGELU) {
-    const bf16x8 z = *reinterpret_cast<const bf16x8*>(z_in + idx);
+  } else if constexpr (EPI == EPI_GELU_PRIME) {
+    if (z_out) store8(z_out + idx, a, b);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) { a[r] *= gelu_prime_fast((float)z[r]); b[r] *= gelu_prime_fast((float)z[4 + r]); }
+    for (int r = 0; r < 4; ++r) { a[r] = gelu_prime_fast(a[r]); b[r] = gelu_prime_fast(b[r]); }
+    store8(out + idx, a, b);
+  } else if constexpr (EPI == EPI_DGELU) {
+    const bf16x8 g = *reinterpret_cast<const bf16x8*>(z_in + idx);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { a[r] *= (float)g[r]; b[r] *= (float)g[4 + r]; }
     store8(out + idx, a, b);
   }
 }
@@ -127,7 +134,8 @@ __device__ __forceinline__ void tile_epilogue(
     // A lane finishes CW consecutive columns at a time: 8 where the output is bf16 (16-byte
     // stores: four lanes fill a 64-byte sector, so the memory side never has to read a sector
     // back in order to merge a partial write), 4 where it is fp32.
-    constexpr bool WIDE = sizeof(TO) == 2 && (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_DGELU);
+    constexpr bool WIDE = sizeof(TO) == 2 && (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_DGELU ||
+                                              EPI == EPI_GELU_PRIME);
     constexpr int CW = WIDE ? 8 : 4;
     constexpr int CI = WTN / CW;                         // items per row
     constexpr int NIT = 32 * CI / 64;                    // items per lane in a 32-row block
@@ -527,7 +535,7 @@ static double gemm_bytes(const GemmArgs& a, double esz) {
   const double G = a.n_groups, MN = (double)a.M * a.N;
   double b = G * ((a.a_slot_stride ? 1.0 : 1.0 / G) * a.M * a.K * esz + (double)a.N * a.K * esz);
   if (EPI == EPI_STORE) b += G * MN * esz;
-  if (EPI == EPI_GELU) b += G * MN * esz * (a.aux ? 2 : 1);
+  if (EPI == EPI_GELU || EPI == EPI_GELU_PRIME) b += G * MN * esz * (a.aux ? 2 : 1);
   if (EPI == EPI_DGELU) b += G * MN * esz * 2;
   if (EPI == EPI_STORE_F32) b += G * MN * 4;
   if (EPI == EPI_RESID_INNER) b += G * MN * 4 * (a.base ? 2 : 1);
@@ -597,6 +605,7 @@ hipError_t launch_gemm(const GemmArgs& a, int epi, bool is_bf16, hipStream_t st)
     case EPI_RESID_OUTER: return launch_epi<EPI_RESID_OUTER>(a, is_bf16, st);
     case EPI_DGELU: return launch_epi<EPI_DGELU>(a, is_bf16, st);
     case EPI_STORE_F32: return launch_epi<EPI_STORE_F32>(a, is_bf16, st);
+    case EPI_GELU_PRIME: return launch_epi<EPI_GELU_PRIME>(a, is_bf16, st);
   }
   return hipErrorInvalidValue;
 }

@@ -147,7 +147,9 @@ struct Engine {
   float *xin, *x3;
   // adjoint: linearisation cache (n_cache slots) and work buffers (Gc slots)
   int n_cache;
-  void *c_qkv, *c_o, *c_z;
+  void *c_qkv, *c_o, *c_z;         // c_z holds gelu'(z): the adjoint only needs the derivative
+  void* c_zraw = nullptr;          // z itself, kept when parameter gradients are wanted (W2's needs GELU(z))
+  bool keep_z = false;
   float *c_lse, *c_xin;
   void *c_xh1, *c_xh2;             // normalised LN1 / LN2 inputs (operand type) ...
   float *c_rs1, *c_rs2;            // ... and their 1/std, one per token
@@ -208,6 +210,7 @@ struct Engine {
     c_qkv = b.take_bytes(C * T * 3 * d * esz);
     c_o = b.take_bytes(C * T * d * esz);
     c_z = b.take_bytes(C * T * f * esz);
+    c_zraw = keep_z ? b.take_bytes(C * T * f * esz) : nullptr;
     c_lse = b.take<float>(C * md.batch * H * md.seq);
     c_xin = b.take<float>(C * T * d);
     c_xh1 = b.take_bytes(C * T * d * esz);
@@ -394,7 +397,8 @@ int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, floa
   g = gemm_base(n, T, f, d, E.u, E.Td(), loc, TH, L.offset[MGRIT_P_W1], L.offset[MGRIT_P_B1]);
   if (cache) {
     g.out = E.c_z; g.out_slot_stride = (long)T * f; g.out_slots = cs;
-    HIPCHK(launch_gemm(g, EPI_STORE, E.bf16, E.st));
+    g.aux = E.c_zraw; g.aux_slot_stride = (long)T * f; g.aux_slots = cs;
+    HIPCHK(launch_gemm(g, EPI_GELU_PRIME, E.bf16, E.st));
     return MGRIT_OK;
   }
   g.out = E.act; g.out_slot_stride = (long)T * f; g.out_slots = loc;
@@ -465,7 +469,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
   memset(&lp, 0, sizeof(lp));
   if (DT) {
     // m = GELU(z) W2^T + b2
-    STCHK(linear_param_grads(E, n, E.cb, E.Td(), loc, d, E.c_z, (long)T * f, cs, f, true, *DT, MGRIT_P_W2,
+    STCHK(linear_param_grads(E, n, E.cb, E.Td(), loc, d, E.c_zraw, (long)T * f, cs, f, true, *DT, MGRIT_P_W2,
                              MGRIT_P_B2, hstep));
     lf.n_groups = n; lf.T = T; lf.d = d; lf.X = LIN; lf.P = TH; lf.eps = E.md.ln_eps;
     lf.out = E.u; lf.out_slot_stride = E.Td(); lf.out_slots = loc;
@@ -473,7 +477,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
     lp.dy = E.du; lp.dy_slot_stride = E.Td(); lp.dy_slots = loc;
   }
 
-  // dz = (c W2) * gelu'(z)        [T,d] x [d,f]: transposed W2 is [f,d]
+  // dz = (c W2) * gelu'(z)        [T,d] x [d,f]: transposed W2 is [f,d]; gelu'(z) comes from the cache
   GemmArgs g = gemm_base(n, T, f, d, E.cb, E.Td(), loc, THT, L.offset[MGRIT_P_W2], -1);
   g.out = E.dz; g.out_slot_stride = (long)T * f; g.out_slots = loc;
   g.aux = E.c_z; g.aux_slot_stride = (long)T * f; g.aux_slots = cs;
@@ -935,6 +939,7 @@ int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, int mod
   int gc = max_groups();
   const int widest = adjoint ? (N > M0 ? N : M0) : M0;      // the cache pass batches over all N layers
   if (gc > widest) gc = widest;
+  E.keep_z = mode == 2;
   if (adjoint) E.carve_adjoint(b, gc, N); else E.carve_forward(b, gc);
   P.two_lanes = widest >= 2 && make_lane(P.E2, E, b, adjoint, ws == nullptr);
   Driver& D = P.D;
@@ -1182,6 +1187,7 @@ int make_stacked_plan(StackedPlan& P, const mgrit_model_desc* md, const mgrit_op
   int gc = max_groups();
   const int widest = adjoint ? (N > M0 ? N : M0) : M0;
   if (gc > widest) gc = widest;
+  P.Ee.keep_z = P.Ed.keep_z = mode == 2;
   if (adjoint) { P.Ee.carve_adjoint(b, gc, n_enc); P.Ed.carve_adjoint(b, gc, n_dec); }
   else { P.Ee.carve_forward(b, gc); P.Ed.carve_forward(b, gc); }
   P.two_lanes = widest >= 2 && make_lane(P.Ee2, P.Ee, b, adjoint, ws == nullptr);
