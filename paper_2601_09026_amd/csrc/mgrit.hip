@@ -830,17 +830,46 @@ struct Driver {
     return adjoint_groups(L1, L2, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep);
   }
 
-  // The serial solve on the coarsest level (level lvl + 1, M steps) and the F-relaxation of level
-  // lvl that follows it, overlapped: interval k of level lvl may relax as soon as its C-point v_k
-  // is final, i.e. after coarse step k.  The coarse steps stay on the caller's stream (single
-  // groups, which leave much of the chip idle); after every `chunk` of them an event hands the
-  // finished intervals to the helper lane, which runs their cf-1 dependent F-steps meanwhile.
+  // The coarse right-hand sides, the serial solve on the coarsest level (level lvl + 1, M steps) and
+  // the F-relaxation of level lvl that follows it, overlapped on the two lanes.  The coarse steps
+  // are single groups, which leave much of the chip idle, and they form MGRIT's serial chain:
+  //  * the right-hand sides g'_k = R_k - Phi'(w_{(k-1) cf}) are formed chunk by chunk, the first
+  //    chunk on the caller's stream, the others on the helper lane; coarse step j reads g'_j and
+  //    overwrites C-point j, which the right-hand side of group j still has to read, so it waits
+  //    (by event) for the chunk that holds group j and no more;
+  //  * interval k of level lvl may relax as soon as its C-point v_k is final, i.e. after coarse
+  //    step k: after every `chunk` steps an event hands the finished intervals to the helper lane,
+  //    which runs their cf-1 dependent F-steps meanwhile; the last chunk relaxes on this stream.
   // Same kernels on the same data as the sequential order: results are identical.
-  int coarse_solve_with_relaxation(int lvl, int M) {
+  int coarse_solve_with_relaxation(int lvl, int M, Rows R, Rows Gn) {
     AuxStream& a = aux_stream();
     const int chunk = E2->Gc;
-    int k0 = 0, ev = 0;
-    auto relax = [&](Engine* lane, int ka, int kb) {      // F-relaxation of intervals ka .. kb-1 on one lane
+    const int n_chunks = (M + chunk - 1) / chunk;
+    constexpr int HALF = PIPE_EVENTS / 2;                // events 0..HALF-1: right-hand sides; the others: hand-overs
+    auto rhs_chunk = [&](Engine* lane, int g0, int n) -> int {
+      only = lane;
+      const int st = step(lvl + 1, g0, 1, n, shift(Gn, g0), NO_ROWS);
+      only = nullptr;
+      STCHK(st);
+      HIPCHK(launch_sub_rows(n, state_elems(), shift(R, g0), shift(Gn, g0), shift(Gn, g0), lane->st));
+      return MGRIT_OK;
+    };
+    const bool split_rhs = n_chunks >= 2 && n_chunks <= HALF;
+    if (!split_rhs) {
+      STCHK(step(lvl + 1, 0, 1, M, Gn, NO_ROWS));
+      HIPCHK(launch_sub_rows(M, state_elems(), R, Gn, Gn, E->st));
+    } else {
+      // the helper lane starts from everything enqueued so far (relaxation, residual)
+      HIPCHK(hipEventRecord(a.fork, E->st));
+      HIPCHK(hipStreamWaitEvent(E2->st, a.fork, 0));
+      STCHK(rhs_chunk(E, 0, chunk));
+      for (int c = 1; c < n_chunks; ++c) {
+        const int g0 = c * chunk;
+        STCHK(rhs_chunk(E2, g0, M - g0 < chunk ? M - g0 : chunk));
+        HIPCHK(hipEventRecord(a.pipe[c], E2->st));
+      }
+    }
+    auto relax = [&](Engine* lane, int ka, int kb) -> int {   // F-relaxation of intervals ka .. kb-1 on one lane
       only = lane;
       int st = MGRIT_OK;
       for (int i = 0; i + 1 < cf && st == MGRIT_OK; ++i)
@@ -848,11 +877,17 @@ struct Driver {
       only = nullptr;
       return st;
     };
+    int k0 = 0, ev = 0;
     for (int j = 0; j <= M; ++j) {                       // j coarse steps done: v_0 .. v_j are final
-      if (j >= 1) STCHK(step(lvl + 1, j - 1, 1, 1, W(lvl + 1, j, 1), Gr(lvl + 1, j, 1)));
+      if (j >= 1) {
+        const int need = j < M ? j : M - 1;              // groups 0 .. need must have read their C-point
+        if (split_rhs && need % chunk == 0 && need >= chunk)
+          HIPCHK(hipStreamWaitEvent(E->st, a.pipe[need / chunk], 0));
+        STCHK(step(lvl + 1, j - 1, 1, 1, W(lvl + 1, j, 1), Gr(lvl + 1, j, 1)));
+      }
       const int k1 = j + 1;                              // intervals k0 .. k1-1 can relax now
       if (k1 >= M || k1 % chunk != 0) continue;          // the last chunk stays on this lane, see below
-      hipEvent_t e = a.pipe[ev++ % PIPE_EVENTS];
+      hipEvent_t e = a.pipe[HALF + ev++ % HALF];
       HIPCHK(hipEventRecord(e, E->st));
       HIPCHK(hipStreamWaitEvent(E2->st, e, 0));
       STCHK(relax(E2, k0, k1));
@@ -898,10 +933,10 @@ struct Driver {
       HIPCHK(launch_resnorm(M, state_elems(), R, W(lvl, cf, cf), partial, max_partial, resnorm + iter, E->st));
     // g'_k = R_k - Phi'(w_{(k-1) cf}),  k = 1..M
     Rows Gn = {(const void* const*)(E ? tabG[lvl + 1] : nullptr), 1, 1};
+    if (E && E2 && g_pipeline && lvl + 1 == L - 1 && M >= 2 && cf >= 2)
+      return coarse_solve_with_relaxation(lvl, M, R, Gn);
     STCHK(step(lvl + 1, 0, 1, M, Gn, NO_ROWS));
     if (E) HIPCHK(launch_sub_rows(M, state_elems(), R, Gn, Gn, E->st));
-    if (E && E2 && g_pipeline && lvl + 1 == L - 1 && M >= 2 && cf >= 2)
-      return coarse_solve_with_relaxation(lvl, M);
     STCHK(vcycle(lvl + 1, iter, false));
     STCHK(f_relax(lvl, M));
     return MGRIT_OK;
