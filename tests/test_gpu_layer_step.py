@@ -107,6 +107,16 @@ def test_long_sequence_head_dimension_128_wide_blocks_bf16(arch):
         mb.lib().mgrit_debug_attention_wide_blocks(5)
 
 
+@pytest.mark.parametrize("d,H,f", [(2048, 16, 1024), (1280, 10, 512)])
+def test_widest_supported_model_bf16(d, H, f):
+    """d_model = 2048 is the documented maximum (eight 4-element vectors per lane in the LayerNorm kernels,
+    reduction length 2048 in the projections, d_head = 128); 1280 is a width that does not fill the last
+    vector of a row."""
+    wl = make(wls.ARCH_CAUSAL, wls.DTYPE_BF16, d=d, H=H, f=f, B=1, S=40)
+    run_forward_case(wl, G=2, hstep=0.5, with_rhs=True, weight_std=0.02, force_simple=0)
+    run_adjoint_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.02, force_simple=0)
+
+
 def test_forward_step_tiny_config_shape_fp32():
     """d=64, 4 heads of 16, f=256, S=32: the shape of the smallest benchmark configuration."""
     wl = wls.named_workloads()["tiny_encoder"]

@@ -169,3 +169,10 @@ def test_full_size_mt_decoder_sampled_layers_and_memory_gradient():
     e = relerr(dE.cpu().numpy(), omgrit.memory_gradient(list(lam), list(Y), dm.host, wl.h, sh, mem))
     print(f"  memory gradient: relative error {e:.2e} (bar {tol})", flush=True)
     assert e <= tol
+
+
+def test_wide_model_bf16():
+    """d_model = 1280 (five vectors per lane in the LayerNorm parameter sums, the last one partly filled),
+    d_head = 128."""
+    run_case(tiny(arch=wls.ARCH_ENCODER, dtype=wls.DTYPE_BF16, N=4, cf=2, levels=2, iters=1, h=0.5, d=1280, H=10,
+                  f=512, B=1, S=40), weight_std=0.02)
