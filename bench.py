@@ -20,6 +20,7 @@ import sys
 import time
 
 import numpy as np
+from ctypes import byref as C_byref
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
@@ -45,6 +46,7 @@ def parse():
                          "the line then says so in `metric` and in config.param_grads)")
     ap.add_argument("--attn-wide", type=int, default=-1,
                     help="tuning: mask of d_head=128 attention kernels with 256-row blocks (1 fwd, 2 dQ, 4 dK/dV)")
+    ap.add_argument("--pipe-chunk", type=int, default=0, help="tuning: intervals per hand-over of the coarse solve")
     ap.add_argument("--no-pipeline", action="store_true",
                     help="tuning: serial coarse solve and the following F-relaxation one after the other")
     ap.add_argument("--no-kernel-events", action="store_true",
@@ -107,6 +109,8 @@ def main():
         mb.mgrit_set_lanes(args.lanes)
     if args.attn_wide >= 0:
         mb.lib().mgrit_debug_attention_wide_blocks(args.attn_wide)
+    if args.pipe_chunk:
+        mb.lib().mgrit_debug_pipeline_chunk(args.pipe_chunk)
     if args.no_pipeline:
         mb.lib().mgrit_debug_pipeline_coarse_solve(0)
     if args.gemm_tile:
@@ -275,7 +279,8 @@ def main():
                    "batch": wl.batch, "seq": wl.seq, "N": wl.N, "h": wl.h, "cf": wl.cf, "levels": wl.levels,
                    "iters": wl.iters, "relax": "FCF" if wl.relax else "F", "adjoint": adjoint,
                    "phi_evaluations": n_phi, "psi_evaluations": n_psi,
-                   "max_groups_per_launch": args.max_groups or "default", "lanes": args.lanes or 2,
+                   "max_groups_per_launch": args.max_groups or mb.lib().mgrit_default_groups_per_launch(
+                       C_byref(desc), max(wl.N // wl.cf, 1)), "lanes": args.lanes or 2,
                    "param_grads": bool(grads),
                    **({"stacked": True, "n_enc": sw.n_enc, "src_seq": sw.enc.seq} if sw else {})},
         "residual_norms": {"forward": [float(x) for x in res_f.cpu()[:wl.iters]],

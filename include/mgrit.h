@@ -274,8 +274,12 @@ const char* mgrit_status_string(int status);
 int         mgrit_last_hip_error(void);          /* hipError_t of the last MGRIT_HIP_ERROR */
 
 /* Tuning knob: at most this many groups go into one kernel launch (larger sweeps
- * are split into chunks that run one after another).  0 restores the default. */
+ * are split into chunks that run one after another).  0 restores the default, which the library
+ * chooses per model and sweep width (3..6 for bf16 models: the count whose projection GEMMs fill
+ * their last round of tiles best; 4 for fp32); mgrit_default_groups_per_launch reports it for
+ * sweeps of `sweep` groups (opts->N / opts->cf intervals on level 0).  Host only. */
 void mgrit_set_max_groups_per_launch(int n);
+int  mgrit_default_groups_per_launch(const mgrit_model_desc* desc, int sweep);
 
 /* Tuning knob: 2 (default) lets the independent launch chunks of a sweep alternate between the
  * caller's stream and one helper stream, forked from and joined back into the caller's stream
@@ -316,6 +320,10 @@ void mgrit_debug_attention_wide_blocks(int mask);
 /* Tuning hook: 1 (default) overlaps the serial solve on the coarsest level with the F-relaxation
  * that follows it (needs the two lanes); 0 runs them one after the other.  Results are identical. */
 void mgrit_debug_pipeline_coarse_solve(int on);
+
+/* Tuning hook: intervals per hand-over of the overlapped coarse solve (0 = the launch chunk, the
+ * default; values above the launch chunk are ignored). */
+void mgrit_debug_pipeline_chunk(int n);
 
 #ifdef __cplusplus
 }

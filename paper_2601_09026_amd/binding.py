@@ -119,6 +119,10 @@ def lib() -> C.CDLL:
         L.mgrit_last_hip_error.restype = C.c_int
         L.mgrit_set_max_groups_per_launch.argtypes = [C.c_int]
         L.mgrit_set_max_groups_per_launch.restype = None
+        L.mgrit_default_groups_per_launch.argtypes = [C.POINTER(ModelDesc), C.c_int]
+        L.mgrit_default_groups_per_launch.restype = C.c_int
+        L.mgrit_debug_pipeline_chunk.argtypes = [C.c_int]
+        L.mgrit_debug_pipeline_chunk.restype = None
         L.mgrit_set_lanes.argtypes = [C.c_int]
         L.mgrit_set_lanes.restype = None
         L.mgrit_debug_force_simple_kernels.argtypes = [C.c_int, C.c_int]

@@ -552,7 +552,7 @@ static double gemm_bytes(const GemmArgs& a, double esz) {
 // operands, the time of a round hardly depends on how full it is, and relative to a round of
 // 256x256 tiles a round of 256x192 tiles takes 0.9 and a (double) round of 128x128 tiles 0.62:
 // pick the configuration with the cheapest sum of rounds.
-static int choose_tile_config(int n_groups, int M, int N) {
+static int choose_tile_config(int n_groups, int M, int N, double* cost_out = nullptr) {
   struct Cand { int cfg, bm, bn, occ; double round_cost; };
   static const Cand cands[] = {{1, 256, 256, 1, 1.0}, {3, 256, 192, 1, 0.9}, {4, 128, 128, 2, 0.62}};
   const long cus = compute_units();
@@ -565,7 +565,20 @@ static int choose_tile_config(int n_groups, int M, int N) {
     const double cost = rounds * c.round_cost;
     if (cost < best_cost) { best_cost = cost; best = c.cfg; }
   }
+  if (best == 2) {                                       // 256x128x32, two blocks per CU
+    const long tiles = (long)((M + 255) / 256) * ((N + 127) / 128) * n_groups;
+    best_cost = (double)((tiles + cus * 2 - 1) / (cus * 2));
+  }
+  if (cost_out) *cost_out = best_cost;
   return best;
+}
+
+// Modelled time of one grouped launch, in rounds of 256x256 tiles per 64 of reduction length (the
+// driver sizes its launch chunks with it).
+double gemm_model_cost(int n_groups, int M, int N, int K) {
+  double c = 0.0;
+  choose_tile_config(n_groups, M, N, &c);
+  return c * K / 64.0;
 }
 
 template <int EPI>

@@ -8,6 +8,7 @@ namespace mg {
 hipError_t launch_gemm(const GemmArgs& a, int epi, bool is_bf16, hipStream_t st);
 void gemm_force_simple(int on);
 void gemm_set_tile_config(int cfg);
+double gemm_model_cost(int n_groups, int M, int N, int K);
 void attn_set_wide_blocks(int mask);
 
 // ---- rowwise.hip -------------------------------------------------------------

@@ -37,7 +37,35 @@ thread_local int g_last_hip_error = 0;
 int g_max_groups = 0;                       // 0 = default
 constexpr int DEFAULT_MAX_GROUPS = 4;
 
-inline int max_groups() { return g_max_groups > 0 ? g_max_groups : DEFAULT_MAX_GROUPS; }
+// Groups per launch chunk for sweeps of `sweep` groups when the caller has not fixed it.  A launch
+// runs in whole rounds of tiles over the CUs, so the group count decides how full the last round of
+// every projection GEMM is (at d = 768, 5 groups of 4096 tokens make 240 tiles of 256x256 for the
+// d-wide outputs, one round; 4 groups need the smaller 256x192 tiles): take the count in 3..6 with the
+// smallest modelled GEMM time over the sweep, near-ties (1 %) going to the larger count.
+inline int default_groups(const mgrit_model_desc* md, int sweep) {
+  if (md->dtype != MGRIT_DTYPE_BF16 || sweep < 2) return DEFAULT_MAX_GROUPS;
+  const int T = md->batch * md->seq, d = md->d_model, f = md->d_ff;
+  double cost[7] = {0};
+  double best = 1e300;
+  for (int gc = 3; gc <= 6; ++gc) {
+    const int chunk = gc < (sweep + 1) / 2 ? gc : (sweep + 1) / 2;       // as run_chunks splits a sweep over two lanes
+    double c = 0.0;
+    for (int k = 0; k < sweep; k += chunk) {
+      const int n = sweep - k < chunk ? sweep - k : chunk;
+      c += gemm_model_cost(n, T, 3 * d, d) + gemm_model_cost(n, T, d, d) + gemm_model_cost(n, T, f, d) +
+           gemm_model_cost(n, T, d, f);
+    }
+    cost[gc] = c;
+    if (c < best) best = c;
+  }
+  int pick = DEFAULT_MAX_GROUPS;
+  for (int gc = 3; gc <= 6; ++gc)
+    if (cost[gc] <= 1.01 * best) pick = gc;
+  return pick;
+}
+inline int max_groups(const mgrit_model_desc* md, int sweep) {
+  return g_max_groups > 0 ? g_max_groups : default_groups(md, sweep);
+}
 
 #define HIPCHK(expr)                                   \
   do {                                                 \
@@ -283,6 +311,7 @@ AuxStream& aux_stream() {
 }
 int g_lanes = 2;                            // 1 = everything on the caller's stream
 int g_pipeline = 1;                         // overlap the serial coarse solve with the F-relaxation that follows it
+int g_pipe_chunk = 0;                       // intervals per hand-over (0 = the launch chunk)
 
 // Engine of the second lane: same model and shared buffers, own work buffers and stream.
 inline bool make_lane(Engine& E2, const Engine& E, Bump& b, bool adjoint, bool measure_only) {
@@ -843,7 +872,7 @@ struct Driver {
   // Same kernels on the same data as the sequential order: results are identical.
   int coarse_solve_with_relaxation(int lvl, int M, Rows R, Rows Gn) {
     AuxStream& a = aux_stream();
-    const int chunk = E2->Gc;
+    const int chunk = g_pipe_chunk > 0 && g_pipe_chunk < E2->Gc ? g_pipe_chunk : E2->Gc;
     const int n_chunks = (M + chunk - 1) / chunk;
     constexpr int HALF = PIPE_EVENTS / 2;                // events 0..HALF-1: right-hand sides; the others: hand-overs
     auto rhs_chunk = [&](Engine* lane, int g0, int n) -> int {
@@ -971,7 +1000,7 @@ int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, int mod
   const int N = op->N;
   const bool serial = serial_run(op);
   const int M0 = serial ? 1 : N / op->cf;
-  int gc = max_groups();
+  int gc = max_groups(md, M0);
   const int widest = adjoint ? (N > M0 ? N : M0) : M0;      // the cache pass batches over all N layers
   if (gc > widest) gc = widest;
   E.keep_z = mode == 2;
@@ -1056,7 +1085,7 @@ size_t mgrit_layer_step_workspace_bytes(const mgrit_model_desc* desc, int adjoin
   Engine E;
   E.init(desc, nullptr);
   Bump b(nullptr);
-  int gc = max_groups() < n_groups ? max_groups() : n_groups;
+  int gc = max_groups(desc, n_groups) < n_groups ? max_groups(desc, n_groups) : n_groups;
   Engine E2;
   if (adjoint) {
     E.carve_adjoint(b, gc, n_groups);
@@ -1219,7 +1248,7 @@ int make_stacked_plan(StackedPlan& P, const mgrit_model_desc* md, const mgrit_op
   const int N = op->N, n_dec = N - n_enc;
   const bool serial = serial_run(op);
   const int M0 = serial ? 1 : N / op->cf;
-  int gc = max_groups();
+  int gc = max_groups(md, M0);
   const int widest = adjoint ? (N > M0 ? N : M0) : M0;
   if (gc > widest) gc = widest;
   P.Ee.keep_z = P.Ed.keep_z = mode == 2;
@@ -1484,7 +1513,7 @@ int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups, 
   Engine E;
   E.init(desc, st);
   Bump b(workspace);
-  const int gc = max_groups() < n_groups ? max_groups() : n_groups;
+  const int gc = max_groups(desc, n_groups) < n_groups ? max_groups(desc, n_groups) : n_groups;
   const int G = n_groups;
   Engine E2;
   Engine* L2 = nullptr;
@@ -1541,6 +1570,10 @@ const char* mgrit_status_string(int status) {
 int mgrit_last_hip_error(void) { return g_last_hip_error; }
 
 void mgrit_set_max_groups_per_launch(int n) { g_max_groups = n > 0 ? n : 0; }
+int mgrit_default_groups_per_launch(const mgrit_model_desc* desc, int sweep) {
+  if (validate_desc(desc) != MGRIT_OK) return 0;
+  return default_groups(desc, sweep);
+}
 
 void mgrit_set_lanes(int n) { g_lanes = n >= 2 ? 2 : 1; }
 
@@ -1553,5 +1586,6 @@ void mgrit_debug_force_simple_kernels(int gemm, int attn) {
 void mgrit_debug_gemm_tile_config(int cfg) { gemm_set_tile_config(cfg); }
 void mgrit_debug_attention_wide_blocks(int mask) { attn_set_wide_blocks(mask); }
 void mgrit_debug_pipeline_coarse_solve(int on) { g_pipeline = on ? 1 : 0; }
+void mgrit_debug_pipeline_chunk(int n) { g_pipe_chunk = n > 0 ? n : 0; }
 
 }  // extern "C"
