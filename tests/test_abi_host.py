@@ -157,6 +157,30 @@ def test_stacked_grid_workspace_and_argument_checks():
                                    None) == -1
 
 
+def test_default_groups_per_launch_follow_the_tile_model():
+    """Without a caller's choice the launch chunk comes from the GEMM tile model: 3..6 groups for bf16
+    models (5 at d = 768, where five groups of 4096 tokens fill one round of 256x256 tiles for the d-wide
+    outputs), 4 for fp32, and the workspace is sized for it."""
+    L = mb.lib()
+    for name, wl in wls.named_workloads().items():
+        desc = mb.model_desc(wl)
+        g = L.mgrit_default_groups_per_launch(C.byref(desc), wl.N // wl.cf)
+        assert (g == 4) if wl.dtype == wls.DTYPE_F32 else (3 <= g <= 6), (name, g)
+    bert = mb.model_desc(wls.named_workloads()["bert_base"])
+    assert L.mgrit_default_groups_per_launch(C.byref(bert), 16) == 5
+    opts = mb.mgrit_opts(64, 1 / 64, 4, 2, 2)
+    auto = mb.mgrit_workspace_bytes(bert, opts, 0)
+    try:
+        mb.mgrit_set_max_groups_per_launch(5)
+        assert mb.mgrit_workspace_bytes(bert, opts, 0) == auto
+        mb.mgrit_set_max_groups_per_launch(3)
+        assert mb.mgrit_workspace_bytes(bert, opts, 0) < auto
+    finally:
+        mb.mgrit_set_max_groups_per_launch(0)
+    bad = mb.ModelDesc(0, 770, 12, 3072, 32, 128, 0, 1, 1e-5)
+    assert L.mgrit_default_groups_per_launch(C.byref(bad), 16) == 0
+
+
 def test_workspace_grows_with_groups_and_levels():
     desc = mb.model_desc(wls.named_workloads()["bert_base"])
     a = mb.mgrit_layer_step_workspace_bytes(desc, False, 1)
