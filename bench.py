@@ -8,7 +8,8 @@ all levels) x (batch*seq) / wall time, with all inputs resident in HBM before th
 region.  The adjoint's one-off N-layer linearisation pass is timed but not counted as
 evaluations.
 
-Prints ONE JSON line (see README / DESIGN.md for the fields).  Everything runs on one GPU;
+Prints ONE JSON line: metric, value, timing, the workload in `config`, `roofline` of the dominant
+kernel and `cpu_baseline` (the oracle timed on the host).  Everything runs on one GPU;
 --gpus above 1 is refused.
 """
 from __future__ import annotations
