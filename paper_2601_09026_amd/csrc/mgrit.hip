@@ -471,6 +471,7 @@ int linear_param_grads(Engine& E, int n, const void* dY, long dy_stride, Slots d
 struct GradPass {
   const Params* DT = nullptr;      // gradient blocks of the chunk's layers, or null
   float* dE_all = nullptr;         // cross-attention decoder: [layer slot, Tm, d] fp32 memory-gradient terms, or null
+  bool write_state = false;        // also finish the step (OUT written): a relaxation step that emits its layer's gradients
 };
 // Decoder step of a stacked encoder-decoder grid (paper section 3.1, eq. "fp_transformer"): the
 // memory of group g is the X part of its linearisation state, and the transposed step adds the
@@ -584,7 +585,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
       STCHK(linear_param_grads(E, n, E.dkvc, (long)E.Tm * 2 * d, loc, 2 * d, sd ? E.membG : E.memb,
                                sd ? (long)E.Tm * d : 0, loc, d, false, *DT, MGRIT_P_WKV_C, MGRIT_P_BKV_C, hstep, E.Tm));
     }
-    if (sd && !gp) {
+    if (sd && (!gp || gp->write_state)) {
       // lambda_X <- lambda_X + hstep * [dK | dV] Wkv_c (+ rhs)    [Tm,2d] x [2d,d]: transposed Wkv_c is [d,2d]
       g = gemm_base(n, E.Tm, d, 2 * d, E.dkvc, (long)E.Tm * 2 * d, loc, THT, L.offset[MGRIT_P_WKV_C], -1);
       g.X = sd->INX; g.OUT = sd->OUTX; g.RHS = sd->RHSX; g.hstep = hstep;
@@ -663,7 +664,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
     lp.gamma_off = E.glay.offset[MGRIT_P_LN1_G]; lp.beta_off = E.glay.offset[MGRIT_P_LN1_B];
     HIPCHK(launch_ln_param_grad(lp, E.gpart, E.bf16, E.st));
   }
-  if (gp) return MGRIT_OK;           // a gradient pass writes no state
+  if (gp && !gp->write_state) return MGRIT_OK;           // a pure gradient pass writes no state
 
   // dX = dX' + LN1^T du1 ;  OUT = c + hstep dX (+ RHS)
   memset(&lb, 0, sizeof(lb));
@@ -707,13 +708,23 @@ int forward_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Pa
   });
 }
 
+// emit: the steps also write the parameter gradients of their layers (DT, may be null) and the
+// memory-gradient terms (dE_all, may be null); the caller guarantees that IN holds final values
 int adjoint_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Params TH, Params THT, Rows LIN,
-                   Slots cs, float hstep, const StackedDec* sd = nullptr) {
+                   Slots cs, float hstep, const StackedDec* sd = nullptr, bool emit = false,
+                   const Params* DT = nullptr, float* dE_all = nullptr) {
   return run_chunks(E, E2, G, [&](Engine& L, int c0, int n) {
     StackedDec s;
     if (sd) s = shift(*sd, c0);
+    Params dt = {nullptr, 0, 0};
+    GradPass gp;
+    if (emit) {
+      if (DT) { dt = shift(*DT, c0); gp.DT = &dt; }
+      gp.dE_all = dE_all;
+      gp.write_state = true;
+    }
     return adjoint_chunk(L, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), shift(THT, c0),
-                         shift(LIN, c0), shift(cs, c0), hstep, nullptr, sd ? &s : nullptr);
+                         shift(LIN, c0), shift(cs, c0), hstep, emit ? &gp : nullptr, sd ? &s : nullptr);
   });
 }
 
@@ -834,6 +845,13 @@ struct Driver {
   }
 
   Engine* only = nullptr;          // when set, step() enqueues on this engine's stream alone (no fork / join)
+  // Parameter gradients (adjoint only): dtheta_n = h (dF/dtheta_n (Z_n))^T lambda_{n+1} needs the final
+  // lambda_{n+1}, which is exactly the input of the level-0 steps of the last cycle's closing
+  // F-relaxation (and of every step of a serial run): those steps emit their layer's gradients on
+  // the way (emit_final), the remaining N / cf layers get a pass of their own afterwards.
+  void** tabDT = nullptr;          // layer n -> gradient block, or null
+  float* dE_all = nullptr;         // per-layer memory-gradient terms, or null
+  bool want_grads = false, last_cycle = false, emit_now = false, emitted = false;
 
   // cnt steps of level `lvl`, group k starting at point j = j0 + k*js
   int step(int lvl, int j0, int js, int cnt, Rows OUT, Rows RHS) {
@@ -856,6 +874,12 @@ struct Driver {
     Params TH = {(const void* const*)tabTh, n0, ns};
     Params THT = {(const void* const*)tabThT, n0, ns};
     Rows LIN = {(const void* const*)tabZ, n0, ns};
+    if (emit_now && lvl == 0) {
+      emitted = true;
+      const Params DT = {(const void* const*)tabDT, n0, ns};
+      return adjoint_groups(L1, L2, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep, nullptr, true,
+                            tabDT ? &DT : nullptr, dE_all);
+    }
     return adjoint_groups(L1, L2, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep);
   }
 
@@ -900,10 +924,12 @@ struct Driver {
     }
     auto relax = [&](Engine* lane, int ka, int kb) -> int {   // F-relaxation of intervals ka .. kb-1 on one lane
       only = lane;
+      emit_now = want_grads && last_cycle && lvl == 0 && !Ed;
       int st = MGRIT_OK;
       for (int i = 0; i + 1 < cf && st == MGRIT_OK; ++i)
         st = step(lvl, ka * cf + i, cf, kb - ka, W(lvl, ka * cf + i + 1, cf), Gr(lvl, ka * cf + i + 1, cf));
       only = nullptr;
+      emit_now = false;
       return st;
     };
     int k0 = 0, ev = 0;
@@ -967,18 +993,27 @@ struct Driver {
     STCHK(step(lvl + 1, 0, 1, M, Gn, NO_ROWS));
     if (E) HIPCHK(launch_sub_rows(M, state_elems(), R, Gn, Gn, E->st));
     STCHK(vcycle(lvl + 1, iter, false));
-    STCHK(f_relax(lvl, M));
-    return MGRIT_OK;
+    emit_now = want_grads && last_cycle && lvl == 0 && !Ed;
+    const int st = f_relax(lvl, M);
+    emit_now = false;
+    return st;
   }
 
   int run(int iters) {
     if (L == 1 || cf == 1) {
-      for (int n = 0; n < N; ++n) STCHK(step(0, n, 1, 1, W(0, n + 1, 1), NO_ROWS));
-      return MGRIT_OK;
+      emit_now = want_grads && !Ed;
+      int st = MGRIT_OK;
+      for (int n = 0; n < N && st == MGRIT_OK; ++n) st = step(0, n, 1, 1, W(0, n + 1, 1), NO_ROWS);
+      emit_now = false;
+      return st;
     }
-    for (int it = 0; it < iters; ++it) STCHK(vcycle(0, it, it > 0));
+    for (int it = 0; it < iters; ++it) {
+      last_cycle = it == iters - 1;
+      STCHK(vcycle(0, it, it > 0));
+    }
     return MGRIT_OK;
   }
+  bool serial() const { return L == 1 || cf == 1; }
 };
 
 struct Plan {                       // workspace of mgrit_forward / mgrit_adjoint
@@ -1189,14 +1224,26 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
                             hipMemcpyDeviceToDevice, st));
   }
   D.resnorm = resnorm;
+  if (dtheta) HIPCHK(upload_pointers(P.tabDT, (const void* const*)dtheta, N, st));
+  D.tabDT = dtheta ? P.tabDT : nullptr;
+  D.dE_all = dmemory ? P.dE_all : nullptr;
+  D.want_grads = dtheta || dmemory;
   STCHK(D.run(opts->iters));
   if (dtheta || dmemory) {
-    // one batched pass over all layers: layer n takes lambda_{n+1} (point N-1-n of the reversed grid)
-    if (dtheta) HIPCHK(upload_pointers(P.tabDT, (const void* const*)dtheta, N, st));
-    Rows LamNext = {(const void* const*)D.tabW, N - 1, -1};
-    Params DT = {(const void* const*)P.tabDT, 0, 1};
-    STCHK(gradient_groups(E, D.E2, N, LamNext, TH, THT, Zrows, Slots{0, 1}, dtheta ? &DT : nullptr,
-                          dmemory ? P.dE_all : nullptr, opts->h));
+    // Layer n takes lambda_{n+1} (point N-1-n of the reversed grid).  The closing F-relaxation (a serial
+    // run: every step) has already emitted the layers whose lambda_{n+1} it read; one batched pass covers
+    // the others: with emission the layers n = 0, cf, 2 cf, .. (lambda_{n+1} is the last F-point of an
+    // interval), otherwise all of them.
+    const bool emitted = D.emitted;
+    const int stride = emitted ? opts->cf : 1;
+    const int count = emitted ? (D.serial() ? 0 : N / opts->cf) : N;
+    Rows LamNext = {(const void* const*)D.tabW, N - 1, -stride};
+    Params DT = {(const void* const*)P.tabDT, 0, stride};
+    const Params THs = {(const void* const*)D.tabTh, 0, stride}, THTs = {(const void* const*)D.tabThT, 0, stride};
+    const Rows Zs = {(const void* const*)D.tabZ, 0, stride};
+    if (count > 0)
+      STCHK(gradient_groups(E, D.E2, count, LamNext, THs, THTs, Zs, Slots{0, stride}, dtheta ? &DT : nullptr,
+                            dmemory ? P.dE_all : nullptr, opts->h));
     // dL/dE = sum over layers of the per-layer terms, in layer order
     if (dmemory)
       HIPCHK(launch_sum_slots(P.dE_all, N, (long)E.Tm * E.d, static_cast<float*>(dmemory), 1.0f, st));
