@@ -832,13 +832,16 @@ struct Driver {
       }
       Params THT = {(const void* const*)tabThT, nl, ns};
       Rows LIN = {(const void* const*)tabZ, nl, ns};
+      const bool emit = emit_now && tabDT != nullptr;         // see step(): these steps read final values
+      const Params DT = {(const void* const*)tabDT, nl, ns};
+      if (emit) emitted = true;
       if (enc) {
-        STCHK(adjoint_groups(Le, Le2, n, inx, outx, rhsx, TH, THT, LIN, Slots{nl, ns}, hstep));
+        STCHK(adjoint_groups(Le, Le2, n, inx, outx, rhsx, TH, THT, LIN, Slots{nl, ns}, hstep, nullptr, emit, &DT));
         HIPCHK(launch_add_rows(n, y_elems, iny, rhsy, outy, Le.st));
       } else {
         StackedDec sd = {LIN, inx, outx, rhsx};
         STCHK(adjoint_groups(Ld, Ld2, n, iny, outy, rhsy, TH, THT, part(LIN, x_elems), Slots{nl - n_enc, ns}, hstep,
-                             &sd));
+                             &sd, emit, &DT));
       }
     }
     return MGRIT_OK;
@@ -864,7 +867,11 @@ struct Driver {
     Rows IN = {(const void* const*)tabW, j0 * s, js * s};
     if (Ed) {
       if (!adjoint) return step_stacked(cnt, j0 * s, js * s, IN, OUT, RHS, hstep);
-      return step_stacked(cnt, N - (j0 + 1) * s, -js * s, IN, OUT, RHS, hstep);
+      const bool keep = emit_now;
+      emit_now = keep && lvl == 0;
+      const int st = step_stacked(cnt, N - (j0 + 1) * s, -js * s, IN, OUT, RHS, hstep);
+      emit_now = keep;
+      return st;
     }
     if (!adjoint) {
       Params TH = {(const void* const*)tabTh, j0 * s, js * s};
@@ -924,7 +931,7 @@ struct Driver {
     }
     auto relax = [&](Engine* lane, int ka, int kb) -> int {   // F-relaxation of intervals ka .. kb-1 on one lane
       only = lane;
-      emit_now = want_grads && last_cycle && lvl == 0 && !Ed;
+      emit_now = want_grads && last_cycle && lvl == 0;
       int st = MGRIT_OK;
       for (int i = 0; i + 1 < cf && st == MGRIT_OK; ++i)
         st = step(lvl, ka * cf + i, cf, kb - ka, W(lvl, ka * cf + i + 1, cf), Gr(lvl, ka * cf + i + 1, cf));
@@ -993,7 +1000,7 @@ struct Driver {
     STCHK(step(lvl + 1, 0, 1, M, Gn, NO_ROWS));
     if (E) HIPCHK(launch_sub_rows(M, state_elems(), R, Gn, Gn, E->st));
     STCHK(vcycle(lvl + 1, iter, false));
-    emit_now = want_grads && last_cycle && lvl == 0 && !Ed;
+    emit_now = want_grads && last_cycle && lvl == 0;
     const int st = f_relax(lvl, M);
     emit_now = false;
     return st;
@@ -1001,7 +1008,7 @@ struct Driver {
 
   int run(int iters) {
     if (L == 1 || cf == 1) {
-      emit_now = want_grads && !Ed;
+      emit_now = want_grads;
       int st = MGRIT_OK;
       for (int n = 0; n < N && st == MGRIT_OK; ++n) st = step(0, n, 1, 1, W(0, n + 1, 1), NO_ROWS);
       emit_now = false;
@@ -1428,17 +1435,33 @@ int mgrit_adjoint_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, 
                             hipMemcpyDeviceToDevice, st));
   }
   D.resnorm = resnorm;
+  if (dtheta) HIPCHK(upload_pointers(P.tabDT, (const void* const*)dtheta, N, st));
+  D.tabDT = dtheta ? P.tabDT : nullptr;
+  D.want_grads = dtheta != nullptr;
   STCHK(D.run(opts->iters));
   if (dtheta) {
-    // layer n takes lambda_{n+1}: point N-1-n of the reversed grid
-    HIPCHK(upload_pointers(P.tabDT, (const void* const*)dtheta, N, st));
-    const Rows LamNext = {(const void* const*)D.tabW, N - 1, -1};
-    const Params DT = {(const void* const*)P.tabDT, 0, 1};
-    STCHK(gradient_groups(P.Ee, D.E2, n_enc, LamNext, TH, THT, Zrows, Slots{0, 1}, &DT, nullptr, opts->h));
-    const Params DTd = shift(DT, n_enc);
-    StackedDec sd = {ZdecX, NO_ROWS, NO_ROWS, NO_ROWS};
-    STCHK(gradient_groups(P.Ed, D.Ed2, n_dec, Driver::part(shift(LamNext, n_enc), D.x_elems), shift(TH, n_enc),
-                          shift(THT, n_enc), ZdecY, Slots{0, 1}, &DTd, nullptr, opts->h, &sd));
+    // Layer n takes lambda_{n+1}: point N-1-n of the reversed grid.  After the closing F-relaxation has
+    // emitted the layers whose lambda_{n+1} it read, the layers n = 0, cf, 2 cf, .. are left (all of them
+    // without emission; none after a serial run): the encoder layers among them, then the decoder layers.
+    const bool emitted = D.emitted;
+    const int stride = emitted ? opts->cf : 1;
+    const int count = emitted ? (D.serial() ? 0 : N / opts->cf) : N;
+    int count_e = (n_enc + stride - 1) / stride;           // groups g with g * stride < n_enc
+    if (count_e > count) count_e = count;
+    const Rows LamNext = {(const void* const*)D.tabW, N - 1, -stride};
+    const Params DT = {(const void* const*)P.tabDT, 0, stride};
+    const Params THs = {(const void* const*)D.tabTh, 0, stride}, THTs = {(const void* const*)D.tabThT, 0, stride};
+    const Rows Zs = {(const void* const*)D.tabZ, 0, stride};
+    if (count_e > 0)
+      STCHK(gradient_groups(P.Ee, D.E2, count_e, LamNext, THs, THTs, Zs, Slots{0, stride}, &DT, nullptr, opts->h));
+    if (count - count_e > 0) {
+      const Params DTd = shift(DT, count_e);
+      const Rows Zx = shift(Zs, count_e);
+      StackedDec sd = {Zx, NO_ROWS, NO_ROWS, NO_ROWS};
+      STCHK(gradient_groups(P.Ed, D.Ed2, count - count_e, Driver::part(shift(LamNext, count_e), D.x_elems),
+                            shift(THs, count_e), shift(THTs, count_e), Driver::part(Zx, D.x_elems),
+                            Slots{count_e * stride - n_enc, stride}, &DTd, nullptr, opts->h, &sd));
+    }
   }
   return MGRIT_OK;
 }

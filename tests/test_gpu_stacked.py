@@ -102,15 +102,15 @@ def test_two_level_fp32(relax):
 def test_switch_inside_a_coarse_interval_three_levels_fp32():
     """n_enc = 6 is neither a C-point of level 0 (cf = 2: it is) nor of level 1 (multiples of 4):
     a coarse step that starts at layer 4 is an encoder step of size 4 h."""
-    run_case(stacked(n_enc=6, n_dec=10, cf=2, levels=3))
+    run_case(stacked(n_enc=6, n_dec=10, cf=2, levels=3), grads=True)
 
 
 def test_unaligned_switch_chunked_single_lane_fp32():
-    run_case(stacked(n_enc=5, n_dec=11, cf=4, levels=2), max_groups=3, lanes=1)
+    run_case(stacked(n_enc=5, n_dec=11, cf=4, levels=2), max_groups=3, lanes=1, grads=True)
 
 
 def test_serial_limit_fp32():
-    run_case(stacked(n_enc=3, n_dec=4, cf=4, levels=1, iters=1))
+    run_case(stacked(n_enc=3, n_dec=4, cf=4, levels=1, iters=1), grads=True)
 
 
 def test_parameter_gradients_fp32():
