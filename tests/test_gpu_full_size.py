@@ -30,6 +30,15 @@ def golden(name):
     return json.load(open(GOLDEN)).get(name)
 
 
+def check_norms(what, got, ref, tol, increment_norm):
+    """Stored oracle residual norms against the library's: 10 x the tolerance relative, plus the resolution
+    floor of the arithmetic, tol x |w_N - w_0| (a residual is the difference of two propagator evaluations,
+    each granted tol x its increment: see check_resnorms in test_gpu_mgrit.py); late norms of a fast-converging
+    run (the third of the ViT configuration) lie below it."""
+    for i, r in enumerate(ref):
+        assert abs(got[i] - r) <= 10 * tol * r + tol * increment_norm, f"{what} resnorm[{i}]: {got[i]} vs oracle {r}"
+
+
 def rows_of(wl, b, seq=None):
     s = wl.seq if seq is None else seq
     return slice(b * s, (b + 1) * s)
@@ -77,8 +86,7 @@ def run_full(name, fwd_seqs, adj_seqs, memory=None, memory_host=None, prefix=Non
     gold = golden(name)
     rg_host = rg.cpu().numpy()
     if gold is not None:
-        for i, r in enumerate(gold["forward"]):
-            assert abs(rg_host[i] - r) <= 10 * tol * r, f"forward resnorm[{i}]: {rg_host[i]} vs oracle {r}"
+        check_norms("forward", rg_host, gold["forward"], tol, gold["increment_norm"])
     else:
         print("  (no stored oracle residual norms for this workload: norms not compared)")
     assert all(rg_host[i + 1] < rg_host[i] for i in range(wl.iters - 1)), "residual norms must decrease"
@@ -100,8 +108,9 @@ def run_full(name, fwd_seqs, adj_seqs, memory=None, memory_host=None, prefix=Non
             check_sequence(f"lambda(seq {b})", got, lr, wl.N, tol, {"far": 0, "mid": wl.N // 2})
         ag_host = ag.cpu().numpy()
         if gold is not None and "adjoint" in gold:
-            for i, r in enumerate(gold["adjoint"]):
-                assert abs(ag_host[i] - r) <= 10 * tol * r, f"adjoint resnorm[{i}]: {ag_host[i]} vs oracle {r}"
+            # scale of the floor: the adjoint's own total increment (the stored file holds the forward one only)
+            inc = float(torch.linalg.vector_norm((lg[0] - lg[wl.N]).double()))
+            check_norms("adjoint", ag_host, gold["adjoint"], tol, inc)
     return Zg, lg
 
 
@@ -141,8 +150,8 @@ def test_full_gpt2_small_adjoint_residuals_and_samples():
     assert ag_host[1] < ag_host[0]
     gold = golden("gpt2_small")
     if gold is not None and "adjoint" in gold:
-        for i, r in enumerate(gold["adjoint"]):
-            assert abs(ag_host[i] - r) <= 10 * tol * r, f"adjoint resnorm[{i}]: {ag_host[i]} vs oracle {r}"
+        inc = float(torch.linalg.vector_norm((lg[0] - lg[wl.N]).double()))
+        check_norms("adjoint", ag_host, gold["adjoint"], tol, inc)
     # after the closing F-relaxation every F-point satisfies lambda_n = Psi(lambda_{n+1}; Z_n) exactly
     sh1 = tode.Shape(wl.arch, wl.d_model, wl.n_heads, 1, wl.seq, 0, wl.ln_eps)
     b = 2
