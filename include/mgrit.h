@@ -284,9 +284,11 @@ int  mgrit_default_groups_per_launch(const mgrit_model_desc* desc, int sweep);
 /* Tuning knob: 2 (default) lets the independent launch chunks of a sweep alternate between the
  * caller's stream and one helper stream, forked from and joined back into the caller's stream
  * with events before the call's remaining work is enqueued (stream-ordered semantics for the
- * caller are unchanged); 1 keeps everything on the caller's stream.  The helper stream and its
- * two events are created once per process on first use.  Both knobs change the workspace
- * size: set them before querying it. */
+ * caller are unchanged); with two lanes the serial solve on the coarsest level also overlaps the
+ * right-hand sides before it and the F-relaxation after it, handed over chunk by chunk through
+ * events (same results, bit for bit); 1 keeps everything on the caller's stream.  The helper
+ * stream and its events (34, no timing) are created once per process on first use.  Both knobs
+ * change the workspace size: set them before querying it. */
 void mgrit_set_lanes(int n);
 
 /* ---- instrumentation (benchmark and tests; not needed for normal use) ------------------

@@ -289,7 +289,8 @@ struct Engine {
 // Second lane: independent chunks of a sweep alternate between the caller's stream and one
 // helper stream (forked from and joined back into the caller's stream with events), so that
 // the bandwidth-bound kernels of one chunk overlap the matrix kernels of the other.  The
-// helper stream and its two events are created once per process, on first use.
+// helper stream and its events (fork, join and a pool for the hand-overs of the overlapped coarse
+// solve) are created once per process, on first use.
 constexpr int PIPE_EVENTS = 32;
 struct AuxStream {
   hipStream_t s = nullptr;
