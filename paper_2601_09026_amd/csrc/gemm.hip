@@ -45,6 +45,23 @@ __device__ __forceinline__ EpiPtrs resolve_epi(const GemmArgs& a, int g, int epi
   return p;
 }
 
+// Epilogue operands and outputs are touched once per launch: they are moved with the
+// non-temporal hint, so that they do not displace the operand panels that the tiles running
+// on an XCD share through its L2.
+template <typename T> __device__ __forceinline__ void estore4(T* p, f32x4 v);
+template <> __device__ __forceinline__ void estore4<float>(float* p, f32x4 v) { st_stream(reinterpret_cast<f32x4*>(p), v); }
+template <> __device__ __forceinline__ void estore4<bf16>(bf16* p, f32x4 v) {
+  bf16x4 r = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
+  st_stream(reinterpret_cast<bf16x4*>(p), r);
+}
+template <typename T> __device__ __forceinline__ f32x4 eload4(const T* p);
+template <> __device__ __forceinline__ f32x4 eload4<float>(const float* p) { return ld_stream(reinterpret_cast<const f32x4*>(p)); }
+template <> __device__ __forceinline__ f32x4 eload4<bf16>(const bf16* p) {
+  bf16x4 v = ld_stream(reinterpret_cast<const bf16x4*>(p));
+  f32x4 r = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+  return r;
+}
+
 template <int EPI, typename TO>
 __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restrict__ out_f32,
                                        TO* __restrict__ z_out, const TO* __restrict__ z_in,
@@ -52,36 +69,36 @@ __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restric
                                        const float* __restrict__ ybar, const float* __restrict__ RHS,
                                        float* __restrict__ OUT, float hstep, long idx, f32x4 acc) {
   if constexpr (EPI == EPI_STORE) {
-    store4<TO>(out_op + idx, acc);
+    estore4<TO>(out_op + idx, acc);
   } else if constexpr (EPI == EPI_STORE_F32) {
-    store4<float>(out_f32 + idx, hstep * acc);
+    estore4<float>(out_f32 + idx, hstep * acc);
   } else if constexpr (EPI == EPI_GELU) {
-    if (z_out) store4<TO>(z_out + idx, acc);
+    if (z_out) estore4<TO>(z_out + idx, acc);
     f32x4 y = {gelu_t<TO>(acc[0]), gelu_t<TO>(acc[1]), gelu_t<TO>(acc[2]), gelu_t<TO>(acc[3])};
-    store4<TO>(out_op + idx, y);
+    estore4<TO>(out_op + idx, y);
   } else if constexpr (EPI == EPI_GELU_PRIME) {
-    if (z_out) store4<TO>(z_out + idx, acc);
+    if (z_out) estore4<TO>(z_out + idx, acc);
     f32x4 y = {gelu_prime_t<TO>(acc[0]), gelu_prime_t<TO>(acc[1]), gelu_prime_t<TO>(acc[2]),
                gelu_prime_t<TO>(acc[3])};
-    store4<TO>(out_op + idx, y);
+    estore4<TO>(out_op + idx, y);
   } else if constexpr (EPI == EPI_DGELU) {
-    store4<TO>(out_op + idx, acc * load4<TO>(z_in + idx));
+    estore4<TO>(out_op + idx, acc * eload4<TO>(z_in + idx));
   } else if constexpr (EPI == EPI_RESID_INNER) {
-    if (base) acc += *reinterpret_cast<const f32x4*>(base + idx);
-    store4<float>(out_f32 + idx, acc);
+    if (base) acc += eload4<float>(base + idx);
+    estore4<float>(out_f32 + idx, acc);
   } else if constexpr (EPI == EPI_RESID_OUTER) {
-    f32x4 x = *reinterpret_cast<const f32x4*>(X + idx);
-    if (ybar) acc += *reinterpret_cast<const f32x4*>(ybar + idx);
+    f32x4 x = eload4<float>(X + idx);
+    if (ybar) acc += eload4<float>(ybar + idx);
     f32x4 r = x + hstep * acc;
-    if (RHS) r += *reinterpret_cast<const f32x4*>(RHS + idx);
-    store4<float>(OUT + idx, r);
+    if (RHS) r += eload4<float>(RHS + idx);
+    estore4<float>(OUT + idx, r);
   }
 }
 
 // 8 consecutive columns of a bf16 output (the epilogues whose operands are all bf16)
 __device__ __forceinline__ void store8(bf16* p, f32x4 a, f32x4 b) {
   bf16x8 r = {(bf16)a[0], (bf16)a[1], (bf16)a[2], (bf16)a[3], (bf16)b[0], (bf16)b[1], (bf16)b[2], (bf16)b[3]};
-  *reinterpret_cast<bf16x8*>(p) = r;
+  st_stream(reinterpret_cast<bf16x8*>(p), r);
 }
 template <int EPI>
 __device__ __forceinline__ void apply8(bf16* __restrict__ out, bf16* __restrict__ z_out,
@@ -99,7 +116,7 @@ __device__ __forceinline__ void apply8(bf16* __restrict__ out, bf16* __restrict_
     for (int r = 0; r < 4; ++r) { a[r] = gelu_prime_fast(a[r]); b[r] = gelu_prime_fast(b[r]); }
     store8(out + idx, a, b);
   } else if constexpr (EPI == EPI_DGELU) {
-    const bf16x8 g = *reinterpret_cast<const bf16x8*>(z_in + idx);
+    const bf16x8 g = ld_stream(reinterpret_cast<const bf16x8*>(z_in + idx));
 #pragma unroll
     for (int r = 0; r < 4; ++r) { a[r] *= (float)g[r]; b[r] *= (float)g[4 + r]; }
     store8(out + idx, a, b);

@@ -7,6 +7,15 @@
 #include "prof.h"
 
 namespace mg {
+// streamed inputs (read once per launch): non-temporal loads; outputs are stored normally, the
+// next kernel of the chain reads them
+template <typename T> __device__ __forceinline__ f32x4 rload4(const T* p);
+template <> __device__ __forceinline__ f32x4 rload4<float>(const float* p) { return ld_stream(reinterpret_cast<const f32x4*>(p)); }
+template <> __device__ __forceinline__ f32x4 rload4<bf16>(const bf16* p) {
+  bf16x4 v = ld_stream(reinterpret_cast<const bf16x4*>(p));
+  f32x4 r = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+  return r;
+}
 
 // One 64-lane wavefront walks token rows with a grid stride and keeps the next row's loads
 // in flight while it reduces and writes the current one (few long-lived waves instead of one
@@ -18,8 +27,8 @@ constexpr int LN_BWD_BLOCKS_PER_CU = 16;   // the VJP likewise once it no longer
 // LN input = state row (optional) + packed fp32 addend (optional); at least one is present
 __device__ __forceinline__ f32x4 load_sum(const float* x, const float* xa, int c) {
   f32x4 v = {0.f, 0.f, 0.f, 0.f};
-  if (x) v = *reinterpret_cast<const f32x4*>(x + c);
-  if (xa) v += *reinterpret_cast<const f32x4*>(xa + c);
+  if (x) v = ld_stream(reinterpret_cast<const f32x4*>(x + c));
+  if (xa) v += ld_stream(reinterpret_cast<const f32x4*>(xa + c));
   return v;
 }
 
@@ -163,7 +172,7 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         const int c = (i * LPR + lane) * 4;
-        if (c < d) { v[i] = load4<TO>(xh + c); w[i] = load4<TO>(dy + c); }
+        if (c < d) { v[i] = rload4<TO>(xh + c); w[i] = rload4<TO>(dy + c); }
       }
     } else {
       const float* x = a.X.present() ? a.X.at(g) + ro : nullptr;
@@ -171,7 +180,7 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         const int c = (i * LPR + lane) * 4;
-        if (c < d) { v[i] = load_sum(x, xa, c); w[i] = load4<TO>(dy + c); }
+        if (c < d) { v[i] = load_sum(x, xa, c); w[i] = rload4<TO>(dy + c); }
       }
     }
   };
@@ -223,15 +232,15 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
       const int c = (i * LPR + lane) * 4;
       if (c < d) {
         f32x4 r = rstd * (w[i] - m1 - v[i] * m2);
-        if (add) r += *reinterpret_cast<const f32x4*>(add + c);
+        if (add) r += ld_stream(reinterpret_cast<const f32x4*>(add + c));
         if (of) *reinterpret_cast<f32x4*>(of + c) = r;
-        if (oo && cop) store4<TO>(oo + c, load4<TO>(cop + c) + r);
+        if (oo && cop) store4<TO>(oo + c, rload4<TO>(cop + c) + r);
         if (need_c) {
           f32x4 cc = *reinterpret_cast<const f32x4*>(cvec + c);
           if (oo && !cop) store4<TO>(oo + c, cc + r);
           if (OUT) {
             f32x4 res = cc + a.hstep * r;
-            if (RHS) res += *reinterpret_cast<const f32x4*>(RHS + c);
+            if (RHS) res += ld_stream(reinterpret_cast<const f32x4*>(RHS + c));
             *reinterpret_cast<f32x4*>(OUT + c) = res;
           }
         }
@@ -289,7 +298,7 @@ __global__ void __launch_bounds__(256) cast_rows_kernel(long elems, Rows X, TO* 
   const float* x = X.at(g);
   TO* o = out + out_slots.of(g) * out_slot_stride;
   for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (long)gridDim.x * 256 * 4)
-    store4<TO>(o + i, *reinterpret_cast<const f32x4*>(x + i));
+    store4<TO>(o + i, ld_stream(reinterpret_cast<const f32x4*>(x + i)));
 }
 
 hipError_t launch_cast_rows(int n_groups, long elems, Rows X, void* out, long out_slot_stride,
@@ -310,7 +319,7 @@ hipError_t launch_cast_rows(int n_groups, long elems, Rows X, void* out, long ou
 template <typename TO>
 __global__ void __launch_bounds__(256) cast_flat_kernel(const float* in, TO* out, long elems) {
   for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (long)gridDim.x * 256 * 4)
-    store4<TO>(out + i, *reinterpret_cast<const f32x4*>(in + i));
+    store4<TO>(out + i, ld_stream(reinterpret_cast<const f32x4*>(in + i)));
 }
 
 hipError_t launch_cast_flat(const float* in, void* out, long elems, bool is_bf16, hipStream_t st) {
@@ -332,7 +341,7 @@ __global__ void __launch_bounds__(256) sub_rows_kernel(long elems, Rows A, Rows 
   float* pd = D.at(g);
   for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (long)gridDim.x * 256 * 4)
     *reinterpret_cast<f32x4*>(pd + i) =
-        *reinterpret_cast<const f32x4*>(pa + i) - *reinterpret_cast<const f32x4*>(pb + i);
+        ld_stream(reinterpret_cast<const f32x4*>(pa + i)) - ld_stream(reinterpret_cast<const f32x4*>(pb + i));
 }
 
 hipError_t launch_sub_rows(int n_groups, long elems, Rows A, Rows B, Rows D, hipStream_t st) {
@@ -351,8 +360,8 @@ __global__ void __launch_bounds__(256) add_rows_kernel(long elems, Rows A, Rows 
   const float* pb = B.present() ? B.at(g) : nullptr;
   float* pd = D.at(g);
   for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (long)gridDim.x * 256 * 4) {
-    f32x4 v = *reinterpret_cast<const f32x4*>(pa + i);
-    if (pb) v += *reinterpret_cast<const f32x4*>(pb + i);
+    f32x4 v = ld_stream(reinterpret_cast<const f32x4*>(pa + i));
+    if (pb) v += ld_stream(reinterpret_cast<const f32x4*>(pb + i));
     *reinterpret_cast<f32x4*>(pd + i) = v;
   }
 }
@@ -378,7 +387,7 @@ __global__ void __launch_bounds__(256) resnorm_partial_kernel(long elems, Rows A
   double acc = 0.0;
   int cnt = 0;
   for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (long)gridDim.x * 256 * 4) {
-    f32x4 e = *reinterpret_cast<const f32x4*>(pa + i) - *reinterpret_cast<const f32x4*>(pb + i);
+    f32x4 e = ld_stream(reinterpret_cast<const f32x4*>(pa + i)) - ld_stream(reinterpret_cast<const f32x4*>(pb + i));
     s += (e[0] * e[0] + e[1] * e[1]) + (e[2] * e[2] + e[3] * e[3]);
     if (++cnt == 64) { acc += (double)s; s = 0.f; cnt = 0; }
   }
