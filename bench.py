@@ -226,7 +226,21 @@ def main():
                         "flop_per_launch": fl / n,
                         "algorithmic_bytes_per_launch": sum(v["bytes"] for v in gemm) / n,
                         "share_of_instrumented_step_time": ms / args.steps / events_ms_per_step,
-                        "instrumented_ms_per_step": events_ms_per_step}
+                        "instrumented_ms_per_step": events_ms_per_step,
+                        # the launches over several groups (relaxation sweeps) and the single-group ones
+                        # of the serial coarse chain, each by epilogue
+                        "by_class": {k: {"TFLOPs": v["flops"] / (v["ms"] * 1e-3) / 1e12,
+                                         "launches_per_step": v["launches"] / args.steps,
+                                         "avg_launch_us": v["ms"] * 1e3 / v["launches"]}
+                                     for k, v in sorted(totals.items()) if k.startswith("gemm_mfma") and v["ms"] > 0}}
+            for part, pre in (("sweeps", "gemm_mfma_"), ("coarse_chain", "gemm_mfma_single_")):
+                sel = [v for k, v in totals.items()
+                       if k.startswith(pre) and (part == "coarse_chain" or not k.startswith("gemm_mfma_single_"))]
+                if sel and sum(v["ms"] for v in sel) > 0:
+                    p_ach = sum(v["flops"] for v in sel) / (sum(v["ms"] for v in sel) * 1e-3) / 1e12
+                    roofline[part] = {"achieved": p_ach, "frac": p_ach / PEAK_BF16_TFLOPS,
+                                      "launches_per_step": sum(v["launches"] for v in sel) / args.steps,
+                                      "ms_per_step": sum(v["ms"] for v in sel) / args.steps}
         else:
             gen = totals.get("gemm_generic")
             if gen:

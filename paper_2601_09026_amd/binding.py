@@ -227,6 +227,9 @@ PROFILE_CLASSES = {0: "gemm_generic", 1: "attn_fwd", 2: "attn_bwd", 3: "ln_fwd",
                    8: "gemm_mfma_store", 9: "gemm_mfma_gelu", 10: "gemm_mfma_sublayer_sum",
                    11: "gemm_mfma_euler", 12: "gemm_mfma_dgelu", 13: "gemm_mfma_store_f32",
                    14: "gemm_mfma_gelu_prime"}
+# the same epilogues launched over a single group (the serial coarse chain)
+PROFILE_CLASSES.update({c + 8: n.replace("gemm_mfma_", "gemm_mfma_single_") for c, n in list(PROFILE_CLASSES.items())
+                        if c >= 8})
 
 
 def mgrit_profile_enable(max_records: int) -> None:

@@ -605,7 +605,8 @@ static hipError_t launch_epi(const GemmArgs& a, bool is_bf16, hipStream_t st) {
   // the MFMA kernel needs whole 64-deep k-tiles and 128-wide column tiles, and 32-bit element offsets
   const bool mfma_ok = is_bf16 && !g_force_simple && (a.K % 64 == 0) && (a.N % 128 == 0) &&
                        (double)a.M * a.K < 4e9 && (double)a.N * a.K < 4e9;
-  ProfScope ps(mfma_ok ? PC_GEMM_MFMA + EPI : PC_GEMM_SIMPLE, flops, gemm_bytes<EPI>(a, is_bf16 ? 2 : 4), st);
+  const int cls = mfma_ok ? (a.n_groups > 1 ? PC_GEMM_MFMA : PC_GEMM_MFMA_SINGLE) + EPI : PC_GEMM_SIMPLE;
+  ProfScope ps(cls, flops, gemm_bytes<EPI>(a, is_bf16 ? 2 : 4), st);
   if (!is_bf16) return launch_simple<float, EPI>(a, st);
   if (!mfma_ok) return launch_simple<bf16, EPI>(a, st);
   int cfg = g_tile_cfg;
