@@ -90,6 +90,9 @@ __device__ __forceinline__ f32x16 zero16() {
   for (int i = 0; i < 16; ++i) z[i] = 0.f;
   return z;
 }
+// 2^x as the bare hardware instruction: the library routine wraps it in a range reduction for
+// results below 2^-126, which a probability that small does not need (it is 0 in bf16 anyway)
+__device__ __forceinline__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 
 struct HeadPtrs {
@@ -200,13 +203,13 @@ __global__ void __launch_bounds__(NW * 64, (fa_fwd_blocks<DH, NW>())) attn_fwd_m
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
     const float mn = fmaxf(m, mloc * c);
     const float ms = mn == -INFINITY ? 0.f : mn;         // fully masked so far: keep exp2 finite
-    const float corr = exp2f(m - ms);
+    const float corr = exp2_raw(m - ms);
     float lsum = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const float p = exp2f(fmaf(s[kt][i], c, -ms));
+        const float p = exp2_raw(fmaf(s[kt][i], c, -ms));
         s[kt][i] = p;
         lsum += p;
       }
@@ -293,13 +296,13 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, f
       }
       if (full) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] = exp2f(fmaf(s[i], c, -lse2)) * (dp[i] - Dq);      // dA^T
+        for (int i = 0; i < 16; ++i) s[i] = exp2_raw(fmaf(s[i], c, -lse2)) * (dp[i] - Dq);      // dA^T
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int key = k0 + 32 * kt + 8 * (i >> 2) + 4 * lh + (i & 3);
           const bool valid = key < a.Sk && (!a.causal || key <= qi);
-          const float p = valid ? exp2f(fmaf(s[i], c, -lse2)) : 0.f;
+          const float p = valid ? exp2_raw(fmaf(s[i], c, -lse2)) : 0.f;
           s[i] = p * (dp[i] - Dq);
         }
       }
@@ -378,7 +381,7 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int ql = 32 * qt + 8 * (i >> 2) + 4 * lh + (i & 3);
-          const float p = exp2f(fmaf(s[i], c, -Ls[ql]));
+          const float p = exp2_raw(fmaf(s[i], c, -Ls[ql]));
           s[i] = p;
           dp[i] = p * (dp[i] - Ds[ql]);
         }
@@ -388,7 +391,7 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
           const int ql = 32 * qt + 8 * (i >> 2) + 4 * lh + (i & 3);
           const int qq = i0 + ql;
           const bool valid = qq < a.Sq && kj < a.Sk && (!a.causal || kj <= qq);
-          const float p = valid ? exp2f(fmaf(s[i], c, -Ls[ql])) : 0.f;
+          const float p = valid ? exp2_raw(fmaf(s[i], c, -Ls[ql])) : 0.f;
           s[i] = p;
           dp[i] = p * (dp[i] - Ds[ql]);
         }
