@@ -317,7 +317,7 @@ void mgrit_debug_gemm_tile_config(int cfg);
 
 /* Tuning hook: which attention kernels use 256-row blocks on long sequences.  Bits 0-2: forward,
  * dQ pass, dK/dV pass at d_head = 128 (sequences of 1024 tokens or more); bits 4-6: the same at
- * d_head = 64 (512 tokens or more; measured slower, off by default).  Default 5; 0 keeps 128-row
+ * d_head = 64 (512 tokens or more; measured slower, off by default).  Default 7; 0 keeps 128-row
  * blocks everywhere. */
 void mgrit_debug_attention_wide_blocks(int mask);
 

@@ -323,12 +323,13 @@ template <int DH> constexpr int bwd_dq_lds() { return 2 * 64 * fa_ld<DH>() + DH 
 template <int DH> constexpr int bwd_dkv_lds() { return 2 * 64 * fa_ld<DH>() + 2 * DH * FA_LDT; }
 
 // d_local: if not null, D of the block's query rows is also left there (index = row - q0)
-template <int NW, int DH>
+// DB: `lds` holds two sets of tiles; the next key tile is fetched while the current one is used
+// and written after it, one barrier per tile
+template <int NW, int DH, bool DB = false>
 __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, float* d_local) {
   constexpr int KS = DH / 16, DT = DH / 32, FA_LD = fa_ld<DH>();
-  bf16* Ks = lds;                        // [key][d]
-  bf16* Vs = Ks + 64 * FA_LD;            // [key][d]
-  bf16* Kt = Vs + 64 * FA_LD;            // [d][key]
+  // one set of tiles: K [key][d], V [key][d], K transposed [d][key]
+  constexpr int V_OFF = 64 * FA_LD, KT_OFF = 2 * 64 * FA_LD, SET = bwd_dq_lds<DH>();
   const int g = blockIdx.z;
   const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
   const int q0 = blockIdx.x * (NW * 32);
@@ -358,13 +359,34 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, f
   const int q_blk_last = min(q0 + NW * 32, a.Sq) - 1;
   const int k_end = a.causal ? min(a.Sk, q_blk_last + 1) : a.Sk;
   const int q_wave_first = q0 + wave * 32, q_wave_last = q_wave_first + 31;
-  for (int k0 = 0; k0 < k_end; k0 += 64) {
+  TileRegs<NW * 64, DH> kr, vr;
+  if constexpr (DB) {                                    // k_end >= 1: the launcher rejects empty sequences
+    tile_load(kr, P.K, a.k_row_stride, 0, a.Sk);
+    tile_load(vr, P.V, a.v_row_stride, 0, a.Sk);
+    tile_store<NW * 64, DH, true, true>(kr, lds, lds + KT_OFF);
+    tile_store<NW * 64, DH, true, false>(vr, lds + V_OFF, nullptr);
     __syncthreads();
-    stage64<NW * 64, DH, true, true>(Ks, Kt, P.K, a.k_row_stride, k0, a.Sk);
-    stage64<NW * 64, DH, true, false>(Vs, nullptr, P.V, a.v_row_stride, k0, a.Sk);
-    __syncthreads();
-    if (a.causal && k0 > q_wave_last) continue;
+    // every load issued so far has landed (the tile was waited for and loads return in order);
+    // saying so keeps the loop's waits on the query fragments from also covering its prefetches
+    __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
+  }
+  int cur = 0;
+  for (int k0 = 0; k0 < k_end; k0 += 64, cur ^= DB ? 1 : 0) {
+    bf16* Ks = lds + cur * SET;
+    bf16* Vs = Ks + V_OFF;
+    bf16* Kt = Ks + KT_OFF;
+    const bool more = DB && k0 + 64 < k_end;               // block-uniform
+    if constexpr (!DB) {
+      __syncthreads();
+      stage64<NW * 64, DH, true, true>(Ks, Kt, P.K, a.k_row_stride, k0, a.Sk);
+      stage64<NW * 64, DH, true, false>(Vs, nullptr, P.V, a.v_row_stride, k0, a.Sk);
+      __syncthreads();
+    } else if (more) {
+      tile_load(kr, P.K, a.k_row_stride, k0 + 64, a.Sk);
+      tile_load(vr, P.V, a.v_row_stride, k0 + 64, a.Sk);
+    }
     const bool full = k0 + 64 <= a.Sk && (!a.causal || k0 + 63 <= q_wave_first);   // no mask needed
+    if (!(a.causal && k0 > q_wave_last)) {                 // wave-uniform: the tile lies above the diagonal
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
       f32x16 s = zero16(), dp = zero16();
@@ -392,14 +414,25 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, f
         for (int dt = 0; dt < DT; ++dt) dq[dt] = MFMA(frag_trans(Kt, 32 * dt + lr, kt, t, lh), ab, dq[dt]);
       }
     }
+    }
+    if constexpr (DB) {
+      if (more) {
+        bf16* other = lds + (cur ^ 1) * SET;
+        tile_store<NW * 64, DH, true, true>(kr, other, other + KT_OFF);
+        tile_store<NW * 64, DH, true, false>(vr, other + V_OFF, nullptr);
+      }
+      __syncthreads();    // the other set is complete, and nobody reads this one any more
+    }
   }
   if (qi < a.Sq) store_rows_T<DH>(P.dQ, a.dqkv_row_stride, qi, dq, rsqrtf((float)DH), lh);
 }
 
 template <int NW, int DH>
 __global__ void __launch_bounds__(NW * 64, (fa_bwd_blocks<DH, NW>())) attn_bwd_dq_mfma_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16 lds[bwd_dq_lds<DH>()];
-  attn_bwd_dq_body<NW, DH>(a, lds, nullptr);
+  // the 256-row blocks at d_head = 128 (one block per CU) double-buffer their key tiles
+  constexpr bool DB = NW == 8 && DH == 128;
+  __shared__ __attribute__((aligned(16))) bf16 lds[(DB ? 2 : 1) * bwd_dq_lds<DH>()];
+  attn_bwd_dq_body<NW, DH, DB>(a, lds, nullptr);
 }
 
 // ---------------------------------------------------------------------------
@@ -523,8 +556,9 @@ bool attn_mfma_supported(const AttnArgs& a) {
 // Long sequences: blocks of 256 rows halve the K/V (Q/dO) bytes staged from L2 per flop, which is
 // what bounds these kernels once a head no longer fits a block or two.  Mask bits 0-2: forward,
 // dQ pass, dK/dV pass at d_head = 128 (sequences from 1024 tokens); bits 4-6: the same at
-// d_head = 64 (from 512 tokens).
-int g_attn_wide = 5;
+// d_head = 64 (from 512 tokens).  Default: all three passes at d_head = 128 (forward and dQ pass
+// with double-buffered tiles), none at d_head = 64.
+int g_attn_wide = 7;
 void attn_set_wide_blocks(int mask) { g_attn_wide = mask & 0x77; }
 template <int DH> static bool attn_wide(int pass, int seq) {
   return DH == 128 ? (seq >= 1024 && ((g_attn_wide >> pass) & 1)) : (seq >= 512 && ((g_attn_wide >> (4 + pass)) & 1));
@@ -552,6 +586,7 @@ hipError_t attn_fwd_mfma(const AttnArgs& a, hipStream_t st) {
 
 template <int DH>
 static hipError_t attn_bwd_mfma_dh(const AttnArgs& a, hipStream_t st) {
+  if (a.Sq <= 0 || a.Sk <= 0) return hipErrorInvalidValue;
   if (a.dk && a.Sq <= 128 && a.Sk <= 128) {
     dim3 grid(1, a.B * a.H, a.n_groups);
     if (a.Sq <= 64 && a.Sk <= 64) hipLaunchKernelGGL((attn_bwd_fused_mfma_kernel<2, DH>), grid, dim3(128), 0, st, a);
