@@ -615,7 +615,11 @@ static hipError_t launch_epi(const GemmArgs& a, bool is_bf16, hipStream_t st) {
     case 1: if (a.N % 256 == 0) return launch_mfma<256, 256, 64, 2, 1, true, EPI, 2, 4>(a, st); break;
     case 2: return launch_mfma<256, 128, 32, 3, 2, true, EPI>(a, st);
     case 3: if (a.N % 192 == 0) return launch_mfma<256, 192, 64, 2, 1, true, EPI, 4, 2>(a, st); break;
-    case 4: return launch_mfma<128, 128, 64, 2, 2, true, EPI>(a, st);
+    case 4:
+      // long reductions: 8 wavefronts of 32x64 (four per SIMD with two blocks resident) hide the
+      // k-loop's latencies better than 4 of 64x64; short ones are all epilogue, where 4 do better
+      if (a.K >= 512) return launch_mfma<128, 128, 64, 2, 2, true, EPI, 4, 2>(a, st);
+      return launch_mfma<128, 128, 64, 2, 2, true, EPI>(a, st);
 #ifdef MG_GEMM_DEBUG
     case 5: return launch_mfma<256, 128, 32, 2, 2, true, EPI>(a, st);
     case 6: if (a.N % 256 == 0) return launch_mfma<256, 256, 64, 2, 1, true, EPI, 2, 4>(a, st); break;
