@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--no-adjoint", action="store_true", help="time mgrit_forward only")
     ap.add_argument("--max-groups", type=int, default=0, help="groups per kernel launch (0 = library default)")
     ap.add_argument("--lanes", type=int, default=0, help="1 = single stream, 2 = two lanes (0 = library default)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of one step captured into a HIP graph instead of eager launches")
     ap.add_argument("--gemm-tile", type=int, default=0, help="tuning: force a GEMM tile configuration (0 = by shape)")
     ap.add_argument("--param-grads", action="store_true",
                     help="also produce the parameter gradients in every step (not part of the headline metric: "
@@ -159,29 +161,39 @@ def main():
     n_psi = n_phi if adjoint else 0
     stream = torch.cuda.current_stream()
 
-    def step_stacked():
+    def step_stacked(stream):
         mb.mgrit_forward_stacked(desc, opts, sw.n_enc, Z0, theta, Z_all=Z_all, resnorm=res_f, workspace=ws,
                                  stream=stream)
         if adjoint:
             mb.mgrit_adjoint_stacked(desc, opts, sw.n_enc, Z_all, theta, lamN, dtheta=grads, lambda_all=lam_all,
                                      resnorm=res_a, workspace=ws, stream=stream)
 
-    def step():
+    def step(stream=stream):
         if sw:
-            return step_stacked()
+            return step_stacked(stream)
         mb.mgrit_forward(desc, opts, Z0, theta, memory=mem, Z_all=Z_all, resnorm=res_f, workspace=ws,
                          stream=stream)
         if adjoint:
             mb.mgrit_adjoint(desc, opts, Z_all, theta, lamN, memory=mem, lambda_all=lam_all, resnorm=res_a,
                              workspace=ws, stream=stream, dtheta=grads)
 
-    for _ in range(args.warmup):
+    # --graph: the caller captures one step (kernels, copies and the library's fork/join events)
+    # into a HIP graph and replays it; what the launch-bound small workloads gain from that
+    timed_step = step
+    if args.graph:
         step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(torch.cuda.current_stream())
+        timed_step = graph.replay
+    for _ in range(args.warmup):
+        timed_step()
     torch.cuda.synchronize()
     # timed region: exactly K steps, nothing else enqueued, no instrumentation
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -296,7 +308,7 @@ def main():
                    "phi_evaluations": n_phi, "psi_evaluations": n_psi,
                    "max_groups_per_launch": args.max_groups or mb.lib().mgrit_default_groups_per_launch(
                        C_byref(desc), max(wl.N // wl.cf, 1)), "lanes": args.lanes or 2,
-                   "param_grads": bool(grads),
+                   "param_grads": bool(grads), "launch": "hip graph replay" if args.graph else "eager",
                    **({"stacked": True, "n_enc": sw.n_enc, "src_seq": sw.enc.seq} if sw else {})},
         "residual_norms": {"forward": [float(x) for x in res_f.cpu()[:wl.iters]],
                            "adjoint": [float(x) for x in res_a.cpu()[:wl.iters]] if adjoint else None},
