@@ -94,17 +94,18 @@ def test_head_dimension_128_bf16(arch, S):
 @pytest.mark.parametrize("arch", [wls.ARCH_ENCODER, wls.ARCH_CAUSAL])
 def test_long_sequence_head_dimension_128_wide_blocks_bf16(arch):
     """S = 1100 with one head of 128: the 256-row attention blocks (five blocks, the last one ragged; 18
-    key tiles, the last one ragged), forward and adjoint, against the 128-row blocks as well."""
+    key tiles, the last one ragged; forward and dQ pass with double-buffered tiles), forward and adjoint,
+    against the 128-row blocks as well."""
     wl = make(arch, wls.DTYPE_BF16, d=128, H=1, f=128, B=1, S=1100)
     run_forward_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.05, force_simple=0)
     run_adjoint_case(wl, G=2, hstep=0.5, with_rhs=True, weight_std=0.05, force_simple=0)
     try:
-        for mask in (0, 7):        # 128-row blocks everywhere; 256-row blocks in all three kernels
+        for mask in (0, 5):        # 128-row blocks everywhere; 256-row blocks except in the dQ pass
             mb.lib().mgrit_debug_attention_wide_blocks(mask)
             run_forward_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.05, force_simple=0)
             run_adjoint_case(wl, G=2, hstep=0.5, with_rhs=True, weight_std=0.05, force_simple=0)
     finally:
-        mb.lib().mgrit_debug_attention_wide_blocks(5)
+        mb.lib().mgrit_debug_attention_wide_blocks(7)      # the default: all three kernels
 
 
 @pytest.mark.parametrize("d,H,f", [(2048, 16, 1024), (1280, 10, 512)])
