@@ -279,7 +279,9 @@ def main():
                             "instrumented_ms_per_step": events_ms_per_step,
                             "grouped_gemm_TFLOPs": roofline["achieved"]}
         hbm = {}
-        for k in ("ln_fwd", "ln_vjp", "elementwise"):
+        # LayerNorm: the launches over several groups (relaxation sweeps: tens of MB, beyond the caches
+        # between producer and consumer) and the single-group ones of the coarse chain apart
+        for k in ("ln_fwd", "ln_vjp", "ln_fwd_single", "ln_vjp_single", "elementwise"):
             if k in totals and totals[k]["ms"] > 0:
                 gbs = totals[k]["bytes"] / (totals[k]["ms"] * 1e-3) / 1e9
                 hbm[k] = {"achieved_GBs": gbs, "frac_of_8TBs": gbs / PEAK_HBM_GBS,

@@ -298,7 +298,8 @@ void mgrit_set_lanes(int n);
  * After synchronising the stream, mgrit_profile_read() returns the totals of one class
  * since the last mgrit_profile_reset(): summed kernel time, algorithmic flops and bytes,
  * launches.  Classes: 0 generic GEMM, 1 attention fwd, 2 attention bwd, 3 LayerNorm fwd,
- * 4 LayerNorm VJP, 5 other elementwise, 8+e MFMA grouped GEMM with epilogue e launched over
+ * 4 LayerNorm VJP (3, 4: launches over several groups; 6, 7: the same over a single group),
+ * 5 other elementwise, 8+e MFMA grouped GEMM with epilogue e launched over
  * several groups (relaxation sweeps), 16+e the same over a single group (the serial coarse
  * chain); e: 0 store, 1 bias+GELU, 2 sublayer sum, 3 Euler update, 4 multiply by GELU',
  * 5 fp32 store, 6 GELU' of the cache pass.

@@ -224,6 +224,7 @@ def mgrit_set_lanes(n: int) -> None:
 
 
 PROFILE_CLASSES = {0: "gemm_generic", 1: "attn_fwd", 2: "attn_bwd", 3: "ln_fwd", 4: "ln_vjp", 5: "elementwise",
+                   6: "ln_fwd_single", 7: "ln_vjp_single",
                    8: "gemm_mfma_store", 9: "gemm_mfma_gelu", 10: "gemm_mfma_sublayer_sum",
                    11: "gemm_mfma_euler", 12: "gemm_mfma_dgelu", 13: "gemm_mfma_store_f32",
                    14: "gemm_mfma_gelu_prime"}

@@ -138,7 +138,7 @@ hipError_t launch_ln_fwd(const LnFwdArgs& a, bool is_bf16, hipStream_t st) {
   if (rows > 0x7fffffffL || a.d > 256 * LN_MAXV) return hipErrorInvalidValue;
   const unsigned blocks = ln_grid(rows, a.d, LN_FWD_BLOCKS_PER_CU);
   const double esz = is_bf16 ? 2 : 4;
-  ProfScope ps(PC_LN_FWD, 8.0 * rows * a.d,
+  ProfScope ps(a.n_groups > 1 ? PC_LN_FWD : PC_LN_FWD_SINGLE, 8.0 * rows * a.d,
                (double)rows * a.d * ((a.X.present() ? 4 : 0) + (a.xp ? 4 : 0) + esz), st);
   if (is_bf16) ln_fwd_dispatch<bf16>(a, blocks, st);
   else ln_fwd_dispatch<float>(a, blocks, st);
@@ -282,7 +282,7 @@ hipError_t launch_ln_bwd(const LnBwdArgs& a, bool is_bf16, hipStream_t st) {
   const double per_elem = esz + (xh ? esz : (a.X.present() ? 4 : 0) + (a.xp ? 4 : 0)) + (a.add ? 4 : 0) +
                           (a.out_f32 ? 4 : 0) + (c_rows ? 4 : 0) + (a.out_op && a.cop ? esz : 0) +
                           (a.out_op ? esz : 0) + (a.OUT.present() ? 4 : 0) + (a.RHS.present() ? 4 : 0);
-  ProfScope ps(PC_LN_BWD, 16.0 * rows * a.d, (double)rows * a.d * per_elem, st);
+  ProfScope ps(a.n_groups > 1 ? PC_LN_BWD : PC_LN_BWD_SINGLE, 16.0 * rows * a.d, (double)rows * a.d * per_elem, st);
   if (is_bf16) { if (xh) ln_bwd_dispatch<bf16, true>(a, blocks, st); else ln_bwd_dispatch<bf16, false>(a, blocks, st); }
   else { if (xh) ln_bwd_dispatch<float, true>(a, blocks, st); else ln_bwd_dispatch<float, false>(a, blocks, st); }
   return hipGetLastError();
