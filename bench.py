@@ -308,6 +308,8 @@ def main():
                    "batch": wl.batch, "seq": wl.seq, "N": wl.N, "h": wl.h, "cf": wl.cf, "levels": wl.levels,
                    "iters": wl.iters, "relax": "FCF" if wl.relax else "F", "adjoint": adjoint,
                    "phi_evaluations": n_phi, "psi_evaluations": n_psi,
+                   # dependent chain of batched sweeps per solve, against the N steps of serial propagation
+                   "dependent_sweeps_per_solve": mb.mgrit_step_depth(opts), "serial_depth": wl.N,
                    "max_groups_per_launch": args.max_groups or mb.lib().mgrit_default_groups_per_launch(
                        C_byref(desc), max(wl.N // wl.cf, 1)), "lanes": args.lanes or 2,
                    "param_grads": bool(grads), "launch": "hip graph replay" if args.graph else "eager",

@@ -120,6 +120,13 @@ size_t mgrit_layer_step_workspace_bytes(const mgrit_model_desc* desc, int adjoin
  * Host only. */
 int64_t mgrit_step_evaluations(const mgrit_opts* opts);
 
+/* Number of batched sweeps those evaluations are enqueued in: a sweep advances all its
+ * intervals at once (one evaluation deep) and needs the sweep before it, so this is the
+ * length of the dependent chain of layer steps, to set against the N of serial propagation
+ * (sec. 3.2: relaxation sweeps are parallel over the intervals, the coarsest level is a chain
+ * of N / cf^(levels-1) steps).  -1 on invalid arguments.  Host only. */
+int64_t mgrit_step_depth(const mgrit_opts* opts);
+
 /* MGRIT forward propagation (sec. 3.2.1).
  *   Z0        device, [T,d] fp32: initial value (embedded input)
  *   theta     HOST array of N device pointers, one packed block per layer

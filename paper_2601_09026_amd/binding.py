@@ -81,6 +81,8 @@ def lib() -> C.CDLL:
         L.mgrit_layer_step_workspace_bytes.restype = C.c_size_t
         L.mgrit_step_evaluations.argtypes = [C.POINTER(Opts)]
         L.mgrit_step_evaluations.restype = C.c_int64
+        L.mgrit_step_depth.argtypes = [C.POINTER(Opts)]
+        L.mgrit_step_depth.restype = C.c_int64
         L.mgrit_forward.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), vp, vpp, vp, vp, vp, vp,
                                     C.c_size_t, vp]
         L.mgrit_forward.restype = C.c_int
@@ -195,6 +197,10 @@ def mgrit_layer_step_workspace_bytes(desc: ModelDesc, adjoint: bool, n_groups: i
 
 def mgrit_step_evaluations(opts: Opts) -> int:
     return int(lib().mgrit_step_evaluations(C.byref(opts)))
+
+
+def mgrit_step_depth(opts: Opts) -> int:
+    return int(lib().mgrit_step_depth(C.byref(opts)))
 
 
 def mgrit_indicator_init(iters: int, probe_every: int, mitigation: int = MITIGATE_SERIAL, max_iters: int = 0,

@@ -775,6 +775,7 @@ struct Driver {
   int max_partial = 0;
   float* resnorm = nullptr;
   int64_t evals = 0;
+  int64_t sweeps = 0;              // batched sweeps enqueued: each depends on the one before it
   // stacked encoder-decoder grid (paper section 3.1, eq. "fp_transformer"): E, E2 are the encoder's
   // engines, Ed, Ed2 the decoder's; layers below n_enc are encoder layers.  A state is the X rows
   // (x_elems floats) followed by the Y rows (y_elems floats).
@@ -860,6 +861,7 @@ struct Driver {
   // cnt steps of level `lvl`, group k starting at point j = j0 + k*js
   int step(int lvl, int j0, int js, int cnt, Rows OUT, Rows RHS) {
     evals += cnt;
+    ++sweeps;
     if (!E) return MGRIT_OK;
     Engine& L1 = only ? *only : *E;
     Engine* L2 = only ? nullptr : E2;
@@ -1150,6 +1152,15 @@ int64_t mgrit_step_evaluations(const mgrit_opts* opts) {
   D.tabG.assign(D.L, nullptr);
   D.run(opts->iters);
   return D.evals;
+}
+
+int64_t mgrit_step_depth(const mgrit_opts* opts) {
+  if (validate_opts(opts) != MGRIT_OK) return -1;
+  Driver D;
+  D.N = opts->N; D.cf = opts->cf; D.L = serial_run(opts) ? 1 : opts->levels; D.relax = opts->relax;
+  D.tabG.assign(D.L, nullptr);
+  D.run(opts->iters);
+  return D.sweeps;
 }
 
 int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z0,

@@ -70,6 +70,23 @@ def test_evaluation_count_equals_oracle_minus_redundant_relaxations(N, cf, level
         assert got == 880
 
 
+@pytest.mark.parametrize("N,cf,levels,iters,relax,depth", [
+    # two levels, FCF: per cycle F (cf-1) + C (1) + F (cf-1) + residual (1) + coarse right-hand side (1)
+    # + N/cf coarse steps; the interpolation after a cycle is the next cycle's opening F; closing F (cf-1)
+    (64, 4, 2, 2, 1, 2 * (3 + 1 + 3 + 1 + 1 + 16) + 3),
+    # F-relaxation only, one cycle: F 3 + residual 1 + right-hand side 1 + 4 coarse steps + closing F 3
+    (16, 4, 2, 1, 0, 12),
+    # three levels: level 0 (8) + its right-hand side (1) + level 1 (8 + right-hand side 1 + 8 coarse steps
+    # + interpolation 3) per cycle, closing F
+    (128, 4, 3, 2, 1, 2 * (8 + 1 + 8 + 1 + 8 + 3) + 3),
+    (64, 4, 1, 2, 1, 64), (16, 1, 3, 2, 1, 16)])       # serial propagation: N dependent steps
+def test_dependent_depth_of_a_step(N, cf, levels, iters, relax, depth):
+    """mgrit_step_depth counts the batched sweeps, each one evaluation deep (sec. 3.2: the sweeps are
+    parallel over the intervals, the coarsest level is a serial chain)."""
+    assert mb.mgrit_step_depth(mb.mgrit_opts(N, 0.1, cf, levels, iters, relax)) == depth
+    assert mb.mgrit_step_depth(mb.mgrit_opts(10, 0.1, 4, 2, 1)) == -1
+
+
 def test_invalid_arguments_are_rejected_without_a_device():
     wl = wls.named_workloads()["tiny_encoder"]
     desc = mb.model_desc(wl)
