@@ -288,6 +288,19 @@ def main():
                           "avg_launch_us": totals[k]["ms"] * 1e3 / totals[k]["launches"]}
         if roofline is not None:
             roofline["hbm_bound_kernels"] = hbm
+            # what this machine reaches: a register-resident MFMA loop and a 1 GiB streaming copy, so that
+            # the fractions can be read against the achievable as well as against the datasheet
+            a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+            b = torch.empty_like(a)
+            a.fill_(1.0)
+            mfma_c = mb.mgrit_measure_mfma_ceiling(b, 20000, stream)
+            copy_c = mb.mgrit_measure_copy_ceiling(a, b, stream)
+            del a, b
+            roofline["measured_ceilings"] = {"mfma_bf16_TFLOPs": mfma_c, "copy_GBs": copy_c}
+            if roofline["bound"] == "mfma":
+                roofline["frac_of_measured_ceiling"] = roofline["achieved"] / mfma_c
+            for v in hbm.values():
+                v["frac_of_copy"] = v["achieved_GBs"] / copy_c
     if args.breakdown and totals:
         print(f"{'class':28s} {'launches/step':>13s} {'ms/step':>9s} {'TFLOP/s':>9s} {'GB/s':>9s}", file=sys.stderr)
         for k, v in sorted(totals.items(), key=lambda kv: -kv[1]["ms"]):

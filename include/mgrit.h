@@ -315,6 +315,16 @@ int  mgrit_profile_enable(int max_records);
 void mgrit_profile_reset(void);
 int  mgrit_profile_read(int cls, double* total_ms, double* flops, double* bytes, int64_t* launches);
 
+/* Measured ceilings of the device, for stating a kernel's rate as a fraction of what the box
+ * reaches as well as of the datasheet: a register-resident 32x32x16 bf16 MFMA loop on every
+ * compute unit (`scratch`: device, at least 512 KiB, overwritten; `iters` MFMA rounds, 1..2^20;
+ * result in TFLOP/s) and a grid-stride copy of `bytes` (a multiple of 16, at least 1 MiB) from
+ * `src` to `dst` (device, not overlapping; result = bytes read + written per second, in GB/s).
+ * Both enqueue on `stream`, wait for it and create two events meanwhile; 0 on success, -1 on
+ * bad arguments, -4 on a HIP error. */
+int mgrit_measure_mfma_ceiling(void* scratch, size_t scratch_bytes, int iters, double* tflops, void* stream);
+int mgrit_measure_copy_ceiling(const void* src, void* dst, size_t bytes, double* gbs, void* stream);
+
 /* Test hook: route GEMMs (first flag) / attention (second flag) to the generic kernels. */
 void mgrit_debug_force_simple_kernels(int gemm, int attn);
 

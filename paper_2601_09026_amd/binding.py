@@ -81,6 +81,10 @@ def lib() -> C.CDLL:
         L.mgrit_layer_step_workspace_bytes.restype = C.c_size_t
         L.mgrit_step_evaluations.argtypes = [C.POINTER(Opts)]
         L.mgrit_step_evaluations.restype = C.c_int64
+        L.mgrit_measure_mfma_ceiling.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_double), C.c_void_p]
+        L.mgrit_measure_mfma_ceiling.restype = C.c_int
+        L.mgrit_measure_copy_ceiling.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.c_void_p]
+        L.mgrit_measure_copy_ceiling.restype = C.c_int
         L.mgrit_step_depth.argtypes = [C.POINTER(Opts)]
         L.mgrit_step_depth.restype = C.c_int64
         L.mgrit_forward.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), vp, vpp, vp, vp, vp, vp,
@@ -261,6 +265,27 @@ def mgrit_profile_read() -> Dict[str, dict]:
             out[name] = {"ms": ms.value, "flops": fl.value, "bytes": by.value, "launches": n.value,
                          "overflow": st == -3}
     return out
+
+
+def mgrit_measure_mfma_ceiling(scratch: torch.Tensor, iters: int = 20000, stream=None) -> float:
+    """TFLOP/s of the register-resident MFMA loop (scratch: device tensor of at least 512 KiB)."""
+    out = C.c_double()
+    st = lib().mgrit_measure_mfma_ceiling(scratch.data_ptr(), scratch.numel() * scratch.element_size(), int(iters),
+                                          C.byref(out), _stream_handle(stream))
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_measure_mfma_ceiling")
+    return out.value
+
+
+def mgrit_measure_copy_ceiling(src: torch.Tensor, dst: torch.Tensor, stream=None) -> float:
+    """GB/s (read + written) of a grid-stride copy of src into dst (device tensors of equal size)."""
+    out = C.c_double()
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    st = lib().mgrit_measure_copy_ceiling(src.data_ptr(), dst.data_ptr(), nbytes, C.byref(out), _stream_handle(stream))
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_measure_copy_ceiling")
+    return out.value
 
 
 # ------------------------------------------------------------------ parameter packing (byte copies only)

@@ -30,7 +30,104 @@ void prof_end(hipStream_t st) {
 
 }  // namespace mg
 
+// ---------------------------------------------------------------------------
+// Measured ceilings of the box, for the "fraction of achievable" beside the datasheet fractions:
+// a register-resident 32x32x16 bf16 MFMA loop (8 independent accumulators per wavefront, operands
+// pseudo-random so that the clock sees a realistic power draw) and a streaming copy.
+// ---------------------------------------------------------------------------
+namespace mg {
+namespace {
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 pk_bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float pk_f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float pk_f32x4;
+
+__global__ void __launch_bounds__(256) mfma_ceiling_kernel(float* out, int iters) {
+  constexpr int NACC = 8;
+  pk_f32x16 acc[NACC];
+#pragma unroll
+  for (int i = 0; i < NACC; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  pk_bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    unsigned x = (threadIdx.x * 8 + e) * 2654435761u;
+    a[e] = (__bf16)(((x >> 8) & 0xffff) / 65536.0f - 0.5f);
+    x = x * 1664525u + 1013904223u;
+    b[e] = (__bf16)(((x >> 8) & 0xffff) / 65536.0f - 0.5f);
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NACC; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += acc[i][r];
+  out[blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
+__global__ void __launch_bounds__(256) copy_ceiling_kernel(const pk_f32x4* in, pk_f32x4* out, long n) {
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) out[i] = in[i];
+}
+
+// time `launch()` (already warmed up by one call) between two events on `st`; host-synchronous
+template <typename F>
+int timed_ms(F launch, hipStream_t st, float* ms) {
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return -4;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return -4; }
+  launch();
+  int rc = 0;
+  if (hipEventRecord(e0, st) != hipSuccess) rc = -4;
+  launch();
+  if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+      hipEventElapsedTime(ms, e0, e1) != hipSuccess || hipGetLastError() != hipSuccess)
+    rc = -4;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  return rc;
+}
+}  // namespace
+}  // namespace mg
+
 extern "C" {
+
+// scratch: device, at least 512 KiB.  Returns 0 and the rate of the MFMA loop, -1 on bad arguments,
+// -4 on a HIP error.  Synchronises the stream.
+int mgrit_measure_mfma_ceiling(void* scratch, size_t scratch_bytes, int iters, double* tflops, void* stream) {
+  using namespace mg;
+  const int blocks = 512;                                // two 4-wavefront blocks per compute unit
+  if (!scratch || !tflops || iters <= 0 || iters > (1 << 20) || scratch_bytes < (size_t)blocks * 256 * sizeof(float))
+    return -1;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float ms = 0.f;
+  const int rc = timed_ms([&] {
+    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(blocks), dim3(256), 0, st, static_cast<float*>(scratch), iters);
+  }, st, &ms);
+  if (rc != 0) return rc;
+  *tflops = (double)blocks * 4 * iters * 8 * 32768.0 / (ms * 1e-3) / 1e12;
+  return 0;
+}
+
+// src, dst: device, `bytes` each (a multiple of 16, at least 1 MiB), not overlapping.  Returns 0 and
+// the read + write rate of a grid-stride copy in GB/s.  Synchronises the stream.
+int mgrit_measure_copy_ceiling(const void* src, void* dst, size_t bytes, double* gbs, void* stream) {
+  using namespace mg;
+  if (!src || !dst || !gbs || bytes < (1u << 20) || bytes % 16 != 0) return -1;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const long n = (long)(bytes / 16);
+  float ms = 0.f;
+  const int rc = timed_ms([&] {
+    hipLaunchKernelGGL(copy_ceiling_kernel, dim3(8192), dim3(256), 0, st, static_cast<const pk_f32x4*>(src),
+                       static_cast<pk_f32x4*>(dst), n);
+  }, st, &ms);
+  if (rc != 0) return rc;
+  *gbs = 2.0 * (double)bytes / (ms * 1e-3) / 1e9;
+  return 0;
+}
+
 
 // max_records > 0: create the event pool and start recording; 0: stop and destroy it.
 int mgrit_profile_enable(int max_records) {

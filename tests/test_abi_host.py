@@ -87,6 +87,18 @@ def test_dependent_depth_of_a_step(N, cf, levels, iters, relax, depth):
     assert mb.mgrit_step_depth(mb.mgrit_opts(10, 0.1, 4, 2, 1)) == -1
 
 
+def test_ceiling_measurements_reject_bad_arguments_without_a_device():
+    import ctypes as C
+    out = C.c_double()
+    L = mb.lib()
+    assert L.mgrit_measure_mfma_ceiling(None, 1 << 20, 100, C.byref(out), None) == -1
+    assert L.mgrit_measure_mfma_ceiling(C.c_void_p(4096), 1024, 100, C.byref(out), None) == -1      # scratch too small
+    assert L.mgrit_measure_mfma_ceiling(C.c_void_p(4096), 1 << 20, 0, C.byref(out), None) == -1
+    assert L.mgrit_measure_copy_ceiling(None, C.c_void_p(4096), 1 << 20, C.byref(out), None) == -1
+    assert L.mgrit_measure_copy_ceiling(C.c_void_p(4096), C.c_void_p(8192), (1 << 20) + 8, C.byref(out), None) == -1
+    assert L.mgrit_measure_copy_ceiling(C.c_void_p(4096), C.c_void_p(8192), 1 << 10, C.byref(out), None) == -1
+
+
 def test_invalid_arguments_are_rejected_without_a_device():
     wl = wls.named_workloads()["tiny_encoder"]
     desc = mb.model_desc(wl)

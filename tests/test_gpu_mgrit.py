@@ -245,3 +245,17 @@ def test_deep_narrow_shape_reduced_f_relaxation(levels, cf, N):
     sequence length and batch cut to what the oracle finishes in seconds."""
     wl = wls.named_workloads()["mc_deep_narrow"].scaled(batch=2, seq=192, N=N, h=1.0 / N, cf=cf, levels=levels)
     run_case(wl, relax="F", adjoint=True)
+
+
+def test_measured_ceilings_are_plausible():
+    """The two ceiling measurements run and land between a tenth of and the whole datasheet figure
+    (2.5 PFLOP/s dense bf16 MFMA, 8 TB/s HBM)."""
+    print("[case] measured ceilings", flush=True)
+    a = torch.ones(1 << 26, dtype=torch.float32, device="cuda")
+    b = torch.empty_like(a)
+    tf = mb.mgrit_measure_mfma_ceiling(b, 2000)
+    gbs = mb.mgrit_measure_copy_ceiling(a, b)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    assert 250.0 < tf < 2500.0, tf
+    assert 800.0 < gbs < 8000.0, gbs
