@@ -117,7 +117,8 @@ def test_two_level_inexact_iterates_fp32(relax, iters):
     assert relerr(Zr[-1], ser[-1]) > 1e-4, "case is not a genuine inexact iterate"
 
 
-@pytest.mark.parametrize("levels,cf,N", [(3, 2, 16), (3, 4, 32), (4, 2, 16)])
+# (the ends of the paper's parameter study, Table 2: coarsening factors 2 to 16, 2 to 5 levels)
+@pytest.mark.parametrize("levels,cf,N", [(3, 2, 16), (3, 4, 32), (4, 2, 16), (5, 2, 32), (2, 16, 32)])
 def test_multilevel_vcycles_fp32(levels, cf, N):
     run_case(tiny(arch=wls.ARCH_CAUSAL, N=N, cf=cf, levels=levels, iters=2), weight_std=0.08, adjoint=True)
 
