@@ -39,6 +39,10 @@ def parse():
                     help="tiny_encoder | bert_base | gpt2_small | vit_small | mt_encoder | mt_decoder | "
                          "mc_deep_narrow | mt_stacked (encoder and decoder on one grid)")
     ap.add_argument("--no-adjoint", action="store_true", help="time mgrit_forward only")
+    ap.add_argument("--layers", type=int, default=0, help="parameter study: override N (h becomes 1/N)")
+    ap.add_argument("--cf", type=int, default=0, help="parameter study: override the coarsening factor")
+    ap.add_argument("--levels", type=int, default=0, help="parameter study: override the number of levels")
+    ap.add_argument("--iters", type=int, default=0, help="parameter study: override the number of cycles")
     ap.add_argument("--max-groups", type=int, default=0, help="groups per kernel launch (0 = library default)")
     ap.add_argument("--lanes", type=int, default=0, help="1 = single stream, 2 = two lanes (0 = library default)")
     ap.add_argument("--graph", action="store_true",
@@ -104,6 +108,13 @@ def main():
 
     sw = wls.stacked_workloads().get(args.workload)        # encoder + decoder on one grid, or None
     wl = sw.dec.scaled(name=sw.name, N=sw.N) if sw else wls.named_workloads()[args.workload]
+    if args.layers or args.cf or args.levels or args.iters:
+        if sw:
+            print("bench.py: --layers/--cf/--levels/--iters apply to the single-network workloads", file=sys.stderr)
+            sys.exit(2)
+        n_layers = args.layers or wl.N
+        wl = wl.scaled(N=n_layers, h=1.0 / n_layers, cf=args.cf or wl.cf, levels=args.levels or wl.levels,
+                       iters=args.iters or wl.iters)
     adjoint = not args.no_adjoint
     torch.cuda.set_device(0)
     if args.max_groups:
@@ -233,7 +244,7 @@ def main():
             ach = fl / (ms * 1e-3) / 1e12
             roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel (grouped projection GEMMs, all epilogues)",
                         "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                        "frac": ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(wl, adjoint),
+                        "frac": ach / PEAK_BF16_TFLOPS, "traffic": None if (args.layers or args.cf or args.levels or args.iters) else measured_traffic(wl, adjoint),
                         "launches_per_step": n / args.steps, "avg_launch_us": ms * 1e3 / n,
                         "flop_per_launch": fl / n,
                         "algorithmic_bytes_per_launch": sum(v["bytes"] for v in gemm) / n,
