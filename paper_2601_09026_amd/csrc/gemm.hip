@@ -266,8 +266,7 @@ template <int BK> __device__ __forceinline__ int swz(int row) {
   return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 
-template <int BM, int BN, int BK, int STAGES, int OCC, bool STAGED, int EPI, typename TO, int DBG = 0,
-          int WM = 2, int WN = 2>
+template <int BM, int BN, int BK, int STAGES, int OCC, bool STAGED, int EPI, typename TO, int WM = 2, int WN = 2>
 __global__ void __launch_bounds__(64 * WM * WN, OCC)
 gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd, int pm, int pn) {
   constexpr int NW = WM * WN;                            // wavefronts per block
@@ -336,7 +335,6 @@ gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, in
   }
 
   auto issue_one = [&](int stage, int k0, int idx) {
-    if (DBG == 2 || DBG == 3) return;
     unsigned char* sa = smem2 + stage * STAGE;
     if (idx < A_LD)
       __builtin_amdgcn_global_load_lds((gas_ptr)(A + aoff[idx] + k0), (las_ptr)(sa + (wave * A_LD + idx) * 1024),
@@ -377,36 +375,32 @@ gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, in
     const unsigned char* sA = smem2 + cur * STAGE + wm0 * RB;
     const unsigned char* sB = smem2 + cur * STAGE + A_BYTES + wn0 * RB;
     bf16x8 fa[2][TM], fb[2][TN];
-    if (DBG != 1 && DBG != 3) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * RB + foff[0]);
+    for (int i = 0; i < TM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * RB + foff[0]);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * RB + foff[0]);
+    for (int j = 0; j < TN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * RB + foff[0]);
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int cb = ks & 1, nb = cb ^ 1;
-        if (ks + 1 < KS) {
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cb = ks & 1, nb = cb ^ 1;
+      if (ks + 1 < KS) {
 #pragma unroll
-          for (int i = 0; i < TM; ++i)
-            fa[nb][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * RB + foff[ks + 1 < KS ? ks + 1 : 0]);
+        for (int i = 0; i < TM; ++i)
+          fa[nb][i] = *reinterpret_cast<const bf16x8*>(sA + i * 32 * RB + foff[ks + 1 < KS ? ks + 1 : 0]);
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
-            fb[nb][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * RB + foff[ks + 1 < KS ? ks + 1 : 0]);
-        }
+        for (int j = 0; j < TN; ++j)
+          fb[nb][j] = *reinterpret_cast<const bf16x8*>(sB + j * 32 * RB + foff[ks + 1 < KS ? ks + 1 : 0]);
+      }
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+      for (int i = 0; i < TM; ++i) {
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cb][j], fa[cb][i], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cb][j], fa[cb][i], acc[i][j], 0, 0, 0);
 #pragma unroll
-          for (int u = 0; u < PER_SLOT; ++u) {
-            const int idx = (ks * TM + i) * PER_SLOT + u;
-            if (idx < PER_TILE && pf) issue_one(pstage, pk0, idx);
-          }
+        for (int u = 0; u < PER_SLOT; ++u) {
+          const int idx = (ks * TM + i) * PER_SLOT + u;
+          if (idx < PER_TILE && pf) issue_one(pstage, pk0, idx);
         }
       }
-    } else if (pf) {
-      issue(pstage, pk0);
     }
     // tile kt+1 must have landed (later tiles may still be in flight), and every wave must be
     // done reading this stage before it is refilled
@@ -481,10 +475,8 @@ gemm_simple_kernel(const GemmArgs a, int tiles_m, int tiles_n) {
 // ---------------------------------------------------------------------------
 static int g_force_simple = 0;
 static int g_tile_cfg = 0;                 // 0 = choose by shape
-static int g_dbg_mode = 0;
 void gemm_force_simple(int on) { g_force_simple = on; }
 void gemm_set_tile_config(int cfg) { g_tile_cfg = cfg; }
-void gemm_set_debug_mode(int m) { g_dbg_mode = m; }
 
 // Compute units of the current device (256 if the query fails).
 static int compute_units() {
@@ -514,7 +506,7 @@ static hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
     pn = 4;
     pm = resident / 4;
   }
-  auto kern = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 0, WM, WN>;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, WM, WN>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -522,17 +514,6 @@ static hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-#ifdef MG_GEMM_DEBUG
-  if (g_dbg_mode >= 1 && g_dbg_mode <= 3) {
-    auto k1 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 1, WM, WN>;
-    auto k2 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 2, WM, WN>;
-    auto k3 = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, 3, WM, WN>;
-    auto kd = g_dbg_mode == 1 ? k1 : (g_dbg_mode == 2 ? k2 : k3);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kd), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    hipLaunchKernelGGL(kd, dim3(per_xcd * 8), dim3(64 * WM * WN), smem, st, a, tiles_m, tiles_n, total, per_xcd, pm, pn);
-    return hipGetLastError();
-  }
-#endif
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(64 * WM * WN), smem, st, a, tiles_m, tiles_n, total,
                      per_xcd, pm, pn);
   return hipGetLastError();
@@ -620,13 +601,6 @@ static hipError_t launch_epi(const GemmArgs& a, bool is_bf16, hipStream_t st) {
       // k-loop's latencies better than 4 of 64x64; short ones are all epilogue, where 4 do better
       if (a.K >= 512) return launch_mfma<128, 128, 64, 2, 2, true, EPI, 4, 2>(a, st);
       return launch_mfma<128, 128, 64, 2, 2, true, EPI>(a, st);
-#ifdef MG_GEMM_DEBUG
-    case 5: return launch_mfma<256, 128, 32, 2, 2, true, EPI>(a, st);
-    case 6: if (a.N % 256 == 0) return launch_mfma<256, 256, 64, 2, 1, true, EPI, 2, 4>(a, st); break;
-    case 7: if (a.N % 256 == 0) return launch_mfma<256, 256, 32, 4, 1, true, EPI, 2, 4>(a, st); break;
-    case 9: return launch_mfma<256, 128, 64, 2, 1, true, EPI, 4, 2>(a, st);
-    case 10: return launch_mfma<256, 128, 32, 3, 2, true, EPI, 4, 2>(a, st);
-#endif
     default: break;
   }
   return launch_mfma<256, 128, 32, 3, 2, true, EPI>(a, st);
