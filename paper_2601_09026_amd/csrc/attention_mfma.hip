@@ -439,9 +439,13 @@ __global__ void __launch_bounds__(NW * 64, (fa_bwd_blocks<DH, NW>())) attn_bwd_d
 // backward pass 2: dK and dV, one wavefront per 32 key rows
 // ---------------------------------------------------------------------------
 // d_src: D of query row i at d_src[i] (the global array of pass 1, or the fused kernel's LDS copy)
-template <int NW, int DH>
+// VLDS: the wavefronts keep their V fragments there (64 lanes x 16 bytes per k-step and
+// wavefront in `vpriv`, each lane reading back what it wrote) instead of in registers: at d_head = 128 the two
+// accumulator sets and both fragment sets do not fit the 256 registers of two waves per SIMD, and a
+// register spilled to scratch costs far more than an LDS read
+template <int NW, int DH, bool VLDS = false>
 __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, float* Ls, float* Ds,
-                                                  const float* d_src) {
+                                                  const float* d_src, bf16* vpriv = nullptr) {
   constexpr int KS = DH / 16, DT = DH / 32, FA_LD = fa_ld<DH>();
   bf16* Qs = lds;                        // [query][d]
   bf16* dOs = Qs + 64 * FA_LD;           // [query][d]
@@ -454,11 +458,14 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
   const HeadPtrs P = head_ptrs(a, g, b, h);
   const int kj = j0 + wave * 32 + lr;
   const int kc = kj < a.Sk ? kj : a.Sk - 1;
-  bf16x8 kf[KS], vf[KS];
+  bf16x8 kf[KS], vf[VLDS ? 1 : KS];
+  bf16* vmine = VLDS ? vpriv + (wave * KS * 64 + lane) * 8 : nullptr;          // + ks * 512 per k-step
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     kf[ks] = *reinterpret_cast<const bf16x8*>(P.K + (long)kc * a.k_row_stride + 16 * ks + 8 * lh);
-    vf[ks] = *reinterpret_cast<const bf16x8*>(P.V + (long)kc * a.v_row_stride + 16 * ks + 8 * lh);
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(P.V + (long)kc * a.v_row_stride + 16 * ks + 8 * lh);
+    if constexpr (VLDS) *reinterpret_cast<bf16x8*>(vmine + ks * 512) = v;
+    else vf[ks] = v;
   }
   const float c = rsqrtf((float)DH) * LOG2E;
   f32x16 dk[DT], dv[DT];
@@ -487,7 +494,10 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         s = MFMA(frag_plain<DH>(Qs, 32 * qt + lr, ks, lh), kf[ks], s);
-        dp = MFMA(frag_plain<DH>(dOs, 32 * qt + lr, ks, lh), vf[ks], dp);
+        bf16x8 vk;
+        if constexpr (VLDS) vk = *reinterpret_cast<const bf16x8*>(vmine + ks * 512);
+        else vk = vf[ks];
+        dp = MFMA(frag_plain<DH>(dOs, 32 * qt + lr, ks, lh), vk, dp);
       }
       if (full) {
 #pragma unroll
@@ -515,6 +525,9 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
         for (int dt = 0; dt < DT; ++dt) {
           dv[dt] = MFMA(frag_trans(dOt, 32 * dt + lr, qt, t, lh), pb, dv[dt]);
           dk[dt] = MFMA(frag_trans(Qt, 32 * dt + lr, qt, t, lh), ab, dk[dt]);
+          // d_head = 128 runs at the register limit: keep the scheduler from fetching the fragments
+          // of all feature tiles ahead (it then spills the key fragments to scratch)
+          if constexpr (DH == 128) __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
@@ -528,9 +541,11 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
 
 template <int NW, int DH>
 __global__ void __launch_bounds__(NW * 64, (fa_bwd_blocks<DH, NW>())) attn_bwd_dkv_mfma_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16 lds[bwd_dkv_lds<DH>()];
+  // the 256-row blocks at d_head = 128 (one block per CU) park their V fragments in LDS
+  constexpr bool VLDS = NW == 8 && DH == 128;
+  __shared__ __attribute__((aligned(16))) bf16 lds[bwd_dkv_lds<DH>() + (VLDS ? NW * (DH / 16) * 64 * 8 : 0)];
   __shared__ float Ls[64], Ds[64];
-  attn_bwd_dkv_body<NW, DH>(a, lds, Ls, Ds, nullptr);
+  attn_bwd_dkv_body<NW, DH, VLDS>(a, lds, Ls, Ds, nullptr, lds + bwd_dkv_lds<DH>());
 }
 
 // Sequences that fit one block (Sq, Sk <= 32 NW): both passes in one launch.  The head's Q, K, V,
