@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--cf", type=int, default=0, help="parameter study: override the coarsening factor")
     ap.add_argument("--levels", type=int, default=0, help="parameter study: override the number of levels")
     ap.add_argument("--iters", type=int, default=0, help="parameter study: override the number of cycles")
+    ap.add_argument("--seq", type=int, default=0, help="parameter study: override the sequence length")
+    ap.add_argument("--batch", type=int, default=0, help="parameter study: override the batch size")
     ap.add_argument("--max-groups", type=int, default=0, help="groups per kernel launch (0 = library default)")
     ap.add_argument("--lanes", type=int, default=0, help="1 = single stream, 2 = two lanes (0 = library default)")
     ap.add_argument("--graph", action="store_true",
@@ -108,13 +110,14 @@ def main():
 
     sw = wls.stacked_workloads().get(args.workload)        # encoder + decoder on one grid, or None
     wl = sw.dec.scaled(name=sw.name, N=sw.N) if sw else wls.named_workloads()[args.workload]
-    if args.layers or args.cf or args.levels or args.iters:
+    overridden = bool(args.layers or args.cf or args.levels or args.iters or args.seq or args.batch)
+    if overridden:
         if sw:
-            print("bench.py: --layers/--cf/--levels/--iters apply to the single-network workloads", file=sys.stderr)
+            print("bench.py: the parameter-study overrides apply to the single-network workloads", file=sys.stderr)
             sys.exit(2)
         n_layers = args.layers or wl.N
         wl = wl.scaled(N=n_layers, h=1.0 / n_layers, cf=args.cf or wl.cf, levels=args.levels or wl.levels,
-                       iters=args.iters or wl.iters)
+                       iters=args.iters or wl.iters, seq=args.seq or wl.seq, batch=args.batch or wl.batch)
     adjoint = not args.no_adjoint
     torch.cuda.set_device(0)
     if args.max_groups:
@@ -244,7 +247,7 @@ def main():
             ach = fl / (ms * 1e-3) / 1e12
             roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel (grouped projection GEMMs, all epilogues)",
                         "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                        "frac": ach / PEAK_BF16_TFLOPS, "traffic": None if (args.layers or args.cf or args.levels or args.iters) else measured_traffic(wl, adjoint),
+                        "frac": ach / PEAK_BF16_TFLOPS, "traffic": None if overridden else measured_traffic(wl, adjoint),
                         "launches_per_step": n / args.steps, "avg_launch_us": ms * 1e3 / n,
                         "flop_per_launch": fl / n,
                         "algorithmic_bytes_per_launch": sum(v["bytes"] for v in gemm) / n,

@@ -333,10 +333,10 @@ void mgrit_debug_force_simple_kernels(int gemm, int attn);
  * blocks per CU).  A configuration that does not fit a shape falls back to configuration 2. */
 void mgrit_debug_gemm_tile_config(int cfg);
 
-/* Tuning hook: which attention kernels use 256-row blocks on long sequences.  Bits 0-2: forward,
- * dQ pass, dK/dV pass at d_head = 128 (sequences of 1024 tokens or more); bits 4-6: the same at
- * d_head = 64 (512 tokens or more; measured slower, off by default).  Default 7; 0 keeps 128-row
- * blocks everywhere. */
+/* Tuning hook: which attention kernels use 256-row blocks.  Bits 0-2: forward, dQ pass, dK/dV
+ * pass at d_head = 128 (sequences of more than 128 tokens; the backward passes only when the
+ * last block is more than half full); bits 4-6: the same at d_head = 64 (512 tokens or more;
+ * measured slower, off by default).  Default 7; 0 keeps 128-row blocks everywhere. */
 void mgrit_debug_attention_wide_blocks(int mask);
 
 /* Tuning hook: 1 (default) overlaps the serial solve on the coarsest level with the F-relaxation

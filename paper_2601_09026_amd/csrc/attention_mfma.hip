@@ -568,15 +568,19 @@ bool attn_mfma_supported(const AttnArgs& a) {
          (a.v_row_stride % 8 == 0) && (a.o_row_stride % 8 == 0);
 }
 
-// Long sequences: blocks of 256 rows halve the K/V (Q/dO) bytes staged from L2 per flop, which is
-// what bounds these kernels once a head no longer fits a block or two.  Mask bits 0-2: forward,
-// dQ pass, dK/dV pass at d_head = 128 (sequences from 1024 tokens); bits 4-6: the same at
-// d_head = 64 (from 512 tokens).  Default: all three passes at d_head = 128 (forward and dQ pass
-// with double-buffered tiles), none at d_head = 64.
+// Blocks of 256 rows halve the K/V (Q/dO) bytes staged from L2 per flop, which is what bounds these
+// kernels once a head no longer fits a block of 128.  Mask bits 0-2: forward, dQ pass, dK/dV pass at
+// d_head = 128, where these blocks also double-buffer their tiles (forward, dQ) or keep their V
+// fragments in LDS (dK/dV): they win from 129 tokens on; the two backward passes keep 128-row
+// blocks when the last 256-row block would be at most half full.  Bits 4-6: the same at d_head = 64
+// (from 512 tokens; measured slower, off).  Default: all three passes at d_head = 128.
 int g_attn_wide = 7;
 void attn_set_wide_blocks(int mask) { g_attn_wide = mask & 0x77; }
 template <int DH> static bool attn_wide(int pass, int seq) {
-  return DH == 128 ? (seq >= 1024 && ((g_attn_wide >> pass) & 1)) : (seq >= 512 && ((g_attn_wide >> (4 + pass)) & 1));
+  if (DH == 64) return seq >= 512 && ((g_attn_wide >> (4 + pass)) & 1);
+  if (!((g_attn_wide >> pass) & 1) || seq <= 128) return false;
+  const int tail = seq % 256;
+  return pass == 0 || tail == 0 || tail > 128;
 }
 
 template <int DH>

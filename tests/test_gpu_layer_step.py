@@ -81,11 +81,13 @@ def test_small_head_dimension_uses_generic_attention_bf16():
 
 
 @pytest.mark.parametrize("arch,S", [(wls.ARCH_ENCODER, 200), (wls.ARCH_CAUSAL, 200), (wls.ARCH_CROSS, 50),
-                                    (wls.ARCH_ENCODER, 40), (wls.ARCH_CAUSAL, 100)])
+                                    (wls.ARCH_ENCODER, 40), (wls.ARCH_CAUSAL, 100), (wls.ARCH_CAUSAL, 300),
+                                    (wls.ARCH_ENCODER, 384)])
 def test_head_dimension_128_bf16(arch, S):
     """d_head = 128 (the deep-narrow configuration has one head of 128): matrix-core attention with
-    four feature tiles; S = 200 spans several key blocks with a ragged tail, S <= 128 takes the
-    fused backward."""
+    four feature tiles; S = 200 spans several key blocks with a ragged tail in one 256-row block,
+    S = 300 and 384 take 256-row blocks forward and 128-row blocks backward (last block at most half
+    full), S <= 128 takes the fused backward."""
     wl = make(arch, wls.DTYPE_BF16, d=256, H=2, B=2, S=S, Sm=70)
     run_forward_case(wl, G=2, hstep=0.5, with_rhs=False, weight_std=0.05, force_simple=0)
     run_adjoint_case(wl, G=2, hstep=0.5, with_rhs=True, weight_std=0.05, force_simple=0)
