@@ -7,6 +7,8 @@
 //  * gemm_mfma  : bf16 operands, fp32 accumulate on the 32x32x16 MFMA of gfx950; operands
 //                 stream global -> LDS directly through a ring of k-tiles, see below.
 //  * gemm_simple: any operand type (fp32 path and odd shapes), LDS-tiled FMA.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 #include "prof.h"
@@ -62,7 +64,14 @@ template <> __device__ __forceinline__ f32x4 eload4<bf16>(const bf16* p) {
   return r;
 }
 
-template <int EPI, typename TO>
+// OPT: what is known at compile time about the optional operands of an epilogue: -1 nothing (tested
+// per call), else bit 0 = the first one is there (ybar / base / the pre-activation output), bit 1 =
+// RHS is there.  With OPT >= 0 a run of items is straight-line code.
+template <int OPT> __device__ __forceinline__ bool has_opt(int bit, const void* p) {
+  return OPT < 0 ? p != nullptr : ((OPT >> bit) & 1) != 0;
+}
+
+template <int EPI, typename TO, int OPT = -1>
 __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restrict__ out_f32,
                                        TO* __restrict__ z_out, const TO* __restrict__ z_in,
                                        const float* __restrict__ base, const float* __restrict__ X,
@@ -73,24 +82,24 @@ __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restric
   } else if constexpr (EPI == EPI_STORE_F32) {
     estore4<float>(out_f32 + idx, hstep * acc);
   } else if constexpr (EPI == EPI_GELU) {
-    if (z_out) estore4<TO>(z_out + idx, acc);
+    if (has_opt<OPT>(0, z_out)) estore4<TO>(z_out + idx, acc);
     f32x4 y = {gelu_t<TO>(acc[0]), gelu_t<TO>(acc[1]), gelu_t<TO>(acc[2]), gelu_t<TO>(acc[3])};
     estore4<TO>(out_op + idx, y);
   } else if constexpr (EPI == EPI_GELU_PRIME) {
-    if (z_out) estore4<TO>(z_out + idx, acc);
+    if (has_opt<OPT>(0, z_out)) estore4<TO>(z_out + idx, acc);
     f32x4 y = {gelu_prime_t<TO>(acc[0]), gelu_prime_t<TO>(acc[1]), gelu_prime_t<TO>(acc[2]),
                gelu_prime_t<TO>(acc[3])};
     estore4<TO>(out_op + idx, y);
   } else if constexpr (EPI == EPI_DGELU) {
     estore4<TO>(out_op + idx, acc * eload4<TO>(z_in + idx));
   } else if constexpr (EPI == EPI_RESID_INNER) {
-    if (base) acc += eload4<float>(base + idx);
+    if (has_opt<OPT>(0, base)) acc += eload4<float>(base + idx);
     estore4<float>(out_f32 + idx, acc);
   } else if constexpr (EPI == EPI_RESID_OUTER) {
     f32x4 x = eload4<float>(X + idx);
-    if (ybar) acc += eload4<float>(ybar + idx);
+    if (has_opt<OPT>(0, ybar)) acc += eload4<float>(ybar + idx);
     f32x4 r = x + hstep * acc;
-    if (RHS) r += eload4<float>(RHS + idx);
+    if (has_opt<OPT>(1, RHS)) r += eload4<float>(RHS + idx);
     estore4<float>(OUT + idx, r);
   }
 }
@@ -100,18 +109,18 @@ __device__ __forceinline__ void store8(bf16* p, f32x4 a, f32x4 b) {
   bf16x8 r = {(bf16)a[0], (bf16)a[1], (bf16)a[2], (bf16)a[3], (bf16)b[0], (bf16)b[1], (bf16)b[2], (bf16)b[3]};
   st_stream(reinterpret_cast<bf16x8*>(p), r);
 }
-template <int EPI>
+template <int EPI, int OPT = -1>
 __device__ __forceinline__ void apply8(bf16* __restrict__ out, bf16* __restrict__ z_out,
                                        const bf16* __restrict__ z_in, long idx, f32x4 a, f32x4 b) {
   if constexpr (EPI == EPI_STORE) {
     store8(out + idx, a, b);
   } else if constexpr (EPI == EPI_GELU) {
-    if (z_out) store8(z_out + idx, a, b);
+    if (has_opt<OPT>(0, z_out)) store8(z_out + idx, a, b);
 #pragma unroll
     for (int r = 0; r < 4; ++r) { a[r] = gelu_fast(a[r]); b[r] = gelu_fast(b[r]); }
     store8(out + idx, a, b);
   } else if constexpr (EPI == EPI_GELU_PRIME) {
-    if (z_out) store8(z_out + idx, a, b);
+    if (has_opt<OPT>(0, z_out)) store8(z_out + idx, a, b);
 #pragma unroll
     for (int r = 0; r < 4; ++r) { a[r] = gelu_prime_fast(a[r]); b[r] = gelu_prime_fast(b[r]); }
     store8(out + idx, a, b);
@@ -168,8 +177,16 @@ __device__ __forceinline__ void tile_epilogue(
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
         bv[p][h] = bias ? *reinterpret_cast<const f32x4*>(bias + ncol0 + CW * ((p * 64 + lane) % CI) + 4 * h) : z;
       }
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    // The bias vectors have landed before the first item uses them; saying so once, outside the
+    // row guards below, keeps the per-item waits on them from also waiting for every earlier
+    // store (stores count on the same counter), which would serialise the stores of a tile.
+    if (bias) __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0)
+    // GUARD: the wavefront's tile reaches past row M (ragged last tile of a group): per-row tests.
+    // Otherwise the items of a 32-row block are straight-line code, whose operand loads the
+    // compiler may issue ahead of the stores of earlier items (outputs never alias inputs).
+    auto rows32 = [&](auto guard_tag, auto opt_tag, int i) {
+      constexpr bool GUARD = decltype(guard_tag)::value;
+      constexpr int OPT = decltype(opt_tag)::value;
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -187,13 +204,33 @@ __device__ __forceinline__ void tile_epilogue(
         const long idx = (long)m * N + ncol0 + CW * ci;
         if constexpr (WIDE) {
           const f32x4 v1 = *reinterpret_cast<const f32x4*>(src + 16) + bv[it % NB][1];
-          if (m < M)
-            apply8<EPI>(reinterpret_cast<bf16*>(out_op), reinterpret_cast<bf16*>(z_out),
-                        reinterpret_cast<const bf16*>(z_in), idx, v0, v1);
+          if (!GUARD || m < M)
+            apply8<EPI, OPT>(reinterpret_cast<bf16*>(out_op), reinterpret_cast<bf16*>(z_out),
+                             reinterpret_cast<const bf16*>(z_in), idx, v0, v1);
         } else {
-          if (m < M) apply4<EPI, TO>(out_op, out_f32, z_out, z_in, base, X, ybar, RHS, OUT, hstep, idx, v0);
+          if (!GUARD || m < M)
+            apply4<EPI, TO, OPT>(out_op, out_f32, z_out, z_in, base, X, ybar, RHS, OUT, hstep, idx, v0);
         }
       }
+    };
+    // which optional operands this launch has (uniform over the launch): resolved once, so that
+    // the items carry no tests of their own
+    constexpr int NOPT = EPI == EPI_RESID_OUTER ? 4
+                         : (EPI == EPI_RESID_INNER || EPI == EPI_GELU || EPI == EPI_GELU_PRIME) ? 2 : 1;
+    const void* first = EPI == EPI_RESID_OUTER ? static_cast<const void*>(ybar)
+                        : EPI == EPI_RESID_INNER ? static_cast<const void*>(base) : static_cast<const void*>(z_out);
+    const int opt = NOPT == 1 ? 0 : ((first ? 1 : 0) | (NOPT == 4 && RHS ? 2 : 0));
+    auto all_rows = [&](auto guard_tag, auto opt_tag) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) rows32(guard_tag, opt_tag, i);
+    };
+    if (mrow0 + 32 * TM <= M) {                            // wave-uniform
+      if (opt == 0) all_rows(std::false_type{}, std::integral_constant<int, 0>{});
+      else if (opt == 1) all_rows(std::false_type{}, std::integral_constant<int, NOPT >= 2 ? 1 : 0>{});
+      else if (opt == 2) all_rows(std::false_type{}, std::integral_constant<int, NOPT == 4 ? 2 : 0>{});
+      else all_rows(std::false_type{}, std::integral_constant<int, NOPT == 4 ? 3 : 0>{});
+    } else {
+      all_rows(std::true_type{}, std::integral_constant<int, -1>{});
     }
   } else {
     // acc[i][j] register 4q+r of lane l  =  C[m = 32i + l%32][n = 32j + 8q + 4*(l/32) + r]
