@@ -106,9 +106,17 @@ template <typename T> __device__ __forceinline__ float gelu_prime_t(float z);
 template <> __device__ __forceinline__ float gelu_prime_t<float>(float z) { return gelu_prime_f(z); }
 template <> __device__ __forceinline__ float gelu_prime_t<bf16>(float z) { return gelu_prime_fast(z); }
 
-// accesses with the non-temporal hint, for data a kernel touches once
-template <typename V> __device__ __forceinline__ void st_stream(V* p, V v) { __builtin_nontemporal_store(v, p); }
-template <typename V> __device__ __forceinline__ V ld_stream(const V* p) { return __builtin_nontemporal_load(p); }
+// Accesses with the non-temporal hint, for data a kernel touches once.  Only for pointers into
+// device global memory (never LDS or scratch): they are issued as global, not flat, instructions,
+// which do not count against the counter that LDS reads are waited for on.
+template <typename V> __device__ __forceinline__ void st_stream(V* p, V v) {
+  typedef __attribute__((address_space(1))) V* gptr;
+  __builtin_nontemporal_store(v, (gptr)p);
+}
+template <typename V> __device__ __forceinline__ V ld_stream(const V* p) {
+  typedef const __attribute__((address_space(1))) V* gptr;
+  return __builtin_nontemporal_load((gptr)p);
+}
 
 // load / store 4 consecutive elements as floats
 template <typename T> __device__ __forceinline__ f32x4 load4(const T* p);
