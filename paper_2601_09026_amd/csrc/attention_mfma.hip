@@ -513,7 +513,10 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
           const int ql = 32 * qt + 8 * (i >> 2) + 4 * lh + (i & 3);
           const int qq = i0 + ql;
           const bool valid = qq < a.Sq && kj < a.Sk && (!a.causal || kj <= qq);
-          const float p = valid ? exp2_raw(fmaf(s[i], c, -Ls[ql])) : 0.f;
+          // computed for every pair and zeroed afterwards: a conditional evaluation would put the
+          // LDS read of the row's lse behind a branch per element
+          const float e = exp2_raw(fmaf(s[i], c, -Ls[ql]));
+          const float p = valid ? e : 0.f;
           s[i] = p;
           dp[i] = p * (dp[i] - Ds[ql]);
         }
