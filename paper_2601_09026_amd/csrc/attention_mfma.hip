@@ -524,13 +524,29 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const bf16x8 pb = regs_to_b(s, t), ab = regs_to_b(dp, t);
+        if constexpr (DH == 128) {
+          // d_head = 128 runs at the register limit: the fragments of one feature tile are fetched
+          // while the products of the tile before it run, and a fence per tile keeps the scheduler
+          // from fetching all of them ahead (it then spills the key fragments to scratch)
+          bf16x8 fo = frag_trans(dOt, lr, qt, t, lh), fq = frag_trans(Qt, lr, qt, t, lh);
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          dv[dt] = MFMA(frag_trans(dOt, 32 * dt + lr, qt, t, lh), pb, dv[dt]);
-          dk[dt] = MFMA(frag_trans(Qt, 32 * dt + lr, qt, t, lh), ab, dk[dt]);
-          // d_head = 128 runs at the register limit: keep the scheduler from fetching the fragments
-          // of all feature tiles ahead (it then spills the key fragments to scratch)
-          if constexpr (DH == 128) __builtin_amdgcn_sched_barrier(0);
+          for (int dt = 0; dt < DT; ++dt) {
+            bf16x8 fo_n = fo, fq_n = fq;
+            if (dt + 1 < DT) {
+              fo_n = frag_trans(dOt, 32 * (dt + 1) + lr, qt, t, lh);
+              fq_n = frag_trans(Qt, 32 * (dt + 1) + lr, qt, t, lh);
+            }
+            dv[dt] = MFMA(fo, pb, dv[dt]);
+            dk[dt] = MFMA(fq, ab, dk[dt]);
+            __builtin_amdgcn_sched_barrier(0);
+            fo = fo_n; fq = fq_n;
+          }
+        } else {
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) {
+            dv[dt] = MFMA(frag_trans(dOt, 32 * dt + lr, qt, t, lh), pb, dv[dt]);
+            dk[dt] = MFMA(frag_trans(Qt, 32 * dt + lr, qt, t, lh), ab, dk[dt]);
+          }
         }
       }
     }
