@@ -43,7 +43,11 @@ the coarse forward step that starts at layer n.
 Pins (tests/test_oracle_mgrit.py): one level or cf = 1 == serial; exactness
 front of two-level MGRIT (k C-points per F-iteration, 2k per FCF-iteration);
 serial solution is a fixed point with zero residual; closed-form recurrences
-for a scalar linear F; three-level fixed point and limit.  Stacked
+for a scalar linear F; three-level fixed point and limit; the coarse-level steps
+(step size cf^l h, parameters and linearisation point of the fine layer the step starts at,
+levels 1 and 2, forward, adjoint and stacked) against the layer function with explicit
+integers, and the first two-level iterate v_k = Phi_c(v_{k-1}) + Phi^cf(u_{k-1}) - Phi_c(u_{k-1})
+written out from the layer function alone (forward and adjoint).  Stacked
 encoder-decoder grid: serial pass == encoder stack then decoder stack run by
 the single-network functions; lambda_0 and parameter gradients against central
 differences of the stacked network; the hand-over lambda_X(N_enc) == terminal

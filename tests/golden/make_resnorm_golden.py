@@ -32,19 +32,45 @@ def run(name, memory=None):
     sh = tode.Shape(wl.arch, wl.d_model, wl.n_heads, wl.batch, wl.seq, wl.mem_seq, wl.ln_eps)
     th = [wls.layer_params(wl, n) for n in range(wl.N)]
     Z0 = wls.initial_state(wl)
+    relax = "FCF" if wl.relax else "F"
     t = time.time()
-    Z, rf, counts = omgrit.mgrit_forward(Z0, th, wl.h, wl.cf, wl.levels, wl.iters, sh, memory)
+    Z, rf, counts = omgrit.mgrit_forward(Z0, th, wl.h, wl.cf, wl.levels, wl.iters, sh, memory, relax)
     entry = {"forward": rf, "forward_evaluations": counts, "forward_seconds": time.time() - t,
              "Z_N_norm": float(np.linalg.norm(Z[-1])), "increment_norm": float(np.linalg.norm(Z[-1] - Z[0]))}
     print(name, "forward", rf, f"{entry['forward_seconds']:.0f}s", flush=True)
     if True:
         t = time.time()
         lam, ra, _ = omgrit.mgrit_adjoint(wls.terminal_adjoint(wl), Z, th, wl.h, wl.cf, wl.levels, wl.iters, sh,
-                                          memory)
+                                          memory, relax)
         entry.update({"adjoint": ra, "adjoint_seconds": time.time() - t,
-                      "lambda_0_norm": float(np.linalg.norm(lam[0]))})
+                      "lambda_0_norm": float(np.linalg.norm(lam[0])),
+                      "adjoint_increment_norm": float(np.linalg.norm(lam[0] - lam[-1]))})
         print(name, "adjoint", ra, f"{entry['adjoint_seconds']:.0f}s", flush=True)
     return entry, Z[-1]
+
+
+def run_stacked(name):
+    """The stacked encoder-decoder grid (one MGRIT over encoder layers followed by decoder layers)."""
+    sw = wls.stacked_workloads()[name]
+    e, d = sw.enc, sw.dec
+    she = tode.Shape(e.arch, e.d_model, e.n_heads, e.batch, e.seq, 0, e.ln_eps)
+    shd = tode.Shape(d.arch, d.d_model, d.n_heads, d.batch, d.seq, d.mem_seq, d.ln_eps)
+    th = [wls.stacked_layer_params(sw, n) for n in range(sw.N)]
+    relax = "FCF" if d.relax else "F"
+    Z0 = wls.stacked_initial_state(sw)
+    t = time.time()
+    Z, rf, counts = omgrit.stacked_mgrit_forward(Z0, th, sw.n_enc, d.h, d.cf, d.levels, d.iters, she, shd, relax)
+    entry = {"forward": rf, "forward_evaluations": counts, "forward_seconds": time.time() - t,
+             "Z_N_norm": float(np.linalg.norm(Z[-1])), "increment_norm": float(np.linalg.norm(Z[-1] - Z[0]))}
+    print(name, "forward", rf, f"{entry['forward_seconds']:.0f}s", flush=True)
+    t = time.time()
+    lam, ra, _ = omgrit.stacked_mgrit_adjoint(wls.stacked_terminal_adjoint(sw), Z, th, sw.n_enc, d.h, d.cf,
+                                              d.levels, d.iters, she, shd, relax)
+    entry.update({"adjoint": ra, "adjoint_seconds": time.time() - t,
+                  "lambda_0_norm": float(np.linalg.norm(lam[0])),
+                  "adjoint_increment_norm": float(np.linalg.norm(lam[0] - lam[-1]))})
+    print(name, "adjoint", ra, f"{entry['adjoint_seconds']:.0f}s", flush=True)
+    return entry
 
 
 def main():
@@ -53,6 +79,11 @@ def main():
     enc_out = None
     for name in names:
         memory = None
+        if name in wls.stacked_workloads():
+            data[name] = run_stacked(name)
+            with open(OUT, "w") as f:
+                json.dump(data, f, indent=1, sort_keys=True)
+            continue
         if name == "mt_decoder":
             if enc_out is None:
                 _, enc_out = run("mt_encoder")

@@ -287,6 +287,146 @@ def test_adjoint_coarse_step_is_transpose_of_coarse_forward_step():
     assert abs((mu * Jv).sum() - (adj(1, 0, mu) * v).sum()) < 1e-7 * abs((mu * Jv).sum())
 
 
+# ------------------------------------------------------------------ coarse-level operators
+def test_coarse_forward_step_uses_step_cf_pow_l_h_and_the_injected_layer():
+    """Section 3.2.1: level l has the step size cf^l h, and a coarse step takes the parameters of
+    the fine layer it starts at ("injected weights"): Phi^l_j(w) = w + cf^l h F(w; theta_{j cf^l}).
+    Written out here with the layer function and explicit integers (cf = 4: cf^2 = 16 differs
+    from 2 cf = 8, so a product in place of the power fails too)."""
+    wl, sh, th = tiny(N=32, cf=4, h=0.125, std=0.4)
+    w = wls.initial_state(wl).astype(np.float64)
+    step = mgrit.forward_propagator(th, 0.125, 4, sh)
+    #            level, j, fine layer, step size
+    for lvl, j, layer, hstep in [(0, 5, 5, 0.125), (1, 0, 0, 0.5), (1, 3, 12, 0.5), (1, 7, 28, 0.5),
+                                 (2, 0, 0, 2.0), (2, 1, 16, 2.0)]:
+        want = w + hstep * tode.F(w, th[layer], sh)
+        assert np.abs(step(lvl, j, w) - want).max() < 1e-13 * np.abs(want).max(), (lvl, j)
+        # the neighbouring layers and the fine step size give something else
+        assert np.abs(step(lvl, j, w) - (w + hstep * tode.F(w, th[layer + 1], sh))).max() > 1e-4
+        if lvl:
+            assert np.abs(step(lvl, j, w) - (w + 0.125 * tode.F(w, th[layer], sh))).max() > 1e-4
+
+
+def test_coarse_adjoint_step_uses_step_cf_pow_l_h_and_lands_on_the_injected_layer():
+    """Section 3.2.2: the adjoint runs the same grid backwards.  The level-l step from reversed
+    point j to j+1 is the transpose of the forward coarse step that starts at layer
+    n = N - (j+1) cf^l: mu + cf^l h (dF/dZ(Z_n; theta_n))^T mu."""
+    wl, sh, th = tiny(arch=wls.ARCH_CAUSAL, N=32, cf=4, h=0.125, std=0.4)
+    Z = mgrit.serial_forward(wls.initial_state(wl), th, 0.125, sh)
+    mu = wls.terminal_adjoint(wl).astype(np.float64)
+    step = mgrit.adjoint_propagator(th, Z, 0.125, 4, sh)
+    for lvl, j, layer, hstep in [(0, 0, 31, 0.125), (0, 9, 22, 0.125), (1, 0, 28, 0.5), (1, 2, 20, 0.5),
+                                 (1, 7, 0, 0.5), (2, 0, 16, 2.0), (2, 1, 0, 2.0)]:
+        dX, _ = tode.F_vjp(Z[layer], th[layer], mu, sh)
+        want = mu + hstep * dX
+        assert np.abs(step(lvl, j, mu) - want).max() < 1e-13 * np.abs(want).max(), (lvl, j)
+        near = layer - 1 if layer else layer + 1
+        other, _ = tode.F_vjp(Z[near], th[near], mu, sh)
+        assert np.abs(step(lvl, j, mu) - (mu + hstep * other)).max() > 1e-5
+        if lvl:
+            assert np.abs(step(lvl, j, mu) - (mu + 0.125 * dX)).max() > 1e-5
+
+
+def test_stacked_coarse_steps_use_step_cf_pow_l_h_and_the_layer_they_start_at():
+    """The same two statements for the stacked encoder-decoder grid (section 3.1, eq.
+    "fp_transformer"): a coarse step takes type, parameters and step size cf^l h of the fine layer
+    n it starts at: an encoder step on X below N_enc, a decoder step on Y (memory = the X part of
+    its input) from there on; its transpose also adds the memory cotangent to the X part."""
+    cf, h, n_enc, n_dec = 4, 0.125, 8, 24
+    enc = wls.Workload("e", wls.ARCH_ENCODER, 16, 2, 32, 1, 4, 0, n_enc, h, cf, 3, 1, wls.DTYPE_F32, 31)
+    dec = wls.Workload("d", wls.ARCH_CROSS, 16, 2, 32, 1, 3, 4, n_dec, h, cf, 3, 1, wls.DTYPE_F32, 32)
+    sw = wls.StackedWorkload("s", enc, dec)
+    she, shd = tode.Shape(enc.arch, 16, 2, 1, 4), tode.Shape(dec.arch, 16, 2, 1, 3, 4)
+    th = [wls.stacked_layer_params(sw, n, 0.4) for n in range(sw.N)]
+    w = wls.stacked_initial_state(sw).astype(np.float64)
+    X, Y = w[:4], w[4:]
+    fwd = mgrit.stacked_forward_propagator(th, n_enc, h, cf, she, shd)
+    for lvl, j, layer, hstep in [(1, 1, 4, 0.5), (1, 2, 8, 0.5), (1, 5, 20, 0.5), (2, 0, 0, 2.0), (2, 1, 16, 2.0)]:
+        if layer < n_enc:
+            want = np.concatenate([X + hstep * tode.F(X, th[layer], she), Y])
+        else:
+            want = np.concatenate([X, Y + hstep * tode.F(Y, th[layer], shd, X)])
+        assert np.abs(fwd(lvl, j, w) - want).max() < 1e-13 * np.abs(want).max(), (lvl, j)
+    Z = mgrit.stacked_serial_forward(w, th, n_enc, h, she, shd)
+    mu = wls.stacked_terminal_adjoint(sw).astype(np.float64)
+    mx, my = mu[:4], mu[4:]
+    adj = mgrit.stacked_adjoint_propagator(th, Z, n_enc, h, cf, she, shd)
+    for lvl, j, layer, hstep in [(1, 0, 28, 0.5), (1, 4, 12, 0.5), (1, 5, 8, 0.5), (1, 6, 4, 0.5),
+                                 (2, 0, 16, 2.0), (2, 1, 0, 2.0)]:
+        Xn, Yn = Z[layer][:4], Z[layer][4:]
+        if layer < n_enc:
+            dX, _ = tode.F_vjp(Xn, th[layer], mx, she)
+            want = np.concatenate([mx + hstep * dX, my])
+        else:
+            dY, dE = tode.F_vjp(Yn, th[layer], my, shd, Xn)
+            want = np.concatenate([mx + hstep * dE, my + hstep * dY])
+        assert np.abs(adj(lvl, j, mu) - want).max() < 1e-13 * np.abs(want).max(), (lvl, j)
+
+
+def test_two_level_first_iterate_written_out_from_the_layer_function():
+    """Fig. 2 / section 3.2.1 for two levels with F-relaxation, in the form the error equation
+    takes once r and the injected values are substituted: with u the C-point values before the
+    cycle (all equal to Z_0 here),
+        v_k = Phi_c,k-1(v_{k-1}) + Phi_{k cf - 1} o .. o Phi_{(k-1) cf}(u_{k-1}) - Phi_c,k-1(u_{k-1}),
+    Phi_n(w) = w + h F(w; theta_n) the fine steps and Phi_c,k(w) = w + cf h F(w; theta_{k cf}) the
+    coarse one -- layer-dependent theta, so a wrong layer index or step size on the coarse level
+    changes v.  Nothing of the oracle's driver or propagators is used to build the expected values."""
+    cf, h = 4, 0.5
+    wl, sh, th = tiny(N=16, cf=cf, h=h, std=0.4)
+    Z0 = wls.initial_state(wl).astype(np.float64)
+    M = wl.N // cf
+    u = [Z0.copy() for _ in range(M + 1)]
+    v = [Z0.copy()]
+    for k in range(1, M + 1):
+        fine = u[k - 1]
+        for n in range((k - 1) * cf, k * cf):
+            fine = fine + h * tode.F(fine, th[n], sh)
+        coarse_v = v[k - 1] + cf * h * tode.F(v[k - 1], th[(k - 1) * cf], sh)
+        coarse_u = u[k - 1] + cf * h * tode.F(u[k - 1], th[(k - 1) * cf], sh)
+        v.append(coarse_v + fine - coarse_u)
+    W, res, _ = mgrit.mgrit_forward(Z0, th, h, cf, 2, 1, sh, relax="F")
+    scale = np.abs(v[-1]).max()
+    for k in range(M + 1):
+        assert np.abs(W[k * cf] - v[k]).max() < 1e-12 * scale, k
+    # the second C-point is a genuine inexact iterate: it is not what serial propagation gives
+    ser = mgrit.serial_forward(Z0, th, h, sh)
+    assert np.abs(v[2] - ser[2 * cf]).max() > 1e-3 * scale
+    # F-points follow their corrected C-point by fine steps (interpolation)
+    z = v[2]
+    for i in range(1, cf):
+        z = z + h * tode.F(z, th[2 * cf + i - 1], sh)
+        assert np.abs(W[2 * cf + i] - z).max() < 1e-12 * scale
+
+
+def test_two_level_first_adjoint_iterate_written_out_from_the_layer_vjp():
+    """The same cycle for the adjoint (section 3.2.2) on the reversed index m = N - n, mu_m =
+    lambda_{N-m}: the fine step from m to m+1 is mu + h J(Z_n; theta_n)^T mu with n = N - 1 - m, the
+    coarse step from coarse point k-1 to k is mu + cf h J(Z_n; theta_n)^T mu with n = N - k cf."""
+    cf, h = 4, 0.5
+    wl, sh, th = tiny(arch=wls.ARCH_CAUSAL, N=16, cf=cf, h=h, std=0.4)
+    N, M = wl.N, wl.N // cf
+    Z = mgrit.serial_forward(wls.initial_state(wl), th, h, sh)
+    lamN = wls.terminal_adjoint(wl).astype(np.float64)
+
+    def jt(n, mu):
+        return tode.F_vjp(Z[n], th[n], mu, sh)[0]
+
+    u = [lamN.copy() for _ in range(M + 1)]
+    v = [lamN.copy()]
+    for k in range(1, M + 1):
+        fine = u[k - 1]
+        for m in range((k - 1) * cf, k * cf):
+            fine = fine + h * jt(N - 1 - m, fine)
+        n_c = N - k * cf
+        v.append(v[k - 1] + cf * h * jt(n_c, v[k - 1]) + fine - (u[k - 1] + cf * h * jt(n_c, u[k - 1])))
+    lam, _, _ = mgrit.mgrit_adjoint(lamN, Z, th, h, cf, 2, 1, sh, relax="F")
+    scale = np.abs(v[-1]).max()
+    for k in range(M + 1):
+        assert np.abs(lam[N - k * cf] - v[k]).max() < 1e-12 * scale, k
+    ser = mgrit.serial_adjoint(lamN, Z, th, h, sh)
+    assert np.abs(v[2] - ser[N - 2 * cf]).max() > 1e-4 * scale
+
+
 def test_cross_attention_decoder_mgrit_runs_and_converges():
     wl, sh, th = tiny(arch=wls.ARCH_CROSS, N=8, cf=2, h=1.0, std=0.3)
     mem = wls.cross_memory(wl)
