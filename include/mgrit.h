@@ -237,6 +237,27 @@ int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups,
                              const void* const* rhs, const void* memory, float hstep,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* layer_step_batched for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results as layer_step_batched without the workspace: the scratch memory is a fixed array of
+ * MGRIT_STATIC_SCRATCH_BYTES inside the library's device code (each GPU the library is loaded on
+ * holds its own copy until the process ends).  The call allocates nothing -- no device or host
+ * memory, no stream, no event -- and enqueues every launch on `stream` alone (no helper lane).
+ *   - Sizes whose scratch need, mgrit_layer_step_static_bytes(), exceeds MGRIT_STATIC_SCRATCH_BYTES are
+ *     rejected with MGRIT_WORKSPACE_TOO_SMALL (0 from the query = invalid arguments); nothing is enqueued.
+ *   - All calls on one GPU share that GPU's array, which keeps the previous call's contents (no kernel
+ *     reads a scratch location before writing it, so nothing needs clearing).  Calls that overlap in
+ *     time on one GPU -- two streams, two host threads -- race on it: serialise them.
+ *   - The first call on a device looks up the array's device address (hipGetSymbolAddress, no
+ *     allocation); make that call outside stream capture.
+ * Results are bit-identical to layer_step_batched run with mgrit_set_lanes(1). */
+#define MGRIT_STATIC_SCRATCH_BYTES (256u << 20)
+size_t mgrit_layer_step_static_bytes(const mgrit_model_desc* desc, int adjoint, int n_groups);
+int layer_step_batched_static(const mgrit_model_desc* desc, int adjoint, int n_groups,
+                              const void* const* in, void* const* out,
+                              const void* const* theta, const void* const* lin_state,
+                              const void* const* rhs, const void* memory, float hstep, void* stream);
+
 /* ---- adaptive control of the inexactness (sec. 3.2.3), host only ---------------------------
  * The convergence factor of MGRIT iteration k is ||r^(k+1)|| / ||r^(k)||, the ratio of consecutive
  * entries of the `resnorm` output above.  Policy of the paper: every `probe_every` batches run one

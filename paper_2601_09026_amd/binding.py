@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmgrit_hip.so")
 
 MGRIT_OK = 0
+MGRIT_INVALID_ARG, MGRIT_UNSUPPORTED, MGRIT_WORKSPACE_TOO_SMALL, MGRIT_HIP_ERROR = -1, -2, -3, -4
 P_NAMES = ["ln1_g", "ln1_b", "bqkv", "bo", "ln2_g", "ln2_b", "b1", "b2", "ln3_g", "ln3_b", "bq_c",
            "bkv_c", "bo_c", "Wqkv", "Wo", "W1", "W2", "Wq_c", "Wkv_c", "Wo_c"]
 P_COUNT = len(P_NAMES)
@@ -96,6 +97,11 @@ def lib() -> C.CDLL:
         L.layer_step_batched.argtypes = [C.POINTER(ModelDesc), C.c_int, C.c_int, vpp, vpp, vpp, vpp, vpp, vp,
                                          C.c_float, vp, C.c_size_t, vp]
         L.layer_step_batched.restype = C.c_int
+        L.mgrit_layer_step_static_bytes.argtypes = [C.POINTER(ModelDesc), C.c_int, C.c_int]
+        L.mgrit_layer_step_static_bytes.restype = C.c_size_t
+        L.layer_step_batched_static.argtypes = [C.POINTER(ModelDesc), C.c_int, C.c_int, vpp, vpp, vpp, vpp, vpp, vp,
+                                                C.c_float, vp]
+        L.layer_step_batched_static.restype = C.c_int
         L.mgrit_buffered_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.POINTER(BufferOpts),
                                                      C.c_int]
         L.mgrit_buffered_workspace_bytes.restype = C.c_size_t
@@ -407,6 +413,31 @@ def layer_step_batched(desc: ModelDesc, adjoint: bool, inputs: List[torch.Tensor
                                   float(hstep), _ptr(workspace), workspace.numel(), _stream_handle(stream))
     if st != MGRIT_OK:
         raise MgritError(st, "layer_step_batched")
+    return outputs
+
+
+STATIC_SCRATCH_BYTES = 256 << 20     # MGRIT_STATIC_SCRATCH_BYTES of the header
+
+
+def mgrit_layer_step_static_bytes(desc: ModelDesc, adjoint: bool, n_groups: int) -> int:
+    return int(lib().mgrit_layer_step_static_bytes(C.byref(desc), int(adjoint), n_groups))
+
+
+def layer_step_batched_static(desc: ModelDesc, adjoint: bool, inputs: List[torch.Tensor],
+                              outputs: List[torch.Tensor], theta: List[torch.Tensor], hstep: float,
+                              lin_state: Optional[List[torch.Tensor]] = None,
+                              rhs: Optional[List[torch.Tensor]] = None, memory: Optional[torch.Tensor] = None,
+                              stream: Optional[torch.cuda.Stream] = None):
+    """layer_step_batched on the library's own fixed scratch array: no workspace, nothing allocated."""
+    G = len(inputs)
+    T, d = desc.batch * desc.seq, desc.d_model
+    for t in list(inputs) + list(outputs) + list(lin_state or []) + list(rhs or []):
+        _check_state(t, (T, d), "state")
+    st = lib().layer_step_batched_static(C.byref(desc), int(adjoint), G, _ptr_array(inputs), _ptr_array(outputs),
+                                         _ptr_array(theta), _ptr_array(lin_state), _ptr_array(rhs), _ptr(memory),
+                                         float(hstep), _stream_handle(stream))
+    if st != MGRIT_OK:
+        raise MgritError(st, "layer_step_batched_static")
     return outputs
 
 

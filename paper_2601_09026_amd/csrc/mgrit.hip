@@ -21,6 +21,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "../../include/mgrit.h"
@@ -1103,6 +1104,121 @@ int check_ptr_array(const void* const* a, int n) {
   return MGRIT_OK;
 }
 
+// Scratch need of one batched layer step; second_lane: the helper lane's work buffers included
+// (when two lanes are switched on and there are at least two groups).
+size_t layer_step_bytes(const mgrit_model_desc* desc, int adjoint, int n_groups, bool second_lane) {
+  if (validate_desc(desc) != MGRIT_OK || n_groups < 1) return 0;
+  Engine E;
+  E.init(desc, nullptr);
+  Bump b(nullptr);
+  int gc = max_groups(desc, n_groups) < n_groups ? max_groups(desc, n_groups) : n_groups;
+  Engine E2;
+  if (adjoint) {
+    E.carve_adjoint(b, gc, n_groups);
+    if (second_lane && n_groups >= 2) make_lane(E2, E, b, true, true);
+    b.take_bytes((size_t)n_groups * E.lay.block_bytes);
+    b.take<void*>((size_t)n_groups * 6);
+  } else {
+    E.carve_forward(b, gc);
+    if (second_lane && n_groups >= 2) make_lane(E2, E, b, false, true);
+    b.take<void*>((size_t)n_groups * 4);
+  }
+  return (b.off + 255) / 256 * 256;
+}
+
+// The batched layer step on scratch memory of `workspace_bytes` at `workspace`; second_lane as above
+// (false: every launch goes to `stream`, no helper stream or event is touched).
+int layer_step_on(const mgrit_model_desc* desc, int adjoint, int n_groups, const void* const* in,
+                  void* const* out, const void* const* theta, const void* const* lin_state,
+                  const void* const* rhs, const void* memory, float hstep, void* workspace,
+                  size_t workspace_bytes, void* stream, bool second_lane) {
+  STCHK(validate_desc(desc));
+  if (n_groups < 1 || !workspace || !isfinite(hstep)) return MGRIT_INVALID_ARG;
+  STCHK(check_ptr_array(in, n_groups));
+  STCHK(check_ptr_array((const void* const*)out, n_groups));
+  STCHK(check_ptr_array(theta, n_groups));
+  if (rhs) STCHK(check_ptr_array(rhs, n_groups));
+  if (adjoint) STCHK(check_ptr_array(lin_state, n_groups));
+  if (desc->arch == MGRIT_ARCH_CROSS && !memory) return MGRIT_INVALID_ARG;
+  const size_t need = layer_step_bytes(desc, adjoint, n_groups, second_lane);
+  if (need == 0) return MGRIT_INVALID_ARG;
+  if (workspace_bytes < need) return MGRIT_WORKSPACE_TOO_SMALL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  Engine E;
+  E.init(desc, st);
+  Bump b(workspace);
+  const int gc = max_groups(desc, n_groups) < n_groups ? max_groups(desc, n_groups) : n_groups;
+  const int G = n_groups;
+  Engine E2;
+  Engine* L2 = nullptr;
+  if (adjoint) {
+    E.carve_adjoint(b, gc, G);
+    if (second_lane && G >= 2 && make_lane(E2, E, b, true, false)) L2 = &E2;
+    char* tblocks = static_cast<char*>(b.take_bytes((size_t)G * E.lay.block_bytes));
+    void** tabs = b.take<void*>((size_t)G * 6);
+    void **tIn = tabs, **tOut = tabs + G, **tTh = tabs + 2 * G, **tLin = tabs + 3 * G, **tRhs = tabs + 4 * G,
+         **tThT = tabs + 5 * G;
+    HIPCHK(upload_pointers(tIn, in, G, st));
+    HIPCHK(upload_pointers(tOut, (const void* const*)out, G, st));
+    HIPCHK(upload_pointers(tTh, theta, G, st));
+    HIPCHK(upload_pointers(tLin, lin_state, G, st));
+    if (rhs) HIPCHK(upload_pointers(tRhs, rhs, G, st));
+    HIPCHK(launch_fill_table(tThT, tblocks, (long)E.lay.block_bytes, G, st));
+    Params TH = {(const void* const*)tTh, 0, 1}, THT = {(const void* const*)tThT, 0, 1};
+    Rows IN = {(const void* const*)tIn, 0, 1}, OUT = {(const void* const*)tOut, 0, 1};
+    Rows LIN = {(const void* const*)tLin, 0, 1};
+    Rows RHS = rhs ? Rows{(const void* const*)tRhs, 0, 1} : NO_ROWS;
+    STCHK(transpose_blocks(E, G, TH, THT));
+    if (desc->arch == MGRIT_ARCH_CROSS)
+      HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
+    STCHK(forward_groups(E, L2, G, LIN, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
+    return adjoint_groups(E, L2, G, IN, OUT, RHS, TH, THT, LIN, Slots{0, 1}, hstep);
+  }
+  E.carve_forward(b, gc);
+  if (second_lane && G >= 2 && make_lane(E2, E, b, false, false)) L2 = &E2;
+  void** tabs = b.take<void*>((size_t)G * 4);
+  void **tIn = tabs, **tOut = tabs + G, **tTh = tabs + 2 * G, **tRhs = tabs + 3 * G;
+  HIPCHK(upload_pointers(tIn, in, G, st));
+  HIPCHK(upload_pointers(tOut, (const void* const*)out, G, st));
+  HIPCHK(upload_pointers(tTh, theta, G, st));
+  if (rhs) HIPCHK(upload_pointers(tRhs, rhs, G, st));
+  if (desc->arch == MGRIT_ARCH_CROSS)
+    HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
+  Params TH = {(const void* const*)tTh, 0, 1};
+  Rows IN = {(const void* const*)tIn, 0, 1}, OUT = {(const void* const*)tOut, 0, 1};
+  Rows RHS = rhs ? Rows{(const void* const*)tRhs, 0, 1} : NO_ROWS;
+  return forward_groups(E, L2, G, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
+}
+
+}  // namespace
+
+// Scratch memory of layer_step_batched_static: one array per GPU, part of the loaded code object (the
+// runtime places it when the library is loaded on a device; nothing is allocated at call time).
+// On the host this name is only a handle for hipGetSymbolAddress: the device address is looked up once
+// per device and that pointer, never the name, is what host code passes on.
+static __device__ __align__(256) unsigned char scratch[MGRIT_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device.
+int static_scratch(void** out) {
+  int dev = -1;
+  HIPCHK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return MGRIT_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return MGRIT_HIP_ERROR;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MGRIT_OK;
+}
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -1126,23 +1242,7 @@ size_t mgrit_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opt
 }
 
 size_t mgrit_layer_step_workspace_bytes(const mgrit_model_desc* desc, int adjoint, int n_groups) {
-  if (validate_desc(desc) != MGRIT_OK || n_groups < 1) return 0;
-  Engine E;
-  E.init(desc, nullptr);
-  Bump b(nullptr);
-  int gc = max_groups(desc, n_groups) < n_groups ? max_groups(desc, n_groups) : n_groups;
-  Engine E2;
-  if (adjoint) {
-    E.carve_adjoint(b, gc, n_groups);
-    if (n_groups >= 2) make_lane(E2, E, b, true, true);
-    b.take_bytes((size_t)n_groups * E.lay.block_bytes);
-    b.take<void*>((size_t)n_groups * 6);
-  } else {
-    E.carve_forward(b, gc);
-    if (n_groups >= 2) make_lane(E2, E, b, false, true);
-    b.take<void*>((size_t)n_groups * 4);
-  }
-  return (b.off + 255) / 256 * 256;
+  return layer_step_bytes(desc, adjoint, n_groups, true);
 }
 
 int64_t mgrit_step_evaluations(const mgrit_opts* opts) {
@@ -1579,63 +1679,26 @@ int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups, 
                        void* const* out, const void* const* theta, const void* const* lin_state,
                        const void* const* rhs, const void* memory, float hstep, void* workspace,
                        size_t workspace_bytes, void* stream) {
-  STCHK(validate_desc(desc));
-  if (n_groups < 1 || !workspace || !isfinite(hstep)) return MGRIT_INVALID_ARG;
-  STCHK(check_ptr_array(in, n_groups));
-  STCHK(check_ptr_array((const void* const*)out, n_groups));
-  STCHK(check_ptr_array(theta, n_groups));
-  if (rhs) STCHK(check_ptr_array(rhs, n_groups));
-  if (adjoint) STCHK(check_ptr_array(lin_state, n_groups));
-  if (desc->arch == MGRIT_ARCH_CROSS && !memory) return MGRIT_INVALID_ARG;
-  const size_t need = mgrit_layer_step_workspace_bytes(desc, adjoint, n_groups);
-  if (need == 0) return MGRIT_INVALID_ARG;
-  if (workspace_bytes < need) return MGRIT_WORKSPACE_TOO_SMALL;
-  hipStream_t st = static_cast<hipStream_t>(stream);
+  return layer_step_on(desc, adjoint, n_groups, in, out, theta, lin_state, rhs, memory, hstep, workspace,
+                       workspace_bytes, stream, true);
+}
 
-  Engine E;
-  E.init(desc, st);
-  Bump b(workspace);
-  const int gc = max_groups(desc, n_groups) < n_groups ? max_groups(desc, n_groups) : n_groups;
-  const int G = n_groups;
-  Engine E2;
-  Engine* L2 = nullptr;
-  if (adjoint) {
-    E.carve_adjoint(b, gc, G);
-    if (G >= 2 && make_lane(E2, E, b, true, false)) L2 = &E2;
-    char* tblocks = static_cast<char*>(b.take_bytes((size_t)G * E.lay.block_bytes));
-    void** tabs = b.take<void*>((size_t)G * 6);
-    void **tIn = tabs, **tOut = tabs + G, **tTh = tabs + 2 * G, **tLin = tabs + 3 * G, **tRhs = tabs + 4 * G,
-         **tThT = tabs + 5 * G;
-    HIPCHK(upload_pointers(tIn, in, G, st));
-    HIPCHK(upload_pointers(tOut, (const void* const*)out, G, st));
-    HIPCHK(upload_pointers(tTh, theta, G, st));
-    HIPCHK(upload_pointers(tLin, lin_state, G, st));
-    if (rhs) HIPCHK(upload_pointers(tRhs, rhs, G, st));
-    HIPCHK(launch_fill_table(tThT, tblocks, (long)E.lay.block_bytes, G, st));
-    Params TH = {(const void* const*)tTh, 0, 1}, THT = {(const void* const*)tThT, 0, 1};
-    Rows IN = {(const void* const*)tIn, 0, 1}, OUT = {(const void* const*)tOut, 0, 1};
-    Rows LIN = {(const void* const*)tLin, 0, 1};
-    Rows RHS = rhs ? Rows{(const void* const*)tRhs, 0, 1} : NO_ROWS;
-    STCHK(transpose_blocks(E, G, TH, THT));
-    if (desc->arch == MGRIT_ARCH_CROSS)
-      HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
-    STCHK(forward_groups(E, L2, G, LIN, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
-    return adjoint_groups(E, L2, G, IN, OUT, RHS, TH, THT, LIN, Slots{0, 1}, hstep);
-  }
-  E.carve_forward(b, gc);
-  if (G >= 2 && make_lane(E2, E, b, false, false)) L2 = &E2;
-  void** tabs = b.take<void*>((size_t)G * 4);
-  void **tIn = tabs, **tOut = tabs + G, **tTh = tabs + 2 * G, **tRhs = tabs + 3 * G;
-  HIPCHK(upload_pointers(tIn, in, G, st));
-  HIPCHK(upload_pointers(tOut, (const void* const*)out, G, st));
-  HIPCHK(upload_pointers(tTh, theta, G, st));
-  if (rhs) HIPCHK(upload_pointers(tRhs, rhs, G, st));
-  if (desc->arch == MGRIT_ARCH_CROSS)
-    HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
-  Params TH = {(const void* const*)tTh, 0, 1};
-  Rows IN = {(const void* const*)tIn, 0, 1}, OUT = {(const void* const*)tOut, 0, 1};
-  Rows RHS = rhs ? Rows{(const void* const*)tRhs, 0, 1} : NO_ROWS;
-  return forward_groups(E, L2, G, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
+size_t mgrit_layer_step_static_bytes(const mgrit_model_desc* desc, int adjoint, int n_groups) {
+  return layer_step_bytes(desc, adjoint, n_groups, false);
+}
+
+int layer_step_batched_static(const mgrit_model_desc* desc, int adjoint, int n_groups, const void* const* in,
+                              void* const* out, const void* const* theta, const void* const* lin_state,
+                              const void* const* rhs, const void* memory, float hstep, void* stream) {
+  STCHK(validate_desc(desc));
+  if (n_groups < 1) return MGRIT_INVALID_ARG;
+  const size_t need = layer_step_bytes(desc, adjoint, n_groups, false);
+  if (need == 0) return MGRIT_INVALID_ARG;
+  if (need > (size_t)MGRIT_STATIC_SCRATCH_BYTES) return MGRIT_WORKSPACE_TOO_SMALL;
+  void* ws = nullptr;
+  STCHK(static_scratch(&ws));
+  return layer_step_on(desc, adjoint, n_groups, in, out, theta, lin_state, rhs, memory, hstep, ws,
+                       (size_t)MGRIT_STATIC_SCRATCH_BYTES, stream, false);
 }
 
 const char* mgrit_status_string(int status) {
