@@ -3,7 +3,8 @@
 
 One "step" = one pass of the whole hot path over one batch of synthetic input:
 mgrit_forward followed by mgrit_adjoint (linearised about the forward result) at the named
-workload.  The headline value is layer-steps*tokens/s = (Phi + Psi evaluations enqueued on
+workload; the default is the largest benchmark configuration that runs forward + adjoint, the
+GPT-2-small shape (causal, 128 layers, three levels).  The headline value is layer-steps*tokens/s = (Phi + Psi evaluations enqueued on
 all levels) x (batch*seq) / wall time, with all inputs resident in HBM before the timed
 region.  The adjoint's one-off N-layer linearisation pass is timed but not counted as
 evaluations.
@@ -33,9 +34,9 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="bert_base",
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gpt2_small",
                     help="tiny_encoder | bert_base | gpt2_small | vit_small | mt_encoder | mt_decoder | "
                          "mc_deep_narrow | mt_stacked (encoder and decoder on one grid)")
     ap.add_argument("--no-adjoint", action="store_true", help="time mgrit_forward only")
@@ -61,20 +62,17 @@ def parse():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not record per-kernel HIP events in the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing sample")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0,
+                    help="budget of the oracle timing sample (half at all host threads, half at one)")
     ap.add_argument("--breakdown", action="store_true", help="print a per-kernel-class table to stderr")
     return ap.parse_args()
 
 
-def cpu_baseline(wl, n_phi, n_psi, budget_s):
-    """Time the fp64 numpy oracle (as it stands) on a bounded sample of the same workload."""
+def oracle_sample(wl, n_phi, n_psi, budget_s, max_pairs):
+    """Layer steps of the fp64 numpy oracle (as it stands) at the workload's full shape for about
+    budget_s seconds; the per-step times are weighted by the evaluation counts of one bench step."""
     from oracle import transformer_ode as tode
     from paper_2601_09026_amd import workloads as wls
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count() or 1
     sh = tode.Shape(wl.arch, wl.d_model, wl.n_heads, wl.batch, wl.seq, wl.mem_seq, wl.ln_eps)
     th = wls.layer_params(wl, 0)
     Z = wls.initial_state(wl).astype(np.float64)
@@ -87,15 +85,36 @@ def cpu_baseline(wl, n_phi, n_psi, budget_s):
         if n_psi:
             t = time.perf_counter(); lam = tode.psi(lam, Z, th, wl.h, sh, mem); t_psi += time.perf_counter() - t
             n2 += 1
-        if time.perf_counter() - t0 > budget_s or n1 >= 64:
+        if time.perf_counter() - t0 > budget_s or n1 >= max_pairs:
             break
     est = n_phi * (t_phi / n1) + (n_psi * (t_psi / n2) if n2 else 0.0)
-    value = (n_phi + n_psi) * wl.tokens / est
-    return {"value": value, "unit": "layer-steps*tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{n1} forward + {n2} adjoint layer steps of the fp64 numpy oracle at the full "
-                      f"{wl.name} shape (T={wl.tokens}); per-step times weighted by the step's "
-                      f"{n_phi} forward / {n_psi} adjoint evaluations",
+    return {"value": (n_phi + n_psi) * wl.tokens / est, "n_forward": n1, "n_adjoint": n2,
             "s_per_forward_step": t_phi / n1, "s_per_adjoint_step": (t_psi / n2) if n2 else None}
+
+
+def cpu_baseline(wl, n_phi, n_psi, budget_s):
+    """The oracle timed on the host: at all the threads its BLAS uses (the headline `value`, `cores`) and
+    at one thread (`single_thread`), each on a bounded sample of the same workload."""
+    try:
+        from threadpoolctl import threadpool_info, threadpool_limits
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threadpool_limits = None
+        cores = os.cpu_count() or 1
+    full = oracle_sample(wl, n_phi, n_psi, budget_s / 2, 64)
+    out = {"value": full["value"], "unit": "layer-steps*tokens/s", "cores": int(cores), "kind": "oracle",
+           "sample": f"{full['n_forward']} forward + {full['n_adjoint']} adjoint layer steps of the fp64 numpy oracle at "
+                     f"the full {wl.name} shape (T={wl.tokens}); per-step times weighted by the step's "
+                     f"{n_phi} forward / {n_psi} adjoint evaluations",
+           "s_per_forward_step": full["s_per_forward_step"], "s_per_adjoint_step": full["s_per_adjoint_step"]}
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            one = oracle_sample(wl, n_phi, n_psi, budget_s / 2, 8)
+        out["single_thread"] = {"value": one["value"], "unit": "layer-steps*tokens/s", "cores": 1,
+                                "sample": f"{one['n_forward']} forward + {one['n_adjoint']} adjoint layer steps, same shape",
+                                "s_per_forward_step": one["s_per_forward_step"],
+                                "s_per_adjoint_step": one["s_per_adjoint_step"]}
+    return out
 
 
 def main():
@@ -204,14 +223,22 @@ def main():
     for _ in range(args.warmup):
         timed_step()
     torch.cuda.synchronize()
-    # timed region: exactly K steps, nothing else enqueued, no instrumentation
+    # timed region: exactly K steps, nothing else enqueued, no instrumentation beyond one event per step
+    # boundary on the caller's stream (the library joins its helper lane back into that stream before a
+    # call returns, so consecutive events bracket a whole step)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
+    marks[0].record(stream)
     for i in range(args.steps):
         timed_step()
+        marks[i + 1].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = (n_phi + n_psi) * T_eval / (ms_per_step * 1e-3)
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    median_ms = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] +
+                                                                          step_ms[len(step_ms) // 2])
 
     # second pass over the same K steps with a HIP event pair around every kernel launch (recorded
     # by the library on the launch stream).  Recording ~2500 event pairs per step costs several
@@ -329,7 +356,12 @@ def main():
         "metric": ("MGRIT fwd+adjoint+param-grads layer-steps*tokens/sec" if grads else
                    "MGRIT fwd+adjoint layer-steps*tokens/sec" if adjoint else "MGRIT fwd layer-steps*tokens/sec"),
         "value": value, "unit": "layer-steps*tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": ms_per_step,
+        # each step also timed on the stream by an event pair: median, fastest and slowest step, and the
+        # metric at the median (`value` itself is K steps over the wall clock between two synchronisations)
+        "step_ms_by_events": {"median": median_ms, "min": step_ms[0], "max": step_ms[-1],
+                              "value_at_median": (n_phi + n_psi) * T_eval / (median_ms * 1e-3)},
+        "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if wl.dtype == wls.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "d_model": wl.d_model, "n_heads": wl.n_heads, "d_ff": wl.d_ff,
                    "batch": wl.batch, "seq": wl.seq, "N": wl.N, "h": wl.h, "cf": wl.cf, "levels": wl.levels,

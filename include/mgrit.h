@@ -21,6 +21,14 @@
  *    MGRIT_UNSUPPORTED and MGRIT_WORKSPACE_TOO_SMALL nothing has been enqueued or
  *    written.  No exception or abort crosses this boundary.
  *  - Results are run-to-run bit-identical (no atomics feed any state).
+ *  - Threads: the library is meant to be driven by ONE host thread at a time per process.  The
+ *    tuning knobs below (lanes, groups per launch, debug hooks) are process-global, and so are the
+ *    helper stream and its events that the two-lane mode creates once per process: two calls that
+ *    are in flight at the same time -- from two host threads, or enqueued on two different caller
+ *    streams without an ordering between them -- would share that helper stream and those events
+ *    and are not supported with lanes = 2 (mgrit_set_lanes(1) uses the caller's stream only; then
+ *    concurrent calls on different streams with different workspaces are independent, as long as
+ *    no knob is changed meanwhile).  Only the last-error code is per thread.
  *
  * State layout: a state is [T, d_model] row-major fp32 with T = batch*seq tokens,
  * sequence b owning rows b*seq .. (b+1)*seq-1.  States, lambda, and every
@@ -68,7 +76,8 @@ typedef struct mgrit_model_desc {
 
 /* MGRIT knobs (sec. 3.2, Table 3): N fine steps of size h, coarsening factor cf,
  * `levels` grid levels (level l has N/cf^l steps of size cf^l h), `iters`
- * V-cycles.  levels == 1 or cf == 1 means plain serial propagation.
+ * V-cycles (at least 1 unless the run is serial: MGRIT_INVALID_ARG otherwise).  levels == 1 or
+ * cf == 1 means plain serial propagation.
  * init_guess: 0 = the initial value copied into every C-point; 1 = the caller has
  * filled rows 1..N of the output array with a guess (row 0 is overwritten). */
 typedef struct mgrit_opts {

@@ -141,6 +141,8 @@ int validate_opts(const mgrit_opts* o) {
       if (p > o->N) return MGRIT_INVALID_ARG;
     }
     if (o->N % p != 0) return MGRIT_INVALID_ARG;
+    // without a V-cycle the F-points of the output would never be written
+    if (o->iters < 1) return MGRIT_INVALID_ARG;
   }
   return MGRIT_OK;
 }
@@ -694,11 +696,15 @@ int run_chunks(Engine& E, Engine* E2, int G, F fn) {
   AuxStream& a = aux_stream();
   HIPCHK(hipEventRecord(a.fork, E.st));
   HIPCHK(hipStreamWaitEvent(E2->st, a.fork, 0));
-  int lane = 0;
-  for (int c0 = 0; c0 < G; c0 += chunk, lane ^= 1)
-    STCHK(fn(lane ? *E2 : E, c0, G - c0 < chunk ? G - c0 : chunk));
-  HIPCHK(hipEventRecord(a.join, E2->st));
-  HIPCHK(hipStreamWaitEvent(E.st, a.join, 0));
+  int lane = 0, status = MGRIT_OK;
+  for (int c0 = 0; c0 < G && status == MGRIT_OK; c0 += chunk, lane ^= 1)
+    status = fn(lane ? *E2 : E, c0, G - c0 < chunk ? G - c0 : chunk);
+  // the helper lane is joined back whatever happened, so that a failed call leaves no work behind
+  // that the caller's stream does not wait for
+  const hipError_t e1 = hipEventRecord(a.join, E2->st);
+  const hipError_t e2 = e1 == hipSuccess ? hipStreamWaitEvent(E.st, a.join, 0) : e1;
+  STCHK(status);
+  HIPCHK(e2);
   return MGRIT_OK;
 }
 
@@ -907,6 +913,18 @@ struct Driver {
   // Same kernels on the same data as the sequential order: results are identical.
   int coarse_solve_with_relaxation(int lvl, int M, Rows R, Rows Gn) {
     AuxStream& a = aux_stream();
+    const int status = coarse_solve_pipeline(lvl, M, R, Gn);
+    // join the helper lane whatever happened (see run_chunks)
+    only = nullptr;
+    emit_now = false;
+    const hipError_t e1 = hipEventRecord(a.join, E2->st);
+    const hipError_t e2 = e1 == hipSuccess ? hipStreamWaitEvent(E->st, a.join, 0) : e1;
+    STCHK(status);
+    HIPCHK(e2);
+    return MGRIT_OK;
+  }
+  int coarse_solve_pipeline(int lvl, int M, Rows R, Rows Gn) {
+    AuxStream& a = aux_stream();
     const int chunk = g_pipe_chunk > 0 && g_pipe_chunk < E2->Gc ? g_pipe_chunk : E2->Gc;
     const int n_chunks = (M + chunk - 1) / chunk;
     constexpr int HALF = PIPE_EVENTS / 2;                // events 0..HALF-1: right-hand sides; the others: hand-overs
@@ -960,10 +978,7 @@ struct Driver {
       k0 = k1;
     }
     // the helper lane still has its chunks to finish: the remaining intervals relax on this lane
-    STCHK(relax(E, k0, M));
-    HIPCHK(hipEventRecord(a.join, E2->st));
-    HIPCHK(hipStreamWaitEvent(E->st, a.join, 0));
-    return MGRIT_OK;
+    return relax(E, k0, M);
   }
 
   Rows W(int lvl, int j0, int js) const {

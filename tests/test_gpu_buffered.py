@@ -29,8 +29,8 @@ def run_case(wl, n_open, n_close, h_buffer=1.0, weight_std=0.08, grads=False):
     Zg, rg = mb.mgrit_forward_buffered(dm.desc, opts, buf, dev(Z0), dm.blocks)
     torch.cuda.synchronize()
     Zr, rr = omgrit.buffered_forward(Z0, dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh, n_open, n_close, h_buffer)
-    check_states(Zg, Zr, tol, "Z")
-    check_resnorms(rg, rr, tol, Zr)
+    _, einc = check_states(Zg, Zr, tol, "Z")
+    check_resnorms(rg, rr, tol, Zr, einc)
     lamN = wls.terminal_adjoint(wl)
     blocks = grad_blocks(dm.desc, n_total) if grads else None
     lg, ag = mb.mgrit_adjoint_buffered(dm.desc, opts, buf, Zg, dm.blocks, dev(lamN), dtheta=blocks)
@@ -38,8 +38,8 @@ def run_case(wl, n_open, n_close, h_buffer=1.0, weight_std=0.08, grads=False):
     Zlin = list(Zg.cpu().numpy().astype(np.float64))
     lr, ar = omgrit.buffered_adjoint(lamN, Zlin, dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh, n_open, n_close,
                                      h_buffer)
-    check_states(lg, lr, tol, "lambda")
-    check_resnorms(ag, ar, tol, lr[::-1])
+    _, einc = check_states(lg, lr, tol, "lambda")
+    check_resnorms(ag, ar, tol, lr[::-1], einc)
     if grads:
         steps = [h_buffer] * n_open + [wl.h] * wl.N + [h_buffer] * n_close
         from oracle import transformer_ode as tode

@@ -18,25 +18,34 @@ from oracle import mgrit as omgrit, transformer_ode as tode
 from paper_2601_09026_amd import binding as mb
 from paper_2601_09026_amd import workloads as wls
 
-from gpu_util import TOL, DeviceModel, dev, increment_tolerance, relerr
+from gpu_util import TOL, DeviceModel, dev, increment_tolerance, relerr, resnorm_bounds
 
 pytestmark = pytest.mark.gpu
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "resnorms.json")
 
 
 def golden(name):
-    if not os.path.exists(GOLDEN):
-        return None
-    return json.load(open(GOLDEN)).get(name)
+    """Stored oracle values of a workload; a missing entry fails the test (it is never skipped)."""
+    assert os.path.exists(GOLDEN), f"{GOLDEN} is missing: python tests/golden/make_resnorm_golden.py"
+    entry = json.load(open(GOLDEN)).get(name)
+    assert entry is not None, f"no stored oracle residual norms for {name}: python tests/golden/make_resnorm_golden.py {name}"
+    return entry
 
 
-def check_norms(what, got, ref, tol, increment_norm):
-    """Stored oracle residual norms against the library's: 10 x the tolerance relative, plus the resolution
-    floor of the arithmetic, tol x |w_N - w_0| (a residual is the difference of two propagator evaluations,
-    each granted tol x its increment: see check_resnorms in test_gpu_mgrit.py); late norms of a fast-converging
-    run (the third of the ViT configuration) lie below it."""
+def check_norms(what, got, ref, tol, increment_norm, inc_err):
+    """Stored oracle residual norms (full batch) against the library's.  `inc_err`: the relative error of the
+    library's increments measured against the oracle on the sampled sequences of this same run; the allowed
+    interval is resnorm_bounds' (relative tol, widened upwards by the noise that error implies, added in
+    quadrature); the convergence factors follow from the norms and are printed."""
+    got = np.asarray(got, np.float64)
+    noise = inc_err * increment_norm
     for i, r in enumerate(ref):
-        assert abs(got[i] - r) <= 10 * tol * r + tol * increment_norm, f"{what} resnorm[{i}]: {got[i]} vs oracle {r}"
+        lo, hi = resnorm_bounds(r, tol, increment_norm, inc_err)
+        print(f"  {what} resnorm[{i}]: {got[i]:.6g} vs oracle {r:.6g} ({(got[i] - r) / r:+.2%}; allowed {lo:.6g} .. "
+              f"{hi:.6g}; noise level {noise:.3g})")
+        assert lo <= got[i] <= hi, f"{what} resnorm[{i}]: {got[i]} vs oracle {r}, allowed {lo} .. {hi}"
+        if i > 0:
+            print(f"  {what} convergence factor {i}: {got[i] / got[i - 1]:.5g} vs oracle {r / ref[i - 1]:.5g}")
 
 
 def rows_of(wl, b, seq=None):
@@ -45,6 +54,8 @@ def rows_of(wl, b, seq=None):
 
 
 def check_sequence(what, got, ref, base_row, tol, n_steps_of):
+    """Every state of one sequence; returns the worst increment error seen (far end and middle)."""
+    worst = 0.0
     for n in range(len(ref)):
         e = relerr(got[n], ref[n])
         assert e <= tol, f"{what}[{n}]: value error {e:.3e} > {tol}"
@@ -55,6 +66,8 @@ def check_sequence(what, got, ref, base_row, tol, n_steps_of):
             bar = increment_tolerance(tol, ref[n], base, abs(n - base_row))
             print(f"  {what}[{n}] value err {relerr(got[n], ref[n]):.2e} increment err {e:.2e} (bar {bar:.2e})")
             assert e <= bar, f"{what}[{n}]: increment error {e:.3e} > {bar:.3e}"
+            worst = max(worst, e)
+    return worst
 
 
 def run_full(name, fwd_seqs, adj_seqs, memory=None, memory_host=None, prefix=None):
@@ -76,19 +89,17 @@ def run_full(name, fwd_seqs, adj_seqs, memory=None, memory_host=None, prefix=Non
     plen = wl.seq if prefix is None else prefix
     sh1 = tode.Shape(wl.arch, wl.d_model, wl.n_heads, 1, plen, wl.mem_seq, wl.ln_eps)
     Zg_host = {}
+    einc = 0.0
     for b in fwd_seqs:
         r = slice(b * wl.seq, b * wl.seq + plen)
         mem_b = None if memory_host is None else memory_host[rows_of(wl, b, wl.mem_seq)]
         Zr, _, _ = omgrit.mgrit_forward(Z0[r], dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh1, mem_b)
         got = Zg[:, r, :].cpu().numpy().astype(np.float64)
         Zg_host[b] = got
-        check_sequence(f"Z(seq {b})", got, Zr, 0, tol, {"far": wl.N, "mid": wl.N // 2})
+        einc = max(einc, check_sequence(f"Z(seq {b})", got, Zr, 0, tol, {"far": wl.N, "mid": wl.N // 2}))
     gold = golden(name)
     rg_host = rg.cpu().numpy()
-    if gold is not None:
-        check_norms("forward", rg_host, gold["forward"], tol, gold["increment_norm"])
-    else:
-        print("  (no stored oracle residual norms for this workload: norms not compared)")
+    check_norms("forward", rg_host, gold["forward"], tol, gold["increment_norm"], einc)
     assert all(rg_host[i + 1] < rg_host[i] for i in range(wl.iters - 1)), "residual norms must decrease"
     lg = None
     if adj_seqs:
@@ -96,6 +107,7 @@ def run_full(name, fwd_seqs, adj_seqs, memory=None, memory_host=None, prefix=Non
         lg, ag = mb.mgrit_adjoint(desc, opts, Zg, dm.blocks, dev(lamN), memory=memory)
         torch.cuda.synchronize()
         sh1 = tode.Shape(wl.arch, wl.d_model, wl.n_heads, 1, wl.seq, wl.mem_seq, wl.ln_eps)
+        einc = 0.0
         for b in adj_seqs:
             r = rows_of(wl, b)
             Zlin = Zg_host.get(b)
@@ -105,12 +117,11 @@ def run_full(name, fwd_seqs, adj_seqs, memory=None, memory_host=None, prefix=Non
             lr, _, _ = omgrit.mgrit_adjoint(lamN[r], list(Zlin), dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh1,
                                             mem_b)
             got = lg[:, r, :].cpu().numpy().astype(np.float64)
-            check_sequence(f"lambda(seq {b})", got, lr, wl.N, tol, {"far": 0, "mid": wl.N // 2})
+            einc = max(einc, check_sequence(f"lambda(seq {b})", got, lr, wl.N, tol, {"far": 0, "mid": wl.N // 2}))
         ag_host = ag.cpu().numpy()
-        if gold is not None and "adjoint" in gold:
-            # scale of the floor: the adjoint's own total increment (the stored file holds the forward one only)
-            inc = float(torch.linalg.vector_norm((lg[0] - lg[wl.N]).double()))
-            check_norms("adjoint", ag_host, gold["adjoint"], tol, inc)
+        # scale of the noise: the adjoint's own total increment
+        inc = float(torch.linalg.vector_norm((lg[0] - lg[wl.N]).double()))
+        check_norms("adjoint", ag_host, gold["adjoint"], tol, inc, einc)
     return Zg, lg
 
 
@@ -132,33 +143,74 @@ def test_full_gpt2_small_forward():
     run_full("gpt2_small", fwd_seqs=[6], adj_seqs=[], prefix=160)
 
 
-def test_full_gpt2_small_adjoint_residuals_and_samples():
-    """The full-batch adjoint of the deepest configuration: the oracle's adjoint for one sequence
-    takes minutes, so the sampled check uses the two coarsest-level-exact properties instead:
-    lambda_N is copied exactly, residual norms decrease and match the stored oracle values, and
-    one F-point relation lambda_n = Psi_n(lambda_{n+1}) is recomputed by the oracle on one sequence."""
+SEQ_GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "gpt2_small_seq5.npz")
+
+
+def test_full_gpt2_small_forward_and_adjoint_against_the_stored_oracle_sequence():
+    """The deepest configuration (three levels, N = 128, causal, forward + adjoint) at its full size, as
+    bench.py launches it, against the oracle's complete MGRIT iterate of one sequence, computed offline by
+    tests/golden/make_sequence_golden.py (the oracle needs a quarter of an hour for it): Z_n and lambda_n
+    at every level-0 C-point (they include every coarser level's C-points: the points that the relaxation,
+    the right-hand sides, the coarse solves and the corrections of all three levels write) on 16 sampled
+    token rows, element by element, plus the whole-sequence norms of the increments at every point, F-points
+    included.  The stored adjoint is linearised about the oracle's own forward iterate and the library's
+    about its own (sec. 3.2.2): the two differ by the forward tolerance, which moves lambda far less than
+    the bar.  Then the full-batch residual norms against the stored ones."""
     wl = wls.named_workloads()["gpt2_small"]
     tol = TOL[wl.dtype]
-    dm = DeviceModel(wl)
+    print(f"[case] full size gpt2_small forward + adjoint vs stored oracle sequence", flush=True)
+    assert os.path.exists(SEQ_GOLDEN), f"{SEQ_GOLDEN} is missing: python tests/golden/make_sequence_golden.py"
+    g = np.load(SEQ_GOLDEN)
+    b, points, tokens = int(g["sequence"]), g["points"], g["tokens"]
+    assert list(points) == list(range(0, wl.N + 1, wl.cf))
+    dm = DeviceModel(wl, keep_host=False)
     opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters)
     Z0, lamN = wls.initial_state(wl), wls.terminal_adjoint(wl)
-    Zg, _ = mb.mgrit_forward(dm.desc, opts, dev(Z0), dm.blocks)
+    Zg, rg = mb.mgrit_forward(dm.desc, opts, dev(Z0), dm.blocks)
     lg, ag = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN))
     torch.cuda.synchronize()
+    assert torch.equal(Zg[0].cpu(), torch.from_numpy(Z0))
     assert torch.equal(lg[wl.N].cpu(), torch.from_numpy(lamN))
-    ag_host = ag.cpu().numpy()
-    assert ag_host[1] < ag_host[0]
+    seq = rows_of(wl, b)
+    einc = {}
+    for what, got_all, ref_pts, base_n, inc_norm, val_norm in (("Z", Zg, g["Z"], 0, g["Z_inc_norm"], g["Z_norm"]),
+                                                             ("lambda", lg, g["lam"], wl.N, g["lam_inc_norm"],
+                                                              g["lam_norm"])):
+        got_seq = got_all[:, seq, :].cpu().numpy().astype(np.float64)          # [N+1, S, d]
+        base = got_seq[base_n][tokens]                                       # start value: identical on both sides
+        worst_val = worst_inc = 0.0
+        for i, n in enumerate(points):
+            ref = ref_pts[i].astype(np.float64)
+            got = got_seq[n][tokens]
+            e = relerr(got, ref)
+            assert e <= tol, f"{what}[{n}]: value error {e:.3e} > {tol}"
+            worst_val = max(worst_val, e)
+            if n != base_n:
+                ei = relerr(got - base, ref - base)
+                bar = increment_tolerance(tol, ref, base, abs(int(n) - base_n))
+                assert ei <= bar, f"{what}[{n}]: increment error {ei:.3e} > {bar:.3e}"
+                worst_inc = max(worst_inc, ei)
+        print(f"  {what}: {len(points)} C-points x {len(tokens)} tokens: worst value err {worst_val:.2e}, worst increment "
+              f"err {worst_inc:.2e} (bar {tol})")
+        einc[what] = worst_inc
+        # whole sequence, every point (F-points too): size of the increment over the start value
+        for n in range(wl.N + 1):
+            if n == base_n:
+                continue
+            mine = np.linalg.norm(got_seq[n] - got_seq[base_n])
+            floor = 4.0 * np.sqrt(abs(n - base_n)) * 2.0 ** -24 * val_norm[n]
+            assert abs(mine - inc_norm[n]) <= tol * inc_norm[n] + floor, f"|{what}[{n}] - start|: {mine} vs {inc_norm[n]}"
     gold = golden("gpt2_small")
-    if gold is not None and "adjoint" in gold:
-        inc = float(torch.linalg.vector_norm((lg[0] - lg[wl.N]).double()))
-        check_norms("adjoint", ag_host, gold["adjoint"], tol, inc)
+    check_norms("forward", rg.cpu().numpy(), gold["forward"], tol, gold["increment_norm"], einc["Z"])
+    inc = float(torch.linalg.vector_norm((lg[0] - lg[wl.N]).double()))
+    check_norms("adjoint", ag.cpu().numpy(), gold["adjoint"], tol, inc, einc["lambda"])
     # after the closing F-relaxation every F-point satisfies lambda_n = Psi(lambda_{n+1}; Z_n) exactly
     sh1 = tode.Shape(wl.arch, wl.d_model, wl.n_heads, 1, wl.seq, 0, wl.ln_eps)
-    b = 2
-    r = rows_of(wl, b)
+    r = rows_of(wl, 2)
+    host = {n: wls.layer_params(wl, n) for n in (wl.N - 2, 65, 1)}
     for n in (wl.N - 2, 65, 1):                 # F-points of the reversed grid (N - n not a multiple of cf)
         assert (wl.N - n) % wl.cf != 0
-        ref = tode.psi(lg[n + 1, r, :].cpu().numpy(), Zg[n, r, :].cpu().numpy(), dm.host[n], wl.h, sh1)
+        ref = tode.psi(lg[n + 1, r, :].cpu().numpy(), Zg[n, r, :].cpu().numpy(), host[n], wl.h, sh1)
         got = lg[n, r, :].cpu().numpy()
         base = lg[n + 1, r, :].cpu().numpy().astype(np.float64)
         e = relerr(got - base, ref - base)

@@ -14,17 +14,19 @@ from oracle import mgrit as omgrit
 from paper_2601_09026_amd import binding as mb
 from paper_2601_09026_amd import workloads as wls
 
-from gpu_util import TOL, DeviceModel, dev, increment_tolerance, relerr, shape_of
+from gpu_util import TOL, DeviceModel, dev, increment_tolerance, relerr, resnorm_bounds, shape_of
 
 pytestmark = pytest.mark.gpu
 
 
 def check_states(got_all, ref_list, tol, what):
+    """Every state against the oracle's (normwise relative error), and the increments over the start
+    value at the far end and in the middle.  Returns (worst value error, worst increment error)."""
     ref = np.stack(ref_list)
     got = got_all.cpu().numpy().astype(np.float64)
     assert np.isfinite(got).all(), f"{what}: non-finite"
     base = ref[0] if what.startswith("Z") else ref[-1]
-    worst = 0.0
+    worst, worst_inc = 0.0, 0.0
     for n in range(ref.shape[0]):
         e = relerr(got[n], ref[n])
         assert e <= tol, f"{what}[{n}]: value error {e:.3e} > {tol}"
@@ -37,26 +39,26 @@ def check_states(got_all, ref_list, tol, what):
             tol_inc = increment_tolerance(tol, ref[n], base, steps)
             assert e <= tol_inc, f"{what}[{n}]: increment error {e:.3e} > {tol_inc:.3e}"
             print(f"  {what}[{n}] value err {relerr(got[n], ref[n]):.2e} increment err {e:.2e} (bar {tol_inc:.2e})")
-    return worst
+            worst_inc = max(worst_inc, e)
+    return worst, worst_inc
 
 
-def check_resnorms(got, ref, tol, states):
-    """Residual norms of the GPU run against the oracle's; `states` are the oracle's states.
-
-    A residual is the difference of two propagator evaluations at nearly equal inputs, and
-    parity grants each evaluation an error of `tol` times its increment.  So the residual norm
-    is only resolved down to about tol * |w_N - w_0| (bf16: a few 1e-2 of the total increment;
-    perturbing the oracle's increments by that much moves its late residuals by this amount):
-    the bar is 10 * tol relative plus that absolute floor, and norms at the fp32 rounding level
-    of the state only have to be small."""
-    got = got.cpu().numpy()
-    scale = float(np.linalg.norm(states[-1]))
-    floor = tol * float(np.linalg.norm(np.asarray(states[-1], np.float64) - np.asarray(states[0], np.float64)))
+def check_resnorms(got, ref, tol, states, inc_err):
+    """Residual norms of the GPU run against the oracle's.  `states`: the oracle's states, first to
+    last in the direction of the solve; `inc_err`: the relative error of the GPU's increments measured
+    against the oracle in this same run (check_states).  The interval comes from resnorm_bounds:
+    relative `tol`, widened upwards by the noise the measured increment error implies, added in
+    quadrature; the convergence factors (ratios of consecutive norms, sec. 3.2.3) follow from the norms
+    and are printed."""
+    got = got.cpu().numpy().astype(np.float64)
+    inc = float(np.linalg.norm(np.asarray(states[-1], np.float64) - np.asarray(states[0], np.float64)))
+    noise = inc_err * inc
     for i, r in enumerate(ref):
-        if r < 100 * np.finfo(np.float32).eps * scale:      # at rounding level: only require smallness
-            assert got[i] < 1000 * np.finfo(np.float32).eps * scale + floor, (i, got[i], r)
-        else:
-            assert abs(got[i] - r) <= 10 * tol * r + floor, f"resnorm[{i}]: {got[i]} vs {r} (floor {floor})"
+        lo, hi = resnorm_bounds(r, tol, inc, inc_err)
+        print(f"  resnorm[{i}]: {got[i]:.6g} vs oracle {r:.6g} (allowed {lo:.6g} .. {hi:.6g}; noise level {noise:.3g})")
+        assert lo <= got[i] <= hi, f"resnorm[{i}]: {got[i]} vs {r}, allowed {lo} .. {hi}"
+        if i > 0:
+            print(f"  convergence factor {i}: {got[i] / got[i - 1]:.5g} vs oracle {r / ref[i - 1]:.5g}")
 
 
 def run_case(wl, weight_std=0.02, relax="FCF", adjoint=False, init_from_serial=False, max_groups=0):
@@ -81,8 +83,8 @@ def run_case(wl, weight_std=0.02, relax="FCF", adjoint=False, init_from_serial=F
         torch.cuda.synchronize()
         Zr, rr, counts = omgrit.mgrit_forward(Z0, dm.host, wl.h, wl.cf, wl.levels, wl.iters, sh, mem,
                                               relax=relax, init=init)
-        check_states(Zg, Zr, tol, "Z")
-        check_resnorms(rg, rr, tol, Zr)
+        _, einc = check_states(Zg, Zr, tol, "Z")
+        check_resnorms(rg, rr, tol, Zr, einc)
         if adjoint:
             lamN = wls.terminal_adjoint(wl)
             # linearise both sides about the same states: the GPU's own forward result
@@ -92,8 +94,8 @@ def run_case(wl, weight_std=0.02, relax="FCF", adjoint=False, init_from_serial=F
             torch.cuda.synchronize()
             lr, arr, _ = omgrit.mgrit_adjoint(lamN, list(Zlin), dm.host, wl.h, wl.cf, wl.levels, wl.iters,
                                               sh, mem, relax=relax)
-            check_states(lg, lr, tol, "lambda")
-            check_resnorms(arg, arr, tol, lr[::-1])
+            _, einc = check_states(lg, lr, tol, "lambda")
+            check_resnorms(arg, arr, tol, lr[::-1], einc)
         return Zg, Zr, rr
     finally:
         mb.mgrit_set_max_groups_per_launch(0)
@@ -145,14 +147,17 @@ def test_sweeps_split_into_launch_chunks():
     run_case(tiny(N=32, cf=4, levels=2, iters=1), weight_std=0.08, adjoint=True, max_groups=3)
 
 
-def test_zero_iterations_return_the_initial_guess():
+def test_zero_iterations_are_refused_unless_serial():
+    """Without a V-cycle the F-points would never be written: refused before anything is enqueued."""
     wl = tiny(N=8, cf=4, levels=2, iters=0)
     dm = DeviceModel(wl)
     Z0 = dev(wls.initial_state(wl))
-    Zg, _ = mb.mgrit_forward(dm.desc, mb.mgrit_opts(8, 1.0, 4, 2, 0), Z0, dm.blocks)
+    with pytest.raises(mb.MgritError) as e:
+        mb.mgrit_forward(dm.desc, mb.mgrit_opts(8, 1.0, 4, 2, 0), Z0, dm.blocks)
+    assert e.value.status == mb.MGRIT_INVALID_ARG
+    Zg, _ = mb.mgrit_forward(dm.desc, mb.mgrit_opts(8, 1.0, 4, 1, 0), Z0, dm.blocks)     # serial: iters unused
     torch.cuda.synchronize()
-    for n in (0, 4, 8):
-        assert torch.equal(Zg[n], Z0)
+    assert torch.isfinite(Zg).all()
 
 
 def test_run_to_run_bit_identical():
@@ -191,6 +196,35 @@ def test_overlapped_coarse_solve_is_bit_identical_to_the_sequential_order(levels
             assert torch.equal(x, y)
 
 
+@pytest.mark.parametrize("chunk", [1, 3])
+def test_overlapped_coarse_solve_with_many_hand_overs_is_bit_identical(chunk):
+    """40 intervals handed over one at a time: 39 hand-overs go through the pool of 16 events, which
+    wraps around, and with more than 16 chunks the right-hand sides are formed in one sweep instead of
+    chunk by chunk; 3 at a time gives 14 chunks with a ragged last one (right-hand sides chunk by
+    chunk).  Forward and adjoint against the sequential order, bit for bit."""
+    N, cf = 160, 4
+    wl = tiny(arch=wls.ARCH_CAUSAL, dtype=wls.DTYPE_BF16, N=N, cf=cf, levels=2, iters=2, d=128, f=256, B=1, S=40)
+    print(f"[case] many hand-overs: N={N} cf={cf} chunk={chunk}", flush=True)
+    dm = DeviceModel(wl, weight_std=0.05, keep_host=False)
+    Z0, lamN = dev(wls.initial_state(wl)), dev(wls.terminal_adjoint(wl))
+    opts = mb.mgrit_opts(N, 0.1, cf, 2, 2)
+    out = []
+    try:
+        for on in (1, 0):
+            mb.lib().mgrit_debug_pipeline_coarse_solve(on)
+            mb.lib().mgrit_debug_pipeline_chunk(chunk if on else 0)
+            Z, rz = mb.mgrit_forward(dm.desc, opts, Z0, dm.blocks)
+            lam, rl = mb.mgrit_adjoint(dm.desc, opts, Z, dm.blocks, lamN)
+            torch.cuda.synchronize()
+            out.append((Z, rz, lam, rl))
+    finally:
+        mb.lib().mgrit_debug_pipeline_coarse_solve(1)
+        mb.lib().mgrit_debug_pipeline_chunk(0)
+    assert torch.isfinite(out[0][0]).all() and torch.isfinite(out[0][2]).all()
+    for x, y in zip(out[0], out[1]):
+        assert torch.equal(x, y)
+
+
 # ----------------------------------------------------------------- benchmark configurations
 def test_config1_tiny_encoder_full():
     wl = wls.named_workloads()["tiny_encoder"]
@@ -227,16 +261,16 @@ def test_config5_mt_encoder_decoder_reduced_batch():
     Yg, rg = mb.mgrit_forward(dm.desc, opts, dev(Y0), dm.blocks, memory=Zg[-1].contiguous())
     torch.cuda.synchronize()
     Yr, rr, _ = omgrit.mgrit_forward(Y0, dm.host, dec.h, dec.cf, dec.levels, dec.iters, sh, Zr[-1])
-    check_states(Yg, Yr, tol, "Z")
-    check_resnorms(rg, rr, tol, Yr)
+    _, einc = check_states(Yg, Yr, tol, "Z")
+    check_resnorms(rg, rr, tol, Yr, einc)
     # decoder adjoint, both sides linearised about the GPU's decoder states and encoder output
     lamN = wls.terminal_adjoint(dec)
     lg, ag = mb.mgrit_adjoint(dm.desc, opts, Yg, dm.blocks, dev(lamN), memory=Zg[-1].contiguous())
     torch.cuda.synchronize()
     lr, ar, _ = omgrit.mgrit_adjoint(lamN, list(Yg.cpu().numpy()), dm.host, dec.h, dec.cf, dec.levels, dec.iters,
                                      sh, Zg[-1].cpu().numpy())
-    check_states(lg, lr, tol, "lambda")
-    check_resnorms(ag, ar, tol, lr[::-1])
+    _, einc = check_states(lg, lr, tol, "lambda")
+    check_resnorms(ag, ar, tol, lr[::-1], einc)
 
 
 # ----------------------------------------------------------------- deep-narrow shape of the scaling study

@@ -56,8 +56,8 @@ def run_case(sw, weight_std=0.08, grads=False, max_groups=0, lanes=2):
         Zg, rg = mb.mgrit_forward_stacked(desc_d, opts, sw.n_enc, dev(Z0), blocks)
         torch.cuda.synchronize()
         Zr, rr, _ = omgrit.stacked_mgrit_forward(Z0, host, sw.n_enc, d.h, d.cf, d.levels, d.iters, she, shd, relax)
-        check_states(Zg, Zr, tol, "Z")
-        check_resnorms(rg, rr, tol, Zr)
+        _, einc = check_states(Zg, Zr, tol, "Z")
+        check_resnorms(rg, rr, tol, Zr, einc)
         # the parts a step leaves alone are copied exactly
         tx = e.tokens
         if d.levels == 1 or d.cf == 1:
@@ -70,8 +70,8 @@ def run_case(sw, weight_std=0.08, grads=False, max_groups=0, lanes=2):
         Zlin = list(Zg.cpu().numpy().astype(np.float64))
         lr, ar, _ = omgrit.stacked_mgrit_adjoint(lamN, Zlin, host, sw.n_enc, d.h, d.cf, d.levels, d.iters, she, shd,
                                                  relax)
-        check_states(lg, lr, tol, "lambda")
-        check_resnorms(ag, ar, tol, lr[::-1])
+        _, einc = check_states(lg, lr, tol, "lambda")
+        check_resnorms(ag, ar, tol, lr[::-1], einc)
         # the X part carries the memory cotangent: checked on its own so that the larger Y part cannot hide it
         lx_g = lg[:, :tx].cpu().numpy().astype(np.float64)
         for n in (0, sw.n_enc):
@@ -200,5 +200,34 @@ def test_overlapped_coarse_solve_is_bit_identical_on_the_stacked_grid():
             out.append((Z, rz, lam, rl))
     finally:
         mb.lib().mgrit_debug_pipeline_coarse_solve(1)
+    for x, y in zip(out[0], out[1]):
+        assert torch.equal(x, y)
+
+
+def test_overlapped_coarse_solve_with_many_hand_overs_on_the_stacked_grid():
+    """36 intervals handed over one at a time (the pool of 16 hand-over events wraps around; the
+    right-hand sides are formed in one sweep): bit-identical to the sequential order."""
+    sw = stacked(dtype=wls.DTYPE_BF16, d=128, H=2, f=256, B=1, Sx=24, Sy=20, n_enc=60, n_dec=84, cf=4, levels=2, h=0.1)
+    d = sw.dec
+    print(f"[case] stacked, many hand-overs: N={sw.N} n_enc={sw.n_enc}", flush=True)
+    desc_d = mb.model_desc(d)
+    desc_e = mb.encoder_desc(desc_d)
+    blocks = [mb.pack_theta(desc_e if n < sw.n_enc else desc_d, wls.stacked_layer_params(sw, n, 0.05))
+              for n in range(sw.N)]
+    opts = mb.mgrit_opts(sw.N, d.h, d.cf, d.levels, d.iters, d.relax)
+    Z0, lamN = dev(wls.stacked_initial_state(sw)), dev(wls.stacked_terminal_adjoint(sw))
+    out = []
+    try:
+        for on in (1, 0):
+            mb.lib().mgrit_debug_pipeline_coarse_solve(on)
+            mb.lib().mgrit_debug_pipeline_chunk(1 if on else 0)
+            Z, rz = mb.mgrit_forward_stacked(desc_d, opts, sw.n_enc, Z0, blocks)
+            lam, rl = mb.mgrit_adjoint_stacked(desc_d, opts, sw.n_enc, Z, blocks, lamN)
+            torch.cuda.synchronize()
+            out.append((Z, rz, lam, rl))
+    finally:
+        mb.lib().mgrit_debug_pipeline_coarse_solve(1)
+        mb.lib().mgrit_debug_pipeline_chunk(0)
+    assert torch.isfinite(out[0][0]).all() and torch.isfinite(out[0][2]).all()
     for x, y in zip(out[0], out[1]):
         assert torch.equal(x, y)
