@@ -134,9 +134,11 @@ def test_full_size_mt_stacked_sampled_sentence_pairs():
     """The translation configuration on one grid at its full size (64 sentence pairs, 32 + 32 layers), in
     the launch configuration bench.py times.  Sentence pairs are independent through the whole method, so
     the oracle recomputes sampled pairs alone (the complete MGRIT iteration, forward and adjoint) and every
-    state of those pairs is compared.  The residual norms couple the batch: no oracle value is stored for
-    them at this size (parity unpinned for the norm itself; it must decrease)."""
+    state of those pairs is compared.  The residual norms couple the batch: they are compared with the values
+    the oracle computed offline for the full batch (tests/golden/resnorms.json, written by
+    tests/golden/make_resnorm_golden.py from the oracle only)."""
     from gpu_util import increment_tolerance
+    from test_gpu_full_size import check_norms, golden
     sw = wls.stacked_workloads()["mt_stacked"]
     e, d = sw.enc, sw.dec
     print(f"[case] full size mt_stacked: B={d.batch} Sx={e.seq} Sy={d.seq} d={d.d_model} N={sw.N} cf={d.cf} "
@@ -155,6 +157,7 @@ def test_full_size_mt_stacked_sampled_sentence_pairs():
     she = tode.Shape(e.arch, e.d_model, e.n_heads, 1, e.seq, 0, e.ln_eps)
     shd = tode.Shape(d.arch, d.d_model, d.n_heads, 1, d.seq, d.mem_seq, d.ln_eps)
     tx = e.tokens
+    einc = {"Z": 0.0, "lambda": 0.0}
     for b in (7, 62):
         rows = np.concatenate([np.arange(b * e.seq, (b + 1) * e.seq), tx + np.arange(b * d.seq, (b + 1) * d.seq)])
         Zr, _, _ = omgrit.stacked_mgrit_forward(Z0[rows], host, sw.n_enc, d.h, d.cf, d.levels, d.iters, she, shd)
@@ -175,8 +178,12 @@ def test_full_size_mt_stacked_sampled_sentence_pairs():
                         bar = increment_tolerance(tol, r[n][sl], base, abs(n - base_row))
                         print(f"  {what}_{part}(pair {b})[{n}] increment err {err:.2e} (bar {bar:.2e})")
                         assert err <= bar, f"{what}_{part}(pair {b})[{n}]: increment error {err:.3e} > {bar:.3e}"
+                        einc[what] = max(einc[what], err)
     for norms in (rg.cpu().numpy(), ag.cpu().numpy()):
         assert np.isfinite(norms).all() and all(norms[i + 1] < norms[i] for i in range(d.iters - 1)), norms
+    gold = golden("mt_stacked")
+    check_norms("forward", rg.cpu().numpy(), gold["forward"], tol, gold["increment_norm"], einc["Z"])
+    check_norms("adjoint", ag.cpu().numpy(), gold["adjoint"], tol, gold["adjoint_increment_norm"], einc["lambda"])
 
 
 def test_overlapped_coarse_solve_is_bit_identical_on_the_stacked_grid():
