@@ -298,7 +298,7 @@ def main():
             gen = totals.get("gemm_generic")
             if gen:
                 ach = gen["flops"] / (gen["ms"] * 1e-3) / 1e12
-                roofline = {"bound": "alu", "kernel": "gemm_simple_kernel (fp32 FMA)", "achieved": ach,
+                roofline = {"bound": "alu", "kernel": "gemm_f32_mfma_kernel (fp32 MFMA 32x32x2; odd shapes on the FMA kernel)", "achieved": ach,
                             "peak": 157.3, "unit": "TFLOP/s", "frac": ach / 157.3, "traffic": None,
                             "avg_launch_us": gen["ms"] * 1e3 / gen["launches"]}
         # long sequences with few features (the deep-narrow workload): the fused attention kernels

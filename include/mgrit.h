@@ -349,7 +349,9 @@ int  mgrit_profile_read(int cls, double* total_ms, double* flops, double* bytes,
  * reaches as well as of the datasheet: a register-resident 32x32x16 bf16 MFMA loop on every
  * compute unit (`scratch`: device, at least 512 KiB, overwritten; `iters` MFMA rounds, 1..2^20;
  * result in TFLOP/s) and a grid-stride copy of `bytes` (a multiple of 16, at least 1 MiB) from
- * `src` to `dst` (device, not overlapping; result = bytes read + written per second, in GB/s).
+ * `src` to `dst` (device, not overlapping; result = bytes read + written per second, in GB/s, the
+ * best of three grid sizes: few resident blocks keep the chip's accesses inside a small window of
+ * DRAM pages and reach the higher rate).
  * Both enqueue on `stream`, wait for it and create two events meanwhile; 0 on success, -1 on
  * bad arguments, -4 on a HIP error. */
 int mgrit_measure_mfma_ceiling(void* scratch, size_t scratch_bytes, int iters, double* tflops, void* stream);

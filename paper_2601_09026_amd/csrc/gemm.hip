@@ -3,10 +3,11 @@
 // its own weight matrix (the layer of its coarse interval), found through the
 // parameter pointer table.
 //
-// Two kernels:
-//  * gemm_mfma  : bf16 operands, fp32 accumulate on the 32x32x16 MFMA of gfx950; operands
-//                 stream global -> LDS directly through a ring of k-tiles, see below.
-//  * gemm_simple: any operand type (fp32 path and odd shapes), LDS-tiled FMA.
+// Three kernels:
+//  * gemm_mfma    : bf16 operands, fp32 accumulate on the 32x32x16 MFMA of gfx950; operands
+//                   stream global -> LDS directly through a ring of k-tiles, see below.
+//  * gemm_f32_mfma: fp32 operands on the 32x32x2 fp32 MFMA (the fp32 configuration).
+//  * gemm_simple  : any operand type and shape, LDS-tiled FMA.
 #include <type_traits>
 
 #include "common.h"
@@ -456,6 +457,57 @@ gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, in
 }
 
 // ---------------------------------------------------------------------------
+// fp32 MFMA kernel (fp32 parameters and operands): 64x64 block tile, 4 wavefronts of 32x32 on
+// the 32x32x2 fp32 MFMA, k-tiles of 16 staged through LDS.  As in the bf16 kernel the weight
+// fragment is the first MFMA operand, so a lane ends up with 4 consecutive output columns of one
+// row per register quad and the shared epilogue code applies.  Needs N % 64 == 0 and K % 16 == 0;
+// M may be ragged (rows are clamped on load and guarded on store).
+// ---------------------------------------------------------------------------
+template <int EPI>
+__global__ void __launch_bounds__(256)
+gemm_f32_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n) {
+  constexpr int BT = 64, BKF = 16, LD = BKF + 4;       // row pitch 20 floats: 16-byte aligned vector stores
+  __shared__ __attribute__((aligned(16))) float As[BT * LD];
+  __shared__ __attribute__((aligned(16))) float Bs[BT * LD];
+  const int g = blockIdx.z;
+  const int tm = blockIdx.x / tiles_n, tn = blockIdx.x - tm * tiles_n;
+  const int m0 = tm * BT, n0 = tn * BT;
+  const float* A = reinterpret_cast<const float*>(a.A) + a.a_slots.of(g) * a.a_slot_stride;
+  const float* B = reinterpret_cast<const float*>(a.B.at(g) + a.b_off);
+  const int M = a.M, K = a.K;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 31, lh = lane >> 5;
+  const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+  const int srow = tid >> 2, sk = (tid & 3) * 4;       // staging: one float4 of each operand per thread
+  int am = m0 + srow;
+  am = am < M ? am : M - 1;
+  const float* ap = A + (long)am * K + sk;
+  const float* bp = B + (long)(n0 + srow) * K + sk;
+  f32x16 acc[1][1];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[0][0][r] = 0.f;
+  f32x4 va = *reinterpret_cast<const f32x4*>(ap), vb = *reinterpret_cast<const f32x4*>(bp);
+  for (int k0 = 0; k0 < K; k0 += BKF) {
+    __syncthreads();                                   // the previous k-tile has been read by every wavefront
+    *reinterpret_cast<f32x4*>(&As[srow * LD + sk]) = va;
+    *reinterpret_cast<f32x4*>(&Bs[srow * LD + sk]) = vb;
+    __syncthreads();
+    if (k0 + BKF < K) {                                // next k-tile's loads fly while this one is multiplied
+      va = *reinterpret_cast<const f32x4*>(ap + k0 + BKF);
+      vb = *reinterpret_cast<const f32x4*>(bp + k0 + BKF);
+    }
+#pragma unroll
+    for (int ks = 0; ks < BKF; ks += 2)
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(Bs[(wn0 + lr) * LD + ks + lh], As[(wm0 + lr) * LD + ks + lh],
+                                                      acc[0][0], 0, 0, 0);
+  }
+  const EpiPtrs P = resolve_epi<float>(a, g, EPI);
+  tile_epilogue<EPI, float, 1, 1, false>(acc, nullptr, P.bias, static_cast<float*>(P.out), static_cast<float*>(P.out),
+                                         static_cast<float*>(P.aux), static_cast<const float*>(P.aux), P.base, P.X,
+                                         static_cast<const float*>(P.aux), P.RHS, P.OUT, a.hstep, a.N, M, m0 + wm0,
+                                         n0 + wn0, lane);
+}
+
+// ---------------------------------------------------------------------------
 // generic kernel: 64x64x16 tile, 256 threads, 4x4 outputs per thread
 // ---------------------------------------------------------------------------
 template <typename TA, int EPI, typename TO>
@@ -556,6 +608,14 @@ static hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <int EPI>
+static hipError_t launch_f32_mfma(const GemmArgs& a, hipStream_t st) {
+  const int tiles_m = (a.M + 63) / 64, tiles_n = a.N / 64;
+  hipLaunchKernelGGL((gemm_f32_mfma_kernel<EPI>), dim3(tiles_m * tiles_n, 1, a.n_groups), dim3(256), 0, st, a,
+                     tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
 template <typename TA, int EPI>
 static hipError_t launch_simple(const GemmArgs& a, hipStream_t st) {
   const int tiles_m = (a.M + 63) / 64, tiles_n = (a.N + 63) / 64;
@@ -625,7 +685,11 @@ static hipError_t launch_epi(const GemmArgs& a, bool is_bf16, hipStream_t st) {
                        (double)a.M * a.K < 4e9 && (double)a.N * a.K < 4e9;
   const int cls = mfma_ok ? (a.n_groups > 1 ? PC_GEMM_MFMA : PC_GEMM_MFMA_SINGLE) + EPI : PC_GEMM_SIMPLE;
   ProfScope ps(cls, flops, gemm_bytes<EPI>(a, is_bf16 ? 2 : 4), st);
-  if (!is_bf16) return launch_simple<float, EPI>(a, st);
+  if (!is_bf16) {
+    // fp32: the 32x32x2 fp32 MFMA where the shape allows it (whole 64-column tiles, whole 16-deep k-tiles)
+    if (!g_force_simple && a.N % 64 == 0 && a.K % 16 == 0) return launch_f32_mfma<EPI>(a, st);
+    return launch_simple<float, EPI>(a, st);
+  }
   if (!mfma_ok) return launch_simple<bf16, EPI>(a, st);
   int cfg = g_tile_cfg;
   if (cfg == 0) cfg = choose_tile_config(a.n_groups, a.M, a.N);

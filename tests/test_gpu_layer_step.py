@@ -53,8 +53,6 @@ def run_forward_case(wl, G, hstep, with_rhs, weight_std, force_simple, max_group
 @pytest.mark.parametrize("arch", [wls.ARCH_ENCODER, wls.ARCH_CAUSAL, wls.ARCH_CROSS])
 @pytest.mark.parametrize("dtype", [wls.DTYPE_F32, wls.DTYPE_BF16])
 def test_forward_step_matches_oracle(arch, dtype, force_simple):
-    if dtype == wls.DTYPE_F32 and not force_simple:
-        pytest.skip("fp32 has a single kernel path")
     run_forward_case(make(arch, dtype), G=3, hstep=0.37, with_rhs=True, weight_std=0.05,
                      force_simple=force_simple)
 
@@ -167,8 +165,6 @@ def run_adjoint_case(wl, G, hstep, with_rhs, weight_std, force_simple, max_group
 @pytest.mark.parametrize("arch", [wls.ARCH_ENCODER, wls.ARCH_CAUSAL, wls.ARCH_CROSS])
 @pytest.mark.parametrize("dtype", [wls.DTYPE_F32, wls.DTYPE_BF16])
 def test_adjoint_step_matches_oracle(arch, dtype, force_simple):
-    if dtype == wls.DTYPE_F32 and not force_simple:
-        pytest.skip("fp32 has a single kernel path")
     run_adjoint_case(make(arch, dtype), G=3, hstep=0.37, with_rhs=True, weight_std=0.05,
                      force_simple=force_simple)
 
