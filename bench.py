@@ -59,6 +59,8 @@ def parse():
     ap.add_argument("--pipe-chunk", type=int, default=0, help="tuning: intervals per hand-over of the coarse solve")
     ap.add_argument("--no-pipeline", action="store_true",
                     help="tuning: serial coarse solve and the following F-relaxation one after the other")
+    ap.add_argument("--no-adjoint-cache", action="store_true",
+                    help="adjoint without the N-layer linearisation cache (recomputed per launch chunk)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not record per-kernel HIP events in the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -151,6 +153,8 @@ def main():
         mb.lib().mgrit_debug_pipeline_coarse_solve(0)
     if args.gemm_tile:
         mb.lib().mgrit_debug_gemm_tile_config(args.gemm_tile)
+    if args.no_adjoint_cache:
+        mb.mgrit_set_adjoint_cache(False)
     desc = mb.model_desc(wl)
     opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters, wl.relax)
     # stacked grid: a state holds the encoder's and the decoder's tokens, an evaluation advances one
@@ -372,6 +376,7 @@ def main():
                    "max_groups_per_launch": args.max_groups or mb.lib().mgrit_default_groups_per_launch(
                        C_byref(desc), max(wl.N // wl.cf, 1)), "lanes": args.lanes or 2,
                    "param_grads": bool(grads), "launch": "hip graph replay" if args.graph else "eager",
+                   "adjoint_cache": not args.no_adjoint_cache, "workspace_bytes": int(ws_bytes),
                    **({"stacked": True, "n_enc": sw.n_enc, "src_seq": sw.enc.seq} if sw else {})},
         "residual_norms": {"forward": [float(x) for x in res_f.cpu()[:wl.iters]],
                            "adjoint": [float(x) for x in res_a.cpu()[:wl.iters]] if adjoint else None},

@@ -328,6 +328,17 @@ int  mgrit_default_groups_per_launch(const mgrit_model_desc* desc, int sweep);
  * change the workspace size: set them before querying it. */
 void mgrit_set_lanes(int n);
 
+/* Memory knob of mgrit_adjoint (and of the buffered and stacked forms): 1 (default) keeps the block
+ * internals of all N layers at their linearisation states in the workspace -- filled once per call by
+ * one forward pass batched over the layers, about 24 d_model bytes per token and layer (5 GB at the
+ * BERT shape, 10 GB at the GPT-2 shape) -- so that every transposed step is pure backward work.
+ * 0 is for callers who cannot spend that memory: the workspace then holds the internals of one launch
+ * chunk per lane only, and every chunk of transposed steps first recomputes those of its own layers
+ * (the forward block up to the FFN activation).  Results are identical bit for bit; the workspace
+ * shrinks by the cache; an adjoint evaluation costs one partial forward evaluation more.  Process-
+ * global like the other knobs, and it changes the workspace size: set it before querying. */
+void mgrit_set_adjoint_cache(int on);
+
 /* ---- instrumentation (benchmark and tests; not needed for normal use) ------------------
  * Per-launch timing with HIP events recorded on the launch stream around every kernel of
  * a class.  mgrit_profile_enable(n > 0) creates a pool of n records (this call allocates

@@ -239,6 +239,11 @@ def mgrit_set_lanes(n: int) -> None:
     lib().mgrit_set_lanes(int(n))
 
 
+def mgrit_set_adjoint_cache(on: bool) -> None:
+    """False: no N-layer linearisation cache in the adjoint workspace (recomputed per launch chunk)."""
+    lib().mgrit_set_adjoint_cache(int(bool(on)))
+
+
 PROFILE_CLASSES = {0: "gemm_generic", 1: "attn_fwd", 2: "attn_bwd", 3: "ln_fwd", 4: "ln_vjp", 5: "elementwise",
                    6: "ln_fwd_single", 7: "ln_vjp_single",
                    8: "gemm_mfma_store", 9: "gemm_mfma_gelu", 10: "gemm_mfma_sublayer_sum",

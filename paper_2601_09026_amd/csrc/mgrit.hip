@@ -198,6 +198,9 @@ struct Engine {
   // input state, so the operand-type copy of the memory is per launch slot ([Tm, d] each)
   bool per_group_mem = false;
   void* membG = nullptr;
+  // adjoint without the N-layer linearisation cache: the cache arrays hold one launch chunk (Gc slots,
+  // one set per lane) and every chunk of transposed steps first recomputes the internals of its layers
+  bool recompute = false;
   int Tmax() const { return T > Tm ? T : Tm; }
   long tA_stride() const { return (long)(f > 3 * d ? f : 3 * d) * Tmax(); }   // elements per slot
   long tB_stride() const { return (long)(f > d ? f : d) * Tmax(); }
@@ -235,7 +238,7 @@ struct Engine {
     memb = md.arch == MGRIT_ARCH_CROSS ? b.take_bytes((size_t)Tm * d * esz) : nullptr;
     carve_forward_work(b, gc);
   }
-  void carve_adjoint(Bump& b, int gc, int ncache) {
+  void carve_cache(Bump& b, int ncache) {
     n_cache = ncache;
     const size_t C = ncache;
     c_qkv = b.take_bytes(C * T * 3 * d * esz);
@@ -248,15 +251,18 @@ struct Engine {
     c_xh2 = b.take_bytes(C * T * d * esz);
     c_rs1 = b.take<float>(C * T);
     c_rs2 = b.take<float>(C * T);
-    memb = nullptr; c_qc = c_kvc = c_oc = nullptr; c_lsec = c_x3 = nullptr;
+    c_qc = c_kvc = c_oc = nullptr; c_lsec = c_x3 = nullptr;
     if (md.arch == MGRIT_ARCH_CROSS) {
       c_qc = b.take_bytes(C * T * d * esz);
       c_kvc = b.take_bytes(C * Tm * 2 * d * esz);
       c_oc = b.take_bytes(C * T * d * esz);
       c_lsec = b.take<float>(C * md.batch * H * md.seq);
       c_x3 = b.take<float>(C * T * d);
-      memb = b.take_bytes((size_t)Tm * d * esz);
     }
+  }
+  void carve_adjoint(Bump& b, int gc, int ncache) {
+    carve_cache(b, recompute ? gc : ncache);
+    memb = md.arch == MGRIT_ARCH_CROSS ? b.take_bytes((size_t)Tm * d * esz) : nullptr;
     carve_adjoint_work(b, gc);
   }
   void carve_adjoint_work(Bump& b, int gc) {
@@ -313,6 +319,7 @@ AuxStream& aux_stream() {
   }
   return a;
 }
+int g_adjoint_cache = 1;                    // 0 = no N-layer linearisation cache: recompute per launch chunk
 int g_lanes = 2;                            // 1 = everything on the caller's stream
 int g_pipeline = 1;                         // overlap the serial coarse solve with the F-relaxation that follows it
 int g_pipe_chunk = 0;                       // intervals per hand-over (0 = the launch chunk)
@@ -321,6 +328,7 @@ int g_pipe_chunk = 0;                       // intervals per hand-over (0 = the 
 inline bool make_lane(Engine& E2, const Engine& E, Bump& b, bool adjoint, bool measure_only) {
   if (g_lanes < 2) return false;
   E2 = E;
+  if (adjoint && E.recompute) E2.carve_cache(b, E.Gc);      // lanes run at the same time: one chunk-sized cache each
   if (adjoint) E2.carve_adjoint_work(b, E.Gc); else E2.carve_forward_work(b, E.Gc);
   if (measure_only) return true;
   AuxStream& a = aux_stream();
@@ -475,6 +483,7 @@ int linear_param_grads(Engine& E, int n, const void* dY, long dy_stride, Slots d
 struct GradPass {
   const Params* DT = nullptr;      // gradient blocks of the chunk's layers, or null
   float* dE_all = nullptr;         // cross-attention decoder: [layer slot, Tm, d] fp32 memory-gradient terms, or null
+  Slots dE_slots = {0, 1};         // layer slots of the chunk's groups in dE_all
   bool write_state = false;        // also finish the step (OUT written): a relaxation step that emits its layer's gradients
 };
 // Decoder step of a stacked encoder-decoder grid (paper section 3.1, eq. "fp_transformer"): the
@@ -598,7 +607,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
     if (gp && gp->dE_all) {
       // this layer's term of dL/dE:  hstep * [dK | dV] Wkv_c       [Tm,2d] x [2d,d]: transposed Wkv_c is [d,2d]
       g = gemm_base(n, E.Tm, d, 2 * d, E.dkvc, (long)E.Tm * 2 * d, loc, THT, L.offset[MGRIT_P_WKV_C], -1);
-      g.out = gp->dE_all; g.out_slot_stride = (long)E.Tm * d; g.out_slots = cs; g.hstep = hstep;
+      g.out = gp->dE_all; g.out_slot_stride = (long)E.Tm * d; g.out_slots = gp->dE_slots; g.hstep = hstep;
       HIPCHK(launch_gemm(g, EPI_STORE_F32, E.bf16, E.st));
     }
     // du3 = dq_c Wq_c
@@ -731,8 +740,15 @@ int adjoint_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Pa
       gp.dE_all = dE_all;
       gp.write_state = true;
     }
+    Slots slots = shift(cs, c0);
+    gp.dE_slots = slots;
+    if (L.recompute) {                    // the internals of this chunk's layers, into the lane's chunk-sized cache
+      slots = Slots{0, 1};
+      STCHK(forward_chunk(L, n, shift(LIN, c0), NO_ROWS, NO_ROWS, shift(TH, c0), 0.f, true, slots,
+                          sd ? s.MEM : NO_ROWS));
+    }
     return adjoint_chunk(L, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), shift(THT, c0),
-                         shift(LIN, c0), shift(cs, c0), hstep, emit ? &gp : nullptr, sd ? &s : nullptr);
+                         shift(LIN, c0), slots, hstep, emit ? &gp : nullptr, sd ? &s : nullptr);
   });
 }
 
@@ -746,8 +762,15 @@ int gradient_groups(Engine& E, Engine* E2, int G, Rows IN, Params TH, Params THT
     gp.dE_all = dE_all;
     StackedDec s;
     if (sd) s = shift(*sd, c0);
+    Slots slots = shift(cs, c0);
+    gp.dE_slots = slots;
+    if (L.recompute) {
+      slots = Slots{0, 1};
+      STCHK(forward_chunk(L, n, shift(LIN, c0), NO_ROWS, NO_ROWS, shift(TH, c0), 0.f, true, slots,
+                          sd ? s.MEM : NO_ROWS));
+    }
     return adjoint_chunk(L, n, shift(IN, c0), NO_ROWS, NO_ROWS, shift(TH, c0), shift(THT, c0), shift(LIN, c0),
-                         shift(cs, c0), hstep, &gp, sd ? &s : nullptr);
+                         slots, hstep, &gp, sd ? &s : nullptr);
   });
 }
 
@@ -1065,6 +1088,7 @@ int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, int mod
   const int widest = adjoint ? (N > M0 ? N : M0) : M0;      // the cache pass batches over all N layers
   if (gc > widest) gc = widest;
   E.keep_z = mode == 2;
+  E.recompute = adjoint && !g_adjoint_cache;
   if (adjoint) E.carve_adjoint(b, gc, N); else E.carve_forward(b, gc);
   P.two_lanes = widest >= 2 && make_lane(P.E2, E, b, adjoint, ws == nullptr);
   Driver& D = P.D;
@@ -1345,9 +1369,9 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
   STCHK(transpose_blocks(E, N, TH, THT));
   if (desc->arch == MGRIT_ARCH_CROSS)
     HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
-  // linearisation cache for all N layers, batched over layers
+  // linearisation cache for all N layers, batched over layers (unless every chunk recomputes its own)
   Rows Zrows = {(const void* const*)D.tabZ, 0, 1};
-  STCHK(forward_groups(E, D.E2, N, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
+  if (!E.recompute) STCHK(forward_groups(E, D.E2, N, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
   // initial values
   if (lambda_N != static_cast<char*>(lambda_all) + (size_t)N * state)     // may be row N of lambda_all itself
     HIPCHK(hipMemcpyAsync(static_cast<char*>(lambda_all) + (size_t)N * state, lambda_N, state,
@@ -1433,6 +1457,7 @@ int make_stacked_plan(StackedPlan& P, const mgrit_model_desc* md, const mgrit_op
   const int widest = adjoint ? (N > M0 ? N : M0) : M0;
   if (gc > widest) gc = widest;
   P.Ee.keep_z = P.Ed.keep_z = mode == 2;
+  P.Ee.recompute = P.Ed.recompute = adjoint && !g_adjoint_cache;
   if (adjoint) { P.Ee.carve_adjoint(b, gc, n_enc); P.Ed.carve_adjoint(b, gc, n_dec); }
   else { P.Ee.carve_forward(b, gc); P.Ed.carve_forward(b, gc); }
   P.two_lanes = widest >= 2 && make_lane(P.Ee2, P.Ee, b, adjoint, ws == nullptr);
@@ -1552,8 +1577,10 @@ int mgrit_adjoint_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, 
   // the Y rows with the X rows of the same state as memory
   const Rows Zrows = {(const void* const*)D.tabZ, 0, 1};
   const Rows ZdecX = shift(Zrows, n_enc), ZdecY = Driver::part(ZdecX, D.x_elems);
-  STCHK(forward_groups(P.Ee, D.E2, n_enc, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
-  STCHK(forward_groups(P.Ed, D.Ed2, n_dec, ZdecY, NO_ROWS, NO_ROWS, shift(TH, n_enc), 0.f, true, Slots{0, 1}, ZdecX));
+  if (!P.Ee.recompute) {
+    STCHK(forward_groups(P.Ee, D.E2, n_enc, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
+    STCHK(forward_groups(P.Ed, D.Ed2, n_dec, ZdecY, NO_ROWS, NO_ROWS, shift(TH, n_enc), 0.f, true, Slots{0, 1}, ZdecX));
+  }
   char* lamN_row = static_cast<char*>(lambda_all) + (size_t)N * state;
   if (lambda_N != lamN_row) HIPCHK(hipMemcpyAsync(lamN_row, lambda_N, state, hipMemcpyDeviceToDevice, st));
   if (!serial_run(opts) && opts->init_guess == 0) {
@@ -1736,6 +1763,7 @@ int mgrit_default_groups_per_launch(const mgrit_model_desc* desc, int sweep) {
 }
 
 void mgrit_set_lanes(int n) { g_lanes = n >= 2 ? 2 : 1; }
+void mgrit_set_adjoint_cache(int on) { g_adjoint_cache = on ? 1 : 0; }
 
 // test / tuning hooks (not part of the documented interface)
 void mgrit_debug_force_simple_kernels(int gemm, int attn) {
