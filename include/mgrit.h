@@ -21,14 +21,14 @@
  *    MGRIT_UNSUPPORTED and MGRIT_WORKSPACE_TOO_SMALL nothing has been enqueued or
  *    written.  No exception or abort crosses this boundary.
  *  - Results are run-to-run bit-identical (no atomics feed any state).
- *  - Threads: the library is meant to be driven by ONE host thread at a time per process.  The
- *    tuning knobs below (lanes, groups per launch, debug hooks) are process-global, and so are the
- *    helper stream and its events that the two-lane mode creates once per process: two calls that
- *    are in flight at the same time -- from two host threads, or enqueued on two different caller
- *    streams without an ordering between them -- would share that helper stream and those events
- *    and are not supported with lanes = 2 (mgrit_set_lanes(1) uses the caller's stream only; then
- *    concurrent calls on different streams with different workspaces are independent, as long as
- *    no knob is changed meanwhile).  Only the last-error code is per thread.
+ *  - Threads: entry points that enqueue work may be called from several host threads; they
+ *    serialise on a process-wide lock while they enqueue (a call holds it for its host-side
+ *    duration, not for the GPU work), because the helper stream and the events of the two-lane
+ *    mode exist once per device and are shared by all calls.  Calls issued on different caller
+ *    streams are then ordered on the helper lane in the order the lock was taken; their results do
+ *    not depend on it.  The tuning knobs below (lanes, groups per launch, adjoint cache, debug
+ *    hooks) are process-global and unsynchronised: set them while no call is in progress, and
+ *    query workspace sizes under the same settings as the call.  The last-error code is per thread.
  *
  * State layout: a state is [T, d_model] row-major fp32 with T = batch*seq tokens,
  * sequence b owning rows b*seq .. (b+1)*seq-1.  States, lambda, and every
@@ -324,7 +324,7 @@ int  mgrit_default_groups_per_launch(const mgrit_model_desc* desc, int sweep);
  * caller are unchanged); with two lanes the serial solve on the coarsest level also overlaps the
  * right-hand sides before it and the F-relaxation after it, handed over chunk by chunk through
  * events (same results, bit for bit); 1 keeps everything on the caller's stream.  The helper
- * stream and its events (34, no timing) are created once per process on first use.  Both knobs
+ * stream and its events (34, no timing) are created once per device on first use.  Both knobs
  * change the workspace size: set them before querying it. */
 void mgrit_set_lanes(int n);
 

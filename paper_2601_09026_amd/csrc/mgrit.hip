@@ -299,7 +299,7 @@ struct Engine {
 // helper stream (forked from and joined back into the caller's stream with events), so that
 // the bandwidth-bound kernels of one chunk overlap the matrix kernels of the other.  The
 // helper stream and its events (fork, join and a pool for the hand-overs of the overlapped coarse
-// solve) are created once per process, on first use.
+// solve) are created once per device, on first use.
 constexpr int PIPE_EVENTS = 32;
 struct AuxStream {
   hipStream_t s = nullptr;
@@ -307,8 +307,18 @@ struct AuxStream {
   hipEvent_t pipe[PIPE_EVENTS] = {};     // hand-overs from the serial coarse solve to the helper lane
   bool tried = false, ok = false;
 };
+// One helper lane per device, created on first use with that device current.  Calls are serialised on
+// the host while they enqueue (g_call_mutex, taken by every entry point that launches work), so the
+// lane's stream and events are never used by two calls at once: hipStreamWaitEvent takes the event's
+// state when it is enqueued, and a call has enqueued all its waits before the next call records again.
+constexpr int MAX_AUX_DEVICES = 64;
+std::recursive_mutex g_call_mutex;
 AuxStream& aux_stream() {
-  static AuxStream a;
+  static AuxStream table[MAX_AUX_DEVICES];
+  static AuxStream none;                    // ok == false: no second lane
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_AUX_DEVICES) return none;
+  AuxStream& a = table[dev];
   if (!a.tried) {
     a.tried = true;
     a.ok = hipStreamCreateWithFlags(&a.s, hipStreamNonBlocking) == hipSuccess &&
@@ -1171,6 +1181,7 @@ int layer_step_on(const mgrit_model_desc* desc, int adjoint, int n_groups, const
                   void* const* out, const void* const* theta, const void* const* lin_state,
                   const void* const* rhs, const void* memory, float hstep, void* workspace,
                   size_t workspace_bytes, void* stream, bool second_lane) {
+  std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
   STCHK(validate_desc(desc));
   if (n_groups < 1 || !workspace || !isfinite(hstep)) return MGRIT_INVALID_ARG;
   STCHK(check_ptr_array(in, n_groups));
@@ -1305,6 +1316,7 @@ int64_t mgrit_step_depth(const mgrit_opts* opts) {
 int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z0,
                   const void* const* theta, const void* memory, void* Z_all, float* resnorm, void* workspace,
                   size_t workspace_bytes, void* stream) {
+  std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
   STCHK(validate_desc(desc));
   STCHK(validate_opts(opts));
   if (!Z0 || !Z_all || !workspace) return MGRIT_INVALID_ARG;
@@ -1340,6 +1352,7 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
                   const void* const* theta, const void* memory, const void* lambda_N, void* lambda_all,
                   void* dmemory, void* const* dtheta, float* resnorm, void* workspace, size_t workspace_bytes,
                   void* stream) {
+  std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
   STCHK(validate_desc(desc));
   STCHK(validate_opts(opts));
   if (dmemory && desc->arch != MGRIT_ARCH_CROSS) return MGRIT_INVALID_ARG;
@@ -1520,6 +1533,7 @@ size_t mgrit_stacked_workspace_bytes(const mgrit_model_desc* desc, const mgrit_o
 int mgrit_forward_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, const void* Z0,
                           const void* const* theta, void* Z_all, float* resnorm, void* workspace,
                           size_t workspace_bytes, void* stream) {
+  std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
   STCHK(validate_stacked(desc, opts, n_enc));
   if (!Z0 || !Z_all || !workspace) return MGRIT_INVALID_ARG;
   STCHK(check_ptr_array(theta, opts->N));
@@ -1548,6 +1562,7 @@ int mgrit_forward_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, 
 int mgrit_adjoint_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, const void* Z_all,
                           const void* const* theta, const void* lambda_N, void* lambda_all, void* const* dtheta,
                           float* resnorm, void* workspace, size_t workspace_bytes, void* stream) {
+  std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
   STCHK(validate_stacked(desc, opts, n_enc));
   if (!Z_all || !lambda_N || !lambda_all || !workspace) return MGRIT_INVALID_ARG;
   STCHK(check_ptr_array(theta, opts->N));
@@ -1652,6 +1667,7 @@ size_t mgrit_buffered_workspace_bytes(const mgrit_model_desc* desc, const mgrit_
 int mgrit_forward_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
                            const void* Z0, const void* const* theta, const void* memory, void* Z_all,
                            float* resnorm, void* workspace, size_t workspace_bytes, void* stream) {
+  std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
   STCHK(validate_desc(desc));
   STCHK(validate_opts(opts));
   STCHK(validate_buffer(buf));
@@ -1683,6 +1699,7 @@ int mgrit_adjoint_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts,
                            const void* Z_all, const void* const* theta, const void* memory, const void* lambda_N,
                            void* lambda_all, void* dmemory, void* const* dtheta, float* resnorm, void* workspace,
                            size_t workspace_bytes, void* stream) {
+  std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
   STCHK(validate_desc(desc));
   STCHK(validate_opts(opts));
   STCHK(validate_buffer(buf));
