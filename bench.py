@@ -324,6 +324,9 @@ def main():
                             "instrumented_ms_per_step": events_ms_per_step,
                             "grouped_gemm_TFLOPs": roofline["achieved"]}
         hbm = {}
+        # an event pair adds a few microseconds to the launch it brackets (reported, not subtracted: the
+        # rates below are lower bounds; a kernel trace of the same launches gives the durations proper)
+        bracket_us = mb.mgrit_measure_event_bracket(stream)
         # LayerNorm: the launches over several groups (relaxation sweeps: tens of MB, beyond the caches
         # between producer and consumer) and the single-group ones of the coarse chain apart
         for k in ("ln_fwd", "ln_vjp", "ln_fwd_single", "ln_vjp_single", "elementwise"):
@@ -333,6 +336,7 @@ def main():
                           "avg_launch_us": totals[k]["ms"] * 1e3 / totals[k]["launches"]}
         if roofline is not None:
             roofline["hbm_bound_kernels"] = hbm
+            roofline["event_bracket_us"] = bracket_us
             # what this machine reaches: a register-resident MFMA loop and a 1 GiB streaming copy, so that
             # the fractions can be read against the achievable as well as against the datasheet
             a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")

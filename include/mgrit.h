@@ -367,6 +367,11 @@ int  mgrit_profile_read(int cls, double* total_ms, double* flops, double* bytes,
  * bad arguments, -4 on a HIP error. */
 int mgrit_measure_mfma_ceiling(void* scratch, size_t scratch_bytes, int iters, double* tflops, void* stream);
 int mgrit_measure_copy_ceiling(const void* src, void* dst, size_t bytes, double* gbs, void* stream);
+/* What the per-launch timing above adds to a launch: the median time, in microseconds, between two
+ * events recorded around a kernel that does nothing (64 launches on `stream`, then a wait for it).
+ * Subtracting it from a bracketed launch gives its duration as a kernel trace shows it, to within a
+ * microsecond; it matters for launches of 10-30 us.  0 on success, -1 / -4 as above. */
+int mgrit_measure_event_bracket(double* us, void* stream);
 
 /* Test hook: route GEMMs (first flag) / attention (second flag) to the generic kernels. */
 void mgrit_debug_force_simple_kernels(int gemm, int attn);

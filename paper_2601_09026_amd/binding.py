@@ -299,6 +299,15 @@ def mgrit_measure_copy_ceiling(src: torch.Tensor, dst: torch.Tensor, stream=None
     return out.value
 
 
+def mgrit_measure_event_bracket(stream=None) -> float:
+    """Microseconds that an event pair adds to the launch it brackets (median around an empty kernel)."""
+    out = C.c_double()
+    st = lib().mgrit_measure_event_bracket(C.byref(out), _stream_handle(stream))
+    if st != MGRIT_OK:
+        raise MgritError(st, "mgrit_measure_event_bracket")
+    return out.value
+
+
 # ------------------------------------------------------------------ parameter packing (byte copies only)
 def pack_theta(desc: ModelDesc, params: Dict[str, np.ndarray], device="cuda") -> torch.Tensor:
     """One layer's named fp32 arrays -> packed device block (uint8 tensor) in the library's layout."""

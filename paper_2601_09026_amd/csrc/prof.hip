@@ -68,6 +68,8 @@ __global__ void __launch_bounds__(256) mfma_ceiling_kernel(float* out, int iters
   out[blockIdx.x * 256 + threadIdx.x] = sum;
 }
 
+__global__ void empty_kernel() {}
+
 __global__ void __launch_bounds__(256) copy_ceiling_kernel(const pk_f32x4* in, pk_f32x4* out, long n) {
   for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) out[i] = in[i];
 }
@@ -142,6 +144,36 @@ int mgrit_measure_copy_ceiling(const void* src, void* dst, size_t bytes, double*
   return 0;
 }
 
+
+// What an event pair adds to the launch it brackets: the median time between two events recorded on
+// `stream` around a kernel that does nothing, over 64 launches.  Synchronises the stream.
+int mgrit_measure_event_bracket(double* us, void* stream) {
+  using namespace mg;
+  if (!us) return -1;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  constexpr int N = 64;
+  hipEvent_t ev[2 * N];
+  int made = 0, rc = 0;
+  for (; made < 2 * N; ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) { rc = -4; break; }
+  float t[N];
+  if (rc == 0) {
+    for (int i = 0; i < N && rc == 0; ++i) {
+      if (hipEventRecord(ev[2 * i], st) != hipSuccess) rc = -4;
+      hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, st);
+      if (hipEventRecord(ev[2 * i + 1], st) != hipSuccess) rc = -4;
+    }
+    if (rc == 0 && hipStreamSynchronize(st) != hipSuccess) rc = -4;
+    for (int i = 0; i < N && rc == 0; ++i)
+      if (hipEventElapsedTime(&t[i], ev[2 * i], ev[2 * i + 1]) != hipSuccess) rc = -4;
+  }
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+  if (rc != 0) return rc;
+  for (int i = 1; i < N; ++i)                            // insertion sort: median of 64
+    for (int j = i; j > 0 && t[j] < t[j - 1]; --j) { const float x = t[j]; t[j] = t[j - 1]; t[j - 1] = x; }
+  *us = 0.5 * (t[N / 2 - 1] + t[N / 2]) * 1e3;
+  return 0;
+}
 
 // max_records > 0: create the event pool and start recording; 0: stop and destroy it.
 int mgrit_profile_enable(int max_records) {
