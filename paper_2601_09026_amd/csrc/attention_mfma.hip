@@ -190,6 +190,21 @@ __device__ __forceinline__ void store_rows_T(bf16* dst, long row_stride, int row
 // forward
 // ---------------------------------------------------------------------------
 // Resident blocks per CU the register budget is set for: the accumulators grow with DH.
+// Which (row block, batch*head, group) a workgroup takes.  Workgroups are dispatched in linear order
+// of their index (x fastest).  With a causal mask the work of a row block grows (query blocks) or
+// shrinks (key blocks) with its position: 4 : 1 between the two ends of a 512-token sequence.  The
+// linear index is therefore re-read as (rank of the row block, head), heaviest rank first, so that the
+// launch ends on its lightest blocks instead of on whichever head happens to come last.
+struct BlockTask { int tile, bh, g; };
+__device__ __forceinline__ BlockTask block_task(bool causal, bool last_tile_heaviest) {
+  if (!causal || gridDim.x == 1) return {(int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z};
+  const int heads = gridDim.y * gridDim.z;
+  const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const int rank = lin / heads, head = lin - rank * heads;
+  const int g = head / (int)gridDim.y;
+  return {last_tile_heaviest ? (int)gridDim.x - 1 - rank : rank, head - g * (int)gridDim.y, g};
+}
+
 template <int DH, int NW = 4> constexpr int fa_fwd_blocks() { return NW == 8 ? 1 : DH == 64 ? 4 : 2; }
 template <int DH, int NW = 4> constexpr int fa_bwd_blocks() { return NW == 8 ? 1 : 2; }
 
@@ -202,9 +217,10 @@ __global__ void __launch_bounds__(NW * 64, (fa_fwd_blocks<DH, NW>())) attn_fwd_m
   constexpr bool DB = NW >= 4 && DH == 128;
   __shared__ __attribute__((aligned(16))) bf16 Ksb[DB ? 2 : 1][64 * fa_ld<DH>()];    // [key][d]
   __shared__ __attribute__((aligned(16))) bf16 Vtb[DB ? 2 : 1][DH * FA_LDT];          // [d][key]
-  const int g = blockIdx.z;
-  const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
-  const int q0 = blockIdx.x * (NW * 32);
+  const BlockTask bt = block_task(a.causal, true);
+  const int g = bt.g;
+  const int b = bt.bh / a.H, h = bt.bh - b * a.H;
+  const int q0 = bt.tile * (NW * 32);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 31, lh = lane >> 5;
   const HeadPtrs P = head_ptrs(a, g, b, h);
   const int qi = q0 + wave * 32 + lr;
@@ -330,9 +346,10 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, bf16* lds, f
   constexpr int KS = DH / 16, DT = DH / 32, FA_LD = fa_ld<DH>();
   // one set of tiles: K [key][d], V [key][d], K transposed [d][key]
   constexpr int V_OFF = 64 * FA_LD, KT_OFF = 2 * 64 * FA_LD, SET = bwd_dq_lds<DH>();
-  const int g = blockIdx.z;
-  const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
-  const int q0 = blockIdx.x * (NW * 32);
+  const BlockTask bt = block_task(a.causal, true);
+  const int g = bt.g;
+  const int b = bt.bh / a.H, h = bt.bh - b * a.H;
+  const int q0 = bt.tile * (NW * 32);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 31, lh = lane >> 5;
   const HeadPtrs P = head_ptrs(a, g, b, h);
   const int qi = q0 + wave * 32 + lr;
@@ -451,9 +468,10 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, bf16* lds, 
   bf16* dOs = Qs + 64 * FA_LD;           // [query][d]
   bf16* Qt = dOs + 64 * FA_LD;           // [d][query]
   bf16* dOt = Qt + DH * FA_LDT;          // [d][query]
-  const int g = blockIdx.z;
-  const int b = blockIdx.y / a.H, h = blockIdx.y - b * a.H;
-  const int j0 = blockIdx.x * (NW * 32);
+  const BlockTask bt = block_task(a.causal, false);
+  const int g = bt.g;
+  const int b = bt.bh / a.H, h = bt.bh - b * a.H;
+  const int j0 = bt.tile * (NW * 32);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 31, lh = lane >> 5;
   const HeadPtrs P = head_ptrs(a, g, b, h);
   const int kj = j0 + wave * 32 + lr;
