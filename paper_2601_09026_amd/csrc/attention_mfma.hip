@@ -189,22 +189,42 @@ __device__ __forceinline__ void store_rows_T(bf16* dst, long row_stride, int row
 // ---------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------
-// Resident blocks per CU the register budget is set for: the accumulators grow with DH.
 // Which (row block, batch*head, group) a workgroup takes.  Workgroups are dispatched in linear order
-// of their index (x fastest).  With a causal mask the work of a row block grows (query blocks) or
-// shrinks (key blocks) with its position: 4 : 1 between the two ends of a 512-token sequence.  The
-// linear index is therefore re-read as (rank of the row block, head), heaviest rank first, so that the
-// launch ends on its lightest blocks instead of on whichever head happens to come last.
+// of their index (x fastest), consecutive ones to consecutive XCDs (8, each with an L2 of its own).
+// Causal mask: the work of a row block grows (query blocks) or shrinks (key blocks) with its
+// position, 4 : 1 between the two ends of a 512-token sequence, so in the natural order some XCDs get
+// only heavy blocks.  The linear index is re-read as (rank of the row block, head), heaviest rank
+// first: every XCD gets the same mix and the launch ends on its lightest blocks.
+// No mask: all blocks are equal; the index is re-read so that the row blocks of one head go to ONE
+// XCD one after the other (they run together and share the head's K and V, or Q and dO, in its L2).
 struct BlockTask { int tile, bh, g; };
 __device__ __forceinline__ BlockTask block_task(bool causal, bool last_tile_heaviest) {
-  if (!causal || gridDim.x == 1) return {(int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z};
-  const int heads = gridDim.y * gridDim.z;
-  const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-  const int rank = lin / heads, head = lin - rank * heads;
-  const int g = head / (int)gridDim.y;
-  return {last_tile_heaviest ? (int)gridDim.x - 1 - rank : rank, head - g * (int)gridDim.y, g};
+  const int nx = gridDim.x, ny = gridDim.y;
+  if (nx == 1) return {0, (int)blockIdx.y, (int)blockIdx.z};
+  const int heads = ny * gridDim.z;
+  const int lin = blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z);
+  int tile, head;
+  if (causal) {
+    const int rank = lin / heads;
+    head = lin - rank * heads;
+    tile = last_tile_heaviest ? nx - 1 - rank : rank;
+  } else {
+    const int whole = (heads >> 3) << 3;                  // heads that fill all 8 XCDs evenly
+    if (lin < whole * nx) {
+      const int s = lin >> 3, hs = s / nx;
+      tile = s - hs * nx;
+      head = (hs << 3) + (lin & 7);
+    } else {
+      const int rem = lin - whole * nx, hs = rem / nx;
+      tile = rem - hs * nx;
+      head = whole + hs;
+    }
+  }
+  const int g = head / ny;
+  return {tile, head - g * ny, g};
 }
 
+// Resident blocks per CU the register budget is set for: the accumulators grow with DH.
 template <int DH, int NW = 4> constexpr int fa_fwd_blocks() { return NW == 8 ? 1 : DH == 64 ? 4 : 2; }
 template <int DH, int NW = 4> constexpr int fa_bwd_blocks() { return NW == 8 ? 1 : 2; }
 
