@@ -17,9 +17,11 @@ template <> __device__ __forceinline__ f32x4 rload4<bf16>(const bf16* p) {
   return r;
 }
 
-// One 64-lane wavefront walks token rows with a grid stride and keeps the next row's loads
-// in flight while it reduces and writes the current one (few long-lived waves instead of one
-// short-lived wave per row).  NV = float4 per lane (row kept in registers), d <= 256*NV.
+// One 64-lane wavefront walks token rows with a grid stride.  NV = float4 per lane (row kept in
+// registers), d <= 256*NV.  Rows of up to 256 elements keep the next row's loads in flight while the
+// current one is reduced and written; for longer rows the second register set costs more in resident
+// wavefronts than the overlap gains (d = 768: 74 -> 48 registers, +5 % bandwidth, and a block then
+// fits beside a resident GEMM block of the other lane).
 constexpr int LN_MAXV = 8;          // d <= 64*4*8 = 2048
 constexpr int LN_FWD_BLOCKS_PER_CU = 16;   // grid caps (measured: the forward kernel gains from the larger one,
 constexpr int LN_BWD_BLOCKS_PER_CU = 16;   // the VJP likewise once it no longer prefetches rows of more than 512 elements)
@@ -68,7 +70,7 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const LnFwdArgs a) {
       if (c < d) v[i] = load_sum(x, xa, c);
     }
   };
-  constexpr bool PREFETCH = NV <= 4;
+  constexpr bool PREFETCH = NV == 1;
   f32x4 cur[NV], nxt[PREFETCH ? NV : 1];
   load(row, cur);
   while (true) {
