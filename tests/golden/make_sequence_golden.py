@@ -5,8 +5,9 @@ adjoint) for ONE sequence of a full-size benchmark configuration, computed by th
 
 Sequences are independent through the whole method (attention never crosses a sequence), so the
 oracle's run on one sequence alone is what the full-batch run holds in that sequence's rows.  The
-three-level adjoint of the deepest configuration takes the oracle a quarter of an hour per
-sequence, too long for a test, which is why its result is stored.  Stored, all float32:
+three-level forward and adjoint iteration of the deepest configurations (gpt2_small, mc_deep_narrow)
+takes the oracle a quarter of an hour per sequence, too long for a test, which is why its result
+is stored.  Stored, all float32:
 
   points        the level-0 C-points n = 0, cf, 2 cf, .. N (they include the C-points of every
                 coarser level), where relaxation, FAS right-hand side, coarse solve and

@@ -143,34 +143,21 @@ def test_full_gpt2_small_forward():
     run_full("gpt2_small", fwd_seqs=[6], adj_seqs=[], prefix=160)
 
 
-SEQ_GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "gpt2_small_seq5.npz")
+def stored_sequence(name, b):
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", f"{name}_seq{b}.npz")
+    assert os.path.exists(path), f"{path} is missing: python tests/golden/make_sequence_golden.py {name} {b}"
+    return np.load(path)
 
 
-def test_full_gpt2_small_forward_and_adjoint_against_the_stored_oracle_sequence():
-    """The deepest configuration (three levels, N = 128, causal, forward + adjoint) at its full size, as
-    bench.py launches it, against the oracle's complete MGRIT iterate of one sequence, computed offline by
-    tests/golden/make_sequence_golden.py (the oracle needs a quarter of an hour for it): Z_n and lambda_n
-    at every level-0 C-point (they include every coarser level's C-points: the points that the relaxation,
-    the right-hand sides, the coarse solves and the corrections of all three levels write) on 16 sampled
-    token rows, element by element, plus the whole-sequence norms of the increments at every point, F-points
-    included.  The stored adjoint is linearised about the oracle's own forward iterate and the library's
-    about its own (sec. 3.2.2): the two differ by the forward tolerance, which moves lambda far less than
-    the bar.  Then the full-batch residual norms against the stored ones."""
-    wl = wls.named_workloads()["gpt2_small"]
-    tol = TOL[wl.dtype]
-    print(f"[case] full size gpt2_small forward + adjoint vs stored oracle sequence", flush=True)
-    assert os.path.exists(SEQ_GOLDEN), f"{SEQ_GOLDEN} is missing: python tests/golden/make_sequence_golden.py"
-    g = np.load(SEQ_GOLDEN)
+def check_against_stored_sequence(wl, g, Zg, lg, tol):
+    """Z_n and lambda_n of the library's full-batch run against the oracle's complete MGRIT iterate of one
+    sequence, stored by tests/golden/make_sequence_golden.py: element by element at every level-0 C-point
+    (they include every coarser level's C-points: the points that the relaxation, the right-hand sides, the
+    coarse solves and the corrections of all levels write) on the sampled token rows, plus the
+    whole-sequence norms of the increments at every point, F-points included.  Returns the worst increment
+    error of Z and of lambda."""
     b, points, tokens = int(g["sequence"]), g["points"], g["tokens"]
     assert list(points) == list(range(0, wl.N + 1, wl.cf))
-    dm = DeviceModel(wl, keep_host=False)
-    opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters)
-    Z0, lamN = wls.initial_state(wl), wls.terminal_adjoint(wl)
-    Zg, rg = mb.mgrit_forward(dm.desc, opts, dev(Z0), dm.blocks)
-    lg, ag = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN))
-    torch.cuda.synchronize()
-    assert torch.equal(Zg[0].cpu(), torch.from_numpy(Z0))
-    assert torch.equal(lg[wl.N].cpu(), torch.from_numpy(lamN))
     seq = rows_of(wl, b)
     einc = {}
     for what, got_all, ref_pts, base_n, inc_norm, val_norm in (("Z", Zg, g["Z"], 0, g["Z_inc_norm"], g["Z_norm"]),
@@ -200,6 +187,29 @@ def test_full_gpt2_small_forward_and_adjoint_against_the_stored_oracle_sequence(
             mine = np.linalg.norm(got_seq[n] - got_seq[base_n])
             floor = 4.0 * np.sqrt(abs(n - base_n)) * 2.0 ** -24 * val_norm[n]
             assert abs(mine - inc_norm[n]) <= tol * inc_norm[n] + floor, f"|{what}[{n}] - start|: {mine} vs {inc_norm[n]}"
+    return einc
+
+
+def test_full_gpt2_small_forward_and_adjoint_against_the_stored_oracle_sequence():
+    """The deepest configuration (three levels, N = 128, causal, forward + adjoint) at its full size, as
+    bench.py launches it, against the oracle's complete MGRIT iterate of one sequence, computed offline
+    (the oracle needs a quarter of an hour for it): see check_against_stored_sequence.  The stored adjoint
+    is linearised about the oracle's own forward iterate and the library's about its own (sec. 3.2.2): the
+    two differ by the forward tolerance, which moves lambda far less than the bar.  Then the full-batch
+    residual norms against the stored ones."""
+    wl = wls.named_workloads()["gpt2_small"]
+    tol = TOL[wl.dtype]
+    print(f"[case] full size gpt2_small forward + adjoint vs stored oracle sequence", flush=True)
+    g = stored_sequence("gpt2_small", 5)
+    dm = DeviceModel(wl, keep_host=False)
+    opts = mb.mgrit_opts(wl.N, wl.h, wl.cf, wl.levels, wl.iters)
+    Z0, lamN = wls.initial_state(wl), wls.terminal_adjoint(wl)
+    Zg, rg = mb.mgrit_forward(dm.desc, opts, dev(Z0), dm.blocks)
+    lg, ag = mb.mgrit_adjoint(dm.desc, opts, Zg, dm.blocks, dev(lamN))
+    torch.cuda.synchronize()
+    assert torch.equal(Zg[0].cpu(), torch.from_numpy(Z0))
+    assert torch.equal(lg[wl.N].cpu(), torch.from_numpy(lamN))
+    einc = check_against_stored_sequence(wl, g, Zg, lg, tol)
     gold = golden("gpt2_small")
     check_norms("forward", rg.cpu().numpy(), gold["forward"], tol, gold["increment_norm"], einc["Z"])
     inc = float(torch.linalg.vector_norm((lg[0] - lg[wl.N]).double()))
@@ -219,13 +229,15 @@ def test_full_gpt2_small_forward_and_adjoint_against_the_stored_oracle_sequence(
         assert e <= bar
 
 
-def test_full_mc_deep_narrow_relations_on_a_sampled_sequence():
+def test_full_mc_deep_narrow_against_the_stored_oracle_sequence():
     """The deep-narrow configuration at its full size (8 sequences of 2048 tokens, one head of 128, 256
-    layers, 3 levels, F-relaxation), as bench.py launches it.  The oracle's complete iteration for one such
-    sequence takes many minutes, so the check uses what holds at any size: Z_0 and lambda_N are copied
-    exactly, residual norms decrease, and after the closing F-relaxation every F-point satisfies
-    Z_{n+1} = Phi(Z_n) and lambda_n = Psi(lambda_{n+1}; Z_n), recomputed by the oracle on one sequence
-    (this is where the 256-row attention blocks and the 2-rows-per-wavefront LayerNorm run at full length)."""
+    layers, 3 levels, F-relaxation), as bench.py launches it (this is where the 256-row attention blocks and
+    the 2-rows-per-wavefront LayerNorm run at full length).  Z_0 and lambda_N are copied exactly; Z and
+    lambda at every C-point against the oracle's complete iterate of one sequence, computed offline (a
+    quarter of an hour): see check_against_stored_sequence; the full-batch residual norms against the
+    oracle's, stored by tests/golden/make_resnorm_golden.py (an hour and a half); and after the closing
+    F-relaxation every F-point satisfies Z_{n+1} = Phi(Z_n) and lambda_n = Psi(lambda_{n+1}; Z_n),
+    recomputed by the oracle on one sequence."""
     wl = wls.named_workloads()["mc_deep_narrow"]
     tol = TOL[wl.dtype]
     print(f"[case] full size {wl.name}: B={wl.batch} S={wl.seq} d={wl.d_model} N={wl.N} cf={wl.cf} L={wl.levels} "
@@ -240,8 +252,12 @@ def test_full_mc_deep_narrow_relations_on_a_sampled_sequence():
     assert torch.equal(lg[wl.N].cpu(), torch.from_numpy(lamN))
     for norms in (rg.cpu().numpy(), ag.cpu().numpy()):
         assert np.isfinite(norms).all() and norms[1] < norms[0], norms
+    einc = check_against_stored_sequence(wl, stored_sequence("mc_deep_narrow", 5), Zg, lg, tol)
+    gold = golden("mc_deep_narrow")
+    check_norms("forward", rg.cpu().numpy(), gold["forward"], tol, gold["increment_norm"], einc["Z"])
+    check_norms("adjoint", ag.cpu().numpy(), gold["adjoint"], tol, gold["adjoint_increment_norm"], einc["lambda"])
     sh1 = tode.Shape(wl.arch, wl.d_model, wl.n_heads, 1, wl.seq, 0, wl.ln_eps)
-    r = rows_of(wl, 5)
+    r = rows_of(wl, 2)
     for n in (0, 129, 254):                     # Z_{n+1} is an F-point: n + 1 not a multiple of cf
         assert (n + 1) % wl.cf != 0
         base = Zg[n, r, :].cpu().numpy().astype(np.float64)
