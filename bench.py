@@ -6,8 +6,10 @@ mgrit_forward followed by mgrit_adjoint (linearised about the forward result) at
 workload; the default is the largest benchmark configuration that runs forward + adjoint, the
 GPT-2-small shape (causal, 128 layers, three levels).  The headline value is layer-steps*tokens/s = (Phi + Psi evaluations enqueued on
 all levels) x (batch*seq) / wall time, with all inputs resident in HBM before the timed
-region.  The adjoint's one-off N-layer linearisation pass is timed but not counted as
-evaluations.
+region.  The pair of calls is mgrit_forward_linearising + mgrit_adjoint_linearised (the forward
+solve's closing relaxation leaves the internals of the layers it steps through to the adjoint; results
+identical to the plain pair, --plain-pair); what is left of the adjoint's linearisation pass is timed
+but not counted as evaluations.
 
 Prints ONE JSON line: metric, value, timing, the workload in `config`, `roofline` of the dominant
 kernel and `cpu_baseline` (the oracle timed on the host).  Everything runs on one GPU;
@@ -59,6 +61,9 @@ def parse():
     ap.add_argument("--pipe-chunk", type=int, default=0, help="tuning: intervals per hand-over of the coarse solve")
     ap.add_argument("--no-pipeline", action="store_true",
                     help="tuning: serial coarse solve and the following F-relaxation one after the other")
+    ap.add_argument("--plain-pair", action="store_true",
+                    help="mgrit_forward + mgrit_adjoint instead of mgrit_forward_linearising + "
+                         "mgrit_adjoint_linearised (the adjoint then evaluates the internals of all N layers itself)")
     ap.add_argument("--no-adjoint-cache", action="store_true",
                     help="adjoint without the N-layer linearisation cache (recomputed per launch chunk)")
     ap.add_argument("--no-kernel-events", action="store_true",
@@ -194,6 +199,12 @@ def main():
         ws_bytes = max(mb.mgrit_workspace_bytes(desc, opts, 0),
                        mb.mgrit_workspace_bytes(desc, opts, 2 if grads else 1) if adjoint else 0, 256)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    # the linearising pair: the forward solve writes into the adjoint's workspace, so it needs one of its own
+    shared = adjoint and not sw and not args.plain_pair and not args.no_adjoint_cache
+    ws_fwd = ws
+    if shared:
+        ws_fwd = torch.empty(max(mb.mgrit_workspace_bytes(desc, opts, 0), 256), dtype=torch.uint8, device="cuda")
+        ws_bytes += ws_fwd.numel()
     n_phi = mb.mgrit_step_evaluations(opts)
     n_psi = n_phi if adjoint else 0
     stream = torch.cuda.current_stream()
@@ -208,11 +219,11 @@ def main():
     def step(stream=stream):
         if sw:
             return step_stacked(stream)
-        mb.mgrit_forward(desc, opts, Z0, theta, memory=mem, Z_all=Z_all, resnorm=res_f, workspace=ws,
-                         stream=stream)
+        mb.mgrit_forward(desc, opts, Z0, theta, memory=mem, Z_all=Z_all, resnorm=res_f, workspace=ws_fwd,
+                         stream=stream, adjoint_workspace=ws if shared else None, with_gradients=bool(grads))
         if adjoint:
             mb.mgrit_adjoint(desc, opts, Z_all, theta, lamN, memory=mem, lambda_all=lam_all, resnorm=res_a,
-                             workspace=ws, stream=stream, dtheta=grads)
+                             workspace=ws, stream=stream, dtheta=grads, linearised=shared)
 
     # --graph: the caller captures one step (kernels, copies and the library's fork/join events)
     # into a HIP graph and replays it; what the launch-bound small workloads gain from that
@@ -381,6 +392,8 @@ def main():
                        C_byref(desc), max(wl.N // wl.cf, 1)), "lanes": args.lanes or 2,
                    "param_grads": bool(grads), "launch": "hip graph replay" if args.graph else "eager",
                    "adjoint_cache": not args.no_adjoint_cache, "workspace_bytes": int(ws_bytes),
+                   "linearisation": "left by the forward solve's closing relaxation" if shared
+                   else "the adjoint's own pass over all layers",
                    **({"stacked": True, "n_enc": sw.n_enc, "src_seq": sw.enc.seq} if sw else {})},
         "residual_norms": {"forward": [float(x) for x in res_f.cpu()[:wl.iters]],
                            "adjoint": [float(x) for x in res_a.cpu()[:wl.iters]] if adjoint else None},

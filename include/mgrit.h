@@ -179,6 +179,36 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts,
                   void* dmemory, void* const* dtheta, float* resnorm,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same two solves for a training step, where the adjoint follows the forward solve (sec. 3.2.2:
+ * the adjoint is linearised about the forward iterate): the adjoint keeps the internals of every
+ * layer's step at Z_n (a linearisation cache of N entries at the start of its workspace), and the
+ * level-0 steps of the forward solve's closing F-relaxation (sec. 3.2.1; every step of a serial run)
+ * evaluate exactly those internals at the final Z_n, for every layer but the last of each coarse
+ * interval.  mgrit_forward_linearising is mgrit_forward whose closing relaxation also leaves them in
+ * `adjoint_workspace`; mgrit_adjoint_linearised is mgrit_adjoint that takes them from its workspace
+ * and evaluates only the remaining N / cf layers (none in a serial run) before it starts.  Z_all,
+ * lambda_all, gradients and residual norms are bit-identical to those of the plain pair.
+ *   adjoint_workspace        device, at least mgrit_workspace_bytes(desc, opts, with_gradients ? 2 : 1)
+ *   with_gradients           non-zero iff the adjoint call will ask for dtheta or dmemory (the cache
+ *                            then also keeps the feed-forward pre-activation)
+ * The caller guarantees, between the two calls: the same desc, opts, theta and memory; Z_all of the
+ * adjoint is the unmodified output of the forward call; `workspace` of the adjoint is the forward
+ * call's `adjoint_workspace`, untouched in between, and with_gradients matches; the adjoint is
+ * enqueued after the forward call on the same stream; the linearisation cache is switched on
+ * (mgrit_set_adjoint_cache, the default; MGRIT_INVALID_ARG otherwise).  None of this can be checked
+ * by the library: a violation gives wrong lambda without an error.  Everything else as above. */
+int mgrit_forward_linearising(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                              const void* Z0, const void* const* theta, const void* memory,
+                              void* Z_all, float* resnorm,
+                              void* workspace, size_t workspace_bytes,
+                              void* adjoint_workspace, size_t adjoint_workspace_bytes, int with_gradients,
+                              void* stream);
+int mgrit_adjoint_linearised(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                             const void* Z_all, const void* const* theta, const void* memory,
+                             const void* lambda_N, void* lambda_all,
+                             void* dmemory, void* const* dtheta, float* resnorm,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 /* Buffer layers (Appendix "Buffer layers"): the first n_open and the last n_close layers of the
  * network are propagated serially (exactly) with their own step size h_buffer (the paper uses 1),
  * and only the N = opts->N layers in between by MGRIT with step opts->h (the paper: 1 / N).

@@ -94,6 +94,11 @@ def lib() -> C.CDLL:
         L.mgrit_adjoint.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), vp, vpp, vp, vp, vp, vp, vpp, vp,
                                     vp, C.c_size_t, vp]
         L.mgrit_adjoint.restype = C.c_int
+        L.mgrit_forward_linearising.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), vp, vpp, vp, vp, vp, vp,
+                                                C.c_size_t, vp, C.c_size_t, C.c_int, vp]
+        L.mgrit_forward_linearising.restype = C.c_int
+        L.mgrit_adjoint_linearised.argtypes = L.mgrit_adjoint.argtypes
+        L.mgrit_adjoint_linearised.restype = C.c_int
         L.layer_step_batched.argtypes = [C.POINTER(ModelDesc), C.c_int, C.c_int, vpp, vpp, vpp, vpp, vpp, vp,
                                          C.c_float, vp, C.c_size_t, vp]
         L.layer_step_batched.restype = C.c_int
@@ -248,7 +253,7 @@ PROFILE_CLASSES = {0: "gemm_generic", 1: "attn_fwd", 2: "attn_bwd", 3: "ln_fwd",
                    6: "ln_fwd_single", 7: "ln_vjp_single",
                    8: "gemm_mfma_store", 9: "gemm_mfma_gelu", 10: "gemm_mfma_sublayer_sum",
                    11: "gemm_mfma_euler", 12: "gemm_mfma_dgelu", 13: "gemm_mfma_store_f32",
-                   14: "gemm_mfma_gelu_prime"}
+                   14: "gemm_mfma_gelu_prime", 15: "gemm_mfma_gelu_both"}
 # the same epilogues launched over a single group (the serial coarse chain)
 PROFILE_CLASSES.update({c + 8: n.replace("gemm_mfma_", "gemm_mfma_single_") for c, n in list(PROFILE_CLASSES.items())
                         if c >= 8})
@@ -353,8 +358,11 @@ def _check_state(t: torch.Tensor, shape, name: str):
 def mgrit_forward(desc: ModelDesc, opts: Opts, Z0: torch.Tensor, theta: List[torch.Tensor],
                   memory: Optional[torch.Tensor] = None, Z_all: Optional[torch.Tensor] = None,
                   resnorm: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                  stream: Optional[torch.cuda.Stream] = None):
-    """Returns (Z_all [(N+1),T,d], resnorm [iters]).  Buffers are allocated here if not given."""
+                  stream: Optional[torch.cuda.Stream] = None, adjoint_workspace: Optional[torch.Tensor] = None,
+                  with_gradients: bool = False):
+    """Returns (Z_all [(N+1),T,d], resnorm [iters]).  Buffers are allocated here if not given.
+    adjoint_workspace: call mgrit_forward_linearising instead, which also leaves the internals of its
+    closing relaxation there for mgrit_adjoint(..., workspace=adjoint_workspace, linearised=True)."""
     T, d = desc.batch * desc.seq, desc.d_model
     _check_state(Z0, (T, d), "Z0")
     if len(theta) != opts.N:
@@ -367,6 +375,14 @@ def mgrit_forward(desc: ModelDesc, opts: Opts, Z0: torch.Tensor, theta: List[tor
     need = mgrit_workspace_bytes(desc, opts, False)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Z0.device)
+    if adjoint_workspace is not None:
+        st = lib().mgrit_forward_linearising(C.byref(desc), C.byref(opts), _ptr(Z0), _ptr_array(theta), _ptr(memory),
+                                             _ptr(Z_all), _ptr(resnorm), _ptr(workspace), workspace.numel(),
+                                             _ptr(adjoint_workspace), adjoint_workspace.numel(),
+                                             int(bool(with_gradients)), _stream_handle(stream))
+        if st != MGRIT_OK:
+            raise MgritError(st, "mgrit_forward_linearising")
+        return Z_all, resnorm
     st = lib().mgrit_forward(C.byref(desc), C.byref(opts), _ptr(Z0), _ptr_array(theta), _ptr(memory),
                              _ptr(Z_all), _ptr(resnorm), _ptr(workspace), workspace.numel(),
                              _stream_handle(stream))
@@ -379,10 +395,12 @@ def mgrit_adjoint(desc: ModelDesc, opts: Opts, Z_all: torch.Tensor, theta: List[
                   lambda_N: torch.Tensor, memory: Optional[torch.Tensor] = None,
                   lambda_all: Optional[torch.Tensor] = None, resnorm: Optional[torch.Tensor] = None,
                   workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
-                  dtheta: Optional[List[torch.Tensor]] = None, dmemory: Optional[torch.Tensor] = None):
+                  dtheta: Optional[List[torch.Tensor]] = None, dmemory: Optional[torch.Tensor] = None,
+                  linearised: bool = False):
     """Returns (lambda_all [(N+1),T,d], resnorm [iters]).  dtheta: N uint8 device tensors of
     grad_layout(desc).block_bytes each, filled with the parameter gradients; dmemory: fp32
-    [batch*mem_seq, d] device tensor filled with the gradient of the cross-attention memory."""
+    [batch*mem_seq, d] device tensor filled with the gradient of the cross-attention memory.
+    linearised: call mgrit_adjoint_linearised (workspace = the adjoint_workspace that mgrit_forward filled)."""
     T, d = desc.batch * desc.seq, desc.d_model
     _check_state(Z_all, (opts.N + 1, T, d), "Z_all")
     _check_state(lambda_N, (T, d), "lambda_N")
@@ -400,12 +418,14 @@ def mgrit_adjoint(desc: ModelDesc, opts: Opts, Z_all: torch.Tensor, theta: List[
     need = mgrit_workspace_bytes(desc, opts, 2 if (dtheta is not None or dmemory is not None) else 1)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Z_all.device)
-    st = lib().mgrit_adjoint(C.byref(desc), C.byref(opts), _ptr(Z_all), _ptr_array(theta), _ptr(memory),
-                             _ptr(lambda_N), _ptr(lambda_all), _ptr(dmemory), _ptr_array(dtheta), _ptr(resnorm),
-                             _ptr(workspace),
-                             workspace.numel(), _stream_handle(stream))
+    if linearised and workspace is None:
+        raise ValueError("linearised: pass the adjoint workspace that the forward call filled")
+    entry = lib().mgrit_adjoint_linearised if linearised else lib().mgrit_adjoint
+    st = entry(C.byref(desc), C.byref(opts), _ptr(Z_all), _ptr_array(theta), _ptr(memory),
+               _ptr(lambda_N), _ptr(lambda_all), _ptr(dmemory), _ptr_array(dtheta), _ptr(resnorm),
+               _ptr(workspace), workspace.numel(), _stream_handle(stream))
     if st != MGRIT_OK:
-        raise MgritError(st, "mgrit_adjoint")
+        raise MgritError(st, "mgrit_adjoint_linearised" if linearised else "mgrit_adjoint")
     return lambda_all, resnorm
 
 

@@ -147,8 +147,10 @@ enum Epi : int {
   EPI_RESID_OUTER = 3,  // OUT[m,n] = X + h*(ybar + acc + bias) + rhs          (the Euler update)
   EPI_DGELU = 4,        // out = acc * g[m,n], g = the cached gelu'(z)          (adjoint of the activation)
   EPI_STORE_F32 = 5,    // out (fp32, packed or inside the group's output block) = hstep * (acc + bias)
-  EPI_GELU_PRIME = 6    // out = gelu'(acc + bias) (operand type); optionally z = acc + bias kept as well:
+  EPI_GELU_PRIME = 6,   // out = gelu'(acc + bias) (operand type); optionally z = acc + bias kept as well:
                         // the linearisation cache holds the derivative, evaluated once per layer
+  EPI_GELU_BOTH = 7     // out = gelu(acc + bias) and aux2 = gelu'(acc + bias); optionally z kept as well:
+                        // a forward step that also leaves its layer's entry of the linearisation cache
 };
 
 struct GemmArgs {
@@ -164,6 +166,7 @@ struct GemmArgs {
   void* out; long out_slot_stride; Slots out_slots;      // packed output (operand type or fp32)
   void* aux; long aux_slot_stride; Slots aux_slots;      // EPI_GELU, EPI_GELU_PRIME: z out (may be null); EPI_DGELU: g in;
                                                          // EPI_RESID_OUTER: ybar (fp32 packed)
+  void* aux2; long aux2_slot_stride; Slots aux2_slots;   // EPI_GELU_BOTH: gelu'(z) out (operand type)
   Rows X;                      // EPI_RESID_OUTER: the step's input state
   const float* base; long base_slot_stride; Slots base_slots;   // EPI_RESID_INNER: optional packed fp32 addend
   Rows OUT;                    // EPI_RESID_OUTER: the step's output state

@@ -25,6 +25,7 @@ struct EpiPtrs {
   const float* bias;          // [N] or null
   void* out;                  // packed output (operand type or fp32)
   void* aux;                  // EPI_GELU: z out (optional); EPI_DGELU: z in; EPI_RESID_OUTER: ybar
+  void* aux2;                 // EPI_GELU_BOTH: gelu'(z) out
   const float* base;          // EPI_RESID_INNER: optional addend
   const float* X;             // EPI_RESID_OUTER
   const float* RHS;           // EPI_RESID_OUTER, optional
@@ -41,6 +42,7 @@ __device__ __forceinline__ EpiPtrs resolve_epi(const GemmArgs& a, int g, int epi
   if (a.out_tab.tab) p.out = const_cast<char*>(a.out_tab.at(g)) + a.out_tab_off;
   const long asz = epi == EPI_RESID_OUTER ? 4 : (long)sizeof(TO);
   p.aux = a.aux ? static_cast<char*>(a.aux) + a.aux_slots.of(g) * a.aux_slot_stride * asz : nullptr;
+  p.aux2 = a.aux2 ? static_cast<char*>(a.aux2) + a.aux2_slots.of(g) * a.aux2_slot_stride * (long)sizeof(TO) : nullptr;
   p.base = a.base ? a.base + a.base_slots.of(g) * a.base_slot_stride : nullptr;
   p.X = a.X.present() ? a.X.at(g) : nullptr;
   p.RHS = a.RHS.present() ? a.RHS.at(g) : nullptr;
@@ -75,6 +77,7 @@ template <int OPT> __device__ __forceinline__ bool has_opt(int bit, const void* 
 template <int EPI, typename TO, int OPT = -1>
 __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restrict__ out_f32,
                                        TO* __restrict__ z_out, const TO* __restrict__ z_in,
+                                       TO* __restrict__ g_out,
                                        const float* __restrict__ base, const float* __restrict__ X,
                                        const float* __restrict__ ybar, const float* __restrict__ RHS,
                                        float* __restrict__ OUT, float hstep, long idx, f32x4 acc) {
@@ -91,6 +94,13 @@ __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restric
     f32x4 y = {gelu_prime_t<TO>(acc[0]), gelu_prime_t<TO>(acc[1]), gelu_prime_t<TO>(acc[2]),
                gelu_prime_t<TO>(acc[3])};
     estore4<TO>(out_op + idx, y);
+  } else if constexpr (EPI == EPI_GELU_BOTH) {
+    if (has_opt<OPT>(0, z_out)) estore4<TO>(z_out + idx, acc);
+    f32x4 y = {gelu_t<TO>(acc[0]), gelu_t<TO>(acc[1]), gelu_t<TO>(acc[2]), gelu_t<TO>(acc[3])};
+    estore4<TO>(out_op + idx, y);
+    f32x4 dy = {gelu_prime_t<TO>(acc[0]), gelu_prime_t<TO>(acc[1]), gelu_prime_t<TO>(acc[2]),
+                gelu_prime_t<TO>(acc[3])};
+    estore4<TO>(g_out + idx, dy);
   } else if constexpr (EPI == EPI_DGELU) {
     estore4<TO>(out_op + idx, acc * eload4<TO>(z_in + idx));
   } else if constexpr (EPI == EPI_RESID_INNER) {
@@ -112,7 +122,8 @@ __device__ __forceinline__ void store8(bf16* p, f32x4 a, f32x4 b) {
 }
 template <int EPI, int OPT = -1>
 __device__ __forceinline__ void apply8(bf16* __restrict__ out, bf16* __restrict__ z_out,
-                                       const bf16* __restrict__ z_in, long idx, f32x4 a, f32x4 b) {
+                                       const bf16* __restrict__ z_in, bf16* __restrict__ g_out, long idx,
+                                       f32x4 a, f32x4 b) {
   if constexpr (EPI == EPI_STORE) {
     store8(out + idx, a, b);
   } else if constexpr (EPI == EPI_GELU) {
@@ -125,6 +136,16 @@ __device__ __forceinline__ void apply8(bf16* __restrict__ out, bf16* __restrict_
 #pragma unroll
     for (int r = 0; r < 4; ++r) { a[r] = gelu_prime_fast(a[r]); b[r] = gelu_prime_fast(b[r]); }
     store8(out + idx, a, b);
+  } else if constexpr (EPI == EPI_GELU_BOTH) {
+    if (has_opt<OPT>(0, z_out)) store8(z_out + idx, a, b);
+    f32x4 da, db;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      da[r] = gelu_prime_fast(a[r]); db[r] = gelu_prime_fast(b[r]);
+      a[r] = gelu_fast(a[r]); b[r] = gelu_fast(b[r]);
+    }
+    store8(out + idx, a, b);
+    store8(g_out + idx, da, db);
   } else if constexpr (EPI == EPI_DGELU) {
     const bf16x8 g = ld_stream(reinterpret_cast<const bf16x8*>(z_in + idx));
 #pragma unroll
@@ -138,8 +159,8 @@ template <int EPI, typename TO>
 __device__ __forceinline__ void epilogue4(const EpiPtrs& p, float hstep, int N, int m, int n, f32x4 acc) {
   if (p.bias) acc += *reinterpret_cast<const f32x4*>(p.bias + n);
   apply4<EPI, TO>(static_cast<TO*>(p.out), static_cast<float*>(p.out), static_cast<TO*>(p.aux),
-                  static_cast<const TO*>(p.aux), p.base, p.X, static_cast<const float*>(p.aux), p.RHS, p.OUT,
-                  hstep, (long)m * N + n, acc);
+                  static_cast<const TO*>(p.aux), static_cast<TO*>(p.aux2), p.base, p.X,
+                  static_cast<const float*>(p.aux), p.RHS, p.OUT, hstep, (long)m * N + n, acc);
 }
 
 constexpr int ce_gcd(int a, int b) { return b == 0 ? a : ce_gcd(b, a % b); }
@@ -150,7 +171,7 @@ constexpr int ce_gcd(int a, int b) { return b == 0 ? a : ce_gcd(b, a % b); }
 template <int EPI, typename TO, int TM, int TN, bool STAGED>
 __device__ __forceinline__ void tile_epilogue(
     f32x16 (&acc)[TM][TN], unsigned char* ep, const float* __restrict__ bias, TO* __restrict__ out_op,
-    float* __restrict__ out_f32, TO* __restrict__ z_out, const TO* __restrict__ z_in,
+    float* __restrict__ out_f32, TO* __restrict__ z_out, const TO* __restrict__ z_in, TO* __restrict__ g_out,
     const float* __restrict__ base, const float* __restrict__ X, const float* __restrict__ ybar,
     const float* __restrict__ RHS, float* __restrict__ OUT, float hstep, int N, int M, int mrow0, int ncol0,
     int lane) {
@@ -162,7 +183,7 @@ __device__ __forceinline__ void tile_epilogue(
     // stores: four lanes fill a 64-byte sector, so the memory side never has to read a sector
     // back in order to merge a partial write), 4 where it is fp32.
     constexpr bool WIDE = sizeof(TO) == 2 && (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_DGELU ||
-                                              EPI == EPI_GELU_PRIME);
+                                              EPI == EPI_GELU_PRIME || EPI == EPI_GELU_BOTH);
     constexpr int CW = WIDE ? 8 : 4;
     constexpr int CI = WTN / CW;                         // items per row
     constexpr int NIT = 32 * CI / 64;                    // items per lane in a 32-row block
@@ -207,17 +228,18 @@ __device__ __forceinline__ void tile_epilogue(
           const f32x4 v1 = *reinterpret_cast<const f32x4*>(src + 16) + bv[it % NB][1];
           if (!GUARD || m < M)
             apply8<EPI, OPT>(reinterpret_cast<bf16*>(out_op), reinterpret_cast<bf16*>(z_out),
-                             reinterpret_cast<const bf16*>(z_in), idx, v0, v1);
+                             reinterpret_cast<const bf16*>(z_in), reinterpret_cast<bf16*>(g_out), idx, v0, v1);
         } else {
           if (!GUARD || m < M)
-            apply4<EPI, TO, OPT>(out_op, out_f32, z_out, z_in, base, X, ybar, RHS, OUT, hstep, idx, v0);
+            apply4<EPI, TO, OPT>(out_op, out_f32, z_out, z_in, g_out, base, X, ybar, RHS, OUT, hstep, idx, v0);
         }
       }
     };
     // which optional operands this launch has (uniform over the launch): resolved once, so that
     // the items carry no tests of their own
     constexpr int NOPT = EPI == EPI_RESID_OUTER ? 4
-                         : (EPI == EPI_RESID_INNER || EPI == EPI_GELU || EPI == EPI_GELU_PRIME) ? 2 : 1;
+                         : (EPI == EPI_RESID_INNER || EPI == EPI_GELU || EPI == EPI_GELU_PRIME ||
+                            EPI == EPI_GELU_BOTH) ? 2 : 1;
     const void* first = EPI == EPI_RESID_OUTER ? static_cast<const void*>(ybar)
                         : EPI == EPI_RESID_INNER ? static_cast<const void*>(base) : static_cast<const void*>(z_out);
     const int opt = NOPT == 1 ? 0 : ((first ? 1 : 0) | (NOPT == 4 && RHS ? 2 : 0));
@@ -253,7 +275,7 @@ __device__ __forceinline__ void tile_epilogue(
           for (int q = 0; q < 4; ++q) {
             const int n = ncol0 + j * 32 + q * 8 + lh * 4;
             f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-            apply4<EPI, TO>(out_op, out_f32, z_out, z_in, base, X, ybar, RHS, OUT, hstep, (long)m * N + n,
+            apply4<EPI, TO>(out_op, out_f32, z_out, z_in, g_out, base, X, ybar, RHS, OUT, hstep, (long)m * N + n,
                             v + bv[j][q]);
           }
       }
@@ -451,7 +473,7 @@ gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, in
   const EpiPtrs P = resolve_epi<TO>(a, g, EPI);
   tile_epilogue<EPI, TO, TM, TN, STAGED>(acc, smem2 + wave * EP_BYTES, P.bias, static_cast<TO*>(P.out),
                                          static_cast<float*>(P.out), static_cast<TO*>(P.aux),
-                                         static_cast<const TO*>(P.aux), P.base, P.X,
+                                         static_cast<const TO*>(P.aux), static_cast<TO*>(P.aux2), P.base, P.X,
                                          static_cast<const float*>(P.aux), P.RHS, P.OUT, a.hstep, a.N, M,
                                          m0 + wm0, n0 + wn0, lane);
 }
@@ -502,7 +524,8 @@ gemm_f32_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n) {
   }
   const EpiPtrs P = resolve_epi<float>(a, g, EPI);
   tile_epilogue<EPI, float, 1, 1, false>(acc, nullptr, P.bias, static_cast<float*>(P.out), static_cast<float*>(P.out),
-                                         static_cast<float*>(P.aux), static_cast<const float*>(P.aux), P.base, P.X,
+                                         static_cast<float*>(P.aux), static_cast<const float*>(P.aux),
+                                         static_cast<float*>(P.aux2), P.base, P.X,
                                          static_cast<const float*>(P.aux), P.RHS, P.OUT, a.hstep, a.N, M, m0 + wm0,
                                          n0 + wn0, lane);
 }
@@ -631,6 +654,7 @@ static double gemm_bytes(const GemmArgs& a, double esz) {
   double b = G * ((a.a_slot_stride ? 1.0 : 1.0 / G) * a.M * a.K * esz + (double)a.N * a.K * esz);
   if (EPI == EPI_STORE) b += G * MN * esz;
   if (EPI == EPI_GELU || EPI == EPI_GELU_PRIME) b += G * MN * esz * (a.aux ? 2 : 1);
+  if (EPI == EPI_GELU_BOTH) b += G * MN * esz * (a.aux ? 3 : 2);
   if (EPI == EPI_DGELU) b += G * MN * esz * 2;
   if (EPI == EPI_STORE_F32) b += G * MN * 4;
   if (EPI == EPI_RESID_INNER) b += G * MN * 4 * (a.base ? 2 : 1);
@@ -716,6 +740,7 @@ hipError_t launch_gemm(const GemmArgs& a, int epi, bool is_bf16, hipStream_t st)
     case EPI_DGELU: return launch_epi<EPI_DGELU>(a, is_bf16, st);
     case EPI_STORE_F32: return launch_epi<EPI_STORE_F32>(a, is_bf16, st);
     case EPI_GELU_PRIME: return launch_epi<EPI_GELU_PRIME>(a, is_bf16, st);
+    case EPI_GELU_BOTH: return a.aux2 ? launch_epi<EPI_GELU_BOTH>(a, is_bf16, st) : hipErrorInvalidValue;
   }
   return hipErrorInvalidValue;
 }

@@ -365,7 +365,11 @@ GemmArgs gemm_base(int n, int M, int N, int K, const void* A, long a_stride, Slo
 // One chunk (n <= Gc groups) of the forward layer step.  `cache`: write the linearisation
 // cache at `cslots` instead of advancing the state (stops before FFN2).
 // MEM (decoder of a stacked grid): group g's cross-attention memory is the fp32 rows MEM.at(g).
-int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, float hstep, bool cache,
+// cache: 0 = the plain step; 1 = fill the layers' entries of the linearisation cache (slots cslots)
+// and stop before the second feed-forward product (no state written); 2 = the whole step, leaving
+// those entries on the way (the step's intermediates live in the cache slots instead of the lane's
+// work buffers, and the first feed-forward product writes gelu(z) and gelu'(z) in one epilogue).
+int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, float hstep, int cache,
                   Slots cslots, Rows MEM = NO_ROWS) {
   const int T = E.T, d = E.d, f = E.f;
   const auto& L = E.lay;
@@ -446,17 +450,23 @@ int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, floa
   HIPCHK(launch_ln_fwd(ln, E.bf16, E.st));
 
   g = gemm_base(n, T, f, d, E.u, E.Td(), loc, TH, L.offset[MGRIT_P_W1], L.offset[MGRIT_P_B1]);
-  if (cache) {
+  if (cache == 1) {
     g.out = E.c_z; g.out_slot_stride = (long)T * f; g.out_slots = cs;
     g.aux = E.c_zraw; g.aux_slot_stride = (long)T * f; g.aux_slots = cs;
     HIPCHK(launch_gemm(g, EPI_GELU_PRIME, E.bf16, E.st));
     return MGRIT_OK;
   }
   g.out = E.act; g.out_slot_stride = (long)T * f; g.out_slots = loc;
-  HIPCHK(launch_gemm(g, EPI_GELU, E.bf16, E.st));
+  if (cache) {
+    g.aux2 = E.c_z; g.aux2_slot_stride = (long)T * f; g.aux2_slots = cs;
+    g.aux = E.c_zraw; g.aux_slot_stride = (long)T * f; g.aux_slots = cs;
+    HIPCHK(launch_gemm(g, EPI_GELU_BOTH, E.bf16, E.st));
+  } else {
+    HIPCHK(launch_gemm(g, EPI_GELU, E.bf16, E.st));
+  }
 
   g = gemm_base(n, T, d, f, E.act, (long)T * f, loc, TH, L.offset[MGRIT_P_W2], L.offset[MGRIT_P_B2]);
-  g.aux = xin; g.aux_slot_stride = E.Td(); g.aux_slots = loc;                   // ybar
+  g.aux = xin; g.aux_slot_stride = E.Td(); g.aux_slots = cs;                    // ybar
   g.X = IN; g.OUT = OUT; g.RHS = RHS; g.hstep = hstep;
   HIPCHK(launch_gemm(g, EPI_RESID_OUTER, E.bf16, E.st));
   return MGRIT_OK;
@@ -727,7 +737,7 @@ int run_chunks(Engine& E, Engine* E2, int G, F fn) {
   return MGRIT_OK;
 }
 
-int forward_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Params TH, float hstep, bool cache,
+int forward_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Params TH, float hstep, int cache,
                    Slots cslots, Rows MEM = NO_ROWS) {
   return run_chunks(E, E2, G, [&](Engine& L, int c0, int n) {
     return forward_chunk(L, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), hstep, cache,
@@ -754,7 +764,7 @@ int adjoint_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Pa
     gp.dE_slots = slots;
     if (L.recompute) {                    // the internals of this chunk's layers, into the lane's chunk-sized cache
       slots = Slots{0, 1};
-      STCHK(forward_chunk(L, n, shift(LIN, c0), NO_ROWS, NO_ROWS, shift(TH, c0), 0.f, true, slots,
+      STCHK(forward_chunk(L, n, shift(LIN, c0), NO_ROWS, NO_ROWS, shift(TH, c0), 0.f, 1, slots,
                           sd ? s.MEM : NO_ROWS));
     }
     return adjoint_chunk(L, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), shift(THT, c0),
@@ -776,7 +786,7 @@ int gradient_groups(Engine& E, Engine* E2, int G, Rows IN, Params TH, Params THT
     gp.dE_slots = slots;
     if (L.recompute) {
       slots = Slots{0, 1};
-      STCHK(forward_chunk(L, n, shift(LIN, c0), NO_ROWS, NO_ROWS, shift(TH, c0), 0.f, true, slots,
+      STCHK(forward_chunk(L, n, shift(LIN, c0), NO_ROWS, NO_ROWS, shift(TH, c0), 0.f, 1, slots,
                           sd ? s.MEM : NO_ROWS));
     }
     return adjoint_chunk(L, n, shift(IN, c0), NO_ROWS, NO_ROWS, shift(TH, c0), shift(THT, c0), shift(LIN, c0),
@@ -864,10 +874,10 @@ struct Driver {
       Params TH = {(const void* const*)tabTh, nl, ns};
       if (!adjoint) {
         if (enc) {
-          STCHK(forward_groups(Le, Le2, n, inx, outx, rhsx, TH, hstep, false, Slots{0, 0}));
+          STCHK(forward_groups(Le, Le2, n, inx, outx, rhsx, TH, hstep, 0, Slots{0, 0}));
           HIPCHK(launch_add_rows(n, y_elems, iny, rhsy, outy, Le.st));
         } else {
-          STCHK(forward_groups(Ld, Ld2, n, iny, outy, rhsy, TH, hstep, false, Slots{0, 0}, inx));
+          STCHK(forward_groups(Ld, Ld2, n, iny, outy, rhsy, TH, hstep, 0, Slots{0, 0}, inx));
           HIPCHK(launch_add_rows(n, x_elems, inx, rhsx, outx, Le.st));
         }
         continue;
@@ -897,6 +907,11 @@ struct Driver {
   void** tabDT = nullptr;          // layer n -> gradient block, or null
   float* dE_all = nullptr;         // per-layer memory-gradient terms, or null
   bool want_grads = false, last_cycle = false, emit_now = false, emitted = false;
+  // Forward solve on behalf of an adjoint that follows: the level-0 steps of the last cycle's closing
+  // F-relaxation (of every step in a serial run) read final states, so they leave their layers'
+  // entries of the adjoint's linearisation cache on the way (the engines' cache pointers then point
+  // into the adjoint's workspace).  The layers n = cf-1, 2cf-1, .. are left to the adjoint.
+  bool fill_cache = false, cache_now = false;
 
   // cnt steps of level `lvl`, group k starting at point j = j0 + k*js
   int step(int lvl, int j0, int js, int cnt, Rows OUT, Rows RHS) {
@@ -918,7 +933,8 @@ struct Driver {
     }
     if (!adjoint) {
       Params TH = {(const void* const*)tabTh, j0 * s, js * s};
-      return forward_groups(L1, L2, cnt, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
+      if (cache_now && lvl == 0) return forward_groups(L1, L2, cnt, IN, OUT, RHS, TH, hstep, 2, Slots{j0, js});
+      return forward_groups(L1, L2, cnt, IN, OUT, RHS, TH, hstep, 0, Slots{0, 0});
     }
     const int n0 = N - (j0 + 1) * s, ns = -js * s;       // layer the coarse step lands on
     Params TH = {(const void* const*)tabTh, n0, ns};
@@ -949,7 +965,7 @@ struct Driver {
     const int status = coarse_solve_pipeline(lvl, M, R, Gn);
     // join the helper lane whatever happened (see run_chunks)
     only = nullptr;
-    emit_now = false;
+    emit_now = cache_now = false;
     const hipError_t e1 = hipEventRecord(a.join, E2->st);
     const hipError_t e2 = e1 == hipSuccess ? hipStreamWaitEvent(E->st, a.join, 0) : e1;
     STCHK(status);
@@ -987,11 +1003,12 @@ struct Driver {
     auto relax = [&](Engine* lane, int ka, int kb) -> int {   // F-relaxation of intervals ka .. kb-1 on one lane
       only = lane;
       emit_now = want_grads && last_cycle && lvl == 0;
+      cache_now = fill_cache && last_cycle && lvl == 0;
       int st = MGRIT_OK;
       for (int i = 0; i + 1 < cf && st == MGRIT_OK; ++i)
         st = step(lvl, ka * cf + i, cf, kb - ka, W(lvl, ka * cf + i + 1, cf), Gr(lvl, ka * cf + i + 1, cf));
       only = nullptr;
-      emit_now = false;
+      emit_now = cache_now = false;
       return st;
     };
     int k0 = 0, ev = 0;
@@ -1053,17 +1070,19 @@ struct Driver {
     if (E) HIPCHK(launch_sub_rows(M, state_elems(), R, Gn, Gn, E->st));
     STCHK(vcycle(lvl + 1, iter, false));
     emit_now = want_grads && last_cycle && lvl == 0;
+    cache_now = fill_cache && last_cycle && lvl == 0;
     const int st = f_relax(lvl, M);
-    emit_now = false;
+    emit_now = cache_now = false;
     return st;
   }
 
   int run(int iters) {
     if (L == 1 || cf == 1) {
       emit_now = want_grads;
+      cache_now = fill_cache;
       int st = MGRIT_OK;
       for (int n = 0; n < N && st == MGRIT_OK; ++n) st = step(0, n, 1, 1, W(0, n + 1, 1), NO_ROWS);
-      emit_now = false;
+      emit_now = cache_now = false;
       return st;
     }
     for (int it = 0; it < iters; ++it) {
@@ -1086,7 +1105,11 @@ struct Plan {                       // workspace of mgrit_forward / mgrit_adjoin
 };
 
 // mode: 0 forward, 1 adjoint, 2 adjoint followed by the parameter-gradient pass
-int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, int mode, void* ws, hipStream_t st) {
+// share_ws, share_mode: a forward plan whose closing relaxation fills the linearisation cache of the
+// adjoint plan (mode 1 or 2) that will be laid out in share_ws: the cache is the first thing an adjoint
+// plan carves, so carving it again from the same base gives the same addresses.
+int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, int mode, void* ws, hipStream_t st,
+              void* share_ws = nullptr, int share_mode = 0) {
   const bool adjoint = mode != 0;
   Bump b(ws);
   Engine& E = P.E;
@@ -1100,6 +1123,12 @@ int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, int mod
   E.keep_z = mode == 2;
   E.recompute = adjoint && !g_adjoint_cache;
   if (adjoint) E.carve_adjoint(b, gc, N); else E.carve_forward(b, gc);
+  if (!adjoint && share_ws) {
+    Bump shared(share_ws);
+    E.keep_z = share_mode == 2;
+    E.carve_cache(shared, N);
+    P.D.fill_cache = true;
+  }
   P.two_lanes = widest >= 2 && make_lane(P.E2, E, b, adjoint, ws == nullptr);
   Driver& D = P.D;
   D.E = &E; D.E2 = P.two_lanes ? &P.E2 : nullptr; D.adjoint = adjoint; D.N = N; D.cf = op->cf; D.L = serial ? 1 : op->levels; D.relax = op->relax;
@@ -1222,7 +1251,7 @@ int layer_step_on(const mgrit_model_desc* desc, int adjoint, int n_groups, const
     STCHK(transpose_blocks(E, G, TH, THT));
     if (desc->arch == MGRIT_ARCH_CROSS)
       HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
-    STCHK(forward_groups(E, L2, G, LIN, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
+    STCHK(forward_groups(E, L2, G, LIN, NO_ROWS, NO_ROWS, TH, 0.f, 1, Slots{0, 1}));
     return adjoint_groups(E, L2, G, IN, OUT, RHS, TH, THT, LIN, Slots{0, 1}, hstep);
   }
   E.carve_forward(b, gc);
@@ -1238,7 +1267,7 @@ int layer_step_on(const mgrit_model_desc* desc, int adjoint, int n_groups, const
   Params TH = {(const void* const*)tTh, 0, 1};
   Rows IN = {(const void* const*)tIn, 0, 1}, OUT = {(const void* const*)tOut, 0, 1};
   Rows RHS = rhs ? Rows{(const void* const*)tRhs, 0, 1} : NO_ROWS;
-  return forward_groups(E, L2, G, IN, OUT, RHS, TH, hstep, false, Slots{0, 0});
+  return forward_groups(E, L2, G, IN, OUT, RHS, TH, hstep, 0, Slots{0, 0});
 }
 
 }  // namespace
@@ -1313,9 +1342,13 @@ int64_t mgrit_step_depth(const mgrit_opts* opts) {
   return D.sweeps;
 }
 
-int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z0,
-                  const void* const* theta, const void* memory, void* Z_all, float* resnorm, void* workspace,
-                  size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+// share_ws != null: the forward solve also fills the linearisation cache of the adjoint workspace share_ws
+int forward_impl(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z0,
+                 const void* const* theta, const void* memory, void* Z_all, float* resnorm, void* workspace,
+                 size_t workspace_bytes, void* share_ws, size_t share_bytes, int share_mode, void* stream) {
   std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
   STCHK(validate_desc(desc));
   STCHK(validate_opts(opts));
@@ -1325,10 +1358,16 @@ int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
   const size_t need = mgrit_workspace_bytes(desc, opts, 0);
   if (need == 0) return MGRIT_INVALID_ARG;
   if (workspace_bytes < need) return MGRIT_WORKSPACE_TOO_SMALL;
+  if (share_ws) {
+    if (!g_adjoint_cache) return MGRIT_INVALID_ARG;       // there is no N-layer cache to fill
+    const size_t need_adj = mgrit_workspace_bytes(desc, opts, share_mode);
+    if (need_adj == 0) return MGRIT_INVALID_ARG;
+    if (share_bytes < need_adj) return MGRIT_WORKSPACE_TOO_SMALL;
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   Plan P;
-  STCHK(make_plan(P, desc, opts, 0, workspace, st));
+  STCHK(make_plan(P, desc, opts, 0, workspace, st, share_ws, share_mode));
   Engine& E = P.E;
   Driver& D = P.D;
   const int N = opts->N;
@@ -1348,11 +1387,13 @@ int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
   return D.run(opts->iters);
 }
 
-int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z_all,
-                  const void* const* theta, const void* memory, const void* lambda_N, void* lambda_all,
-                  void* dmemory, void* const* dtheta, float* resnorm, void* workspace, size_t workspace_bytes,
-                  void* stream) {
+// prefilled: the cache already holds the entries that a forward solve with share_ws = workspace leaves
+int adjoint_impl(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z_all,
+                 const void* const* theta, const void* memory, const void* lambda_N, void* lambda_all,
+                 void* dmemory, void* const* dtheta, float* resnorm, void* workspace, size_t workspace_bytes,
+                 bool prefilled, void* stream) {
   std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
+  if (prefilled && !g_adjoint_cache) return MGRIT_INVALID_ARG;
   STCHK(validate_desc(desc));
   STCHK(validate_opts(opts));
   if (dmemory && desc->arch != MGRIT_ARCH_CROSS) return MGRIT_INVALID_ARG;
@@ -1384,7 +1425,16 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
     HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
   // linearisation cache for all N layers, batched over layers (unless every chunk recomputes its own)
   Rows Zrows = {(const void* const*)D.tabZ, 0, 1};
-  if (!E.recompute) STCHK(forward_groups(E, D.E2, N, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
+  if (prefilled) {
+    // the forward solve's closing relaxation has left every layer it stepped through: all of them in a
+    // serial run, otherwise all but the last layer of each interval (n = cf-1, 2cf-1, ..)
+    const int cf = opts->cf;
+    if (!serial_run(opts))
+      STCHK(forward_groups(E, D.E2, N / cf, Rows{(const void* const*)D.tabZ, cf - 1, cf}, NO_ROWS, NO_ROWS,
+                           Params{(const void* const*)D.tabTh, cf - 1, cf}, 0.f, 1, Slots{cf - 1, cf}));
+  } else if (!E.recompute) {
+    STCHK(forward_groups(E, D.E2, N, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, 1, Slots{0, 1}));
+  }
   // initial values
   if (lambda_N != static_cast<char*>(lambda_all) + (size_t)N * state)     // may be row N of lambda_all itself
     HIPCHK(hipMemcpyAsync(static_cast<char*>(lambda_all) + (size_t)N * state, lambda_N, state,
@@ -1420,6 +1470,41 @@ int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const vo
       HIPCHK(launch_sum_slots(P.dE_all, N, (long)E.Tm * E.d, static_cast<float*>(dmemory), 1.0f, st));
   }
   return MGRIT_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int mgrit_forward(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z0,
+                  const void* const* theta, const void* memory, void* Z_all, float* resnorm, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+  return forward_impl(desc, opts, Z0, theta, memory, Z_all, resnorm, workspace, workspace_bytes, nullptr, 0, 0,
+                      stream);
+}
+
+int mgrit_forward_linearising(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z0,
+                              const void* const* theta, const void* memory, void* Z_all, float* resnorm,
+                              void* workspace, size_t workspace_bytes, void* adjoint_workspace,
+                              size_t adjoint_workspace_bytes, int with_gradients, void* stream) {
+  if (!adjoint_workspace) return MGRIT_INVALID_ARG;
+  return forward_impl(desc, opts, Z0, theta, memory, Z_all, resnorm, workspace, workspace_bytes, adjoint_workspace,
+                      adjoint_workspace_bytes, with_gradients ? 2 : 1, stream);
+}
+
+int mgrit_adjoint(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z_all,
+                  const void* const* theta, const void* memory, const void* lambda_N, void* lambda_all,
+                  void* dmemory, void* const* dtheta, float* resnorm, void* workspace, size_t workspace_bytes,
+                  void* stream) {
+  return adjoint_impl(desc, opts, Z_all, theta, memory, lambda_N, lambda_all, dmemory, dtheta, resnorm, workspace,
+                      workspace_bytes, false, stream);
+}
+
+int mgrit_adjoint_linearised(const mgrit_model_desc* desc, const mgrit_opts* opts, const void* Z_all,
+                             const void* const* theta, const void* memory, const void* lambda_N,
+                             void* lambda_all, void* dmemory, void* const* dtheta, float* resnorm,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  return adjoint_impl(desc, opts, Z_all, theta, memory, lambda_N, lambda_all, dmemory, dtheta, resnorm, workspace,
+                      workspace_bytes, true, stream);
 }
 
 // ---- stacked encoder-decoder grid (paper section 3.1, eq. "fp_transformer") --------------------
@@ -1593,8 +1678,8 @@ int mgrit_adjoint_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, 
   const Rows Zrows = {(const void* const*)D.tabZ, 0, 1};
   const Rows ZdecX = shift(Zrows, n_enc), ZdecY = Driver::part(ZdecX, D.x_elems);
   if (!P.Ee.recompute) {
-    STCHK(forward_groups(P.Ee, D.E2, n_enc, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, true, Slots{0, 1}));
-    STCHK(forward_groups(P.Ed, D.Ed2, n_dec, ZdecY, NO_ROWS, NO_ROWS, shift(TH, n_enc), 0.f, true, Slots{0, 1}, ZdecX));
+    STCHK(forward_groups(P.Ee, D.E2, n_enc, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, 1, Slots{0, 1}));
+    STCHK(forward_groups(P.Ed, D.Ed2, n_dec, ZdecY, NO_ROWS, NO_ROWS, shift(TH, n_enc), 0.f, 1, Slots{0, 1}, ZdecX));
   }
   char* lamN_row = static_cast<char*>(lambda_all) + (size_t)N * state;
   if (lambda_N != lamN_row) HIPCHK(hipMemcpyAsync(lamN_row, lambda_N, state, hipMemcpyDeviceToDevice, st));

@@ -210,6 +210,14 @@ def test_full_gpt2_small_forward_and_adjoint_against_the_stored_oracle_sequence(
     assert torch.equal(Zg[0].cpu(), torch.from_numpy(Z0))
     assert torch.equal(lg[wl.N].cpu(), torch.from_numpy(lamN))
     einc = check_against_stored_sequence(wl, g, Zg, lg, tol)
+    # the pair of calls that bench.py times (the forward solve leaves three quarters of the adjoint's
+    # linearisation cache): the same results, bit for bit, at this size too
+    ws = torch.empty(mb.mgrit_workspace_bytes(dm.desc, opts, 1), dtype=torch.uint8, device="cuda")
+    Z2, r2 = mb.mgrit_forward(dm.desc, opts, dev(Z0), dm.blocks, adjoint_workspace=ws)
+    l2, a2 = mb.mgrit_adjoint(dm.desc, opts, Z2, dm.blocks, dev(lamN), workspace=ws, linearised=True)
+    torch.cuda.synchronize()
+    assert torch.equal(Z2, Zg) and torch.equal(r2, rg) and torch.equal(l2, lg) and torch.equal(a2, ag)
+    del Z2, l2, ws
     gold = golden("gpt2_small")
     check_norms("forward", rg.cpu().numpy(), gold["forward"], tol, gold["increment_norm"], einc["Z"])
     inc = float(torch.linalg.vector_norm((lg[0] - lg[wl.N]).double()))
