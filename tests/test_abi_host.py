@@ -114,6 +114,12 @@ def test_invalid_arguments_are_rejected_without_a_device():
     # null pointers
     st = L.mgrit_forward(C.byref(desc), C.byref(ok), None, None, None, None, None, None, 0, None)
     assert st == -1
+    # the linearising pair: no adjoint workspace, null pointers
+    st = L.mgrit_forward_linearising(C.byref(desc), C.byref(ok), None, None, None, None, None, None, 0, None, 0, 0, None)
+    assert st == -1
+    st = L.mgrit_adjoint_linearised(C.byref(desc), C.byref(ok), None, None, None, None, None, None, None, None, None,
+                                    0, None)
+    assert st == -1
     bad = mb.ModelDesc(0, 65, 4, 256, 2, 32, 0, 0, 1e-5)        # d_model % n_heads != 0
     lay = mb.ThetaLayout()
     assert L.mgrit_theta_layout(C.byref(bad), C.byref(lay)) == -1
