@@ -122,6 +122,14 @@ def run_full(name, fwd_seqs, adj_seqs, memory=None, memory_host=None, prefix=Non
         # scale of the noise: the adjoint's own total increment
         inc = float(torch.linalg.vector_norm((lg[0] - lg[wl.N]).double()))
         check_norms("adjoint", ag_host, gold["adjoint"], tol, inc, einc)
+        # the pair of calls that bench.py times (the forward solve leaves most of the adjoint's
+        # linearisation cache): the same results, bit for bit, at this size too
+        ws = torch.empty(mb.mgrit_workspace_bytes(desc, opts, 1), dtype=torch.uint8, device="cuda")
+        Z2, r2 = mb.mgrit_forward(desc, opts, dev(Z0), dm.blocks, memory=memory, adjoint_workspace=ws)
+        l2, a2 = mb.mgrit_adjoint(desc, opts, Z2, dm.blocks, dev(lamN), memory=memory, workspace=ws, linearised=True)
+        torch.cuda.synchronize()
+        assert torch.equal(Z2, Zg) and torch.equal(r2, rg) and torch.equal(l2, lg) and torch.equal(a2, ag)
+        del Z2, l2, ws
     return Zg, lg
 
 
