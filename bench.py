@@ -200,21 +200,23 @@ def main():
                        mb.mgrit_workspace_bytes(desc, opts, 2 if grads else 1) if adjoint else 0, 256)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     # the linearising pair: the forward solve writes into the adjoint's workspace, so it needs one of its own
-    shared = adjoint and not sw and not args.plain_pair and not args.no_adjoint_cache
+    shared = adjoint and not args.plain_pair and not args.no_adjoint_cache
     ws_fwd = ws
     if shared:
-        ws_fwd = torch.empty(max(mb.mgrit_workspace_bytes(desc, opts, 0), 256), dtype=torch.uint8, device="cuda")
+        fwd_bytes = mb.mgrit_stacked_workspace_bytes(desc, opts, sw.n_enc, 0) if sw else mb.mgrit_workspace_bytes(desc, opts, 0)
+        ws_fwd = torch.empty(max(fwd_bytes, 256), dtype=torch.uint8, device="cuda")
         ws_bytes += ws_fwd.numel()
     n_phi = mb.mgrit_step_evaluations(opts)
     n_psi = n_phi if adjoint else 0
     stream = torch.cuda.current_stream()
 
     def step_stacked(stream):
-        mb.mgrit_forward_stacked(desc, opts, sw.n_enc, Z0, theta, Z_all=Z_all, resnorm=res_f, workspace=ws,
-                                 stream=stream)
+        mb.mgrit_forward_stacked(desc, opts, sw.n_enc, Z0, theta, Z_all=Z_all, resnorm=res_f, workspace=ws_fwd,
+                                 stream=stream, adjoint_workspace=ws if shared else None,
+                                 with_gradients=bool(grads))
         if adjoint:
             mb.mgrit_adjoint_stacked(desc, opts, sw.n_enc, Z_all, theta, lamN, dtheta=grads, lambda_all=lam_all,
-                                     resnorm=res_a, workspace=ws, stream=stream)
+                                     resnorm=res_a, workspace=ws, stream=stream, linearised=shared)
 
     def step(stream=stream):
         if sw:

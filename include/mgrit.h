@@ -261,6 +261,21 @@ int mgrit_adjoint_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, 
                           const void* lambda_N, void* lambda_all,
                           void* const* dtheta, float* resnorm,
                           void* workspace, size_t workspace_bytes, void* stream);
+/* The stacked pair for a training step, as mgrit_forward_linearising / mgrit_adjoint_linearised (same
+ * contract between the two calls): the closing relaxation of the forward solve leaves the internals of
+ * the encoder and decoder layers it steps through in the caches of `adjoint_workspace`
+ * (mgrit_stacked_workspace_bytes(desc, opts, n_enc, with_gradients ? 2 : 1)). */
+int mgrit_forward_stacked_linearising(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc,
+                                      const void* Z0, const void* const* theta,
+                                      void* Z_all, float* resnorm,
+                                      void* workspace, size_t workspace_bytes,
+                                      void* adjoint_workspace, size_t adjoint_workspace_bytes, int with_gradients,
+                                      void* stream);
+int mgrit_adjoint_stacked_linearised(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc,
+                                     const void* Z_all, const void* const* theta,
+                                     const void* lambda_N, void* lambda_all,
+                                     void* const* dtheta, float* resnorm,
+                                     void* workspace, size_t workspace_bytes, void* stream);
 
 /* One batched layer step over n_groups independent (state, layer) pairs -- the
  * launch that F-/C-relaxation of Algorithm 1 is made of.

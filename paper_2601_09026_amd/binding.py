@@ -124,6 +124,11 @@ def lib() -> C.CDLL:
         L.mgrit_adjoint_stacked.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.c_int, vp, vpp, vp, vp, vpp, vp,
                                             vp, C.c_size_t, vp]
         L.mgrit_adjoint_stacked.restype = C.c_int
+        L.mgrit_forward_stacked_linearising.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.c_int, vp, vpp, vp,
+                                                        vp, vp, C.c_size_t, vp, C.c_size_t, C.c_int, vp]
+        L.mgrit_forward_stacked_linearising.restype = C.c_int
+        L.mgrit_adjoint_stacked_linearised.argtypes = L.mgrit_adjoint_stacked.argtypes
+        L.mgrit_adjoint_stacked_linearised.restype = C.c_int
         L.mgrit_indicator_init.argtypes = [C.POINTER(Indicator), C.c_int, C.c_int, C.c_int, C.c_int, C.c_float]
         L.mgrit_indicator_init.restype = C.c_int
         L.mgrit_indicator_begin_batch.argtypes = [C.POINTER(Indicator)]
@@ -534,9 +539,11 @@ def mgrit_stacked_workspace_bytes(desc: ModelDesc, opts: Opts, n_enc: int, adjoi
 
 def mgrit_forward_stacked(desc: ModelDesc, opts: Opts, n_enc: int, Z0: torch.Tensor, theta: List[torch.Tensor],
                           Z_all: Optional[torch.Tensor] = None, resnorm: Optional[torch.Tensor] = None,
-                          workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+                          workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
+                          adjoint_workspace: Optional[torch.Tensor] = None, with_gradients: bool = False):
     """One MGRIT grid over n_enc encoder layers followed by decoder layers; state rows = encoder
-    tokens then decoder tokens.  Returns (Z_all, resnorm).  Buffers are allocated here if not given."""
+    tokens then decoder tokens.  Returns (Z_all, resnorm).  Buffers are allocated here if not given.
+    adjoint_workspace: mgrit_forward_stacked_linearising (see mgrit_forward)."""
     T, d = desc.batch * (desc.mem_seq + desc.seq), desc.d_model
     _check_state(Z0, (T, d), "Z0")
     if len(theta) != opts.N:
@@ -549,6 +556,15 @@ def mgrit_forward_stacked(desc: ModelDesc, opts: Opts, n_enc: int, Z0: torch.Ten
     if workspace is None:
         workspace = torch.empty(max(mgrit_stacked_workspace_bytes(desc, opts, n_enc, 0), 256), dtype=torch.uint8,
                                 device=Z0.device)
+    if adjoint_workspace is not None:
+        st = lib().mgrit_forward_stacked_linearising(C.byref(desc), C.byref(opts), int(n_enc), _ptr(Z0),
+                                                     _ptr_array(theta), _ptr(Z_all), _ptr(resnorm), _ptr(workspace),
+                                                     workspace.numel(), _ptr(adjoint_workspace),
+                                                     adjoint_workspace.numel(), int(bool(with_gradients)),
+                                                     _stream_handle(stream))
+        if st != MGRIT_OK:
+            raise MgritError(st, "mgrit_forward_stacked_linearising")
+        return Z_all, resnorm
     st = lib().mgrit_forward_stacked(C.byref(desc), C.byref(opts), int(n_enc), _ptr(Z0), _ptr_array(theta),
                                      _ptr(Z_all), _ptr(resnorm), _ptr(workspace), workspace.numel(),
                                      _stream_handle(stream))
@@ -560,9 +576,11 @@ def mgrit_forward_stacked(desc: ModelDesc, opts: Opts, n_enc: int, Z0: torch.Ten
 def mgrit_adjoint_stacked(desc: ModelDesc, opts: Opts, n_enc: int, Z_all: torch.Tensor, theta: List[torch.Tensor],
                           lambda_N: torch.Tensor, dtheta: Optional[List[torch.Tensor]] = None,
                           lambda_all: Optional[torch.Tensor] = None, resnorm: Optional[torch.Tensor] = None,
-                          workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+                          workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
+                          linearised: bool = False):
     """Returns (lambda_all, resnorm) of the stacked grid; dtheta as in mgrit_adjoint (encoder
-    layers' blocks in the encoder's fp32 layout, decoder layers' in the decoder's)."""
+    layers' blocks in the encoder's fp32 layout, decoder layers' in the decoder's).
+    linearised: mgrit_adjoint_stacked_linearised on the workspace the forward call filled."""
     T, d = desc.batch * (desc.mem_seq + desc.seq), desc.d_model
     _check_state(Z_all, (opts.N + 1, T, d), "Z_all")
     _check_state(lambda_N, (T, d), "lambda_N")
@@ -576,9 +594,10 @@ def mgrit_adjoint_stacked(desc: ModelDesc, opts: Opts, n_enc: int, Z_all: torch.
     if workspace is None:
         need = mgrit_stacked_workspace_bytes(desc, opts, n_enc, 2 if dtheta is not None else 1)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Z_all.device)
-    st = lib().mgrit_adjoint_stacked(C.byref(desc), C.byref(opts), int(n_enc), _ptr(Z_all), _ptr_array(theta),
-                                     _ptr(lambda_N), _ptr(lambda_all), _ptr_array(dtheta), _ptr(resnorm),
-                                     _ptr(workspace), workspace.numel(), _stream_handle(stream))
+    entry = lib().mgrit_adjoint_stacked_linearised if linearised else lib().mgrit_adjoint_stacked
+    st = entry(C.byref(desc), C.byref(opts), int(n_enc), _ptr(Z_all), _ptr_array(theta),
+               _ptr(lambda_N), _ptr(lambda_all), _ptr_array(dtheta), _ptr(resnorm),
+               _ptr(workspace), workspace.numel(), _stream_handle(stream))
     if st != MGRIT_OK:
-        raise MgritError(st, "mgrit_adjoint_stacked")
+        raise MgritError(st, "mgrit_adjoint_stacked_linearised" if linearised else "mgrit_adjoint_stacked")
     return lambda_all, resnorm

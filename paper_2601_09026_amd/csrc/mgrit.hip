@@ -260,6 +260,13 @@ struct Engine {
       c_x3 = b.take<float>(C * T * d);
     }
   }
+  // the cache pointers of an engine laid out elsewhere (a forward plan that fills an adjoint plan's cache)
+  void take_cache_from(const Engine& o) {
+    n_cache = o.n_cache; keep_z = o.keep_z;
+    c_qkv = o.c_qkv; c_o = o.c_o; c_z = o.c_z; c_zraw = o.c_zraw; c_lse = o.c_lse; c_xin = o.c_xin;
+    c_xh1 = o.c_xh1; c_xh2 = o.c_xh2; c_rs1 = o.c_rs1; c_rs2 = o.c_rs2;
+    c_qc = o.c_qc; c_kvc = o.c_kvc; c_oc = o.c_oc; c_lsec = o.c_lsec; c_x3 = o.c_x3;
+  }
   void carve_adjoint(Bump& b, int gc, int ncache) {
     carve_cache(b, recompute ? gc : ncache);
     memb = md.arch == MGRIT_ARCH_CROSS ? b.take_bytes((size_t)Tm * d * esz) : nullptr;
@@ -843,7 +850,7 @@ struct Driver {
   // encoder step advances the X rows and copies the Y rows (+ right-hand side), a decoder step
   // the other way round, reading the X rows of its input (forward) or of its linearisation
   // state (adjoint) as cross-attention memory.
-  int step_stacked(int cnt, int n0, int ns, Rows IN, Rows OUT, Rows RHS, float hstep) {
+  int step_stacked(int cnt, int n0, int ns, Rows IN, Rows OUT, Rows RHS, float hstep, bool fill = false) {
     // groups k = 0..cnt-1 act on layer n0 + k*ns
     int n_first = 0;                                 // groups of the first run
     const bool first_is_enc = adjoint ? false : true;
@@ -873,11 +880,13 @@ struct Driver {
       const Rows iny = part(in, x_elems), outy = part(out, x_elems), rhsy = part(rhs, x_elems);
       Params TH = {(const void* const*)tabTh, nl, ns};
       if (!adjoint) {
+        // fill: these level-0 steps read final states and leave their layers' cache entries (see fill_cache)
         if (enc) {
-          STCHK(forward_groups(Le, Le2, n, inx, outx, rhsx, TH, hstep, 0, Slots{0, 0}));
+          STCHK(forward_groups(Le, Le2, n, inx, outx, rhsx, TH, hstep, fill ? 2 : 0, fill ? Slots{nl, ns} : Slots{0, 0}));
           HIPCHK(launch_add_rows(n, y_elems, iny, rhsy, outy, Le.st));
         } else {
-          STCHK(forward_groups(Ld, Ld2, n, iny, outy, rhsy, TH, hstep, 0, Slots{0, 0}, inx));
+          STCHK(forward_groups(Ld, Ld2, n, iny, outy, rhsy, TH, hstep, fill ? 2 : 0,
+                               fill ? Slots{nl - n_enc, ns} : Slots{0, 0}, inx));
           HIPCHK(launch_add_rows(n, x_elems, inx, rhsx, outx, Le.st));
         }
         continue;
@@ -924,7 +933,7 @@ struct Driver {
     const float hstep = (float)((double)s * (double)h);
     Rows IN = {(const void* const*)tabW, j0 * s, js * s};
     if (Ed) {
-      if (!adjoint) return step_stacked(cnt, j0 * s, js * s, IN, OUT, RHS, hstep);
+      if (!adjoint) return step_stacked(cnt, j0 * s, js * s, IN, OUT, RHS, hstep, cache_now && lvl == 0);
       const bool keep = emit_now;
       emit_now = keep && lvl == 0;
       const int st = step_stacked(cnt, N - (j0 + 1) * s, -js * s, IN, OUT, RHS, hstep);
@@ -1538,8 +1547,9 @@ int validate_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n
 }
 
 // mode: 0 forward, 1 adjoint, 2 adjoint followed by the parameter-gradient pass
+// share_ws, share_mode: as in make_plan (a forward plan that fills the caches of the adjoint plan in share_ws)
 int make_stacked_plan(StackedPlan& P, const mgrit_model_desc* md, const mgrit_opts* op, int n_enc, int mode,
-                      void* ws, hipStream_t st) {
+                      void* ws, hipStream_t st, void* share_ws = nullptr, int share_mode = 0) {
   const bool adjoint = mode != 0;
   Bump b(ws);
   const mgrit_model_desc me = encoder_of(md);
@@ -1558,6 +1568,22 @@ int make_stacked_plan(StackedPlan& P, const mgrit_model_desc* md, const mgrit_op
   P.Ee.recompute = P.Ed.recompute = adjoint && !g_adjoint_cache;
   if (adjoint) { P.Ee.carve_adjoint(b, gc, n_enc); P.Ed.carve_adjoint(b, gc, n_dec); }
   else { P.Ee.carve_forward(b, gc); P.Ed.carve_forward(b, gc); }
+  if (!adjoint && share_ws) {
+    // the adjoint plan's first carvings repeated on copies of the engines, in its order and with its chunk
+    // size (the encoder's cache, memory copy and work buffers come before the decoder's cache)
+    Bump shared(share_ws);
+    const int widest_a = N > M0 ? N : M0;
+    int gca = max_groups(md, M0);
+    if (gca > widest_a) gca = widest_a;
+    Engine te = P.Ee, td = P.Ed;
+    te.keep_z = td.keep_z = share_mode == 2;
+    te.recompute = td.recompute = false;
+    te.carve_adjoint(shared, gca, n_enc);
+    td.carve_adjoint(shared, gca, n_dec);
+    P.Ee.take_cache_from(te);
+    P.Ed.take_cache_from(td);
+    P.D.fill_cache = true;
+  }
   P.two_lanes = widest >= 2 && make_lane(P.Ee2, P.Ee, b, adjoint, ws == nullptr);
   if (P.two_lanes && !make_lane(P.Ed2, P.Ed, b, adjoint, ws == nullptr)) return MGRIT_HIP_ERROR;
   Driver& D = P.D;
@@ -1615,9 +1641,12 @@ size_t mgrit_stacked_workspace_bytes(const mgrit_model_desc* desc, const mgrit_o
   return P.bytes;
 }
 
-int mgrit_forward_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, const void* Z0,
-                          const void* const* theta, void* Z_all, float* resnorm, void* workspace,
-                          size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+int forward_stacked_impl(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, const void* Z0,
+                         const void* const* theta, void* Z_all, float* resnorm, void* workspace,
+                         size_t workspace_bytes, void* share_ws, size_t share_bytes, int share_mode, void* stream) {
   std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
   STCHK(validate_stacked(desc, opts, n_enc));
   if (!Z0 || !Z_all || !workspace) return MGRIT_INVALID_ARG;
@@ -1625,10 +1654,16 @@ int mgrit_forward_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, 
   const size_t need = mgrit_stacked_workspace_bytes(desc, opts, n_enc, 0);
   if (need == 0) return MGRIT_INVALID_ARG;
   if (workspace_bytes < need) return MGRIT_WORKSPACE_TOO_SMALL;
+  if (share_ws) {
+    if (!g_adjoint_cache) return MGRIT_INVALID_ARG;
+    const size_t need_adj = mgrit_stacked_workspace_bytes(desc, opts, n_enc, share_mode);
+    if (need_adj == 0) return MGRIT_INVALID_ARG;
+    if (share_bytes < need_adj) return MGRIT_WORKSPACE_TOO_SMALL;
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   StackedPlan P;
-  STCHK(make_stacked_plan(P, desc, opts, n_enc, 0, workspace, st));
+  STCHK(make_stacked_plan(P, desc, opts, n_enc, 0, workspace, st, share_ws, share_mode));
   Driver& D = P.D;
   const int N = opts->N;
   const size_t state = (size_t)D.state_elems() * sizeof(float);
@@ -1644,10 +1679,11 @@ int mgrit_forward_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, 
   return D.run(opts->iters);
 }
 
-int mgrit_adjoint_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, const void* Z_all,
-                          const void* const* theta, const void* lambda_N, void* lambda_all, void* const* dtheta,
-                          float* resnorm, void* workspace, size_t workspace_bytes, void* stream) {
+int adjoint_stacked_impl(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, const void* Z_all,
+                         const void* const* theta, const void* lambda_N, void* lambda_all, void* const* dtheta,
+                         float* resnorm, void* workspace, size_t workspace_bytes, bool prefilled, void* stream) {
   std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
+  if (prefilled && !g_adjoint_cache) return MGRIT_INVALID_ARG;
   STCHK(validate_stacked(desc, opts, n_enc));
   if (!Z_all || !lambda_N || !lambda_all || !workspace) return MGRIT_INVALID_ARG;
   STCHK(check_ptr_array(theta, opts->N));
@@ -1677,7 +1713,22 @@ int mgrit_adjoint_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, 
   // the Y rows with the X rows of the same state as memory
   const Rows Zrows = {(const void* const*)D.tabZ, 0, 1};
   const Rows ZdecX = shift(Zrows, n_enc), ZdecY = Driver::part(ZdecX, D.x_elems);
-  if (!P.Ee.recompute) {
+  if (prefilled) {
+    // the forward solve has left every layer but the last of each interval (n = cf-1, 2cf-1, ..): the
+    // encoder layers among those, then the decoder layers
+    const int cf = opts->cf, left = serial_run(opts) ? 0 : N / cf;
+    int left_e = n_enc >= cf ? (n_enc - cf) / cf + 1 : 0;           // layers cf-1 + k cf below n_enc
+    if (left_e > left) left_e = left;
+    if (left_e > 0)
+      STCHK(forward_groups(P.Ee, D.E2, left_e, Rows{(const void* const*)D.tabZ, cf - 1, cf}, NO_ROWS, NO_ROWS,
+                           Params{(const void* const*)D.tabTh, cf - 1, cf}, 0.f, 1, Slots{cf - 1, cf}));
+    if (left - left_e > 0) {
+      const int n0 = cf - 1 + left_e * cf;                           // first of them in the decoder
+      const Rows ZX = {(const void* const*)D.tabZ, n0, cf};
+      STCHK(forward_groups(P.Ed, D.Ed2, left - left_e, Driver::part(ZX, D.x_elems), NO_ROWS, NO_ROWS,
+                           Params{(const void* const*)D.tabTh, n0, cf}, 0.f, 1, Slots{n0 - n_enc, cf}, ZX));
+    }
+  } else if (!P.Ee.recompute) {
     STCHK(forward_groups(P.Ee, D.E2, n_enc, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, 1, Slots{0, 1}));
     STCHK(forward_groups(P.Ed, D.Ed2, n_dec, ZdecY, NO_ROWS, NO_ROWS, shift(TH, n_enc), 0.f, 1, Slots{0, 1}, ZdecX));
   }
@@ -1718,6 +1769,40 @@ int mgrit_adjoint_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, 
     }
   }
   return MGRIT_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int mgrit_forward_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, const void* Z0,
+                          const void* const* theta, void* Z_all, float* resnorm, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  return forward_stacked_impl(desc, opts, n_enc, Z0, theta, Z_all, resnorm, workspace, workspace_bytes, nullptr, 0,
+                              0, stream);
+}
+
+int mgrit_forward_stacked_linearising(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc,
+                                      const void* Z0, const void* const* theta, void* Z_all, float* resnorm,
+                                      void* workspace, size_t workspace_bytes, void* adjoint_workspace,
+                                      size_t adjoint_workspace_bytes, int with_gradients, void* stream) {
+  if (!adjoint_workspace) return MGRIT_INVALID_ARG;
+  return forward_stacked_impl(desc, opts, n_enc, Z0, theta, Z_all, resnorm, workspace, workspace_bytes,
+                              adjoint_workspace, adjoint_workspace_bytes, with_gradients ? 2 : 1, stream);
+}
+
+int mgrit_adjoint_stacked(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc, const void* Z_all,
+                          const void* const* theta, const void* lambda_N, void* lambda_all, void* const* dtheta,
+                          float* resnorm, void* workspace, size_t workspace_bytes, void* stream) {
+  return adjoint_stacked_impl(desc, opts, n_enc, Z_all, theta, lambda_N, lambda_all, dtheta, resnorm, workspace,
+                              workspace_bytes, false, stream);
+}
+
+int mgrit_adjoint_stacked_linearised(const mgrit_model_desc* desc, const mgrit_opts* opts, int n_enc,
+                                     const void* Z_all, const void* const* theta, const void* lambda_N,
+                                     void* lambda_all, void* const* dtheta, float* resnorm, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  return adjoint_stacked_impl(desc, opts, n_enc, Z_all, theta, lambda_N, lambda_all, dtheta, resnorm, workspace,
+                              workspace_bytes, true, stream);
 }
 
 // ---- buffer layers: serial open / close segments around the MGRIT middle ----------------------

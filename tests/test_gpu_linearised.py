@@ -3,7 +3,8 @@ the forward solve's closing relaxation leaves the block internals of the layers 
 adjoint's workspace, the adjoint evaluates only the others.  Same kernels' arithmetic on the same data, so
 Z, lambda, residual norms, parameter gradients and the memory gradient must agree bit for bit.  All three
 block types, two and three levels, F and FCF relaxation, a serial run, one and two lanes, with and without
-gradients; and the argument checks of the two entry points."""
+gradients; the stacked encoder-decoder grid (switch layer aligned with the intervals and inside one); and the
+argument checks of the entry points."""
 import pytest
 import torch
 
@@ -103,3 +104,54 @@ def test_linearising_entry_points_check_their_arguments():
     finally:
         mb.mgrit_set_adjoint_cache(True)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("n_enc,n_dec,cf,levels,relax,dtype,lanes,mg,grads", [
+    (8, 8, 4, 2, 1, wls.DTYPE_BF16, 2, 0, False),
+    (6, 10, 4, 2, 1, wls.DTYPE_BF16, 2, 0, True),           # the decoder starts inside a coarse interval
+    (3, 13, 4, 3, 0, wls.DTYPE_BF16, 2, 2, True),           # no encoder layer is left to the adjoint's own pass
+    (10, 6, 2, 2, 1, wls.DTYPE_F32, 1, 3, False),
+    (5, 4, 4, 1, 1, wls.DTYPE_BF16, 2, 0, True)])           # serial run: the forward solve leaves every layer
+def test_linearising_pair_equals_plain_pair_on_the_stacked_grid(n_enc, n_dec, cf, levels, relax, dtype, lanes, mg,
+                                                                grads):
+    enc = wls.Workload("enc", wls.ARCH_ENCODER, 128, 2, 256, 2, 24, 0, n_enc, 0.5, cf, levels, 2, dtype, 93,
+                       relax=relax)
+    dec = wls.Workload("dec", wls.ARCH_CROSS, 128, 2, 256, 2, 20, 24, n_dec, 0.5, cf, levels, 2, dtype, 94,
+                       relax=relax)
+    sw = wls.StackedWorkload("stacked", enc, dec)
+    print(f"[case] linearising, stacked grid n_enc={n_enc} n_dec={n_dec} cf={cf} L={levels} relax={relax} "
+          f"dtype={dtype} lanes={lanes} mg={mg} grads={grads}", flush=True)
+    desc_d = mb.model_desc(dec)
+    desc_e = mb.encoder_desc(desc_d)
+    blocks = [mb.pack_theta(desc_e if n < sw.n_enc else desc_d, wls.stacked_layer_params(sw, n, 0.05))
+              for n in range(sw.N)]
+    opts = mb.mgrit_opts(sw.N, dec.h, cf, levels, 2, relax)
+    Z0, lamN = dev(wls.stacked_initial_state(sw)), dev(wls.stacked_terminal_adjoint(sw))
+    mb.mgrit_set_lanes(lanes)
+    mb.mgrit_set_max_groups_per_launch(mg)
+    try:
+        def adjoint(Z, ws, linearised):
+            gb = None
+            if grads:
+                gb = [torch.full((mb.grad_layout(desc_e if n < sw.n_enc else desc_d).block_bytes // 4,), float("nan"),
+                                 dtype=torch.float32, device="cuda").view(torch.uint8) for n in range(sw.N)]
+            lam, res = mb.mgrit_adjoint_stacked(desc_d, opts, sw.n_enc, Z, blocks, lamN, dtheta=gb, workspace=ws,
+                                                linearised=linearised)
+            torch.cuda.synchronize()
+            return [lam, res] + (gb or [])
+
+        need = mb.mgrit_stacked_workspace_bytes(desc_d, opts, sw.n_enc, 2 if grads else 1)
+        Zp, rp = mb.mgrit_forward_stacked(desc_d, opts, sw.n_enc, Z0, blocks)
+        plain = [Zp, rp] + adjoint(Zp, poisoned(need), False)
+        ws = poisoned(need)
+        for rep in range(2):
+            Zl, rl = mb.mgrit_forward_stacked(desc_d, opts, sw.n_enc, Z0, blocks, adjoint_workspace=ws,
+                                              with_gradients=grads)
+            shared = [Zl, rl] + adjoint(Zl, ws, True)
+            for i, (x, y) in enumerate(zip(plain, shared)):
+                assert torch.equal(x, y), f"output {i} differs (repetition {rep})"
+        for x in plain:
+            assert torch.isfinite(x.float() if x.dtype != torch.uint8 else x.view(torch.float32)).all()
+    finally:
+        mb.mgrit_set_lanes(2)
+        mb.mgrit_set_max_groups_per_launch(0)
