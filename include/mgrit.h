@@ -231,6 +231,26 @@ int mgrit_adjoint_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts,
                            const void* lambda_N, void* lambda_all,
                            void* dmemory, void* const* dtheta, float* resnorm,
                            void* workspace, size_t workspace_bytes, void* stream);
+/* The buffered pair for a training step, as mgrit_forward_linearising / mgrit_adjoint_linearised (same
+ * contract between the two calls).  The three segments' adjoint solves then cannot share one workspace:
+ * `adjoint_workspace` (the `workspace` of the adjoint call) holds one region per segment,
+ * mgrit_buffered_linearised_workspace_bytes in all.  The serial open and close segments are stepped
+ * through completely by the forward solve, so their adjoints evaluate no layer internals of their own. */
+size_t mgrit_buffered_linearised_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                                                 const mgrit_buffer_opts* buf, int with_gradients);
+int mgrit_forward_buffered_linearising(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                                       const mgrit_buffer_opts* buf,
+                                       const void* Z0, const void* const* theta, const void* memory,
+                                       void* Z_all, float* resnorm,
+                                       void* workspace, size_t workspace_bytes,
+                                       void* adjoint_workspace, size_t adjoint_workspace_bytes, int with_gradients,
+                                       void* stream);
+int mgrit_adjoint_buffered_linearised(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                                      const mgrit_buffer_opts* buf,
+                                      const void* Z_all, const void* const* theta, const void* memory,
+                                      const void* lambda_N, void* lambda_all,
+                                      void* dmemory, void* const* dtheta, float* resnorm,
+                                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* Stacked encoder-decoder system (sec. 3.1, eq. "fp_transformer"): one MGRIT grid over the
  * N = opts->N = N_enc + N_dec layers of an encoder followed by a cross-attention decoder.  The

@@ -116,6 +116,15 @@ def lib() -> C.CDLL:
         L.mgrit_adjoint_buffered.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.POINTER(BufferOpts), vp, vpp,
                                              vp, vp, vp, vp, vpp, vp, vp, C.c_size_t, vp]
         L.mgrit_adjoint_buffered.restype = C.c_int
+        L.mgrit_buffered_linearised_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts),
+                                                                C.POINTER(BufferOpts), C.c_int]
+        L.mgrit_buffered_linearised_workspace_bytes.restype = C.c_size_t
+        L.mgrit_forward_buffered_linearising.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.POINTER(BufferOpts),
+                                                         vp, vpp, vp, vp, vp, vp, C.c_size_t, vp, C.c_size_t, C.c_int,
+                                                         vp]
+        L.mgrit_forward_buffered_linearising.restype = C.c_int
+        L.mgrit_adjoint_buffered_linearised.argtypes = L.mgrit_adjoint_buffered.argtypes
+        L.mgrit_adjoint_buffered_linearised.restype = C.c_int
         L.mgrit_stacked_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.c_int, C.c_int]
         L.mgrit_stacked_workspace_bytes.restype = C.c_size_t
         L.mgrit_forward_stacked.argtypes = [C.POINTER(ModelDesc), C.POINTER(Opts), C.c_int, vp, vpp, vp, vp, vp,
@@ -484,10 +493,17 @@ def mgrit_buffered_workspace_bytes(desc: ModelDesc, opts: Opts, buf: BufferOpts,
     return int(lib().mgrit_buffered_workspace_bytes(C.byref(desc), C.byref(opts), C.byref(buf), int(adjoint)))
 
 
+def mgrit_buffered_linearised_workspace_bytes(desc: ModelDesc, opts: Opts, buf: BufferOpts, with_gradients) -> int:
+    return int(lib().mgrit_buffered_linearised_workspace_bytes(C.byref(desc), C.byref(opts), C.byref(buf),
+                                                               int(bool(with_gradients))))
+
+
 def mgrit_forward_buffered(desc: ModelDesc, opts: Opts, buf: BufferOpts, Z0: torch.Tensor,
                            theta: List[torch.Tensor], memory: Optional[torch.Tensor] = None,
-                           stream: Optional[torch.cuda.Stream] = None):
-    """Serial open / close layers around the MGRIT middle.  Returns (Z_all, resnorm)."""
+                           stream: Optional[torch.cuda.Stream] = None,
+                           adjoint_workspace: Optional[torch.Tensor] = None, with_gradients: bool = False):
+    """Serial open / close layers around the MGRIT middle.  Returns (Z_all, resnorm).
+    adjoint_workspace (mgrit_buffered_linearised_workspace_bytes): mgrit_forward_buffered_linearising."""
     T, d = desc.batch * desc.seq, desc.d_model
     n = buf.n_open + opts.N + buf.n_close
     _check_state(Z0, (T, d), "Z0")
@@ -496,6 +512,15 @@ def mgrit_forward_buffered(desc: ModelDesc, opts: Opts, buf: BufferOpts, Z0: tor
     Z_all = torch.empty((n + 1, T, d), dtype=torch.float32, device=Z0.device)
     resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z0.device)
     ws = torch.empty(max(mgrit_buffered_workspace_bytes(desc, opts, buf, 0), 256), dtype=torch.uint8, device=Z0.device)
+    if adjoint_workspace is not None:
+        st = lib().mgrit_forward_buffered_linearising(C.byref(desc), C.byref(opts), C.byref(buf), _ptr(Z0),
+                                                      _ptr_array(theta), _ptr(memory), _ptr(Z_all), _ptr(resnorm),
+                                                      _ptr(ws), ws.numel(), _ptr(adjoint_workspace),
+                                                      adjoint_workspace.numel(), int(bool(with_gradients)),
+                                                      _stream_handle(stream))
+        if st != MGRIT_OK:
+            raise MgritError(st, "mgrit_forward_buffered_linearising")
+        return Z_all, resnorm
     st = lib().mgrit_forward_buffered(C.byref(desc), C.byref(opts), C.byref(buf), _ptr(Z0), _ptr_array(theta),
                                       _ptr(memory), _ptr(Z_all), _ptr(resnorm), _ptr(ws), ws.numel(),
                                       _stream_handle(stream))
@@ -507,8 +532,10 @@ def mgrit_forward_buffered(desc: ModelDesc, opts: Opts, buf: BufferOpts, Z0: tor
 def mgrit_adjoint_buffered(desc: ModelDesc, opts: Opts, buf: BufferOpts, Z_all: torch.Tensor,
                            theta: List[torch.Tensor], lambda_N: torch.Tensor, memory: Optional[torch.Tensor] = None,
                            dtheta: Optional[List[torch.Tensor]] = None,
-                           stream: Optional[torch.cuda.Stream] = None):
-    """Returns (lambda_all, resnorm) of the buffered network; dtheta as in mgrit_adjoint."""
+                           stream: Optional[torch.cuda.Stream] = None, workspace: Optional[torch.Tensor] = None,
+                           linearised: bool = False):
+    """Returns (lambda_all, resnorm) of the buffered network; dtheta as in mgrit_adjoint.
+    linearised: mgrit_adjoint_buffered_linearised on the workspace the forward call filled."""
     T, d = desc.batch * desc.seq, desc.d_model
     n = buf.n_open + opts.N + buf.n_close
     _check_state(Z_all, (n + 1, T, d), "Z_all")
@@ -517,13 +544,16 @@ def mgrit_adjoint_buffered(desc: ModelDesc, opts: Opts, buf: BufferOpts, Z_all: 
         raise ValueError("theta / dtheta must hold n_open + N + n_close blocks")
     lambda_all = torch.empty_like(Z_all)
     resnorm = torch.zeros(max(opts.iters, 1), dtype=torch.float32, device=Z_all.device)
+    if linearised and workspace is None:
+        raise ValueError("linearised: pass the adjoint workspace that the forward call filled")
     need = mgrit_buffered_workspace_bytes(desc, opts, buf, 2 if dtheta is not None else 1)
-    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=Z_all.device)
-    st = lib().mgrit_adjoint_buffered(C.byref(desc), C.byref(opts), C.byref(buf), _ptr(Z_all), _ptr_array(theta),
-                                      _ptr(memory), _ptr(lambda_N), _ptr(lambda_all), None, _ptr_array(dtheta),
-                                      _ptr(resnorm), _ptr(ws), ws.numel(), _stream_handle(stream))
+    ws = workspace if workspace is not None else torch.empty(max(need, 256), dtype=torch.uint8, device=Z_all.device)
+    entry = lib().mgrit_adjoint_buffered_linearised if linearised else lib().mgrit_adjoint_buffered
+    st = entry(C.byref(desc), C.byref(opts), C.byref(buf), _ptr(Z_all), _ptr_array(theta),
+               _ptr(memory), _ptr(lambda_N), _ptr(lambda_all), None, _ptr_array(dtheta),
+               _ptr(resnorm), _ptr(ws), ws.numel(), _stream_handle(stream))
     if st != MGRIT_OK:
-        raise MgritError(st, "mgrit_adjoint_buffered")
+        raise MgritError(st, "mgrit_adjoint_buffered_linearised" if linearised else "mgrit_adjoint_buffered")
     return lambda_all, resnorm
 
 

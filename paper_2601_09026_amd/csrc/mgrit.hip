@@ -1834,9 +1834,40 @@ size_t mgrit_buffered_workspace_bytes(const mgrit_model_desc* desc, const mgrit_
   return need;
 }
 
-int mgrit_forward_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
-                           const void* Z0, const void* const* theta, const void* memory, void* Z_all,
-                           float* resnorm, void* workspace, size_t workspace_bytes, void* stream) {
+// Segments of a buffered run: the open layers (serial), the MGRIT middle, the close layers (serial).  The
+// linearising pair gives each segment's adjoint plan a region of its own in one workspace, in this order.
+struct BufferedRegions {
+  size_t off[3] = {0, 0, 0}, bytes[3] = {0, 0, 0}, total = 0;
+};
+static int buffered_regions(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
+                            int mode, BufferedRegions& R) {
+  const mgrit_opts so_open = serial_opts(buf->n_open, buf->h_buffer), so_close = serial_opts(buf->n_close, buf->h_buffer);
+  const mgrit_opts* seg[3] = {buf->n_open > 0 ? &so_open : nullptr, opts, buf->n_close > 0 ? &so_close : nullptr};
+  size_t off = 0;
+  for (int i = 0; i < 3; ++i) {
+    R.off[i] = off;
+    if (!seg[i]) continue;
+    R.bytes[i] = mgrit_workspace_bytes(desc, seg[i], mode);
+    if (R.bytes[i] == 0) return MGRIT_INVALID_ARG;
+    off += (R.bytes[i] + 255) / 256 * 256;
+  }
+  R.total = off;
+  return MGRIT_OK;
+}
+
+size_t mgrit_buffered_linearised_workspace_bytes(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                                                 const mgrit_buffer_opts* buf, int with_gradients) {
+  if (validate_desc(desc) != MGRIT_OK || validate_opts(opts) != MGRIT_OK || validate_buffer(buf) != MGRIT_OK) return 0;
+  BufferedRegions R;
+  if (buffered_regions(desc, opts, buf, with_gradients ? 2 : 1, R) != MGRIT_OK) return 0;
+  return R.total;
+}
+
+// share_ws: the adjoint workspace of the linearising pair (regions as above), or null
+static int forward_buffered_impl(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
+                                 const void* Z0, const void* const* theta, const void* memory, void* Z_all,
+                                 float* resnorm, void* workspace, size_t workspace_bytes, void* share_ws,
+                                 size_t share_bytes, int share_mode, void* stream) {
   std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
   STCHK(validate_desc(desc));
   STCHK(validate_opts(opts));
@@ -1845,6 +1876,13 @@ int mgrit_forward_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts,
   const size_t need = mgrit_buffered_workspace_bytes(desc, opts, buf, 0);
   if (need == 0) return MGRIT_INVALID_ARG;
   if (!workspace || workspace_bytes < need) return workspace ? MGRIT_WORKSPACE_TOO_SMALL : MGRIT_INVALID_ARG;
+  BufferedRegions R;
+  if (share_ws) {
+    if (!g_adjoint_cache) return MGRIT_INVALID_ARG;
+    STCHK(buffered_regions(desc, opts, buf, share_mode, R));
+    if (share_bytes < R.total) return MGRIT_WORKSPACE_TOO_SMALL;
+  }
+  char* sw = static_cast<char*>(share_ws);
   const size_t state = (size_t)desc->batch * desc->seq * desc->d_model * sizeof(float);
   char* Z = static_cast<char*>(Z_all);
   const int no = buf->n_open, nc = buf->n_close, N = opts->N;
@@ -1852,23 +1890,27 @@ int mgrit_forward_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts,
   const void* z_in = Z0;
   if (no > 0) {
     const mgrit_opts so = serial_opts(no, buf->h_buffer);
-    STCHK(mgrit_forward(desc, &so, z_in, theta, memory, Z, nullptr, workspace, workspace_bytes, stream));
+    STCHK(forward_impl(desc, &so, z_in, theta, memory, Z, nullptr, workspace, workspace_bytes,
+                       sw ? sw + R.off[0] : nullptr, R.bytes[0], share_mode, stream));
     z_in = Z + (size_t)no * state;
   }
-  STCHK(mgrit_forward(desc, opts, z_in, theta + no, memory, Z + (size_t)no * state, resnorm, workspace,
-                      workspace_bytes, stream));
+  STCHK(forward_impl(desc, opts, z_in, theta + no, memory, Z + (size_t)no * state, resnorm, workspace,
+                     workspace_bytes, sw ? sw + R.off[1] : nullptr, R.bytes[1], share_mode, stream));
   if (nc > 0) {
     const mgrit_opts so = serial_opts(nc, buf->h_buffer);
     char* row = Z + (size_t)(no + N) * state;
-    STCHK(mgrit_forward(desc, &so, row, theta + no + N, memory, row, nullptr, workspace, workspace_bytes, stream));
+    STCHK(forward_impl(desc, &so, row, theta + no + N, memory, row, nullptr, workspace, workspace_bytes,
+                       sw ? sw + R.off[2] : nullptr, R.bytes[2], share_mode, stream));
   }
   return MGRIT_OK;
 }
 
-int mgrit_adjoint_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
-                           const void* Z_all, const void* const* theta, const void* memory, const void* lambda_N,
-                           void* lambda_all, void* dmemory, void* const* dtheta, float* resnorm, void* workspace,
-                           size_t workspace_bytes, void* stream) {
+// prefilled: `workspace` is the region workspace that forward_buffered_impl filled
+static int adjoint_buffered_impl(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
+                                 const void* Z_all, const void* const* theta, const void* memory,
+                                 const void* lambda_N, void* lambda_all, void* dmemory, void* const* dtheta,
+                                 float* resnorm, void* workspace, size_t workspace_bytes, bool prefilled,
+                                 void* stream) {
   std::lock_guard<std::recursive_mutex> call_lock(g_call_mutex);
   STCHK(validate_desc(desc));
   STCHK(validate_opts(opts));
@@ -1877,9 +1919,18 @@ int mgrit_adjoint_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts,
   // the memory gradient would have to be accumulated over the three segments: not offered here
   if (dmemory) return MGRIT_UNSUPPORTED;
   const int mode = dtheta ? 2 : 1;
-  const size_t need = mgrit_buffered_workspace_bytes(desc, opts, buf, mode);
+  BufferedRegions R;                                   // all three segments share the workspace unless prefilled
+  size_t need = mgrit_buffered_workspace_bytes(desc, opts, buf, mode);
   if (need == 0) return MGRIT_INVALID_ARG;
+  if (prefilled) {
+    if (!g_adjoint_cache) return MGRIT_INVALID_ARG;
+    STCHK(buffered_regions(desc, opts, buf, mode, R));
+    need = R.total;
+  }
   if (!workspace || workspace_bytes < need) return workspace ? MGRIT_WORKSPACE_TOO_SMALL : MGRIT_INVALID_ARG;
+  char* ws = static_cast<char*>(workspace);
+  auto region = [&](int i) { return prefilled ? static_cast<void*>(ws + R.off[i]) : workspace; };
+  auto region_bytes = [&](int i) { return prefilled ? R.bytes[i] : workspace_bytes; };
   const size_t state = (size_t)desc->batch * desc->seq * desc->d_model * sizeof(float);
   const char* Z = static_cast<const char*>(Z_all);
   char* Lm = static_cast<char*>(lambda_all);
@@ -1890,18 +1941,52 @@ int mgrit_adjoint_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts,
   if (nc > 0) {
     const mgrit_opts so = serial_opts(nc, buf->h_buffer);
     const size_t off = (size_t)(no + N) * state;
-    STCHK(mgrit_adjoint(desc, &so, Z + off, theta + no + N, memory, lam_in, Lm + off, nullptr,
-                        dtheta ? dtheta + no + N : nullptr, nullptr, workspace, workspace_bytes, stream));
+    STCHK(adjoint_impl(desc, &so, Z + off, theta + no + N, memory, lam_in, Lm + off, nullptr,
+                       dtheta ? dtheta + no + N : nullptr, nullptr, region(2), region_bytes(2), prefilled, stream));
     lam_in = Lm + off;
   }
-  STCHK(mgrit_adjoint(desc, opts, Z + (size_t)no * state, theta + no, memory, lam_in, Lm + (size_t)no * state,
-                      nullptr, dtheta ? dtheta + no : nullptr, resnorm, workspace, workspace_bytes, stream));
+  STCHK(adjoint_impl(desc, opts, Z + (size_t)no * state, theta + no, memory, lam_in, Lm + (size_t)no * state,
+                     nullptr, dtheta ? dtheta + no : nullptr, resnorm, region(1), region_bytes(1), prefilled, stream));
   if (no > 0) {
     const mgrit_opts so = serial_opts(no, buf->h_buffer);
-    STCHK(mgrit_adjoint(desc, &so, Z, theta, memory, Lm + (size_t)no * state, Lm, nullptr, dtheta, nullptr,
-                        workspace, workspace_bytes, stream));
+    STCHK(adjoint_impl(desc, &so, Z, theta, memory, Lm + (size_t)no * state, Lm, nullptr, dtheta, nullptr,
+                       region(0), region_bytes(0), prefilled, stream));
   }
   return MGRIT_OK;
+}
+
+int mgrit_forward_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
+                           const void* Z0, const void* const* theta, const void* memory, void* Z_all,
+                           float* resnorm, void* workspace, size_t workspace_bytes, void* stream) {
+  return forward_buffered_impl(desc, opts, buf, Z0, theta, memory, Z_all, resnorm, workspace, workspace_bytes,
+                               nullptr, 0, 0, stream);
+}
+
+int mgrit_forward_buffered_linearising(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                                       const mgrit_buffer_opts* buf, const void* Z0, const void* const* theta,
+                                       const void* memory, void* Z_all, float* resnorm, void* workspace,
+                                       size_t workspace_bytes, void* adjoint_workspace,
+                                       size_t adjoint_workspace_bytes, int with_gradients, void* stream) {
+  if (!adjoint_workspace) return MGRIT_INVALID_ARG;
+  return forward_buffered_impl(desc, opts, buf, Z0, theta, memory, Z_all, resnorm, workspace, workspace_bytes,
+                               adjoint_workspace, adjoint_workspace_bytes, with_gradients ? 2 : 1, stream);
+}
+
+int mgrit_adjoint_buffered(const mgrit_model_desc* desc, const mgrit_opts* opts, const mgrit_buffer_opts* buf,
+                           const void* Z_all, const void* const* theta, const void* memory, const void* lambda_N,
+                           void* lambda_all, void* dmemory, void* const* dtheta, float* resnorm, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  return adjoint_buffered_impl(desc, opts, buf, Z_all, theta, memory, lambda_N, lambda_all, dmemory, dtheta, resnorm,
+                               workspace, workspace_bytes, false, stream);
+}
+
+int mgrit_adjoint_buffered_linearised(const mgrit_model_desc* desc, const mgrit_opts* opts,
+                                      const mgrit_buffer_opts* buf, const void* Z_all, const void* const* theta,
+                                      const void* memory, const void* lambda_N, void* lambda_all, void* dmemory,
+                                      void* const* dtheta, float* resnorm, void* workspace, size_t workspace_bytes,
+                                      void* stream) {
+  return adjoint_buffered_impl(desc, opts, buf, Z_all, theta, memory, lambda_N, lambda_all, dmemory, dtheta, resnorm,
+                               workspace, workspace_bytes, true, stream);
 }
 
 int layer_step_batched(const mgrit_model_desc* desc, int adjoint, int n_groups, const void* const* in,

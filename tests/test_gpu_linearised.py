@@ -3,8 +3,8 @@ the forward solve's closing relaxation leaves the block internals of the layers 
 adjoint's workspace, the adjoint evaluates only the others.  Same kernels' arithmetic on the same data, so
 Z, lambda, residual norms, parameter gradients and the memory gradient must agree bit for bit.  All three
 block types, two and three levels, F and FCF relaxation, a serial run, one and two lanes, with and without
-gradients; the stacked encoder-decoder grid (switch layer aligned with the intervals and inside one); and the
-argument checks of the entry points."""
+gradients; the stacked encoder-decoder grid (switch layer aligned with the intervals and inside one); buffer
+layers; and the argument checks of the entry points."""
 import pytest
 import torch
 
@@ -155,3 +155,44 @@ def test_linearising_pair_equals_plain_pair_on_the_stacked_grid(n_enc, n_dec, cf
     finally:
         mb.mgrit_set_lanes(2)
         mb.mgrit_set_max_groups_per_launch(0)
+
+
+@pytest.mark.parametrize("arch,n_open,n_close,grads", [(wls.ARCH_CAUSAL, 2, 2, True), (wls.ARCH_ENCODER, 0, 3, False),
+                                                       (wls.ARCH_CROSS, 1, 0, False)])
+def test_linearising_pair_equals_plain_pair_with_buffer_layers(arch, n_open, n_close, grads):
+    wl = wls.Workload("t", arch, 128, 2, 256, 2, 40, 24 if arch == wls.ARCH_CROSS else 0, 8, 0.25, 4, 2, 2,
+                      wls.DTYPE_BF16, 95)
+    print(f"[case] linearising, buffer layers arch={arch} open={n_open} close={n_close} grads={grads}", flush=True)
+    n = n_open + 8 + n_close
+    dm = DeviceModel(wl, n_layers=n, weight_std=0.05, keep_host=False)
+    opts = mb.mgrit_opts(8, wl.h, 4, 2, 2)
+    buf = mb.BufferOpts(n_open, n_close, 1.0)
+    mem = wls.cross_memory(wl)
+    mem = None if mem is None else dev(mem)
+    Z0, lamN = dev(wls.initial_state(wl)), dev(wls.terminal_adjoint(wl))
+
+    def adjoint(Z, ws, linearised):
+        gb = grad_blocks(dm.desc, n) if grads else None
+        lam, res = mb.mgrit_adjoint_buffered(dm.desc, opts, buf, Z, dm.blocks, lamN, memory=mem, dtheta=gb,
+                                             workspace=ws, linearised=linearised)
+        torch.cuda.synchronize()
+        return [lam, res] + (gb or [])
+
+    Zp, rp = mb.mgrit_forward_buffered(dm.desc, opts, buf, Z0, dm.blocks, memory=mem)
+    plain = [Zp, rp] + adjoint(Zp, None, False)
+    need = mb.mgrit_buffered_linearised_workspace_bytes(dm.desc, opts, buf, grads)
+    assert need >= mb.mgrit_buffered_workspace_bytes(dm.desc, opts, buf, 2 if grads else 1)
+    ws = poisoned(need)
+    for rep in range(2):
+        Zl, rl = mb.mgrit_forward_buffered(dm.desc, opts, buf, Z0, dm.blocks, memory=mem, adjoint_workspace=ws,
+                                           with_gradients=grads)
+        shared = [Zl, rl] + adjoint(Zl, ws, True)
+        for i, (x, y) in enumerate(zip(plain, shared)):
+            assert torch.equal(x, y), f"output {i} differs (repetition {rep})"
+    for x in plain:
+        assert torch.isfinite(x.float() if x.dtype != torch.uint8 else x.view(torch.float32)).all()
+    with pytest.raises(mb.MgritError) as e:                   # one region per segment: the shared size is too small
+        small = torch.empty(max(need - 256, 256), dtype=torch.uint8, device="cuda")
+        mb.mgrit_forward_buffered(dm.desc, opts, buf, Z0, dm.blocks, memory=mem, adjoint_workspace=small,
+                                  with_gradients=grads)
+    assert e.value.status == mb.MGRIT_WORKSPACE_TOO_SMALL
