@@ -172,6 +172,8 @@ struct GemmArgs {
   Rows OUT;                    // EPI_RESID_OUTER: the step's output state
   Rows RHS;                    // EPI_RESID_OUTER: optional right-hand side
   float hstep;
+  float rhs_sign;              // EPI_RESID_OUTER with RHS: OUT = RHS + rhs_sign * (X + h*(..)); +1 the step, -1 the
+                               // coarse right-hand side g' = R - Phi'(w) formed in the step that evaluates Phi'
   Params out_tab; long out_tab_off;    // EPI_STORE_F32: if set, group g writes at out_tab[g] + out_tab_off
 };
 

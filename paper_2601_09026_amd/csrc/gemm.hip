@@ -80,7 +80,7 @@ __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restric
                                        TO* __restrict__ g_out,
                                        const float* __restrict__ base, const float* __restrict__ X,
                                        const float* __restrict__ ybar, const float* __restrict__ RHS,
-                                       float* __restrict__ OUT, float hstep, long idx, f32x4 acc) {
+                                       float* __restrict__ OUT, float hstep, float sgn, long idx, f32x4 acc) {
   if constexpr (EPI == EPI_STORE) {
     estore4<TO>(out_op + idx, acc);
   } else if constexpr (EPI == EPI_STORE_F32) {
@@ -110,7 +110,12 @@ __device__ __forceinline__ void apply4(TO* __restrict__ out_op, float* __restric
     f32x4 x = eload4<float>(X + idx);
     if (has_opt<OPT>(0, ybar)) acc += eload4<float>(ybar + idx);
     f32x4 r = x + hstep * acc;
-    if (has_opt<OPT>(1, RHS)) r += eload4<float>(RHS + idx);
+    if (has_opt<OPT>(1, RHS)) {
+      // sgn = 1: r + rhs; sgn = -1: rhs - r, each a single rounding of the exact value
+      const f32x4 rhs = eload4<float>(RHS + idx);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r[e] = __builtin_fmaf(sgn, r[e], rhs[e]);
+    }
     estore4<float>(OUT + idx, r);
   }
 }
@@ -156,11 +161,11 @@ __device__ __forceinline__ void apply8(bf16* __restrict__ out, bf16* __restrict_
 
 // one-off form for the generic kernel
 template <int EPI, typename TO>
-__device__ __forceinline__ void epilogue4(const EpiPtrs& p, float hstep, int N, int m, int n, f32x4 acc) {
+__device__ __forceinline__ void epilogue4(const EpiPtrs& p, float hstep, float sgn, int N, int m, int n, f32x4 acc) {
   if (p.bias) acc += *reinterpret_cast<const f32x4*>(p.bias + n);
   apply4<EPI, TO>(static_cast<TO*>(p.out), static_cast<float*>(p.out), static_cast<TO*>(p.aux),
                   static_cast<const TO*>(p.aux), static_cast<TO*>(p.aux2), p.base, p.X,
-                  static_cast<const float*>(p.aux), p.RHS, p.OUT, hstep, (long)m * N + n, acc);
+                  static_cast<const float*>(p.aux), p.RHS, p.OUT, hstep, sgn, (long)m * N + n, acc);
 }
 
 constexpr int ce_gcd(int a, int b) { return b == 0 ? a : ce_gcd(b, a % b); }
@@ -173,8 +178,8 @@ __device__ __forceinline__ void tile_epilogue(
     f32x16 (&acc)[TM][TN], unsigned char* ep, const float* __restrict__ bias, TO* __restrict__ out_op,
     float* __restrict__ out_f32, TO* __restrict__ z_out, const TO* __restrict__ z_in, TO* __restrict__ g_out,
     const float* __restrict__ base, const float* __restrict__ X, const float* __restrict__ ybar,
-    const float* __restrict__ RHS, float* __restrict__ OUT, float hstep, int N, int M, int mrow0, int ncol0,
-    int lane) {
+    const float* __restrict__ RHS, float* __restrict__ OUT, float hstep, float sgn, int N, int M, int mrow0,
+    int ncol0, int lane) {
   constexpr int WTN = TN * 32;
   const int lr = lane & 31, lh = lane >> 5;
   if constexpr (STAGED) {
@@ -231,7 +236,7 @@ __device__ __forceinline__ void tile_epilogue(
                              reinterpret_cast<const bf16*>(z_in), reinterpret_cast<bf16*>(g_out), idx, v0, v1);
         } else {
           if (!GUARD || m < M)
-            apply4<EPI, TO, OPT>(out_op, out_f32, z_out, z_in, g_out, base, X, ybar, RHS, OUT, hstep, idx, v0);
+            apply4<EPI, TO, OPT>(out_op, out_f32, z_out, z_in, g_out, base, X, ybar, RHS, OUT, hstep, sgn, idx, v0);
         }
       }
     };
@@ -275,8 +280,8 @@ __device__ __forceinline__ void tile_epilogue(
           for (int q = 0; q < 4; ++q) {
             const int n = ncol0 + j * 32 + q * 8 + lh * 4;
             f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-            apply4<EPI, TO>(out_op, out_f32, z_out, z_in, g_out, base, X, ybar, RHS, OUT, hstep, (long)m * N + n,
-                            v + bv[j][q]);
+            apply4<EPI, TO>(out_op, out_f32, z_out, z_in, g_out, base, X, ybar, RHS, OUT, hstep, sgn,
+                            (long)m * N + n, v + bv[j][q]);
           }
       }
     }
@@ -474,8 +479,8 @@ gemm_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, in
   tile_epilogue<EPI, TO, TM, TN, STAGED>(acc, smem2 + wave * EP_BYTES, P.bias, static_cast<TO*>(P.out),
                                          static_cast<float*>(P.out), static_cast<TO*>(P.aux),
                                          static_cast<const TO*>(P.aux), static_cast<TO*>(P.aux2), P.base, P.X,
-                                         static_cast<const float*>(P.aux), P.RHS, P.OUT, a.hstep, a.N, M,
-                                         m0 + wm0, n0 + wn0, lane);
+                                         static_cast<const float*>(P.aux), P.RHS, P.OUT, a.hstep, a.rhs_sign, a.N,
+                                         M, m0 + wm0, n0 + wn0, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -526,8 +531,8 @@ gemm_f32_mfma_kernel(const GemmArgs a, int tiles_m, int tiles_n) {
   tile_epilogue<EPI, float, 1, 1, false>(acc, nullptr, P.bias, static_cast<float*>(P.out), static_cast<float*>(P.out),
                                          static_cast<float*>(P.aux), static_cast<const float*>(P.aux),
                                          static_cast<float*>(P.aux2), P.base, P.X,
-                                         static_cast<const float*>(P.aux), P.RHS, P.OUT, a.hstep, a.N, M, m0 + wm0,
-                                         n0 + wn0, lane);
+                                         static_cast<const float*>(P.aux), P.RHS, P.OUT, a.hstep, a.rhs_sign, a.N, M,
+                                         m0 + wm0, n0 + wn0, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -576,7 +581,7 @@ gemm_simple_kernel(const GemmArgs a, int tiles_m, int tiles_n) {
       const int m = m0 + ty * 4 + i;
       if (m < M) {
         f32x4 v = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
-        epilogue4<EPI, TO>(P, a.hstep, N, m, n, v);
+        epilogue4<EPI, TO>(P, a.hstep, a.rhs_sign, N, m, n, v);
       }
     }
   }

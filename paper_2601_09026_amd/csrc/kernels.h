@@ -37,6 +37,7 @@ struct LnBwdArgs {
   Rows C;                                                     // cotangent rows c (required if out_op or OUT)
   void* out_op; long oo_slot_stride; Slots oo_slots;         // optional packed operand type: c + v
   Rows OUT; Rows RHS; float hstep;                           // optional: OUT = c + hstep*v (+ RHS)
+  float rhs_sign;                                            // with RHS: OUT = RHS + rhs_sign * (c + hstep*v), +1 or -1
   float eps;
   // optional: the LN input given as cached xhat (packed operand type) and rstd ([slot][T]) instead of X / xp
   const void* xhat; long xhat_slot_stride; Slots xhat_slots;

@@ -201,6 +201,8 @@ struct Engine {
   // adjoint without the N-layer linearisation cache: the cache arrays hold one launch chunk (Gc slots,
   // one set per lane) and every chunk of transposed steps first recomputes the internals of its layers
   bool recompute = false;
+  // sign of the step inside OUT = RHS + sign * (step): -1 while the driver forms a coarse right-hand side
+  float rhs_sign = 1.f;
   int Tmax() const { return T > Tm ? T : Tm; }
   long tA_stride() const { return (long)(f > 3 * d ? f : 3 * d) * Tmax(); }   // elements per slot
   long tB_stride() const { return (long)(f > d ? f : d) * Tmax(); }
@@ -366,6 +368,7 @@ GemmArgs gemm_base(int n, int M, int N, int K, const void* A, long a_stride, Slo
   g.n_groups = n; g.M = M; g.N = N; g.K = K;
   g.A = A; g.a_slot_stride = a_stride; g.a_slots = a_slots;
   g.B = B; g.b_off = b_off; g.bias = B; g.bias_off = bias_off;
+  g.rhs_sign = 1.f;
   return g;
 }
 
@@ -474,7 +477,7 @@ int forward_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, floa
 
   g = gemm_base(n, T, d, f, E.act, (long)T * f, loc, TH, L.offset[MGRIT_P_W2], L.offset[MGRIT_P_B2]);
   g.aux = xin; g.aux_slot_stride = E.Td(); g.aux_slots = cs;                    // ybar
-  g.X = IN; g.OUT = OUT; g.RHS = RHS; g.hstep = hstep;
+  g.X = IN; g.OUT = OUT; g.RHS = RHS; g.hstep = hstep; g.rhs_sign = E.rhs_sign;
   HIPCHK(launch_gemm(g, EPI_RESID_OUTER, E.bf16, E.st));
   return MGRIT_OK;
 }
@@ -713,7 +716,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
   lb.xhat = E.c_xh1; lb.xhat_slot_stride = E.Td(); lb.xhat_slots = cs; lb.rstd = E.c_rs1;
   lb.P = TH; lb.gamma_off = L.offset[MGRIT_P_LN1_G];
   lb.add = E.dxin; lb.add_slot_stride = E.Td(); lb.add_slots = loc;
-  lb.C = IN; lb.OUT = OUT; lb.RHS = RHS; lb.hstep = hstep;
+  lb.C = IN; lb.OUT = OUT; lb.RHS = RHS; lb.hstep = hstep; lb.rhs_sign = E.rhs_sign;
   HIPCHK(launch_ln_bwd(lb, E.bf16, E.st));
   return MGRIT_OK;
 }
@@ -958,6 +961,24 @@ struct Driver {
     return adjoint_groups(L1, L2, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep);
   }
 
+  // g'_k = R_k - Phi'(w_{(k-1) cf}) for the groups g0 .. g0+n-1 of level lvl+1 (Gn, R already shifted to g0).
+  // The step that evaluates Phi' takes R as its right-hand side with the sign of the step reversed, which
+  // gives the same rounded values as the step followed by a subtraction.  The stacked grid copies the half
+  // of the state a step leaves alone, so there the subtraction stays a kernel of its own.
+  int coarse_rhs(int lvl, int g0, int n, Rows R, Rows Gn, Engine* lane) {
+    if (Ed || !E) {
+      STCHK(step(lvl + 1, g0, 1, n, Gn, NO_ROWS));
+      if (E) HIPCHK(launch_sub_rows(n, state_elems(), R, Gn, Gn, lane ? lane->st : E->st));
+      return MGRIT_OK;
+    }
+    E->rhs_sign = -1.f;
+    if (E2) E2->rhs_sign = -1.f;
+    const int st = step(lvl + 1, g0, 1, n, Gn, R);
+    E->rhs_sign = 1.f;
+    if (E2) E2->rhs_sign = 1.f;
+    return st;
+  }
+
   // The coarse right-hand sides, the serial solve on the coarsest level (level lvl + 1, M steps) and
   // the F-relaxation of level lvl that follows it, overlapped on the two lanes.  The coarse steps
   // are single groups, which leave much of the chip idle, and they form MGRIT's serial chain:
@@ -988,16 +1009,13 @@ struct Driver {
     constexpr int HALF = PIPE_EVENTS / 2;                // events 0..HALF-1: right-hand sides; the others: hand-overs
     auto rhs_chunk = [&](Engine* lane, int g0, int n) -> int {
       only = lane;
-      const int st = step(lvl + 1, g0, 1, n, shift(Gn, g0), NO_ROWS);
+      const int st = coarse_rhs(lvl, g0, n, shift(R, g0), shift(Gn, g0), lane);
       only = nullptr;
-      STCHK(st);
-      HIPCHK(launch_sub_rows(n, state_elems(), shift(R, g0), shift(Gn, g0), shift(Gn, g0), lane->st));
-      return MGRIT_OK;
+      return st;
     };
     const bool split_rhs = n_chunks >= 2 && n_chunks <= HALF;
     if (!split_rhs) {
-      STCHK(step(lvl + 1, 0, 1, M, Gn, NO_ROWS));
-      HIPCHK(launch_sub_rows(M, state_elems(), R, Gn, Gn, E->st));
+      STCHK(coarse_rhs(lvl, 0, M, R, Gn, nullptr));
     } else {
       // the helper lane starts from everything enqueued so far (relaxation, residual)
       HIPCHK(hipEventRecord(a.fork, E->st));
@@ -1075,8 +1093,7 @@ struct Driver {
     Rows Gn = {(const void* const*)(E ? tabG[lvl + 1] : nullptr), 1, 1};
     if (E && E2 && g_pipeline && lvl + 1 == L - 1 && M >= 2 && cf >= 2)
       return coarse_solve_with_relaxation(lvl, M, R, Gn);
-    STCHK(step(lvl + 1, 0, 1, M, Gn, NO_ROWS));
-    if (E) HIPCHK(launch_sub_rows(M, state_elems(), R, Gn, Gn, E->st));
+    STCHK(coarse_rhs(lvl, 0, M, R, Gn, nullptr));
     STCHK(vcycle(lvl + 1, iter, false));
     emit_now = want_grads && last_cycle && lvl == 0;
     cache_now = fill_cache && last_cycle && lvl == 0;

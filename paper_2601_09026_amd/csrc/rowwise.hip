@@ -242,7 +242,12 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
           if (oo && !cop) store4<TO>(oo + c, cc + r);
           if (OUT) {
             f32x4 res = cc + a.hstep * r;
-            if (RHS) res += ld_stream(reinterpret_cast<const f32x4*>(RHS + c));
+            if (RHS) {
+              // rhs_sign = 1: res + rhs; -1: rhs - res (the coarse right-hand side), each rounded once
+              const f32x4 rhs = ld_stream(reinterpret_cast<const f32x4*>(RHS + c));
+#pragma unroll
+              for (int e = 0; e < 4; ++e) res[e] = __builtin_fmaf(a.rhs_sign, res[e], rhs[e]);
+            }
             *reinterpret_cast<f32x4*>(OUT + c) = res;
           }
         }
