@@ -1446,20 +1446,38 @@ int adjoint_impl(const mgrit_model_desc* desc, const mgrit_opts* opts, const voi
   HIPCHK(launch_fill_table(D.tabThT, static_cast<char*>(P.thT_blocks), (long)E.lay.block_bytes, N, st));
   Params TH = {(const void* const*)D.tabTh, 0, 1};
   Params THT = {(const void* const*)D.tabThT, 0, 1};
-  STCHK(transpose_blocks(E, N, TH, THT));
   if (desc->arch == MGRIT_ARCH_CROSS)
     HIPCHK(launch_cast_flat(static_cast<const float*>(memory), E.memb, (long)E.Tm * E.d, E.bf16, st));
   // linearisation cache for all N layers, batched over layers (unless every chunk recomputes its own)
   Rows Zrows = {(const void* const*)D.tabZ, 0, 1};
-  if (prefilled) {
-    // the forward solve's closing relaxation has left every layer it stepped through: all of them in a
-    // serial run, otherwise all but the last layer of each interval (n = cf-1, 2cf-1, ..)
+  if (prefilled && D.E2 && !serial_run(opts)) {
+    // The forward solve's closing relaxation has left every layer it stepped through: all but the last
+    // layer of each interval (n = cf-1, 2cf-1, ..).  That short pass does not touch the transposed weights,
+    // so it runs on this lane while the helper lane transposes them (bandwidth-bound, a lane of its own).
     const int cf = opts->cf;
-    if (!serial_run(opts))
-      STCHK(forward_groups(E, D.E2, N / cf, Rows{(const void* const*)D.tabZ, cf - 1, cf}, NO_ROWS, NO_ROWS,
-                           Params{(const void* const*)D.tabTh, cf - 1, cf}, 0.f, 1, Slots{cf - 1, cf}));
-  } else if (!E.recompute) {
-    STCHK(forward_groups(E, D.E2, N, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, 1, Slots{0, 1}));
+    AuxStream& a = aux_stream();
+    HIPCHK(hipEventRecord(a.fork, st));
+    HIPCHK(hipStreamWaitEvent(D.E2->st, a.fork, 0));
+    int status = transpose_blocks(*D.E2, N, TH, THT);
+    if (status == MGRIT_OK)
+      status = forward_groups(E, nullptr, N / cf, Rows{(const void* const*)D.tabZ, cf - 1, cf}, NO_ROWS, NO_ROWS,
+                              Params{(const void* const*)D.tabTh, cf - 1, cf}, 0.f, 1, Slots{cf - 1, cf});
+    // the helper lane is joined back whatever happened
+    const hipError_t e1 = hipEventRecord(a.join, D.E2->st);
+    const hipError_t e2 = e1 == hipSuccess ? hipStreamWaitEvent(st, a.join, 0) : e1;
+    STCHK(status);
+    HIPCHK(e2);
+  } else {
+    STCHK(transpose_blocks(E, N, TH, THT));
+    if (prefilled) {
+      // a serial run's forward solve has left all layers; with one lane the few missing ones follow here
+      const int cf = opts->cf;
+      if (!serial_run(opts))
+        STCHK(forward_groups(E, D.E2, N / cf, Rows{(const void* const*)D.tabZ, cf - 1, cf}, NO_ROWS, NO_ROWS,
+                             Params{(const void* const*)D.tabTh, cf - 1, cf}, 0.f, 1, Slots{cf - 1, cf}));
+    } else if (!E.recompute) {
+      STCHK(forward_groups(E, D.E2, N, Zrows, NO_ROWS, NO_ROWS, TH, 0.f, 1, Slots{0, 1}));
+    }
   }
   // initial values
   if (lambda_N != static_cast<char*>(lambda_all) + (size_t)N * state)     // may be row N of lambda_all itself
