@@ -616,12 +616,14 @@ static hipError_t launch_mfma(const GemmArgs& a, hipStream_t st) {
   const size_t ring = (size_t)STAGES * (BM + BN) * BK * 2;
   const size_t staging = STAGED ? (size_t)WM * WN * ((32 * (BN / WN * 4 + 16) + 1023) / 1024 * 1024) : 0;
   const size_t smem = ring > staging ? ring : staging;
-  // patch shape of the tile order: as many tiles as one XCD runs at a time, pn wide
+  // patch shape of the tile order: 4 tiles wide, half of what one XCD runs at a time (two patches next
+  // to each other are resident together; measured against whole-resident-set patches: the bias+GELU
+  // launches 5 % faster at the GPT-2 and BERT shapes, the others unchanged)
   int pm = 0, pn = 0;
   const int resident = compute_units() / 8 * OCC;
-  if (tiles_n > 4 && tiles_n % 4 == 0 && resident % 4 == 0 && tiles_m % (resident / 4) == 0) {
+  if (tiles_n > 4 && tiles_n % 4 == 0 && resident % 8 == 0 && tiles_m % (resident / 8) == 0) {
     pn = 4;
-    pm = resident / 4;
+    pm = resident / 8;
   }
   auto kern = gemm_mfma_kernel<BM, BN, BK, STAGES, OCC, STAGED, EPI, bf16, WM, WN>;
   static bool attr_done = false;
