@@ -44,6 +44,8 @@ struct LnBwdArgs {
   const float* rstd;
   // optional: c as a packed operand-type copy, used for out_op in place of the fp32 rows C
   const void* cop; long cop_slot_stride; Slots cop_slots;
+  // optional (with OUT): the same values as OUT once more as a packed operand-type copy
+  void* out_cast; long oc_slot_stride; Slots oc_slots;
 };
 hipError_t launch_ln_bwd(const LnBwdArgs& a, bool is_bf16, hipStream_t st);
 

@@ -527,22 +527,36 @@ inline StackedDec shift(StackedDec s, int c0) {
   return s;
 }
 
+// Operand-type copies of adjoint states, one [T, d] slot per grid point (index of the driver's point table):
+// a transposed step starts from the operand-type copy of its input, and the kernel that writes a step's
+// output state can write that copy on the way.  in: the copies of this chunk's inputs are there (no cast
+// needed); out: where to leave the copies of its outputs.
+struct CastShadow {
+  const void* in = nullptr; Slots in_slots = {0, 1};
+  void* out = nullptr; Slots out_slots = {0, 1};
+};
+inline CastShadow shift(CastShadow c, int c0) { c.in_slots = shift(c.in_slots, c0); c.out_slots = shift(c.out_slots, c0); return c; }
+
 int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Params THT, Rows LIN, Slots cs,
-                  float hstep, const GradPass* gp = nullptr, const StackedDec* sd = nullptr) {
+                  float hstep, const GradPass* gp = nullptr, const StackedDec* sd = nullptr,
+                  const CastShadow* sh = nullptr) {
   const Params* DT = gp ? gp->DT : nullptr;
   const int T = E.T, d = E.d, f = E.f;
   const auto& L = E.lay;
   const Slots loc = {0, 1};
   const size_t esz = E.esz;
 
-  HIPCHK(launch_cast_rows(n, E.Td(), IN, E.cb, E.Td(), loc, E.bf16, E.st));
+  const void* cbuf = E.cb;                 // operand-type copy of the inputs
+  Slots cbs = loc;
+  if (sh && sh->in) { cbuf = sh->in; cbs = sh->in_slots; }
+  else HIPCHK(launch_cast_rows(n, E.Td(), IN, E.cb, E.Td(), loc, E.bf16, E.st));
   LnFwdArgs lf;
   LnParamArgs lp;
   memset(&lf, 0, sizeof(lf));
   memset(&lp, 0, sizeof(lp));
   if (DT) {
     // m = GELU(z) W2^T + b2
-    STCHK(linear_param_grads(E, n, E.cb, E.Td(), loc, d, E.c_zraw, (long)T * f, cs, f, true, *DT, MGRIT_P_W2,
+    STCHK(linear_param_grads(E, n, cbuf, E.Td(), cbs, d, E.c_zraw, (long)T * f, cs, f, true, *DT, MGRIT_P_W2,
                              MGRIT_P_B2, hstep));
     lf.n_groups = n; lf.T = T; lf.d = d; lf.X = LIN; lf.P = TH; lf.eps = E.md.ln_eps;
     lf.out = E.u; lf.out_slot_stride = E.Td(); lf.out_slots = loc;
@@ -551,7 +565,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
   }
 
   // dz = (c W2) * gelu'(z)        [T,d] x [d,f]: transposed W2 is [f,d]; gelu'(z) comes from the cache
-  GemmArgs g = gemm_base(n, T, f, d, E.cb, E.Td(), loc, THT, L.offset[MGRIT_P_W2], -1);
+  GemmArgs g = gemm_base(n, T, f, d, cbuf, E.Td(), cbs, THT, L.offset[MGRIT_P_W2], -1);
   g.out = E.dz; g.out_slot_stride = (long)T * f; g.out_slots = loc;
   g.aux = E.c_z; g.aux_slot_stride = (long)T * f; g.aux_slots = cs;
   HIPCHK(launch_gemm(g, EPI_DGELU, E.bf16, E.st));
@@ -583,7 +597,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
   lb.xhat = E.c_xh2; lb.xhat_slot_stride = E.Td(); lb.xhat_slots = cs; lb.rstd = E.c_rs2;   // LN2 input X + ybar
   lb.P = TH; lb.gamma_off = L.offset[MGRIT_P_LN2_G];
   lb.out_f32 = E.dxin; lb.of_slot_stride = E.Td(); lb.of_slots = loc;
-  lb.cop = E.cb; lb.cop_slot_stride = E.Td(); lb.cop_slots = loc;
+  lb.cop = cbuf; lb.cop_slot_stride = E.Td(); lb.cop_slots = cbs;
   lb.out_op = E.ds; lb.oo_slot_stride = E.Td(); lb.oo_slots = loc;
   HIPCHK(launch_ln_bwd(lb, E.bf16, E.st));
 
@@ -717,6 +731,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
   lb.P = TH; lb.gamma_off = L.offset[MGRIT_P_LN1_G];
   lb.add = E.dxin; lb.add_slot_stride = E.Td(); lb.add_slots = loc;
   lb.C = IN; lb.OUT = OUT; lb.RHS = RHS; lb.hstep = hstep; lb.rhs_sign = E.rhs_sign;
+  if (sh && sh->out) { lb.out_cast = sh->out; lb.oc_slot_stride = E.Td(); lb.oc_slots = sh->out_slots; }
   HIPCHK(launch_ln_bwd(lb, E.bf16, E.st));
   return MGRIT_OK;
 }
@@ -759,10 +774,12 @@ int forward_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Pa
 // memory-gradient terms (dE_all, may be null); the caller guarantees that IN holds final values
 int adjoint_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Params TH, Params THT, Rows LIN,
                    Slots cs, float hstep, const StackedDec* sd = nullptr, bool emit = false,
-                   const Params* DT = nullptr, float* dE_all = nullptr) {
+                   const Params* DT = nullptr, float* dE_all = nullptr, const CastShadow* sh = nullptr) {
   return run_chunks(E, E2, G, [&](Engine& L, int c0, int n) {
     StackedDec s;
     if (sd) s = shift(*sd, c0);
+    CastShadow shc;
+    if (sh) shc = shift(*sh, c0);
     Params dt = {nullptr, 0, 0};
     GradPass gp;
     if (emit) {
@@ -778,7 +795,7 @@ int adjoint_groups(Engine& E, Engine* E2, int G, Rows IN, Rows OUT, Rows RHS, Pa
                           sd ? s.MEM : NO_ROWS));
     }
     return adjoint_chunk(L, n, shift(IN, c0), shift(OUT, c0), shift(RHS, c0), shift(TH, c0), shift(THT, c0),
-                         shift(LIN, c0), slots, hstep, emit ? &gp : nullptr, sd ? &s : nullptr);
+                         shift(LIN, c0), slots, hstep, emit ? &gp : nullptr, sd ? &s : nullptr, sh ? &shc : nullptr);
   });
 }
 
@@ -924,6 +941,10 @@ struct Driver {
   // entries of the adjoint's linearisation cache on the way (the engines' cache pointers then point
   // into the adjoint's workspace).  The layers n = cf-1, 2cf-1, .. are left to the adjoint.
   bool fill_cache = false, cache_now = false;
+  // adjoint: operand-type copy of every grid point's state, [N+1][T,d], and which of them hold the point's
+  // current value (host-side bookkeeping at enqueue time: grid points are written by steps only)
+  void* shadow = nullptr;
+  std::vector<char> shadow_valid;
 
   // cnt steps of level `lvl`, group k starting at point j = j0 + k*js
   int step(int lvl, int j0, int js, int cnt, Rows OUT, Rows RHS) {
@@ -952,13 +973,29 @@ struct Driver {
     Params TH = {(const void* const*)tabTh, n0, ns};
     Params THT = {(const void* const*)tabThT, n0, ns};
     Rows LIN = {(const void* const*)tabZ, n0, ns};
+    // operand-type copies of the states (see CastShadow): the inputs' copies exist if every input point was
+    // written by a step of this call; the outputs' copies are left when the outputs are grid points
+    CastShadow sh;
+    const bool out_is_point = OUT.tab == (const void* const*)tabW;
+    if (shadow) {
+      bool have = true;
+      for (int k = 0; k < cnt && have; ++k) have = shadow_valid[(size_t)(j0 + k * js) * s] != 0;
+      if (have) { sh.in = shadow; sh.in_slots = Slots{j0 * s, js * s}; }
+      if (out_is_point) { sh.out = shadow; sh.out_slots = Slots{OUT.i0, OUT.is}; }
+    }
+    int st;
     if (emit_now && lvl == 0) {
       emitted = true;
       const Params DT = {(const void* const*)tabDT, n0, ns};
-      return adjoint_groups(L1, L2, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep, nullptr, true,
-                            tabDT ? &DT : nullptr, dE_all);
+      st = adjoint_groups(L1, L2, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep, nullptr, true,
+                          tabDT ? &DT : nullptr, dE_all, shadow ? &sh : nullptr);
+    } else {
+      st = adjoint_groups(L1, L2, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep, nullptr, false, nullptr,
+                          nullptr, shadow ? &sh : nullptr);
     }
-    return adjoint_groups(L1, L2, cnt, IN, OUT, RHS, TH, THT, LIN, Slots{n0, ns}, hstep);
+    if (shadow && out_is_point && st == MGRIT_OK)
+      for (int k = 0; k < cnt; ++k) shadow_valid[(size_t)OUT.i0 + (size_t)k * OUT.is] = 1;
+    return st;
   }
 
   // g'_k = R_k - Phi'(w_{(k-1) cf}) for the groups g0 .. g0+n-1 of level lvl+1 (Gn, R already shifted to g0).
@@ -1176,6 +1213,10 @@ int make_plan(Plan& P, const mgrit_model_desc* md, const mgrit_opts* op, int mod
                     hipSuccess)
         return MGRIT_HIP_ERROR;
     }
+  }
+  if (adjoint) {
+    D.shadow = b.take_bytes((size_t)(N + 1) * E.T * E.d * E.esz);
+    D.shadow_valid.assign((size_t)N + 1, 0);
   }
   D.tabG.assign(D.L, nullptr);
   if (!serial) {

@@ -228,6 +228,7 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
     const bool need_c = (oo != nullptr && !cop) || a.OUT.present();
     const float* cvec = need_c ? a.C.at(g) + ro : nullptr;
     float* OUT = a.OUT.present() ? a.OUT.at(g) + ro : nullptr;
+    TO* ocast = a.out_cast ? reinterpret_cast<TO*>(a.out_cast) + a.oc_slots.of(g) * a.oc_slot_stride + ro : nullptr;
     const float* RHS = a.RHS.present() ? a.RHS.at(g) + ro : nullptr;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -249,6 +250,7 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(const LnBwdArgs a) {
               for (int e = 0; e < 4; ++e) res[e] = __builtin_fmaf(a.rhs_sign, res[e], rhs[e]);
             }
             *reinterpret_cast<f32x4*>(OUT + c) = res;
+            if (ocast) store4<TO>(ocast + c, res);
           }
         }
       }
@@ -288,7 +290,8 @@ hipError_t launch_ln_bwd(const LnBwdArgs& a, bool is_bf16, hipStream_t st) {
   const bool c_rows = (a.out_op && !a.cop) || a.OUT.present();
   const double per_elem = esz + (xh ? esz : (a.X.present() ? 4 : 0) + (a.xp ? 4 : 0)) + (a.add ? 4 : 0) +
                           (a.out_f32 ? 4 : 0) + (c_rows ? 4 : 0) + (a.out_op && a.cop ? esz : 0) +
-                          (a.out_op ? esz : 0) + (a.OUT.present() ? 4 : 0) + (a.RHS.present() ? 4 : 0);
+                          (a.out_op ? esz : 0) + (a.OUT.present() ? 4 : 0) + (a.RHS.present() ? 4 : 0) +
+                          (a.out_cast && a.OUT.present() ? esz : 0);
   ProfScope ps(a.n_groups > 1 ? PC_LN_BWD : PC_LN_BWD_SINGLE, 16.0 * rows * a.d, (double)rows * a.d * per_elem, st);
   if (is_bf16) { if (xh) ln_bwd_dispatch<bf16, true>(a, blocks, st); else ln_bwd_dispatch<bf16, false>(a, blocks, st); }
   else { if (xh) ln_bwd_dispatch<float, true>(a, blocks, st); else ln_bwd_dispatch<float, false>(a, blocks, st); }
