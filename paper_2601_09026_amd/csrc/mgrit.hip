@@ -534,6 +534,12 @@ inline StackedDec shift(StackedDec s, int c0) {
 struct CastShadow {
   const void* in = nullptr; Slots in_slots = {0, 1};
   void* out = nullptr; Slots out_slots = {0, 1};
+  const char* valid = nullptr;            // per grid point: its copy is current (checked per launch chunk)
+  bool have_inputs(int n) const {
+    if (!in || !valid) return false;
+    for (int g = 0; g < n; ++g) if (!valid[in_slots.of(g)]) return false;
+    return true;
+  }
 };
 inline CastShadow shift(CastShadow c, int c0) { c.in_slots = shift(c.in_slots, c0); c.out_slots = shift(c.out_slots, c0); return c; }
 
@@ -548,7 +554,7 @@ int adjoint_chunk(Engine& E, int n, Rows IN, Rows OUT, Rows RHS, Params TH, Para
 
   const void* cbuf = E.cb;                 // operand-type copy of the inputs
   Slots cbs = loc;
-  if (sh && sh->in) { cbuf = sh->in; cbs = sh->in_slots; }
+  if (sh && sh->have_inputs(n)) { cbuf = sh->in; cbs = sh->in_slots; }
   else HIPCHK(launch_cast_rows(n, E.Td(), IN, E.cb, E.Td(), loc, E.bf16, E.st));
   LnFwdArgs lf;
   LnParamArgs lp;
@@ -978,9 +984,7 @@ struct Driver {
     CastShadow sh;
     const bool out_is_point = OUT.tab == (const void* const*)tabW;
     if (shadow) {
-      bool have = true;
-      for (int k = 0; k < cnt && have; ++k) have = shadow_valid[(size_t)(j0 + k * js) * s] != 0;
-      if (have) { sh.in = shadow; sh.in_slots = Slots{j0 * s, js * s}; }
+      sh.in = shadow; sh.in_slots = Slots{j0 * s, js * s}; sh.valid = shadow_valid.data();
       if (out_is_point) { sh.out = shadow; sh.out_slots = Slots{OUT.i0, OUT.is}; }
     }
     int st;
@@ -1528,6 +1532,20 @@ int adjoint_impl(const mgrit_model_desc* desc, const mgrit_opts* opts, const voi
     for (int k = 1; k <= N / opts->cf; ++k)
       HIPCHK(hipMemcpyAsync(static_cast<char*>(lambda_all) + (size_t)(N - k * opts->cf) * state, lambda_N, state,
                             hipMemcpyDeviceToDevice, st));
+  }
+  if (D.shadow) {
+    // operand-type copies of the initial values: point 0 (lambda_N) and the C-points that were set to it
+    const Rows first = {(const void* const*)D.tabW, 0, 1};
+    HIPCHK(launch_cast_rows(1, E.Td(), first, D.shadow, E.Td(), Slots{0, 1}, E.bf16, st));
+    D.shadow_valid[0] = 1;
+    if (!serial_run(opts) && opts->init_guess == 0) {
+      const size_t sbytes = (size_t)E.Td() * E.esz;
+      for (int k = 1; k <= N / opts->cf; ++k) {
+        HIPCHK(hipMemcpyAsync(static_cast<char*>(D.shadow) + (size_t)k * opts->cf * sbytes, D.shadow, sbytes,
+                              hipMemcpyDeviceToDevice, st));
+        D.shadow_valid[(size_t)k * opts->cf] = 1;
+      }
+    }
   }
   D.resnorm = resnorm;
   if (dtheta) HIPCHK(upload_pointers(P.tabDT, (const void* const*)dtheta, N, st));
